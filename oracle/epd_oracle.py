@@ -1,0 +1,229 @@
+"""CPU oracle for the EPD encode stage  --  TEST INFRASTRUCTURE ONLY.
+
+What it is: the plain definition of what the encode stage E computes
+(Section 3.1: multimodal tokens v = E(i_m)) for a vision-transformer encoder
+fed with image slices, one slice at a time, in float64 numpy.  Slices of a
+request are encoded independently of each other and merged in slice order
+(Section 3.2.2, intra-request parallelism); a shard of a request is therefore
+just a range of slices whose rows land at their final place in the request's
+token buffer.
+
+The paper treats E as a given model and prints none of its internals, so each
+step below is the textbook definition (patch embedding, LayerNorm / RMSNorm,
+softmax attention, GELU, space-to-depth pixel shuffle, linear / MLP
+projector); where the workload description leaves a choice open the reading
+taken is written next to the step.
+
+Rules this file keeps:
+  * float64 everywhere; numpy `@` is the only library primitive used for a
+    contraction, `scipy.special.erf` for the error function;
+  * no blocking, fusion or reordering beyond the definitions;
+  * shares no code with the HIP path and imports nothing from it;
+  * may be imported only by tests/, by __graft_entry__.smoke() and by
+    bench.py's cpu_baseline leg.
+
+Pins (tests/test_oracle_*.py): brute-force loops for the contractions and
+attention on tiny shapes, closed forms for the norms and softmax, tabulated
+values of the normal CDF for GELU, index arithmetic for patchify and pixel
+shuffle, an affine special case (zero layers), an identity special case (zero
+output projections), a composition of PyTorch CPU library ops for the whole
+tiny encoder, and the independence / permutation / shard invariants.
+Parity unpinned: fidelity to the *trained* SigLIP / InternViT checkpoints (no
+weights or reference activations exist here; the target does not need them).
+"""
+from __future__ import annotations
+
+from typing import Dict, Iterable, Optional, Sequence
+
+import numpy as np
+from scipy.special import erf as _erf
+
+F64 = np.float64
+
+# integer codes of the model description (same values as the C header)
+NORM_LAYERNORM, NORM_RMSNORM = 0, 1
+QKNORM_NONE, QKNORM_FULL, QKNORM_PER_HEAD = 0, 1, 2
+ACT_GELU_ERF, ACT_GELU_TANH = 0, 1
+PROJ_LINEAR, PROJ_MLP = 0, 1
+
+
+# ---------------------------------------------------------------- steps ----
+
+def patchify(tile: np.ndarray, p: int) -> np.ndarray:
+    """[3, S, S] -> [N, 3*p*p].  Grid cell (y, x) becomes row n = y*g + x; the
+    patch vector is ordered (channel, dy, dx), the order of a convolution
+    weight [D, 3, p, p] flattened over its last three axes."""
+    C, S, S2 = tile.shape
+    assert S == S2 and S % p == 0
+    g = S // p
+    t = np.asarray(tile, dtype=F64).reshape(C, g, p, g, p)   # c, y, dy, x, dx
+    return t.transpose(1, 3, 0, 2, 4).reshape(g * g, C * p * p)
+
+
+def linear(x: np.ndarray, W: np.ndarray, b: Optional[np.ndarray]) -> np.ndarray:
+    """y = x W^T + b with W stored [out, in]."""
+    y = np.asarray(x, F64) @ np.asarray(W, F64).T
+    if b is not None:
+        y = y + np.asarray(b, F64)
+    return y
+
+
+def layer_norm(x, gamma, beta, eps):
+    """(x - mean) / sqrt(biased variance + eps) * gamma + beta over the last axis."""
+    x = np.asarray(x, F64)
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + eps) * np.asarray(gamma, F64) + np.asarray(beta, F64)
+
+
+def rms_norm(x, gamma, eps):
+    """x / sqrt(mean(x^2) + eps) * gamma over the last axis (no shift)."""
+    x = np.asarray(x, F64)
+    ms = (x * x).mean(axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gamma, F64)
+
+
+def gelu_erf(x):
+    x = np.asarray(x, F64)
+    return 0.5 * x * (1.0 + _erf(x / np.sqrt(2.0)))
+
+
+def gelu_tanh(x):
+    x = np.asarray(x, F64)
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+def softmax_rows(s):
+    s = np.asarray(s, F64)
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention(q, k, v, heads: int):
+    """Non-causal softmax attention inside one slice.  q, k, v: [N, D]; head h
+    owns columns h*hd .. (h+1)*hd-1; logits are scaled by 1/sqrt(hd)."""
+    q, k, v = (np.asarray(a, F64) for a in (q, k, v))
+    N, D = q.shape
+    hd = D // heads
+    out = np.empty((N, D), F64)
+    for h in range(heads):
+        sl = slice(h * hd, (h + 1) * hd)
+        P = softmax_rows((q[:, sl] @ k[:, sl].T) / np.sqrt(float(hd)))
+        out[:, sl] = P @ v[:, sl]
+    return out
+
+
+def pixel_shuffle_half(x, g: int):
+    """Space-to-depth with block 2 on a g x g token grid: [g*g, D] -> [g*g/4, 4D].
+    Output token m = Y*(g/2) + X, channel (dy*2 + dx)*D + c, is input token
+    (2Y+dy)*g + (2X+dx), channel c."""
+    x = np.asarray(x)
+    N, D = x.shape
+    assert N == g * g and g % 2 == 0
+    h = g // 2
+    t = x.reshape(h, 2, h, 2, D)            # Y, dy, X, dx, c
+    return t.transpose(0, 2, 1, 3, 4).reshape(h * h, 4 * D)
+
+
+# -------------------------------------------------------------- encoder ----
+
+def _norm(x, w: Dict[str, np.ndarray], prefix: str, kind: int, eps: float):
+    if kind == NORM_LAYERNORM:
+        return layer_norm(x, w[prefix + "_g"], w[prefix + "_b"], eps)
+    return rms_norm(x, w[prefix + "_g"], eps)
+
+
+def _act(x, kind: int):
+    return gelu_erf(x) if kind == ACT_GELU_ERF else gelu_tanh(x)
+
+
+def encoder_layer(x, w, desc, l: int):
+    """One pre-norm transformer layer on the [N, D] tokens of one slice."""
+    D, H = desc.hidden, desc.heads
+    p = f"l{l}_"
+    u = _norm(x, w, p + "n1", desc.norm, desc.eps)
+    qkv = linear(u, w[p + "qkv_w"], w[p + "qkv_b"])      # rows of W: q block, k block, v block
+    q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+    if desc.qk_norm == QKNORM_FULL:
+        # reading: RMSNorm of q and of k over all heads together, after the
+        # bias, before the head split and the 1/sqrt(hd) scale
+        q = rms_norm(q, w[p + "qn_g"], desc.eps)
+        k = rms_norm(k, w[p + "kn_g"], desc.eps)
+    elif desc.qk_norm == QKNORM_PER_HEAD:
+        hd = D // H
+        q = rms_norm(q.reshape(-1, H, hd), w[p + "qn_g"], desc.eps).reshape(-1, D)
+        k = rms_norm(k.reshape(-1, H, hd), w[p + "kn_g"], desc.eps).reshape(-1, D)
+    o = attention(q, k, v, H)
+    x = x + linear(o, w[p + "o_w"], w[p + "o_b"])
+    u = _norm(x, w, p + "n2", desc.norm, desc.eps)
+    hmid = _act(linear(u, w[p + "fc1_w"], w[p + "fc1_b"]), desc.act)
+    x = x + linear(hmid, w[p + "fc2_w"], w[p + "fc2_b"])
+    return x
+
+
+def embed_tile(tile, w, desc):
+    """Patch embedding + learned position embedding; no class token."""
+    a = patchify(tile, desc.patch)
+    return linear(a, w["pe_w"], w["pe_b"]) + np.asarray(w["pos"], F64)
+
+
+def project(x, w, desc):
+    """Optional pixel shuffle, optional LayerNorm, then Linear or
+    Linear-GELU(erf)-Linear."""
+    if desc.pixel_shuffle:
+        x = pixel_shuffle_half(x, desc.tile_size // desc.patch)
+    if desc.proj_prenorm:
+        x = layer_norm(x, w["pn_g"], w["pn_b"], desc.eps)
+    if desc.proj_kind == PROJ_LINEAR:
+        return linear(x, w["pa_w"], w["pa_b"])
+    hmid = gelu_erf(linear(x, w["pa_w"], w["pa_b"]))
+    return linear(hmid, w["pb_w"], w["pb_b"])
+
+
+def encode_tile(tile, w, desc, trace: Optional[dict] = None):
+    """Tokens of one slice: [tokens_per_tile, out_dim], float64."""
+    x = embed_tile(tile, w, desc)
+    if trace is not None:
+        trace["embed"] = x.copy()
+    for l in range(desc.layers):
+        x = encoder_layer(x, w, desc, l)
+        if trace is not None:
+            trace[f"layer{l}"] = x.copy()
+    if desc.final_norm:
+        x = _norm(x, w, "fn", desc.norm, desc.eps)
+    return project(x, w, desc)
+
+
+def tokens_per_tile(desc) -> int:
+    n = (desc.tile_size // desc.patch) ** 2
+    return n // 4 if desc.pixel_shuffle else n
+
+
+def encode_range(tiles, n_tiles_total: int, tile_begin: int, tile_end: int, w, desc,
+                 out: np.ndarray) -> np.ndarray:
+    """Encode slices [tile_begin, tile_end) of a packed batch and write their
+    tokens to rows [tile_begin*N_out, tile_end*N_out) of `out`; other rows are
+    left alone (one encode worker's share of the batch)."""
+    assert 0 <= tile_begin <= tile_end <= n_tiles_total
+    n_out = tokens_per_tile(desc)
+    for t in range(tile_begin, tile_end):
+        out[t * n_out:(t + 1) * n_out, :] = encode_tile(tiles[t], w, desc)
+    return out
+
+
+def encode(tiles, tile_offsets: Sequence[int], w, desc) -> np.ndarray:
+    """Whole batch.  tile_offsets[r] .. tile_offsets[r+1] are request r's
+    slices; request r's token buffer is the contiguous row block
+    out[tile_offsets[r]*N_out : tile_offsets[r+1]*N_out]."""
+    off = list(tile_offsets)
+    assert off[0] == 0 and all(a <= b for a, b in zip(off, off[1:]))
+    n_tiles = off[-1]
+    assert len(tiles) == n_tiles
+    out = np.zeros((n_tiles * tokens_per_tile(desc), desc.proj_out), F64)
+    return encode_range(tiles, n_tiles, 0, n_tiles, w, desc, out)
+
+
+def encode_sample(tile_list: Iterable[np.ndarray], w, desc) -> np.ndarray:
+    """Tokens of the given slices stacked in the given order (used when only a
+    sample of a large batch is affordable on the CPU)."""
+    return np.concatenate([encode_tile(t, w, desc) for t in tile_list], axis=0)

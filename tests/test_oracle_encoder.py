@@ -1,0 +1,223 @@
+"""Pins for the whole-encoder oracle: an independent composition of PyTorch
+CPU library ops (conv2d patch embedding, layer_norm / rms_norm,
+scaled_dot_product_attention, gelu, linear, pixel_unshuffle), special cases
+with closed forms, and the invariants that follow from slices being encoded
+independently (Section 3.2.2)."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import workloads as wl
+from oracle import epd_oracle as O
+
+
+def small_desc(**kw):
+    base = dict(dtype=wl.DT_FP32, tile_size=56, patch=14, hidden=32, heads=2, mlp=64, layers=2,
+                norm=wl.NORM_LAYERNORM, qk_norm=wl.QKNORM_NONE, act=wl.ACT_GELU_ERF, final_norm=0,
+                pixel_shuffle=0, proj_kind=wl.PROJ_LINEAR, proj_prenorm=0, proj_mid=0, proj_out=24,
+                eps=1e-6, max_tiles_per_call=8)
+    base.update(kw)
+    return wl.ModelDesc(**base)
+
+
+VARIANTS = {
+    "ln_linear": dict(),
+    "tanh_mlp": dict(act=wl.ACT_GELU_TANH, proj_kind=wl.PROJ_MLP, proj_mid=40),
+    "shuffle_ln_mlp": dict(pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
+    "rms_qkfull": dict(norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_FULL, pixel_shuffle=1,
+                       proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
+    "rms_qkhead_final": dict(norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_PER_HEAD, final_norm=1),
+    "ln_final": dict(final_norm=1, heads=4),
+}
+
+
+def torch_second_opinion(tile, w, desc):
+    """Same encoder from PyTorch CPU library ops, float64."""
+    t = {k: torch.from_numpy(np.asarray(v, np.float64)) for k, v in w.items()}
+    D, H, p = desc.hidden, desc.heads, desc.patch
+    g = desc.tile_size // p
+    img = torch.from_numpy(np.asarray(tile, np.float64))[None]            # [1,3,S,S]
+    x = F.conv2d(img, t["pe_w"].reshape(D, 3, p, p), t["pe_b"], stride=p)  # [1,D,g,g]
+    x = x.flatten(2).transpose(1, 2)[0] + t["pos"]                         # [N,D]
+
+    def norm(x, prefix, kind):
+        if kind == wl.NORM_LAYERNORM:
+            return F.layer_norm(x, (x.shape[-1],), t[prefix + "_g"], t[prefix + "_b"], desc.eps)
+        return F.rms_norm(x, (x.shape[-1],), t[prefix + "_g"], desc.eps)
+
+    for l in range(desc.layers):
+        pre = f"l{l}_"
+        u = norm(x, pre + "n1", desc.norm)
+        q, k, v = F.linear(u, t[pre + "qkv_w"], t[pre + "qkv_b"]).chunk(3, dim=-1)
+        if desc.qk_norm == wl.QKNORM_FULL:
+            q = F.rms_norm(q, (D,), t[pre + "qn_g"], desc.eps)
+            k = F.rms_norm(k, (D,), t[pre + "kn_g"], desc.eps)
+        hd = D // H
+        q, k, v = (a.reshape(-1, H, hd).transpose(0, 1) for a in (q, k, v))  # [H,N,hd]
+        if desc.qk_norm == wl.QKNORM_PER_HEAD:
+            q = F.rms_norm(q, (hd,), t[pre + "qn_g"], desc.eps)
+            k = F.rms_norm(k, (hd,), t[pre + "kn_g"], desc.eps)
+        o = F.scaled_dot_product_attention(q[None], k[None], v[None])[0]    # [H,N,hd]
+        o = o.transpose(0, 1).reshape(-1, D)
+        x = x + F.linear(o, t[pre + "o_w"], t[pre + "o_b"])
+        u = norm(x, pre + "n2", desc.norm)
+        hmid = F.gelu(F.linear(u, t[pre + "fc1_w"], t[pre + "fc1_b"]),
+                      approximate="tanh" if desc.act == wl.ACT_GELU_TANH else "none")
+        x = x + F.linear(hmid, t[pre + "fc2_w"], t[pre + "fc2_b"])
+    if desc.final_norm:
+        x = norm(x, "fn", desc.norm)
+    if desc.pixel_shuffle:
+        # pixel_unshuffle emits channel c*4 + dy*2 + dx; the encoder's order is (dy*2+dx)*D + c
+        y = F.pixel_unshuffle(x.T.reshape(1, D, g, g), 2)                    # [1, 4D, g/2, g/2]
+        y = y.reshape(D, 4, -1).permute(2, 1, 0).reshape(-1, 4 * D)
+        x = y
+    if desc.proj_prenorm:
+        x = F.layer_norm(x, (x.shape[-1],), t["pn_g"], t["pn_b"], desc.eps)
+    if desc.proj_kind == wl.PROJ_LINEAR:
+        x = F.linear(x, t["pa_w"], t["pa_b"])
+    else:
+        x = F.linear(F.gelu(F.linear(x, t["pa_w"], t["pa_b"])), t["pb_w"], t["pb_b"])
+    return x.numpy()
+
+
+@pytest.mark.parametrize("variant", sorted(VARIANTS))
+def test_encoder_vs_torch_cpu_library_ops(variant):
+    desc = small_desc(**VARIANTS[variant])
+    # std 0.3 and sharper q/k so that every branch matters numerically
+    w = wl.gen_weights(desc, 7, std=0.3)
+    tile = wl.gen_tile(desc, 7, 0)
+    got = O.encode_tile(tile, w, desc)
+    want = torch_second_opinion(tile, w, desc)
+    assert got.shape == (desc.tokens_per_tile, desc.out_dim)
+    np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-10)
+
+
+def test_c1_shape_vs_torch_cpu_library_ops():
+    w_ = wl.workload("c1")
+    desc = w_.desc
+    w = wl.gen_weights(desc, w_.weight_seed)
+    tile = wl.gen_tile(desc, w_.input_seed, 0)
+    got = O.encode_tile(tile, w, desc)
+    assert got.shape == (256, 512)
+    np.testing.assert_allclose(got, torch_second_opinion(tile, w, desc), rtol=1e-9, atol=1e-11)
+
+
+def test_second_opinion_is_sensitive_to_each_part():
+    """Guards against a vacuous pin: breaking any single part of the weights
+    moves the output by far more than the comparison tolerance."""
+    desc = small_desc(**VARIANTS["rms_qkfull"])
+    w = wl.gen_weights(desc, 7, std=0.3)
+    tile = wl.gen_tile(desc, 7, 0)
+    base = O.encode_tile(tile, w, desc)
+    for name in w:
+        w2 = dict(w)
+        # non-constant bump: a constant shift of the last bias is removed by the projector's LayerNorm
+        w2[name] = w[name] + 0.05 * np.cos(np.arange(w[name].size)).reshape(w[name].shape)
+        assert np.abs(O.encode_tile(tile, w2, desc) - base).max() > 1e-6, name
+
+
+def test_zero_layers_linear_projector_is_affine_in_pixels():
+    desc = small_desc(layers=0)
+    w = wl.gen_weights(desc, 11, std=0.2)
+    tile = wl.gen_tile(desc, 11, 0)
+    got = O.encode_tile(tile, w, desc)
+    # brute force: out[n] = pa_w (pe_w a_n + pe_b + pos_n) + pa_b with a_n gathered by hand
+    g, p = desc.grid, desc.patch
+    for n in (0, 5, g * g - 1):
+        y, x = divmod(n, g)
+        a = np.array([tile[c, p * y + dy, p * x + dx] for c in range(3) for dy in range(p) for dx in range(p)],
+                     dtype=np.float64)
+        e = w["pe_w"].astype(np.float64) @ a + w["pe_b"] + w["pos"][n]
+        want = w["pa_w"].astype(np.float64) @ e + w["pa_b"]
+        np.testing.assert_allclose(got[n], want, rtol=1e-11, atol=1e-12)
+
+
+def test_zero_output_projections_make_layers_the_identity():
+    desc = small_desc()
+    w = wl.gen_weights(desc, 12, std=0.2)
+    for l in range(desc.layers):
+        for nm in ("o_w", "o_b", "fc2_w", "fc2_b"):
+            w[f"l{l}_{nm}"] = np.zeros_like(w[f"l{l}_{nm}"])
+    tile = wl.gen_tile(desc, 12, 0)
+    emb = O.embed_tile(tile, w, desc)
+    np.testing.assert_array_equal(O.encode_tile(tile, w, desc), O.linear(emb, w["pa_w"], w["pa_b"]))
+
+
+def test_tiles_are_independent_and_permutation_permutes_rows():
+    desc = small_desc(**VARIANTS["shuffle_ln_mlp"])
+    w = wl.gen_weights(desc, 3, std=0.2)
+    tiles = wl.gen_tiles(desc, 3, 5)
+    n_out = desc.tokens_per_tile
+    full = O.encode(tiles, [0, 2, 2, 5], w, desc)
+    assert full.shape == (5 * n_out, desc.out_dim)
+    perm = [3, 0, 4, 2, 1]
+    permuted = O.encode(tiles[perm], [0, 5], w, desc)
+    for i, src in enumerate(perm):
+        np.testing.assert_array_equal(permuted[i * n_out:(i + 1) * n_out], full[src * n_out:(src + 1) * n_out])
+    # a tile alone equals the tile in the batch
+    np.testing.assert_array_equal(O.encode(tiles[2:3], [0, 1], w, desc), full[2 * n_out:3 * n_out])
+    # changing one tile's pixels changes no other tile's tokens
+    tiles2 = tiles.copy(); tiles2[1] += 0.25
+    full2 = O.encode(tiles2, [0, 2, 2, 5], w, desc)
+    for t in range(5):
+        same = np.array_equal(full2[t * n_out:(t + 1) * n_out], full[t * n_out:(t + 1) * n_out])
+        assert same == (t != 1)
+
+
+def test_shards_write_final_rows_and_union_equals_unsharded():
+    desc = small_desc()
+    w = wl.gen_weights(desc, 4, std=0.2)
+    offsets = [0, 3, 3, 9, 10]                      # requests of 3, 0, 6, 1 tiles
+    tiles = wl.gen_tiles(desc, 4, offsets[-1])
+    n_out = desc.tokens_per_tile
+    full = O.encode(tiles, offsets, w, desc)
+    sentinel = -777.0
+    out = np.full_like(full, sentinel)
+    covered = np.zeros(offsets[-1], dtype=int)
+    for s in range(4):
+        for r in range(len(offsets) - 1):
+            n = offsets[r + 1] - offsets[r]
+            b, e = wl.shard_range(n, s, 4)
+            before = out.copy()
+            O.encode_range(tiles, offsets[-1], offsets[r] + b, offsets[r] + e, w, desc, out)
+            covered[offsets[r] + b:offsets[r] + e] += 1
+            touched = np.any(out != before, axis=1).reshape(-1, n_out).any(axis=1)
+            assert set(np.nonzero(touched)[0]) <= set(range(offsets[r] + b, offsets[r] + e))
+    assert np.all(covered == 1)
+    np.testing.assert_array_equal(out, full)
+
+
+def test_shard_range_is_a_balanced_partition():
+    for n in range(0, 40):
+        pieces = [wl.shard_range(n, s, 4) for s in range(4)]
+        assert pieces[0][0] == 0 and pieces[-1][1] == n
+        assert all(pieces[i][1] == pieces[i + 1][0] for i in range(3))
+        sizes = [e - b for b, e in pieces]
+        assert max(sizes) - min(sizes) <= 1
+
+
+def test_workload_shapes_match_the_paper_tables():
+    # 13 slices per 4K image for the InternVL-style encoders, 10 for the MiniCPM-V style (Table 3)
+    c3 = wl.workload("c3")
+    assert c3.n_tiles == 104 and c3.n_requests == 8 and all(t == (13,) for t in c3.image_tiles)
+    assert wl.workload("c2").n_tiles == 10
+    c5 = wl.workload("c5")
+    assert c5.n_requests == 32
+    assert all(1 <= len(t) <= 10 and all(1 <= v <= 9 for v in t) for t in c5.image_tiles)
+    assert c5.tile_offsets[-1] == sum(sum(t) for t in c5.image_tiles)
+    for name, tokens, dim in (("c1", 256, 512), ("c2", 1024, 3584), ("c3", 256, 4096), ("c4", 256, 5120)):
+        d = wl.workload(name).desc
+        assert (d.tokens_per_tile, d.out_dim) == (tokens, dim)
+    assert abs(wl.flops_per_tile(c3.desc) / 1e9 - 740.0) < 1.0
+
+
+def test_bf16_grid_rounding_is_nearest_even():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -7, -0.3, 1e-3], np.float32)
+    r = wl.to_bf16_grid(x)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(r, want)
+    assert r[1] == 1.0 and r[2] == np.float32(1.0 + 2 ** -6)        # ties go to even
+    bits = wl.bf16_bits(r)
+    back = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(back, r)
