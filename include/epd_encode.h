@@ -1,0 +1,202 @@
+/*
+ * epd_encode.h  --  C boundary of the MI355X (gfx950) encode-stage library.
+ *
+ * The encode stage E of an encode / prefill / decode disaggregated pipeline
+ * turns the multimodal input of a request into multimodal tokens,
+ * v = E(i_m) (Section 3.1, "Encoding (E)").  An encode worker holds only the
+ * encoder weights and a multimodal-token cache (Section 3.2, "System Design
+ * and Optimization"); tokens stay in that cache until the next stage pulls
+ * them (Section 3.2.1).  A request's image slices are encoded independently
+ * of each other, so a request may be split across encode workers and the
+ * token blocks merged in slice order (Section 3.2.2, intra-request
+ * parallelism).  This library is the forward pass of one such worker on one
+ * GPU: packed image slices in, per-request contiguous token buffers out.
+ *
+ * All functions are plain C, never throw, and return an epd_status (0 = ok,
+ * negative = error, nothing enqueued, output untouched).  "dev" = pointer to
+ * device (HBM) memory, "host" = pointer to host memory.  The library never
+ * allocates or frees the caller's buffers; all device work of a call is
+ * enqueued on the caller's HIP stream and the call returns after enqueueing.
+ * A context serves one stream at a time (calls on one context must not
+ * overlap).  epd_encode / epd_encode_range allocate nothing.
+ */
+#ifndef EPD_ENCODE_H
+#define EPD_ENCODE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct epd_ctx epd_ctx; /* opaque: packed weights + workspace */
+
+typedef enum {
+  EPD_OK = 0,
+  EPD_ERR_INVALID_ARG = -1, /* null pointer, bad enum value, misaligned pointer */
+  EPD_ERR_SHAPE = -2,       /* description is inconsistent (hidden % heads, ...) */
+  EPD_ERR_OFFSETS = -3,     /* tile_offsets / tile range not a valid partition   */
+  EPD_ERR_UNSUPPORTED = -4, /* valid but outside what the kernels handle         */
+  EPD_ERR_NOMEM = -5,       /* device allocation failed in epd_create            */
+  EPD_ERR_HIP = -6          /* a HIP call or launch failed                       */
+} epd_status;
+
+enum { EPD_DTYPE_FP32 = 0, EPD_DTYPE_BF16 = 1 };
+enum { EPD_NORM_LAYERNORM = 0, EPD_NORM_RMSNORM = 1 };
+enum { EPD_QKNORM_NONE = 0, EPD_QKNORM_FULL = 1, EPD_QKNORM_PER_HEAD = 2 };
+enum { EPD_ACT_GELU_ERF = 0, EPD_ACT_GELU_TANH = 1 };
+enum { EPD_PROJ_LINEAR = 0, EPD_PROJ_MLP = 1 };
+
+/* Encoder description.  The paper takes the encoder as given (SigLIP-400M,
+ * InternViT-300M / 6B; Appendix "LMM Details"); this struct states which
+ * vision transformer that is. */
+typedef struct {
+  int32_t dtype;         /* EPD_DTYPE_*: type of weights, activations and output        */
+  int32_t tile_size;     /* side S of a square image slice in pixels (448, 224)          */
+  int32_t patch;         /* side p of a ViT patch (14); S % p == 0; g = S/p; N = g*g     */
+  int32_t hidden;        /* D                                                            */
+  int32_t heads;         /* H, D % H == 0, head dim hd = D/H                             */
+  int32_t mlp;           /* F                                                            */
+  int32_t layers;        /* L >= 0                                                       */
+  int32_t norm;          /* EPD_NORM_*: kind of the two pre-norms of every layer         */
+  int32_t qk_norm;       /* EPD_QKNORM_*: RMSNorm of q and k (after bias, before scaling) */
+  int32_t act;           /* EPD_ACT_*: activation of the layer MLP                       */
+  int32_t final_norm;    /* 1: a norm of kind `norm` after the last layer                */
+  int32_t pixel_shuffle; /* 1: space-to-depth by 2 on the g x g grid: N/4 tokens of 4D   */
+  int32_t proj_kind;     /* EPD_PROJ_*: Linear, or Linear - GELU(erf) - Linear           */
+  int32_t proj_prenorm;  /* 1: LayerNorm over the projector input                        */
+  int32_t proj_mid;      /* width of the MLP projector's hidden layer (ignored if Linear) */
+  int32_t proj_out;      /* D_out: width of a token in the cache                         */
+  float   eps;           /* epsilon of every norm                                        */
+  int32_t max_tiles_per_call; /* workspace is sized for this many slices at once; larger
+                                 calls are processed in micro-batches of at most this    */
+} epd_model_desc;
+
+/* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix
+ * W[out, in] row-major, every tensor of type desc.dtype (fp32 or bf16):
+ *   pe_w [D, 3*p*p] (patch vector ordered channel, dy, dx), pe_b [D], pos [N, D];
+ *   per layer l = 0..L-1:
+ *     n1_g [D], n1_b [D] (n1_b only for LayerNorm),
+ *     qkv_w [3D, D] (row blocks q, k, v; head h = rows h*hd..(h+1)*hd-1 of a block), qkv_b [3D],
+ *     qn_g, kn_g ([D] for QKNORM_FULL, [hd] for QKNORM_PER_HEAD, absent for NONE),
+ *     o_w [D, D], o_b [D], n2_g [D], n2_b [D] (LayerNorm only),
+ *     fc1_w [F, D], fc1_b [F], fc2_w [D, F], fc2_b [D];
+ *   fn_g [D], fn_b [D]            (if final_norm; fn_b only for LayerNorm)
+ *   pn_g [Din], pn_b [Din]        (if proj_prenorm; Din = 4D with pixel shuffle else D)
+ *   pa_w [Dmid or D_out, Din], pa_b;  pb_w [D_out, Dmid], pb_b   (pb_* only for MLP)
+ * The tensors are copied / repacked during epd_create and may be freed by the
+ * caller once it returns. */
+typedef struct {
+  const void* const* tensors; /* host array of dev pointers */
+  int32_t n_tensors;
+} epd_weights;
+
+/* Number of tensors epd_weights must hold for this description (host only,
+ * needs no GPU); negative epd_status if the description is invalid. */
+int32_t epd_weight_count(const epd_model_desc* desc);
+
+/* Host-only validation of a description; writes a message to errbuf (may be
+ * null).  EPD_OK, EPD_ERR_INVALID_ARG, EPD_ERR_SHAPE or EPD_ERR_UNSUPPORTED. */
+epd_status epd_check_desc(const epd_model_desc* desc, char* errbuf, int32_t errbuf_len);
+
+/* Host-only validation of a request partition: offsets[0] == 0, non-decreasing,
+ * offsets[n_requests] == n_tiles.  Empty requests are legal. */
+epd_status epd_check_offsets(const int32_t* tile_offsets_per_request /*host*/, int32_t n_requests,
+                             int32_t n_tiles);
+
+/* Create a worker context on the current HIP device: validates the
+ * description, copies and repacks the weights into the kernels' layout
+ * (device allocations owned by the context), allocates the workspace for
+ * max_tiles_per_call slices.  `hip_stream` (a hipStream_t, may be null = the
+ * default stream) carries the packing work; the call synchronises it before
+ * returning.  On error *out is null. */
+epd_status epd_create(const epd_model_desc* desc, const epd_weights* weights, void* hip_stream,
+                      epd_ctx** out);
+
+/* Encode stage, v = E(i_m) (Section 3.1), for a packed batch of requests.
+ *   tiles   dev, float32 [n_tiles, 3, S, S], channel-first, values as the
+ *           (out of scope) CPU preprocessor leaves them; 16-byte aligned.
+ *   tile_offsets_per_request
+ *           host, int32 [n_requests + 1]; request r owns slices
+ *           offsets[r] .. offsets[r+1]-1 in slice order (image-major,
+ *           thumbnail last).
+ *   out_token_cache
+ *           dev, desc.dtype [n_tiles * N_out, D_out] row-major, 16-byte
+ *           aligned, N_out = epd_tokens_per_tile().  Request r's token buffer
+ *           is the contiguous row block
+ *           [offsets[r] * N_out, offsets[r+1] * N_out).  Every row is written.
+ * n_tiles == 0 is a successful no-op.  Results are valid once `hip_stream`
+ * has been synchronised.  Bit-identical from run to run and independent of
+ * how slices are grouped into calls. */
+epd_status epd_encode(epd_ctx* ctx, const float* tiles, int32_t n_tiles,
+                      const int32_t* tile_offsets_per_request, int32_t n_requests,
+                      void* out_token_cache, void* hip_stream);
+
+/* One encode worker's share under intra-request parallelism (Section 3.2.2):
+ * encode slices [tile_begin, tile_end) of the packed batch `tiles`
+ * (dev, [n_tiles_total, 3, S, S]) and write exactly rows
+ * [tile_begin * N_out, tile_end * N_out) of the same out_token_cache; no
+ * other row is touched, so shards need no gather copy.  An empty range is a
+ * successful no-op.  Requires 0 <= tile_begin <= tile_end <= n_tiles_total. */
+epd_status epd_encode_range(epd_ctx* ctx, const float* tiles, int32_t n_tiles_total,
+                            int32_t tile_begin, int32_t tile_end, void* out_token_cache,
+                            void* hip_stream);
+
+int64_t epd_tokens_per_tile(const epd_ctx* ctx); /* N_out = N or N/4 */
+int64_t epd_out_dim(const epd_ctx* ctx);         /* D_out            */
+
+/* Last error message of this context (owned by the context, never freed by
+ * the caller); for a null ctx the message of the last failed epd_create /
+ * host-only check on this thread. */
+const char* epd_last_error(const epd_ctx* ctx);
+
+void epd_destroy(epd_ctx* ctx);
+
+/* ---- measurement and test hooks (not needed to serve) ------------------ */
+
+/* Copy the residual stream (float32 [rows, D], the encoder state after the
+ * last layer of the last micro-batch of the previous call) to host memory.
+ * Synchronises the device.  rows * D * 4 must be <= dst_bytes. */
+epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst /*host*/, int64_t rows, int64_t dst_bytes);
+
+/* Time the dominant kernel family in isolation: runs `iters` launches of the
+ * bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  (+ bias) on dev buffers the
+ * caller provides, bracketed by HIP events on `hip_stream`; returns the mean
+ * milliseconds per launch in *ms_per_launch.  A [M,K] bf16, W [N,K] bf16,
+ * bias [N] fp32 (may be null), C [M,N] bf16.  M % 256 == 0, N % 128 == 0,
+ * K % 64 == 0. */
+epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M,
+                            int32_t N, int32_t K, int32_t iters, float* ms_per_launch,
+                            void* hip_stream);
+
+/* Tile-local non-causal attention on packed slices, bf16:  for every slice t
+ * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
+ * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
+ * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
+ * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 96, 128}, n_tokens % 64 == 0;
+ * `scale` multiplies the logits. */
+epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
+                                 int32_t n_slices, int32_t n_tokens, int32_t heads, int32_t hd_pad,
+                                 int32_t ld_qk, float scale, void* hip_stream);
+
+/* Check of the MFMA operand / result lane layout the kernels assume:
+ * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one
+ * v_mfma_f32_32x32x16_bf16.  All pointers dev. */
+epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream);
+
+/* Per-kernel-family timing of the previous epd_encode / epd_encode_range
+ * call on this context, measured with HIP events on the call's stream.
+ * epd_profile_enable(ctx, 1) makes subsequent calls bracket every launch
+ * with two event records; epd_profile_read synchronises the device and fills
+ * ms[family] (summed) and launches[family].  Families: 0 im2col + patch-embed
+ * GEMM, 1 pre-norms, 2 QKV GEMM, 3 attention, 4 q/k norm, 5 projector input
+ * (shuffle / norm / convert), 6 out-proj GEMM, 7 FC1 GEMM, 8 FC2 GEMM,
+ * 9 projector GEMMs. */
+enum { EPD_PROF_FAMILIES = 10 };
+epd_status epd_profile_enable(epd_ctx* ctx, int32_t on);
+epd_status epd_profile_read(epd_ctx* ctx, float* ms /*host [10]*/, int32_t* launches /*host [10]*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPD_ENCODE_H */

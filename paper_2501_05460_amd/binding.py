@@ -1,0 +1,250 @@
+"""ctypes binding of libepd_encode.so: argument marshalling only.
+
+Every step of the encode path runs in the library's HIP kernels; PyTorch is
+used here for device memory and the current HIP stream, nothing else.  There
+is no CPU fallback: if the library is not built, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libepd_encode.so")
+
+EPD_OK = 0
+EPD_ERR_INVALID_ARG = -1
+EPD_ERR_SHAPE = -2
+EPD_ERR_OFFSETS = -3
+EPD_ERR_UNSUPPORTED = -4
+EPD_ERR_NOMEM = -5
+EPD_ERR_HIP = -6
+
+PROF_FAMILIES = ("embed", "norm", "gemm_qkv", "attention", "qk_norm", "proj_input",
+                 "gemm_out", "gemm_fc1", "gemm_fc2", "gemm_proj")
+
+EXPORTS = (
+    "epd_weight_count", "epd_check_desc", "epd_check_offsets", "epd_create", "epd_encode",
+    "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
+    "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_attention_bf16", "epd_op_mfma_probe",
+    "epd_profile_enable", "epd_profile_read",
+)
+
+
+class ModelDescC(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "dtype", "tile_size", "patch", "hidden", "heads", "mlp", "layers", "norm", "qk_norm", "act",
+        "final_norm", "pixel_shuffle", "proj_kind", "proj_prenorm", "proj_mid", "proj_out")] + [
+        ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32)]
+
+
+class WeightsC(ctypes.Structure):
+    _fields_ = [("tensors", ctypes.POINTER(ctypes.c_void_p)), ("n_tensors", ctypes.c_int32)]
+
+
+class EpdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"epd status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2501_05460_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.epd_weight_count.argtypes = [ctypes.POINTER(ModelDescC)]
+        L.epd_weight_count.restype = i32
+        L.epd_check_desc.argtypes = [ctypes.POINTER(ModelDescC), ctypes.c_char_p, i32]
+        L.epd_check_desc.restype = i32
+        L.epd_check_offsets.argtypes = [ctypes.POINTER(i32), i32, i32]
+        L.epd_check_offsets.restype = i32
+        L.epd_create.argtypes = [ctypes.POINTER(ModelDescC), ctypes.POINTER(WeightsC), vp, ctypes.POINTER(vp)]
+        L.epd_create.restype = i32
+        L.epd_encode.argtypes = [vp, vp, i32, ctypes.POINTER(i32), i32, vp, vp]
+        L.epd_encode.restype = i32
+        L.epd_encode_range.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+        L.epd_encode_range.restype = i32
+        L.epd_tokens_per_tile.argtypes = [vp]
+        L.epd_tokens_per_tile.restype = i64
+        L.epd_out_dim.argtypes = [vp]
+        L.epd_out_dim.restype = i64
+        L.epd_last_error.argtypes = [vp]
+        L.epd_last_error.restype = ctypes.c_char_p
+        L.epd_destroy.argtypes = [vp]
+        L.epd_destroy.restype = None
+        L.epd_debug_read_stream.argtypes = [vp, vp, i64, i64]
+        L.epd_debug_read_stream.restype = i32
+        L.epd_op_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
+        L.epd_op_gemm_bf16.restype = i32
+        L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.epd_op_attention_bf16.restype = i32
+        L.epd_op_mfma_probe.argtypes = [vp, vp, vp, vp]
+        L.epd_op_mfma_probe.restype = i32
+        L.epd_profile_enable.argtypes = [vp, i32]
+        L.epd_profile_enable.restype = i32
+        L.epd_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.epd_profile_read.restype = i32
+        _lib = L
+    return _lib
+
+
+def desc_to_c(desc) -> ModelDescC:
+    d = ModelDescC()
+    for name, _ in ModelDescC._fields_:
+        setattr(d, name, getattr(desc, name))
+    return d
+
+
+def check_desc(desc) -> (int, str):
+    buf = ctypes.create_string_buffer(512)
+    s = lib().epd_check_desc(ctypes.byref(desc_to_c(desc)), buf, 512)
+    return s, buf.value.decode()
+
+
+def weight_count(desc) -> int:
+    return lib().epd_weight_count(ctypes.byref(desc_to_c(desc)))
+
+
+def check_offsets(offsets: Optional[Sequence[int]], n_requests: int, n_tiles: int) -> int:
+    if offsets is None:
+        return lib().epd_check_offsets(None, n_requests, n_tiles)
+    arr = (ctypes.c_int32 * len(offsets))(*offsets)
+    return lib().epd_check_offsets(arr, n_requests, n_tiles)
+
+
+def _stream_ptr() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def to_device(arr: np.ndarray, bf16: bool, device="cuda") -> torch.Tensor:
+    """Upload one fp32 host array; for bf16 the values must already lie on the
+    bf16 grid and their upper 16 bits are shipped as they are."""
+    a = np.ascontiguousarray(arr, dtype=np.float32)
+    if not bf16:
+        return torch.from_numpy(a).to(device)
+    bits = (a.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+
+
+class Encoder:
+    """One encode worker: a library context plus the current device."""
+
+    def __init__(self, desc, device_weights: List[torch.Tensor]):
+        L = lib()
+        if not torch.cuda.is_available():
+            raise RuntimeError("the encode library needs a GPU; there is no CPU path")
+        self.desc = desc
+        self.bf16 = desc.dtype == 1
+        want = torch.bfloat16 if self.bf16 else torch.float32
+        for i, t in enumerate(device_weights):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == want):
+                raise ValueError(f"weight tensor {i} must be a contiguous {want} CUDA tensor")
+        ptrs = (ctypes.c_void_p * len(device_weights))(*[t.data_ptr() for t in device_weights])
+        w = WeightsC(ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p)), len(device_weights))
+        handle = ctypes.c_void_p()
+        s = L.epd_create(ctypes.byref(desc_to_c(desc)), ctypes.byref(w), _stream_ptr(), ctypes.byref(handle))
+        if s != EPD_OK:
+            raise EpdError(s, L.epd_last_error(None).decode())
+        self._h = handle
+        self.tokens_per_tile = int(L.epd_tokens_per_tile(handle))
+        self.out_dim = int(L.epd_out_dim(handle))
+        self.out_dtype = want
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().epd_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _raise(self, s: int):
+        raise EpdError(s, lib().epd_last_error(self._h).decode())
+
+    def alloc_out(self, n_tiles: int) -> torch.Tensor:
+        return torch.empty((n_tiles * self.tokens_per_tile, self.out_dim), dtype=self.out_dtype, device="cuda")
+
+    def encode(self, tiles: torch.Tensor, tile_offsets: Sequence[int], out: Optional[torch.Tensor] = None):
+        n_tiles = int(tiles.shape[0]) if tiles is not None else 0
+        if out is None:
+            out = self.alloc_out(n_tiles)
+        off = (ctypes.c_int32 * len(tile_offsets))(*tile_offsets)
+        s = lib().epd_encode(self._h, tiles.data_ptr() if n_tiles else None, n_tiles, off,
+                             len(tile_offsets) - 1, out.data_ptr() if n_tiles else None, _stream_ptr())
+        if s != EPD_OK:
+            self._raise(s)
+        return out
+
+    def encode_range(self, tiles: torch.Tensor, tile_begin: int, tile_end: int, out: torch.Tensor):
+        s = lib().epd_encode_range(self._h, tiles.data_ptr(), int(tiles.shape[0]), tile_begin, tile_end,
+                                   out.data_ptr(), _stream_ptr())
+        if s != EPD_OK:
+            self._raise(s)
+        return out
+
+    def read_stream(self, rows: int) -> np.ndarray:
+        buf = np.empty((rows, self.desc.hidden), np.float32)
+        s = lib().epd_debug_read_stream(self._h, buf.ctypes.data, rows, buf.nbytes)
+        if s != EPD_OK:
+            self._raise(s)
+        return buf
+
+    def profile_enable(self, on: bool = True):
+        s = lib().epd_profile_enable(self._h, 1 if on else 0)
+        if s != EPD_OK:
+            self._raise(s)
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        ms = (ctypes.c_float * len(PROF_FAMILIES))()
+        n = (ctypes.c_int32 * len(PROF_FAMILIES))()
+        s = lib().epd_profile_read(self._h, ms, n)
+        if s != EPD_OK:
+            self._raise(s)
+        return {name: {"ms": float(ms[i]), "launches": int(n[i])} for i, name in enumerate(PROF_FAMILIES)}
+
+
+def op_gemm_bf16(A: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], iters: int = 1):
+    """C = A W^T (+ bias) with the library's MFMA GEMM; returns (C, ms per launch)."""
+    M, K = A.shape
+    N = W.shape[0]
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    ms = ctypes.c_float()
+    s = lib().epd_op_gemm_bf16(A.data_ptr(), W.data_ptr(), bias.data_ptr() if bias is not None else None,
+                               C.data_ptr(), M, N, K, iters, ctypes.byref(ms), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return C, ms.value
+
+
+def op_attention_bf16(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int,
+                      heads: int, hd_pad: int, ld_qk: int, scale: float) -> torch.Tensor:
+    o = torch.empty((n_slices * n_tokens, heads * hd_pad), dtype=torch.bfloat16, device=q.device)
+    s = lib().epd_op_attention_bf16(q.data_ptr(), k.data_ptr(), vt.data_ptr(), o.data_ptr(), n_slices,
+                                    n_tokens, heads, hd_pad, ld_qk, scale, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return o
+
+
+def op_mfma_probe(A: torch.Tensor, B: torch.Tensor) -> torch.Tensor:
+    D = torch.empty((32, 32), dtype=torch.float32, device=A.device)
+    s = lib().epd_op_mfma_probe(A.data_ptr(), B.data_ptr(), D.data_ptr(), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "mfma probe failed")
+    return D

@@ -1,0 +1,718 @@
+// C boundary of the encode-stage library: validation, weight packing,
+// workspace, and the per-micro-batch launch sequence.  See include/epd_encode.h.
+#include "../../include/epd_encode.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <cmath>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace epd;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+void set_err(char* buf, size_t len, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, len, fmt, ap);
+  va_end(ap);
+}
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// N padding of a weight matrix: a multiple of 256 when that wastes at most
+// ~3 % of the product, else a multiple of 128 (the two block widths).
+inline int pad_n(int n) {
+  const int p256 = round_up(n, 256);
+  if ((long)(p256 - n) * 32 <= n) return p256;
+  return round_up(n, 128);
+}
+
+// --------------------------------------------------------------------------
+// tensor order of epd_weights
+// --------------------------------------------------------------------------
+struct TensorSpec { long rows, cols; };  // vectors: rows = 1
+
+struct LayerIdx { int n1_g, n1_b, qkv_w, qkv_b, qn_g, kn_g, o_w, o_b, n2_g, n2_b, fc1_w, fc1_b, fc2_w, fc2_b; };
+
+struct WeightIndex {
+  int pe_w, pe_b, pos;
+  std::vector<LayerIdx> layers;
+  int fn_g, fn_b, pn_g, pn_b, pa_w, pa_b, pb_w, pb_b;
+  std::vector<TensorSpec> specs;
+};
+
+struct Dims {
+  int S, p, g, N, Kp, D, H, hd, F, L, N_out, Pin, Pmid, Pout;
+};
+
+Dims dims_of(const epd_model_desc& d) {
+  Dims x;
+  x.S = d.tile_size; x.p = d.patch; x.g = d.tile_size / d.patch; x.N = x.g * x.g;
+  x.Kp = 3 * d.patch * d.patch; x.D = d.hidden; x.H = d.heads; x.hd = d.hidden / d.heads;
+  x.F = d.mlp; x.L = d.layers;
+  x.N_out = d.pixel_shuffle ? x.N / 4 : x.N;
+  x.Pin = d.pixel_shuffle ? 4 * x.D : x.D;
+  x.Pmid = d.proj_mid; x.Pout = d.proj_out;
+  return x;
+}
+
+WeightIndex build_index(const epd_model_desc& d) {
+  const Dims x = dims_of(d);
+  WeightIndex w;
+  auto add = [&](long r, long c) { w.specs.push_back({r, c}); return (int)w.specs.size() - 1; };
+  const bool ln = d.norm == EPD_NORM_LAYERNORM;
+  w.pe_w = add(x.D, x.Kp); w.pe_b = add(1, x.D); w.pos = add(x.N, x.D);
+  for (int l = 0; l < x.L; ++l) {
+    LayerIdx i;
+    i.n1_g = add(1, x.D); i.n1_b = ln ? add(1, x.D) : -1;
+    i.qkv_w = add(3L * x.D, x.D); i.qkv_b = add(1, 3L * x.D);
+    i.qn_g = i.kn_g = -1;
+    if (d.qk_norm == EPD_QKNORM_FULL) { i.qn_g = add(1, x.D); i.kn_g = add(1, x.D); }
+    if (d.qk_norm == EPD_QKNORM_PER_HEAD) { i.qn_g = add(1, x.hd); i.kn_g = add(1, x.hd); }
+    i.o_w = add(x.D, x.D); i.o_b = add(1, x.D);
+    i.n2_g = add(1, x.D); i.n2_b = ln ? add(1, x.D) : -1;
+    i.fc1_w = add(x.F, x.D); i.fc1_b = add(1, x.F);
+    i.fc2_w = add(x.D, x.F); i.fc2_b = add(1, x.D);
+    w.layers.push_back(i);
+  }
+  w.fn_g = w.fn_b = w.pn_g = w.pn_b = w.pb_w = w.pb_b = -1;
+  if (d.final_norm) { w.fn_g = add(1, x.D); w.fn_b = ln ? add(1, x.D) : -1; }
+  if (d.proj_prenorm) { w.pn_g = add(1, x.Pin); w.pn_b = add(1, x.Pin); }
+  if (d.proj_kind == EPD_PROJ_LINEAR) {
+    w.pa_w = add(x.Pout, x.Pin); w.pa_b = add(1, x.Pout);
+  } else {
+    w.pa_w = add(x.Pmid, x.Pin); w.pa_b = add(1, x.Pmid);
+    w.pb_w = add(x.Pout, x.Pmid); w.pb_b = add(1, x.Pout);
+  }
+  return w;
+}
+
+epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
+  if (!d) { set_err(err, len, "desc is null"); return EPD_ERR_INVALID_ARG; }
+  if (d->dtype != EPD_DTYPE_FP32 && d->dtype != EPD_DTYPE_BF16) { set_err(err, len, "dtype must be 0 (fp32) or 1 (bf16)"); return EPD_ERR_INVALID_ARG; }
+  if (d->norm < 0 || d->norm > 1 || d->qk_norm < 0 || d->qk_norm > 2 || d->act < 0 || d->act > 1 ||
+      d->final_norm < 0 || d->final_norm > 1 || d->pixel_shuffle < 0 || d->pixel_shuffle > 1 ||
+      d->proj_kind < 0 || d->proj_kind > 1 || d->proj_prenorm < 0 || d->proj_prenorm > 1) {
+    set_err(err, len, "an enum field of the description is out of range"); return EPD_ERR_INVALID_ARG;
+  }
+  if (d->tile_size <= 0 || d->patch <= 0 || d->hidden <= 0 || d->heads <= 0 || d->mlp <= 0 ||
+      d->layers < 0 || d->proj_out <= 0 || d->max_tiles_per_call <= 0 || !(d->eps > 0.f)) {
+    set_err(err, len, "sizes must be positive (layers >= 0, eps > 0, max_tiles_per_call >= 1)"); return EPD_ERR_SHAPE;
+  }
+  if (d->tile_size % d->patch) { set_err(err, len, "tile_size %d is not a multiple of patch %d", d->tile_size, d->patch); return EPD_ERR_SHAPE; }
+  if (d->hidden % d->heads) { set_err(err, len, "hidden %d is not a multiple of heads %d", d->hidden, d->heads); return EPD_ERR_SHAPE; }
+  if (d->proj_kind == EPD_PROJ_MLP && d->proj_mid <= 0) { set_err(err, len, "proj_mid must be positive for an MLP projector"); return EPD_ERR_SHAPE; }
+  const Dims x = dims_of(*d);
+  if (d->pixel_shuffle && (x.g % 2)) { set_err(err, len, "pixel shuffle needs an even patch grid, got %d", x.g); return EPD_ERR_SHAPE; }
+  if ((long)x.N * d->max_tiles_per_call > (1L << 30)) { set_err(err, len, "max_tiles_per_call too large"); return EPD_ERR_UNSUPPORTED; }
+  if (d->dtype == EPD_DTYPE_BF16) {
+    if (x.N % 64) { set_err(err, len, "bf16 mode needs patches per slice %% 64 == 0, got %d", x.N); return EPD_ERR_UNSUPPORTED; }
+    if (x.hd > 128) { set_err(err, len, "bf16 mode supports head dim <= 128, got %d", x.hd); return EPD_ERR_UNSUPPORTED; }
+    if (x.D % 4 || x.F % 4 || x.Pout % 4 || (d->proj_kind == EPD_PROJ_MLP && x.Pmid % 4) || x.hd % 4) {
+      set_err(err, len, "bf16 mode needs hidden, head dim, mlp and projector widths %% 4 == 0"); return EPD_ERR_UNSUPPORTED;
+    }
+  }
+  if (x.N > 16384) { set_err(err, len, "more than 16384 patches per slice is not supported"); return EPD_ERR_UNSUPPORTED; }
+  return EPD_OK;
+}
+
+// --------------------------------------------------------------------------
+// context
+// --------------------------------------------------------------------------
+struct Linear {
+  const void* W = nullptr;  // fp32 mode: float [N,K]; bf16 mode: packed bf16 [Npad,K]
+  const float* b = nullptr; // fp32 (padded to Npad in bf16 mode)
+  int N = 0, K = 0, Npad = 0;
+};
+
+struct LayerW {
+  const float *n1_g = nullptr, *n1_b = nullptr, *n2_g = nullptr, *n2_b = nullptr, *qn_g = nullptr, *kn_g = nullptr;
+  Linear qkv, o, fc1, fc2;
+};
+
+}  // namespace
+
+struct epd_ctx {
+  epd_model_desc d;
+  Dims x;
+  bool bf16;
+  std::vector<void*> allocs;
+  char err[512];
+
+  // weights
+  Linear pe, pa, pb;
+  const float* pos = nullptr;
+  const float *fn_g = nullptr, *fn_b = nullptr, *pn_g = nullptr, *pn_b = nullptr;
+  std::vector<LayerW> layers;
+
+  // bf16 layout
+  int hd_pad = 0, Dq = 0, Dq_k = 0, D_k = 0, F_k = 0, Kp_k = 0, Pin_k = 0, Pmid_k = 0, v_col0 = 0;
+
+  // workspace (sized for mb slices)
+  int mb = 0;
+  long Mp = 0, Mp_out = 0;
+  float* X = nullptr;      // residual stream fp32 [Mp, D]
+  void* Xn = nullptr;      // normalised activations
+  void* QKV = nullptr;     // fp32: [M,3D]; bf16: q,k [Mp, 2Dq]
+  void* VT = nullptr;      // bf16: [mb, H, hd_pad, N]
+  void* O = nullptr;
+  void* Hd = nullptr;
+  void* Ape = nullptr;
+  void* Pin = nullptr;
+  void* Pmid = nullptr;
+  long last_rows = 0;
+
+  // profiling
+  bool prof = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> ev_family;
+  size_t ev_used = 0;
+};
+
+namespace {
+
+struct ProfScope {
+  epd_ctx* c; hipStream_t st; bool on;
+  ProfScope(epd_ctx* c_, int family, hipStream_t st_) : c(c_), st(st_), on(false) {
+    if (c->prof && c->ev_used + 2 <= c->ev.size()) {
+      on = true;
+      c->ev_family.push_back(family);
+      hipEventRecord(c->ev[c->ev_used], st);
+    }
+  }
+  ~ProfScope() {
+    if (on) { hipEventRecord(c->ev[c->ev_used + 1], st); c->ev_used += 2; }
+  }
+};
+
+#define HIP_TRY(ctx, expr)                                                                   \
+  do {                                                                                       \
+    hipError_t e__ = (expr);                                                                 \
+    if (e__ != hipSuccess) {                                                                 \
+      set_err((ctx)->err, sizeof((ctx)->err), "%s failed: %s", #expr, hipGetErrorString(e__)); \
+      return EPD_ERR_HIP;                                                                    \
+    }                                                                                        \
+  } while (0)
+
+void* dalloc(epd_ctx* c, size_t bytes, bool zero, hipStream_t st) {
+  void* p = nullptr;
+  if (bytes == 0) bytes = 256;
+  if (hipMalloc(&p, bytes) != hipSuccess) return nullptr;
+  c->allocs.push_back(p);
+  if (zero && hipMemsetAsync(p, 0, bytes, st) != hipSuccess) return nullptr;
+  return p;
+}
+
+// fp32 copy of a small tensor (bias / gain / position embedding), optionally
+// re-indexed over padded heads and zero-padded to n_pad.
+const float* make_vec(epd_ctx* c, const epd_weights* w, int idx, long n, int n_pad, PackMap map, hipStream_t st) {
+  if (idx < 0) return nullptr;
+  float* dst = (float*)dalloc(c, (size_t)n_pad * sizeof(float), false, st);
+  if (!dst) return nullptr;
+  pack_vector_f32(w->tensors[idx], c->bf16 ? 1 : 0, (int)n, dst, n_pad, map, st);
+  return dst;
+}
+
+bool make_linear(epd_ctx* c, const epd_weights* w, int wi, int bi, int N, int K, Linear* out, hipStream_t st,
+                 int Npad, int Kpad, PackMap rmap, PackMap cmap, int n_packed) {
+  out->N = n_packed; out->K = Kpad; out->Npad = Npad;
+  if (!c->bf16) {
+    const size_t bytes = (size_t)N * K * sizeof(float);
+    void* dst = dalloc(c, bytes, false, st);
+    if (!dst) return false;
+    if (hipMemcpyAsync(dst, w->tensors[wi], bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return false;
+    out->W = dst; out->N = N; out->K = K; out->Npad = N;
+    out->b = make_vec(c, w, bi, N, N, PackMap{0, 0, 0}, st);
+    return out->b != nullptr;
+  }
+  bf16_t* dst = (bf16_t*)dalloc(c, (size_t)Npad * Kpad * sizeof(bf16_t), false, st);
+  if (!dst) return false;
+  pack_matrix_bf16((const bf16_t*)w->tensors[wi], N, K, dst, Npad, Kpad, rmap, cmap, st);
+  out->W = dst;
+  out->b = make_vec(c, w, bi, N, Npad, rmap, st);
+  return out->b != nullptr;
+}
+
+epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
+  const epd_model_desc& d = c->d;
+  const Dims& x = c->x;
+  const WeightIndex wi = build_index(d);
+  const PackMap id{0, 0, 0};
+  const bool bf = c->bf16;
+
+  if (bf) {
+    c->hd_pad = x.hd <= 64 ? 64 : (x.hd <= 96 ? 96 : 128);
+    c->Dq = x.H * c->hd_pad;
+    c->Dq_k = round_up(c->Dq, 64);
+    c->D_k = round_up(x.D, 64);
+    c->Kp_k = round_up(x.Kp, 64);
+    c->Pin_k = round_up(x.Pin, 64);
+    HIP_TRY(c, bf16_gemm_init());
+  }
+  const PackMap heads{x.hd, c->hd_pad, x.H};
+  const PackMap hmap = (bf && c->hd_pad != x.hd) ? heads : id;
+
+#define NOMEM_IF(cond) do { if (cond) { set_err(c->err, sizeof(c->err), "device allocation failed (weights)"); return EPD_ERR_NOMEM; } } while (0)
+
+  // patch embedding and position embedding
+  NOMEM_IF(!make_linear(c, w, wi.pe_w, wi.pe_b, x.D, x.Kp, &c->pe, st, pad_n(x.D), c->Kp_k, id, id, x.D));
+  c->pos = make_vec(c, w, wi.pos, (long)x.N * x.D, x.N * x.D, id, st);
+  NOMEM_IF(!c->pos);
+
+  int f_pad = 0;
+  for (int l = 0; l < x.L; ++l) {
+    const LayerIdx& li = wi.layers[l];
+    LayerW lw;
+    lw.n1_g = make_vec(c, w, li.n1_g, x.D, x.D, id, st);
+    lw.n1_b = make_vec(c, w, li.n1_b, x.D, x.D, id, st);
+    lw.n2_g = make_vec(c, w, li.n2_g, x.D, x.D, id, st);
+    lw.n2_b = make_vec(c, w, li.n2_b, x.D, x.D, id, st);
+    NOMEM_IF(!lw.n1_g || !lw.n2_g);
+    if (!bf) {
+      NOMEM_IF(!make_linear(c, w, li.qkv_w, li.qkv_b, 3 * x.D, x.D, &lw.qkv, st, 0, 0, id, id, 0));
+      NOMEM_IF(!make_linear(c, w, li.o_w, li.o_b, x.D, x.D, &lw.o, st, 0, 0, id, id, 0));
+      NOMEM_IF(!make_linear(c, w, li.fc1_w, li.fc1_b, x.F, x.D, &lw.fc1, st, 0, 0, id, id, 0));
+      NOMEM_IF(!make_linear(c, w, li.fc2_w, li.fc2_b, x.D, x.F, &lw.fc2, st, 0, 0, id, id, 0));
+      if (d.qk_norm) {
+        const int n = d.qk_norm == EPD_QKNORM_FULL ? x.D : x.hd;
+        lw.qn_g = make_vec(c, w, li.qn_g, n, n, id, st);
+        lw.kn_g = make_vec(c, w, li.kn_g, n, n, id, st);
+        NOMEM_IF(!lw.qn_g || !lw.kn_g);
+      }
+    } else {
+      // fused QKV: packed rows [q heads | k heads | gap | v heads], heads padded to hd_pad.
+      // The gap aligns the value block to the GEMM's block width.
+      const int qk_cols = 2 * c->Dq;
+      int v0 = round_up(qk_cols, 256);
+      int npad = round_up(v0 + c->Dq, 256);
+      if ((long)(npad - 3 * c->Dq) * 32 > 3L * c->Dq) {  // too much padding: use the 128-wide blocks
+        v0 = round_up(qk_cols, 128);
+        npad = round_up(v0 + c->Dq, 128);
+      }
+      c->v_col0 = v0;
+      // q,k block and v block are packed by two calls into one matrix
+      bf16_t* Wq = (bf16_t*)dalloc(c, (size_t)npad * c->D_k * sizeof(bf16_t), true, st);
+      float* bq = (float*)dalloc(c, (size_t)npad * sizeof(float), true, st);
+      NOMEM_IF(!Wq || !bq);
+      const PackMap hm = heads;  // always re-index: rows are (block, head, d)
+      pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w], 2 * x.D, x.D, Wq, qk_cols, c->D_k, hm, id, st);
+      pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w] + 2L * x.D * x.D, x.D, x.D,
+                       Wq + (long)v0 * c->D_k, c->Dq, c->D_k, hm, id, st);
+      pack_vector_f32(w->tensors[li.qkv_b], 1, 2 * x.D, bq, qk_cols, hm, st);
+      pack_vector_f32((const bf16_t*)w->tensors[li.qkv_b] + 2 * x.D, 1, x.D, bq + v0, c->Dq, hm, st);
+      lw.qkv.W = Wq; lw.qkv.b = bq; lw.qkv.N = v0 + c->Dq; lw.qkv.K = c->D_k; lw.qkv.Npad = npad;
+
+      NOMEM_IF(!make_linear(c, w, li.o_w, li.o_b, x.D, x.D, &lw.o, st, pad_n(x.D), c->Dq_k, id, heads, x.D));
+      f_pad = pad_n(x.F);
+      NOMEM_IF(!make_linear(c, w, li.fc1_w, li.fc1_b, x.F, x.D, &lw.fc1, st, f_pad, c->D_k, id, id, x.F));
+      NOMEM_IF(!make_linear(c, w, li.fc2_w, li.fc2_b, x.D, x.F, &lw.fc2, st, pad_n(x.D), f_pad, id, id, x.D));
+      if (d.qk_norm == EPD_QKNORM_FULL) {
+        lw.qn_g = make_vec(c, w, li.qn_g, x.D, c->Dq, heads, st);
+        lw.kn_g = make_vec(c, w, li.kn_g, x.D, c->Dq, heads, st);
+        NOMEM_IF(!lw.qn_g || !lw.kn_g);
+      } else if (d.qk_norm == EPD_QKNORM_PER_HEAD) {
+        lw.qn_g = make_vec(c, w, li.qn_g, x.hd, c->hd_pad, id, st);
+        lw.kn_g = make_vec(c, w, li.kn_g, x.hd, c->hd_pad, id, st);
+        NOMEM_IF(!lw.qn_g || !lw.kn_g);
+      }
+    }
+    c->layers.push_back(lw);
+  }
+  c->F_k = bf ? (x.L ? f_pad : pad_n(x.F)) : x.F;
+  (void)hmap;
+
+  if (d.final_norm) {
+    c->fn_g = make_vec(c, w, wi.fn_g, x.D, x.D, id, st);
+    c->fn_b = make_vec(c, w, wi.fn_b, x.D, x.D, id, st);
+    NOMEM_IF(!c->fn_g);
+  }
+  if (d.proj_prenorm) {
+    c->pn_g = make_vec(c, w, wi.pn_g, x.Pin, x.Pin, id, st);
+    c->pn_b = make_vec(c, w, wi.pn_b, x.Pin, x.Pin, id, st);
+    NOMEM_IF(!c->pn_g || !c->pn_b);
+  }
+  if (d.proj_kind == EPD_PROJ_LINEAR) {
+    NOMEM_IF(!make_linear(c, w, wi.pa_w, wi.pa_b, x.Pout, x.Pin, &c->pa, st, pad_n(x.Pout), c->Pin_k, id, id, x.Pout));
+  } else {
+    const int mid_pad = pad_n(x.Pmid);
+    c->Pmid_k = bf ? mid_pad : x.Pmid;
+    NOMEM_IF(!make_linear(c, w, wi.pa_w, wi.pa_b, x.Pmid, x.Pin, &c->pa, st, mid_pad, c->Pin_k, id, id, x.Pmid));
+    NOMEM_IF(!make_linear(c, w, wi.pb_w, wi.pb_b, x.Pout, x.Pmid, &c->pb, st, pad_n(x.Pout), mid_pad, id, id, x.Pout));
+  }
+
+  // ---- workspace ----
+  c->mb = d.max_tiles_per_call;
+  const long M = (long)c->mb * x.N, Mo = (long)c->mb * x.N_out;
+  c->Mp = (M + 255) / 256 * 256;
+  c->Mp_out = (Mo + 255) / 256 * 256;
+  bool ok = true;
+  auto ws = [&](size_t bytes) { void* p = dalloc(c, bytes, true, st); ok = ok && p; return p; };
+  c->X = (float*)ws((size_t)c->Mp * x.D * sizeof(float));
+  if (bf) {
+    c->Xn = ws((size_t)c->Mp * c->D_k * 2);
+    c->QKV = ws((size_t)c->Mp * 2 * c->Dq * 2);
+    c->VT = ws((size_t)c->mb * x.H * c->hd_pad * x.N * 2);
+    c->O = ws((size_t)c->Mp * c->Dq_k * 2);
+    c->Hd = ws((size_t)c->Mp * c->F_k * 2);
+    c->Ape = ws((size_t)c->Mp * c->Kp_k * 2);
+    c->Pin = ws((size_t)c->Mp_out * c->Pin_k * 2);
+    c->Pmid = ws((size_t)c->Mp_out * (c->Pmid_k ? c->Pmid_k : 64) * 2);
+  } else {
+    c->Xn = ws((size_t)M * x.D * 4);
+    c->QKV = ws((size_t)M * 3 * x.D * 4);
+    c->O = ws((size_t)M * x.D * 4);
+    c->Hd = ws((size_t)M * x.F * 4);
+    c->Ape = ws((size_t)M * x.Kp * 4);
+    c->Pin = ws((size_t)Mo * x.Pin * 4);
+    c->Pmid = ws((size_t)Mo * (x.Pmid > 0 ? x.Pmid : 1) * 4);
+  }
+  if (!ok) { set_err(c->err, sizeof(c->err), "device allocation failed (workspace for %d slices)", c->mb); return EPD_ERR_NOMEM; }
+  HIP_TRY(c, hipStreamSynchronize(st));
+  HIP_TRY(c, hipGetLastError());
+  return EPD_OK;
+}
+
+// --------------------------------------------------------------------------
+// one micro-batch, fp32 mode
+// --------------------------------------------------------------------------
+epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_t st) {
+  const epd_model_desc& d = c->d;
+  const Dims& x = c->x;
+  const int M = T * x.N, Mo = T * x.N_out;
+  float* X = c->X; float* Xn = (float*)c->Xn; float* QKV = (float*)c->QKV; float* O = (float*)c->O;
+  float* Hd = (float*)c->Hd; float* Ape = (float*)c->Ape; float* Pin = (float*)c->Pin; float* Pmid = (float*)c->Pmid;
+  const int act_epi = d.act == EPD_ACT_GELU_ERF ? EPI_BIAS_GELU_ERF : EPI_BIAS_GELU_TANH;
+  const float scale = 1.0f / sqrtf((float)x.hd);
+
+  { ProfScope ps(c, 0, st);
+    f32_im2col(tiles, Ape, T, x.S, x.p, st);
+    f32_gemm(EPI_BIAS_POS, Ape, x.Kp, (const float*)c->pe.W, c->pe.b, X, x.D, c->pos, x.N, M, x.D, x.Kp, st); }
+  for (int l = 0; l < x.L; ++l) {
+    const LayerW& w = c->layers[l];
+    { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n1_g, w.n1_b, M, x.D, 1, d.eps, st); }
+    { ProfScope ps(c, 2, st); f32_gemm(EPI_BIAS, Xn, x.D, (const float*)w.qkv.W, w.qkv.b, QKV, 3 * x.D, nullptr, 1, M, 3 * x.D, x.D, st); }
+    if (d.qk_norm == EPD_QKNORM_FULL) {
+      ProfScope ps(c, 4, st);
+      f32_norm(1, QKV, 3 * x.D, QKV, 3 * x.D, w.qn_g, nullptr, M, x.D, 1, d.eps, st);
+      f32_norm(1, QKV + x.D, 3 * x.D, QKV + x.D, 3 * x.D, w.kn_g, nullptr, M, x.D, 1, d.eps, st);
+    } else if (d.qk_norm == EPD_QKNORM_PER_HEAD) {
+      ProfScope ps(c, 4, st);
+      f32_norm(1, QKV, 3 * x.D, QKV, 3 * x.D, w.qn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
+      f32_norm(1, QKV + x.D, 3 * x.D, QKV + x.D, 3 * x.D, w.kn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
+    }
+    { ProfScope ps(c, 3, st); f32_attention(QKV, QKV + x.D, QKV + 2 * x.D, 3 * x.D, O, x.D, T, x.N, x.H, x.hd, scale, st); }
+    { ProfScope ps(c, 6, st); f32_gemm(EPI_BIAS_RESIDUAL, O, x.D, (const float*)w.o.W, w.o.b, X, x.D, nullptr, 1, M, x.D, x.D, st); }
+    { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n2_g, w.n2_b, M, x.D, 1, d.eps, st); }
+    { ProfScope ps(c, 7, st); f32_gemm(act_epi, Xn, x.D, (const float*)w.fc1.W, w.fc1.b, Hd, x.F, nullptr, 1, M, x.F, x.D, st); }
+    { ProfScope ps(c, 8, st); f32_gemm(EPI_BIAS_RESIDUAL, Hd, x.F, (const float*)w.fc2.W, w.fc2.b, X, x.D, nullptr, 1, M, x.D, x.F, st); }
+  }
+  if (d.final_norm) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  const float* pin = X;
+  { ProfScope ps(c, 5, st);
+    if (d.pixel_shuffle) { f32_shuffle(X, Pin, T, x.g, x.D, st); pin = Pin; }
+    if (d.proj_prenorm) { f32_norm(0, pin, x.Pin, Pin, x.Pin, c->pn_g, c->pn_b, Mo, x.Pin, 1, d.eps, st); pin = Pin; } }
+  { ProfScope ps(c, 9, st);
+    if (d.proj_kind == EPD_PROJ_LINEAR) {
+      f32_gemm(EPI_BIAS, pin, x.Pin, (const float*)c->pa.W, c->pa.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pin, st);
+    } else {
+      f32_gemm(EPI_BIAS_GELU_ERF, pin, x.Pin, (const float*)c->pa.W, c->pa.b, Pmid, x.Pmid, nullptr, 1, Mo, x.Pmid, x.Pin, st);
+      f32_gemm(EPI_BIAS, Pmid, x.Pmid, (const float*)c->pb.W, c->pb.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pmid, st);
+    } }
+  HIP_TRY(c, hipGetLastError());
+  return EPD_OK;
+}
+
+// --------------------------------------------------------------------------
+// one micro-batch, bf16 mode
+// --------------------------------------------------------------------------
+GemmParams gp(int epi, const void* A, long lda, const Linear& lin, int M) {
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = epi; p.A = (const bf16_t*)A; p.lda = lda; p.W = (const bf16_t*)lin.W; p.bias = lin.b;
+  p.M = M; p.N = lin.N; p.K = lin.K; p.Npad = lin.Npad; p.n_pos = 1;
+  return p;
+}
+
+epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStream_t st) {
+  const epd_model_desc& d = c->d;
+  const Dims& x = c->x;
+  const int M = T * x.N, Mo = T * x.N_out;
+  float* X = c->X;
+  bf16_t* Xn = (bf16_t*)c->Xn; bf16_t* QK = (bf16_t*)c->QKV; bf16_t* VT = (bf16_t*)c->VT; bf16_t* O = (bf16_t*)c->O;
+  bf16_t* Hd = (bf16_t*)c->Hd; bf16_t* Ape = (bf16_t*)c->Ape; bf16_t* Pin = (bf16_t*)c->Pin; bf16_t* Pmid = (bf16_t*)c->Pmid;
+  const int act_epi = d.act == EPD_ACT_GELU_ERF ? EPI_BIAS_GELU_ERF : EPI_BIAS_GELU_TANH;
+  const float scale = 1.0f / sqrtf((float)x.hd);
+  const long ld_qk = 2L * c->Dq;
+
+  { ProfScope ps(c, 0, st);
+    bf16_im2col(tiles, Ape, c->Kp_k, T, x.S, x.p, st);
+    GemmParams p = gp(EPI_BIAS_POS, Ape, c->Kp_k, c->pe, M);
+    p.R = X; p.ldr = x.D; p.pos = c->pos; p.n_pos = x.N;
+    HIP_TRY(c, bf16_gemm(p, st)); }
+  for (int l = 0; l < x.L; ++l) {
+    const LayerW& w = c->layers[l];
+    { ProfScope ps(c, 1, st);
+      RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n1_g, w.n1_b, M, x.D, 0, x.g, x.D, d.eps};
+      bf16_rowop(r, st); }
+    { ProfScope ps(c, 2, st);
+      GemmParams p = gp(EPI_QKV, Xn, c->D_k, w.qkv, M);
+      p.C = QK; p.ldc = ld_qk; p.VT = VT; p.qk_cols = 2 * c->Dq; p.v_col0 = c->v_col0;
+      p.hd_pad = c->hd_pad; p.heads = x.H; p.n_tok = x.N;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    if (d.qk_norm == EPD_QKNORM_FULL) {
+      ProfScope ps(c, 4, st);
+      bf16_qknorm(QK, ld_qk, w.qn_g, M, c->Dq, 1, x.D, d.eps, st);
+      bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, M, c->Dq, 1, x.D, d.eps, st);
+    } else if (d.qk_norm == EPD_QKNORM_PER_HEAD) {
+      ProfScope ps(c, 4, st);
+      bf16_qknorm(QK, ld_qk, w.qn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
+      bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
+    }
+    { ProfScope ps(c, 3, st);
+      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.N, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
+    { ProfScope ps(c, 6, st);
+      GemmParams p = gp(EPI_BIAS_RESIDUAL, O, c->Dq_k, w.o, M);
+      p.R = X; p.ldr = x.D;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 1, st);
+      RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n2_g, w.n2_b, M, x.D, 0, x.g, x.D, d.eps};
+      bf16_rowop(r, st); }
+    { ProfScope ps(c, 7, st);
+      GemmParams p = gp(act_epi, Xn, c->D_k, w.fc1, M);
+      p.C = Hd; p.ldc = c->F_k;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 8, st);
+      GemmParams p2 = gp(EPI_BIAS_RESIDUAL, Hd, c->F_k, w.fc2, M);
+      p2.R = X; p2.ldr = x.D;
+      HIP_TRY(c, bf16_gemm(p2, st)); }
+  }
+  if (d.final_norm) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  { ProfScope ps(c, 5, st);
+    RowOpParams r{d.proj_prenorm ? 0 : 2, X, x.D, Pin, c->Pin_k, c->pn_g, c->pn_b, Mo, x.Pin, d.pixel_shuffle, x.g, x.D, d.eps};
+    bf16_rowop(r, st); }
+  if (d.proj_kind == EPD_PROJ_LINEAR) {
+      ProfScope ps(c, 9, st);
+      GemmParams p = gp(EPI_BIAS, Pin, c->Pin_k, c->pa, Mo);
+      p.C = out; p.ldc = x.Pout;
+      HIP_TRY(c, bf16_gemm(p, st));
+  } else {
+    { ProfScope ps(c, 9, st);
+      GemmParams p = gp(EPI_BIAS_GELU_ERF, Pin, c->Pin_k, c->pa, Mo);
+      p.C = Pmid; p.ldc = c->Pmid_k;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 9, st);
+      GemmParams p2 = gp(EPI_BIAS, Pmid, c->Pmid_k, c->pb, Mo);
+      p2.C = out; p2.ldc = x.Pout;
+      HIP_TRY(c, bf16_gemm(p2, st)); }
+  }
+  HIP_TRY(c, hipGetLastError());
+  return EPD_OK;
+}
+
+epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, int32_t b, int32_t e, void* out,
+                             hipStream_t st) {
+  if (b < 0 || e < b || e > n_total) {
+    set_err(c->err, sizeof(c->err), "tile range [%d, %d) is not inside [0, %d]", b, e, n_total);
+    return EPD_ERR_OFFSETS;
+  }
+  if (e == b) return EPD_OK;
+  if (!tiles || !out) { set_err(c->err, sizeof(c->err), "tiles / out_token_cache is null"); return EPD_ERR_INVALID_ARG; }
+  if (((uintptr_t)tiles & 15) || ((uintptr_t)out & 15)) {
+    set_err(c->err, sizeof(c->err), "tiles and out_token_cache must be 16-byte aligned");
+    return EPD_ERR_INVALID_ARG;
+  }
+  const Dims& x = c->x;
+  const size_t tile_elems = (size_t)3 * x.S * x.S;
+  const size_t out_row_bytes = (size_t)x.Pout * (c->bf16 ? 2 : 4);
+  if (c->prof) { c->ev_used = 0; c->ev_family.clear(); }
+  for (int t0 = b; t0 < e; t0 += c->mb) {
+    const int T = (e - t0) < c->mb ? (e - t0) : c->mb;
+    const float* tp = tiles + (size_t)t0 * tile_elems;
+    char* op = (char*)out + (size_t)t0 * x.N_out * out_row_bytes;
+    epd_status s = c->bf16 ? run_bf16(c, tp, T, (bf16_t*)op, st) : run_f32(c, tp, T, (float*)op, st);
+    if (s != EPD_OK) return s;
+    c->last_rows = (long)T * x.N;
+  }
+  return EPD_OK;
+}
+
+}  // namespace
+
+// ============================================================================
+// exported functions
+// ============================================================================
+extern "C" {
+
+int32_t epd_weight_count(const epd_model_desc* desc) {
+  epd_status s = check_desc(desc, g_err, sizeof(g_err));
+  if (s != EPD_OK) return (int32_t)s;
+  return (int32_t)build_index(*desc).specs.size();
+}
+
+epd_status epd_check_desc(const epd_model_desc* desc, char* errbuf, int32_t errbuf_len) {
+  epd_status s = check_desc(desc, g_err, sizeof(g_err));
+  if (errbuf && errbuf_len > 0) { strncpy(errbuf, s == EPD_OK ? "" : g_err, errbuf_len - 1); errbuf[errbuf_len - 1] = 0; }
+  return s;
+}
+
+epd_status epd_check_offsets(const int32_t* off, int32_t n_requests, int32_t n_tiles) {
+  if (n_requests < 0 || n_tiles < 0) { set_err(g_err, sizeof(g_err), "negative count"); return EPD_ERR_OFFSETS; }
+  if (!off) { set_err(g_err, sizeof(g_err), "tile_offsets_per_request is null"); return EPD_ERR_INVALID_ARG; }
+  if (off[0] != 0) { set_err(g_err, sizeof(g_err), "tile_offsets[0] must be 0, got %d", off[0]); return EPD_ERR_OFFSETS; }
+  for (int r = 0; r < n_requests; ++r)
+    if (off[r + 1] < off[r]) { set_err(g_err, sizeof(g_err), "tile_offsets decrease at request %d", r); return EPD_ERR_OFFSETS; }
+  if (off[n_requests] != n_tiles) {
+    set_err(g_err, sizeof(g_err), "tile_offsets[n_requests] = %d but n_tiles = %d", off[n_requests], n_tiles);
+    return EPD_ERR_OFFSETS;
+  }
+  return EPD_OK;
+}
+
+epd_status epd_create(const epd_model_desc* desc, const epd_weights* weights, void* hip_stream, epd_ctx** out) {
+  if (!out) { set_err(g_err, sizeof(g_err), "out is null"); return EPD_ERR_INVALID_ARG; }
+  *out = nullptr;
+  epd_status s = check_desc(desc, g_err, sizeof(g_err));
+  if (s != EPD_OK) return s;
+  if (!weights || !weights->tensors) { set_err(g_err, sizeof(g_err), "weights is null"); return EPD_ERR_INVALID_ARG; }
+  const WeightIndex wi = build_index(*desc);
+  if (weights->n_tensors != (int32_t)wi.specs.size()) {
+    set_err(g_err, sizeof(g_err), "expected %d weight tensors, got %d", (int)wi.specs.size(), weights->n_tensors);
+    return EPD_ERR_INVALID_ARG;
+  }
+  for (int i = 0; i < weights->n_tensors; ++i)
+    if (!weights->tensors[i] || ((uintptr_t)weights->tensors[i] & 3)) {
+      set_err(g_err, sizeof(g_err), "weight tensor %d is null or misaligned", i);
+      return EPD_ERR_INVALID_ARG;
+    }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) {
+    set_err(g_err, sizeof(g_err), "no HIP device available");
+    return EPD_ERR_HIP;
+  }
+  epd_ctx* c = new epd_ctx();
+  c->d = *desc; c->x = dims_of(*desc); c->bf16 = desc->dtype == EPD_DTYPE_BF16; c->err[0] = 0;
+  s = build_ctx(c, weights, (hipStream_t)hip_stream);
+  if (s != EPD_OK) {
+    strncpy(g_err, c->err, sizeof(g_err) - 1);
+    epd_destroy(c);
+    return s;
+  }
+  *out = c;
+  return EPD_OK;
+}
+
+epd_status epd_encode(epd_ctx* ctx, const float* tiles, int32_t n_tiles, const int32_t* off, int32_t n_requests,
+                      void* out, void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  epd_status s = epd_check_offsets(off, n_requests, n_tiles);
+  if (s != EPD_OK) { strncpy(ctx->err, g_err, sizeof(ctx->err) - 1); return s; }
+  return encode_range_impl(ctx, tiles, n_tiles, 0, n_tiles, out, (hipStream_t)hip_stream);
+}
+
+epd_status epd_encode_range(epd_ctx* ctx, const float* tiles, int32_t n_tiles_total, int32_t tile_begin,
+                            int32_t tile_end, void* out, void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  return encode_range_impl(ctx, tiles, n_tiles_total, tile_begin, tile_end, out, (hipStream_t)hip_stream);
+}
+
+int64_t epd_tokens_per_tile(const epd_ctx* ctx) { return ctx ? ctx->x.N_out : -1; }
+int64_t epd_out_dim(const epd_ctx* ctx) { return ctx ? ctx->x.Pout : -1; }
+const char* epd_last_error(const epd_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+void epd_destroy(epd_ctx* ctx) {
+  if (!ctx) return;
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst, int64_t rows, int64_t dst_bytes) {
+  if (!ctx || !dst) return EPD_ERR_INVALID_ARG;
+  const int64_t bytes = rows * ctx->x.D * 4;
+  if (rows < 0 || rows > ctx->Mp || bytes > dst_bytes) return EPD_ERR_INVALID_ARG;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  HIP_TRY(ctx, hipMemcpy(dst, ctx->X, bytes, hipMemcpyDeviceToHost));
+  return EPD_OK;
+}
+
+epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M, int32_t N,
+                            int32_t K, int32_t iters, float* ms_per_launch, void* hip_stream) {
+  if (!A || !W || !C || M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 128 || K % 64 || iters < 1) {
+    set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16: bad argument");
+    return EPD_ERR_INVALID_ARG;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (bf16_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  float* zb = nullptr;
+  if (!bias) {
+    if (hipMalloc((void**)&zb, (size_t)N * 4) != hipSuccess) return EPD_ERR_NOMEM;
+    (void)hipMemsetAsync(zb, 0, (size_t)N * 4, st);
+  }
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = EPI_BIAS; p.A = (const bf16_t*)A; p.lda = K; p.W = (const bf16_t*)W; p.bias = bias ? bias : zb;
+  p.M = M; p.N = N; p.K = K; p.Npad = N; p.C = (bf16_t*)C; p.ldc = N; p.n_pos = 1;
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0); (void)hipEventCreate(&e1);
+  hipError_t err = bf16_gemm(p, st);  // warm-up
+  (void)hipEventRecord(e0, st);
+  for (int i = 0; i < iters && err == hipSuccess; ++i) err = bf16_gemm(p, st);
+  (void)hipEventRecord(e1, st);
+  (void)hipEventSynchronize(e1);
+  float ms = 0.f;
+  (void)hipEventElapsedTime(&ms, e0, e1);
+  if (ms_per_launch) *ms_per_launch = ms / iters;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  if (zb) (void)hipFree(zb);
+  if (err != hipSuccess) { set_err(g_err, sizeof(g_err), "gemm launch failed: %s", hipGetErrorString(err)); return EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
+epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o, int32_t n_slices,
+                                 int32_t n_tokens, int32_t heads, int32_t hd_pad, int32_t ld_qk, float scale,
+                                 void* hip_stream) {
+  if (!q || !k || !vt || !o) return EPD_ERR_INVALID_ARG;
+  hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, (bf16_t*)o, n_slices,
+                                n_tokens, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
+epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream) {
+  if (!A || !B || !D) return EPD_ERR_INVALID_ARG;
+  mfma_probe((const bf16_t*)A, (const bf16_t*)B, D, (hipStream_t)hip_stream);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+}
+
+epd_status epd_profile_enable(epd_ctx* ctx, int32_t on) {
+  if (!ctx) return EPD_ERR_INVALID_ARG;
+  if (on && ctx->ev.empty()) {
+    ctx->ev.resize(16384);
+    for (auto& e : ctx->ev) HIP_TRY(ctx, hipEventCreate(&e));
+  }
+  ctx->prof = on != 0;
+  ctx->ev_used = 0;
+  ctx->ev_family.clear();
+  return EPD_OK;
+}
+
+epd_status epd_profile_read(epd_ctx* ctx, float* ms, int32_t* launches) {
+  if (!ctx || !ms || !launches) return EPD_ERR_INVALID_ARG;
+  HIP_TRY(ctx, hipDeviceSynchronize());
+  for (int f = 0; f < EPD_PROF_FAMILIES; ++f) { ms[f] = 0.f; launches[f] = 0; }
+  for (size_t i = 0; i < ctx->ev_family.size(); ++i) {
+    float t = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->ev[2 * i], ctx->ev[2 * i + 1]));
+    ms[ctx->ev_family[i]] += t;
+    launches[ctx->ev_family[i]] += 1;
+  }
+  return EPD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal launcher interface between the C boundary (epd_api.hip) and the
+// gfx950 kernels.  Not part of the public boundary.
+#pragma once
+#include "common.h"
+
+namespace epd {
+
+// ---- fp32 mode (simple_f32.hip) -------------------------------------------
+void f32_im2col(const float* tiles, float* A, int T, int S, int p, hipStream_t st);
+void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
+              const float* pos, int n_pos, int M, int N, int K, hipStream_t st);
+void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, const float* gamma,
+              const float* beta, long rows, int dim, int groups, float eps, hipStream_t st);
+void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
+                   int N, int H, int hd, float scale, hipStream_t st);
+void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t st);
+
+// ---- bf16 mode -------------------------------------------------------------
+// GEMM  C[M,N] = A[M,K] * W[N,K]^T with fused epilogue (gemm_bf16.hip).
+// A must be readable for round_up(M,256) rows, W for Npad rows (zero rows
+// beyond N); K % 64 == 0; N % 4 == 0; Npad % 128 == 0.
+struct GemmParams {
+  int epi;
+  const bf16_t* A; long lda;
+  const bf16_t* W;            // packed [Npad, K]
+  const float* bias;          // [Npad]
+  int M, N, K, Npad;
+  bf16_t* C; long ldc;        // bf16 output (BIAS, GELU_*, q/k part of QKV)
+  float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS)
+  const float* pos; int n_pos;
+  bf16_t* VT;                 // QKV: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
+  int qk_cols;                // QKV: columns [0, qk_cols) are q,k (row-major into C)
+  int v_col0, hd_pad, heads, n_tok;  // QKV: value columns start at v_col0 (block aligned)
+};
+hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
+hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (once per process)
+
+// A_pe[row][e] = bf16(pixel) for e < 3*p*p, 0 for the K padding up to lda.
+void bf16_im2col(const float* tiles, bf16_t* A, int lda, int T, int S, int p, hipStream_t st);
+
+// Row operation fp32 -> bf16 (rowop_bf16.hip): optional pixel-shuffle gather
+// of the source rows, then LayerNorm (kind 0), RMSNorm (1) or plain convert (2).
+struct RowOpParams {
+  int kind;
+  const float* in; long ld_in;   // residual stream [.., D]
+  bf16_t* out; long ld_out;
+  const float* gamma; const float* beta;
+  long rows;                      // output rows
+  int dim;                        // output row length (D, or 4D with shuffle)
+  int shuffle;                    // 1: gather 2x2 grid neighbours, dim == 4*D
+  int g, D;                       // grid side and source row length (shuffle only)
+  float eps;
+};
+void bf16_rowop(const RowOpParams& p, hipStream_t st);
+
+// In-place RMSNorm of bf16 rows (q or k inside the QK buffer).  Logical row R
+// of `dim` (padded) elements at buf + (R / groups) * ld + (R % groups) * dim;
+// `count` = number of real elements the mean runs over.
+void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, int groups, int count,
+                 float eps, hipStream_t st);
+
+// Tile-local flash attention (attention_bf16.hip).
+hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
+                          int n_tok, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
+                          hipStream_t st);
+
+// Weight packing (pack.hip): dst[r][c] for r < rows_pad, c < cols_pad, zero
+// outside the source.  row_hd/col_hd > 0: the packed index runs over heads
+// padded from hd to hd_pad (index = blk*H*hd_pad + h*hd_pad + d -> blk*H*hd + h*hd + d).
+struct PackMap { int hd, hd_pad, heads; };  // hd == 0: identity
+void pack_matrix_bf16(const bf16_t* src, int rows, int cols, bf16_t* dst, int rows_pad, int cols_pad,
+                      PackMap rmap, PackMap cmap, hipStream_t st);
+void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_pad, PackMap map,
+                     hipStream_t st);
+
+// MFMA lane-layout check: D[32,32] = A[32,16] * B[16,32] with operands loaded
+// and the result stored under the layout the kernels assume.
+void mfma_probe(const bf16_t* A, const bf16_t* B, float* D, hipStream_t st);
+
+}  // namespace epd

@@ -1,0 +1,250 @@
+// HBM-bound row kernels of the bf16 path: im2col of the pixels, the
+// fp32 -> bf16 pre-norms (with the optional pixel-shuffle gather in front of
+// the projector), the in-place q/k RMSNorm, weight packing, and the MFMA
+// layout probe.
+#include "kernels.h"
+
+namespace epd {
+
+// ---------------------------------------------------------------- im2col ----
+// One thread per (row, channel, dy): 14 consecutive pixels -> 14 bf16.  The
+// 43rd thread of a row zero-fills the K padding.
+__global__ __launch_bounds__(256) void k_bf16_im2col(const float* __restrict__ tiles,
+                                                     bf16_t* __restrict__ A, int lda, int S, int p,
+                                                     int g, long total) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int per_row = 3 * p + 1;
+  const int j = (int)(i % per_row);
+  const long row = i / per_row;
+  const int N = g * g;
+  const long t = row / N;
+  const int n = (int)(row % N);
+  const int y = n / g, x = n % g;
+  bf16_t* dst = A + row * (long)lda;
+  if (j == 3 * p) {
+    for (int e = 3 * p * p; e < lda; ++e) dst[e] = (bf16_t)0.f;
+    return;
+  }
+  const int c = j / p, dy = j % p;
+  const float* src = tiles + ((t * 3 + c) * S + (p * y + dy)) * (long)S + p * x;
+  dst += (c * p + dy) * p;
+  for (int dx = 0; dx < p; ++dx) dst[dx] = (bf16_t)src[dx];
+}
+
+void bf16_im2col(const float* tiles, bf16_t* A, int lda, int T, int S, int p, hipStream_t st) {
+  const int g = S / p;
+  const long total = (long)T * g * g * (3 * p + 1);
+  if (total == 0) return;
+  k_bf16_im2col<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(tiles, A, lda, S, p, g, total);
+}
+
+// ------------------------------------------------------------- row norms ----
+// One wave per output row, rows of `dim` floats (dim % 4 == 0) held in
+// registers when they fit (NV float4 per lane), otherwise re-read.
+template <int NV>
+__global__ __launch_bounds__(256) void k_bf16_rowop(const RowOpParams p) {
+  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= p.rows) return;
+  const int lane = threadIdx.x & 63;
+  const int nchunk = p.dim >> 2;
+
+  // source address of float4 chunk c of output row R
+  long base_t = 0;
+  int Y = 0, X = 0;
+  if (p.shuffle) {
+    const int hgrid = p.g >> 1;
+    const long tok_per = (long)hgrid * hgrid;
+    const long t = R / tok_per;
+    const int m = (int)(R % tok_per);
+    Y = m / hgrid;
+    X = m % hgrid;
+    base_t = t * p.g * p.g;
+  }
+  auto src = [&](int c) -> const float4* {
+    if (!p.shuffle) return reinterpret_cast<const float4*>(p.in + R * p.ld_in) + c;
+    const int e = c << 2;
+    const int blk = e / p.D, ch = e % p.D;
+    const long srow = base_t + (long)(2 * Y + (blk >> 1)) * p.g + (2 * X + (blk & 1));
+    return reinterpret_cast<const float4*>(p.in + srow * p.ld_in + ch);
+  };
+
+  float4 v[NV > 0 ? NV : 1];
+  float s = 0.f;
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + 64 * i;
+      v[i] = (c < nchunk) ? *src(c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      s += v[i].x + v[i].y + v[i].z + v[i].w;
+    }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) {
+      const float4 a = *src(c);
+      s += a.x + a.y + a.z + a.w;
+    }
+  }
+  float mean = 0.f, rstd = 1.f;
+  if (p.kind != 2) {
+    if (p.kind == 0) mean = wave_sum(s) / p.dim;
+    float qs = 0.f;
+    if (NV > 0) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nchunk) {
+          const float a = v[i].x - mean, b = v[i].y - mean, cc = v[i].z - mean, d = v[i].w - mean;
+          qs += a * a + b * b + cc * cc + d * d;
+        }
+      }
+    } else {
+      for (int c = lane; c < nchunk; c += 64) {
+        const float4 t4 = *src(c);
+        const float a = t4.x - mean, b = t4.y - mean, cc = t4.z - mean, d = t4.w - mean;
+        qs += a * a + b * b + cc * cc + d * d;
+      }
+    }
+    rstd = 1.0f / sqrtf(wave_sum(qs) / p.dim + p.eps);
+  }
+  bf16_t* out = p.out + R * p.ld_out;
+  auto emit = [&](int c, float4 a) {
+    float r[4] = {a.x, a.y, a.z, a.w};
+    if (p.kind != 2) {
+      const float4 gm = *(reinterpret_cast<const float4*>(p.gamma) + c);
+      r[0] = (r[0] - mean) * rstd * gm.x;
+      r[1] = (r[1] - mean) * rstd * gm.y;
+      r[2] = (r[2] - mean) * rstd * gm.z;
+      r[3] = (r[3] - mean) * rstd * gm.w;
+      if (p.kind == 0) {
+        const float4 bt = *(reinterpret_cast<const float4*>(p.beta) + c);
+        r[0] += bt.x; r[1] += bt.y; r[2] += bt.z; r[3] += bt.w;
+      }
+    }
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)r[e];
+    *(reinterpret_cast<bf16x4*>(out) + c) = o;
+  };
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) emit(c, v[i]);
+    }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) emit(c, *src(c));
+  }
+}
+
+void bf16_rowop(const RowOpParams& p, hipStream_t st) {
+  if (p.rows == 0) return;
+  dim3 grid((unsigned)((p.rows + 3) / 4)), block(256);
+  const int per_lane = (p.dim / 4 + 63) / 64;
+  if (per_lane <= 4) k_bf16_rowop<4><<<grid, block, 0, st>>>(p);
+  else if (per_lane <= 8) k_bf16_rowop<8><<<grid, block, 0, st>>>(p);
+  else if (per_lane <= 16) k_bf16_rowop<16><<<grid, block, 0, st>>>(p);
+  else k_bf16_rowop<0><<<grid, block, 0, st>>>(p);
+}
+
+// --------------------------------------------------------- q/k RMSNorm ------
+__global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld,
+                                                     const float* __restrict__ gamma, long rows,
+                                                     int dim, int groups, int count, float eps) {
+  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= rows) return;
+  const int lane = threadIdx.x & 63;
+  bf16_t* x = buf + (R / groups) * ld + (R % groups) * (long)dim;
+  const int nchunk = dim >> 2;
+  float qs = 0.f;
+  for (int c = lane; c < nchunk; c += 64) {
+    const bf16x4 a = *(reinterpret_cast<const bf16x4*>(x) + c);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) qs += (float)a[e] * (float)a[e];
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(qs) / count + eps);
+  for (int c = lane; c < nchunk; c += 64) {
+    const bf16x4 a = *(reinterpret_cast<const bf16x4*>(x) + c);
+    const float4 gm = *(reinterpret_cast<const float4*>(gamma) + c);
+    bf16x4 o;
+    o[0] = (bf16_t)((float)a[0] * rstd * gm.x);
+    o[1] = (bf16_t)((float)a[1] * rstd * gm.y);
+    o[2] = (bf16_t)((float)a[2] * rstd * gm.z);
+    o[3] = (bf16_t)((float)a[3] * rstd * gm.w);
+    *(reinterpret_cast<bf16x4*>(x) + c) = o;
+  }
+}
+
+void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, int groups, int count,
+                 float eps, hipStream_t st) {
+  if (rows == 0) return;
+  k_bf16_qknorm<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(buf, ld, gamma, rows, dim, groups,
+                                                                       count, eps);
+}
+
+// --------------------------------------------------------------- packing ----
+__device__ __forceinline__ int unpad_index(int i, PackMap m, int limit) {
+  if (m.hd == 0) return i < limit ? i : -1;
+  const int per = m.heads * m.hd_pad;
+  const int blk = i / per, w = i % per;
+  const int h = w / m.hd_pad, d = w % m.hd_pad;
+  if (d >= m.hd) return -1;
+  const int s = blk * m.heads * m.hd + h * m.hd + d;
+  return s < limit ? s : -1;
+}
+
+__global__ void k_pack_matrix(const bf16_t* __restrict__ src, int rows, int cols, bf16_t* __restrict__ dst,
+                              int rows_pad, int cols_pad, PackMap rmap, PackMap cmap) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)rows_pad * cols_pad) return;
+  const int r = (int)(i / cols_pad), c = (int)(i % cols_pad);
+  const int sr = unpad_index(r, rmap, rows), sc = unpad_index(c, cmap, cols);
+  dst[i] = (sr >= 0 && sc >= 0) ? src[(long)sr * cols + sc] : (bf16_t)0.f;
+}
+
+void pack_matrix_bf16(const bf16_t* src, int rows, int cols, bf16_t* dst, int rows_pad, int cols_pad,
+                      PackMap rmap, PackMap cmap, hipStream_t st) {
+  const long total = (long)rows_pad * cols_pad;
+  if (total == 0) return;
+  k_pack_matrix<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(src, rows, cols, dst, rows_pad,
+                                                                            cols_pad, rmap, cmap);
+}
+
+__global__ void k_pack_vector(const void* __restrict__ src, int src_is_bf16, int n, float* __restrict__ dst,
+                              int n_pad, PackMap map) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pad) return;
+  const int s = unpad_index(i, map, n);
+  float v = 0.f;
+  if (s >= 0) v = src_is_bf16 ? (float)reinterpret_cast<const bf16_t*>(src)[s] : reinterpret_cast<const float*>(src)[s];
+  dst[i] = v;
+}
+
+void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_pad, PackMap map,
+                     hipStream_t st) {
+  if (n_pad == 0) return;
+  k_pack_vector<<<dim3((n_pad + 255) / 256), dim3(256), 0, st>>>(src, src_is_bf16, n, dst, n_pad, map);
+}
+
+// ------------------------------------------------------------ MFMA probe ----
+__global__ __launch_bounds__(64) void k_mfma_probe(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                   float* __restrict__ D) {
+  const int l = threadIdx.x, l32 = l & 31, lh = l >> 5;
+  bf16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = A[l32 * 16 + lh * 8 + j];          // A[m][k], row-major 32 x 16
+    b[j] = B[(lh * 8 + j) * 32 + l32];        // B[k][n], row-major 16 x 32
+  }
+  f32x16 c;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) c[e] = 0.f;
+  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) D[(8 * (i / 4) + 4 * lh + (i % 4)) * 32 + l32] = c[i];
+}
+
+void mfma_probe(const bf16_t* A, const bf16_t* B, float* D, hipStream_t st) {
+  k_mfma_probe<<<dim3(1), dim3(64), 0, st>>>(A, B, D);
+}
+
+}  // namespace epd

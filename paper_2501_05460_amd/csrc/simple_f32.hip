@@ -1,0 +1,222 @@
+// fp32 mode of the encode stage: plain, bounds-checked kernels with fp32
+// storage and fp32 accumulation.  This mode exists for the small fp32
+// configuration (launch-latency bound) and as the on-device numerical
+// reference of the bf16 MFMA path; it is not tuned.
+#include "kernels.h"
+
+namespace epd {
+
+// ---------------------------------------------------------------- im2col ----
+// A[t*N + y*g + x][(c*p + dy)*p + dx] = tiles[t][c][p*y + dy][p*x + dx]
+__global__ void k_f32_im2col(const float* __restrict__ tiles, float* __restrict__ A, int S, int p,
+                             int g, int Kp, long total) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int e = (int)(i % Kp);
+  long row = i / Kp;
+  int N = g * g;
+  long t = row / N;
+  int n = (int)(row % N);
+  int y = n / g, x = n % g;
+  int c = e / (p * p), r = e % (p * p);
+  int dy = r / p, dx = r % p;
+  A[i] = tiles[((t * 3 + c) * S + (p * y + dy)) * (long)S + (p * x + dx)];
+}
+
+void f32_im2col(const float* tiles, float* A, int T, int S, int p, hipStream_t st) {
+  int g = S / p, Kp = 3 * p * p;
+  long total = (long)T * g * g * Kp;
+  if (total == 0) return;
+  int bs = 256;
+  k_f32_im2col<<<dim3((unsigned)((total + bs - 1) / bs)), dim3(bs), 0, st>>>(tiles, A, S, p, g, Kp, total);
+}
+
+// ------------------------------------------------------------------ GEMM ----
+// C[M,N] = A[M,K] * W[N,K]^T, 64x64 block tile, 16-deep k slab, 4x4 per thread.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, int lda,
+                                                  const float* __restrict__ W,
+                                                  const float* __restrict__ bias, float* C, int ldc,
+                                                  const float* __restrict__ pos, int n_pos, int M,
+                                                  int N, int K) {
+  __shared__ float sA[16][64 + 1];
+  __shared__ float sW[16][64 + 1];
+  const int tid = threadIdx.x;
+  const int tx = tid % 16, ty = tid / 16;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = tid; i < 64 * 16; i += 256) {
+      int r = i / 16, kk = i % 16;
+      int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
+      sA[kk][r] = (gm < M && gk < K) ? A[(long)gm * lda + gk] : 0.f;
+      sW[kk][r] = (gn < N && gk < K) ? W[(long)gn * K + gk] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = sA[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = sW[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int r = m0 + ty * 4 + i;
+    if (r >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int c = n0 + tx * 4 + j;
+      if (c >= N) continue;
+      float v = acc[i][j] + (bias ? bias[c] : 0.f);
+      long o = (long)r * ldc + c;
+      if (EPI == EPI_BIAS_RESIDUAL) {
+        C[o] += v;
+      } else if (EPI == EPI_BIAS_POS) {
+        C[o] = v + pos[(long)(r % n_pos) * N + c];
+      } else {
+        C[o] = apply_act<EPI>(v);
+      }
+    }
+  }
+}
+
+void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
+              const float* pos, int n_pos, int M, int N, int K, hipStream_t st) {
+  if (M == 0 || N == 0) return;
+  dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
+  switch (epi) {
+    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+  }
+}
+
+// ------------------------------------------------------------------ norm ----
+// Logical row R of `dim` elements lives at in + (R / groups) * ld_in + (R % groups) * dim
+// (groups > 1: per-head norm inside a wider row).  One wave per row.
+__global__ __launch_bounds__(256) void k_f32_norm(int kind, const float* in, long ld_in, float* out,
+                                                  long ld_out, const float* __restrict__ gamma,
+                                                  const float* __restrict__ beta, long rows, int dim,
+                                                  int groups, float eps) {
+  long R = (long)blockIdx.x * 4 + threadIdx.x / 64;
+  if (R >= rows) return;
+  int lane = threadIdx.x % 64;
+  const float* x = in + (R / groups) * ld_in + (R % groups) * (long)dim;
+  float* y = out + (R / groups) * ld_out + (R % groups) * (long)dim;
+  float s = 0.f;
+  float mean = 0.f;
+  if (kind == 0) {
+    for (int i = lane; i < dim; i += 64) s += x[i];
+    mean = wave_sum(s) / dim;
+  }
+  float q = 0.f;
+  for (int i = lane; i < dim; i += 64) {
+    float d = x[i] - mean;
+    q += d * d;
+  }
+  float rstd = 1.0f / sqrtf(wave_sum(q) / dim + eps);
+  for (int i = lane; i < dim; i += 64) {
+    float v = (x[i] - mean) * rstd * gamma[i];
+    if (kind == 0) v += beta[i];
+    y[i] = v;
+  }
+}
+
+void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, const float* gamma,
+              const float* beta, long rows, int dim, int groups, float eps, hipStream_t st) {
+  if (rows == 0) return;
+  k_f32_norm<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(kind, in, ld_in, out, ld_out, gamma,
+                                                                    beta, rows, dim, groups, eps);
+}
+
+// ------------------------------------------------------------- attention ----
+// One block per (query, head, slice): logits of the slice's N keys in LDS,
+// block-wide max and sum, then one thread per output channel.
+__global__ __launch_bounds__(128) void k_f32_attention(const float* __restrict__ q,
+                                                       const float* __restrict__ k,
+                                                       const float* __restrict__ v, long ld,
+                                                       float* __restrict__ o, long ldo, int N, int hd,
+                                                       float scale) {
+  extern __shared__ float sm[];
+  float* sc = sm;          // [N]
+  float* sq = sm + N;      // [hd]
+  __shared__ float red[2];
+  const int tid = threadIdx.x;
+  const int qi = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
+  const long row0 = (long)t * N;
+  for (int d = tid; d < hd; d += 128) sq[d] = q[(row0 + qi) * ld + h * hd + d];
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = tid; j < N; j += 128) {
+    const float* kr = k + (row0 + j) * ld + h * hd;
+    float acc = 0.f;
+    for (int d = 0; d < hd; ++d) acc = fmaf(sq[d], kr[d], acc);
+    acc *= scale;
+    sc[j] = acc;
+    mx = fmaxf(mx, acc);
+  }
+  mx = wave_max(mx);
+  if (tid % 64 == 0) red[tid / 64] = mx;
+  __syncthreads();
+  mx = fmaxf(red[0], red[1]);
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = tid; j < N; j += 128) {
+    float e = expf(sc[j] - mx);
+    sc[j] = e;
+    sum += e;
+  }
+  sum = wave_sum(sum);
+  if (tid % 64 == 0) red[tid / 64] = sum;
+  __syncthreads();
+  float inv = 1.0f / (red[0] + red[1]);
+  for (int d = tid; d < hd; d += 128) {
+    float acc = 0.f;
+    for (int j = 0; j < N; ++j) acc = fmaf(sc[j], v[(row0 + j) * ld + h * hd + d], acc);
+    o[(row0 + qi) * ldo + h * hd + d] = acc * inv;
+  }
+}
+
+void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
+                   int N, int H, int hd, float scale, hipStream_t st) {
+  if (T == 0) return;
+  size_t smem = (size_t)(N + hd) * sizeof(float);
+  k_f32_attention<<<dim3(N, H, T), dim3(128), smem, st>>>(q, k, v, ld, o, ldo, N, hd, scale);
+}
+
+// --------------------------------------------------------- pixel shuffle ----
+// out[t*N/4 + Y*(g/2) + X][(dy*2 + dx)*D + c] = in[t*N + (2Y+dy)*g + (2X+dx)][c]
+__global__ void k_f32_shuffle(const float* __restrict__ in, float* __restrict__ out, int g, int D,
+                              long total) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  int D4 = 4 * D;
+  int e = (int)(i % D4);
+  long m = i / D4;
+  int h = g / 2;
+  long t = m / (h * h);
+  int mm = (int)(m % (h * h));
+  int Y = mm / h, X = mm % h;
+  int blk = e / D, c = e % D;
+  int dy = blk / 2, dx = blk % 2;
+  long src = t * g * g + (long)(2 * Y + dy) * g + (2 * X + dx);
+  out[i] = in[src * D + c];
+}
+
+void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t st) {
+  long total = (long)T * (g * g / 4) * 4 * D;
+  if (total == 0) return;
+  k_f32_shuffle<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(in, out, g, D, total);
+}
+
+}  // namespace epd
