@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the encode stage on one MI355X.
+
+One "step" is one epd_encode call over the whole synthetic batch of the
+chosen workload (default: the InternViT-300M-shaped configuration, 8 requests
+of 13 slices).  Inputs and packed weights are resident in HBM before the
+timed region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_FP32_TFLOPS = 157.3
+
+
+def gemm_flops_per_tile(desc):
+    """Dense-contraction flops of the GEMM kernel family per slice, by profile family."""
+    N, D, F, L = desc.n_patches, desc.hidden, desc.mlp, desc.layers
+    No, Pi = desc.tokens_per_tile, desc.proj_in
+    proj = 2 * No * Pi * desc.proj_out if desc.proj_kind == 0 else \
+        2 * No * Pi * desc.proj_mid + 2 * No * desc.proj_mid * desc.proj_out
+    return {
+        "gemm_qkv": L * 2 * N * D * 3 * D,
+        "gemm_out": L * 2 * N * D * D,
+        "gemm_fc1": L * 2 * N * D * F,
+        "gemm_fc2": L * 2 * N * D * F,
+        "gemm_proj": proj,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tiles", type=int, default=0, help="slices the oracle encodes (0: bounded default)")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (slices are independent, so more GPUs would each "
+              "run this same kernel path on a share of the slices); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as wl
+    from paper_2501_05460_amd import binding as B
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2501_05460_amd.build import build
+        build()
+
+    wk = wl.workload(args.workload)
+    desc = wk.desc
+    if args.micro_batch > 0:
+        desc = desc.replace(max_tiles_per_call=args.micro_batch)
+    bf16 = desc.dtype == wl.DT_BF16
+    T = wk.n_tiles
+
+    t0 = time.time()
+    weights_dev = []
+    for i in range(len(wl.weight_specs(desc))):
+        weights_dev.append(B.to_device(wl.gen_weight(desc, wk.weight_seed, i), bf16))
+    enc = B.Encoder(desc, weights_dev)
+    del weights_dev
+    S = desc.tile_size
+    tiles = torch.empty((T, 3, S, S), dtype=torch.float32, device="cuda")
+    for t in range(T):
+        tiles[t] = torch.from_numpy(wl.gen_tile(desc, wk.input_seed, t))
+    out = enc.alloc_out(T)
+    offsets = list(wk.tile_offsets)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    for _ in range(args.warmup):
+        enc.encode(tiles, offsets, out)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        enc.encode(tiles, offsets, out)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t1
+    ms_per_step = elapsed / args.steps * 1e3
+    tiles_per_s = T * args.steps / elapsed
+    tokens_per_s = tiles_per_s * desc.tokens_per_tile
+    total_flops = wl.flops_per_tile(desc) * T
+    tflops = total_flops / (elapsed / args.steps) / 1e12
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+
+    # ---- per-kernel-family timing with HIP events on the call's stream ----
+    enc.profile_enable(True)
+    prof_steps = max(1, min(3, args.steps))
+    fam = {}
+    for _ in range(prof_steps):
+        enc.encode(tiles, offsets, out)
+        for k, v in enc.profile_read().items():
+            f = fam.setdefault(k, {"ms": 0.0, "launches": 0})
+            f["ms"] += v["ms"]
+            f["launches"] += v["launches"]
+    enc.profile_enable(False)
+    gf = gemm_flops_per_tile(desc)
+    gemm_ms = sum(fam[k]["ms"] for k in gf)
+    gemm_launches = sum(fam[k]["launches"] for k in gf)
+    gemm_flops = sum(gf.values()) * T * prof_steps
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    roofline = {
+        "bound": "mfma", "kernel": "k_gemm_bf16 (all epilogue variants)" if bf16 else "k_f32_gemm",
+        "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+        "traffic": None,
+        "flops_per_launch": gemm_flops / max(gemm_launches, 1),
+        "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
+        "families_ms_per_step": {k: round(v["ms"] / prof_steps, 3) for k, v in fam.items()},
+        "families_tflops": {k: round(gf[k] * T * prof_steps / (fam[k]["ms"] * 1e-3) / 1e12, 1)
+                            for k in gf if fam[k]["ms"] > 0},
+    }
+
+    # ---- parity spot check and CPU baseline: the oracle on a bounded sample ----
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import epd_oracle as O
+        n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2}[args.workload]
+        sample = list(wk.oracle_sample_tiles)[:n_cpu]
+        w_host = wl.gen_weights(desc, wk.weight_seed)
+        host_tiles = [wl.gen_tile(desc, wk.input_seed, t) for t in sample]
+        c0 = time.perf_counter()
+        ref = O.encode_sample(host_tiles, w_host, desc)
+        cpu_s = time.perf_counter() - c0
+        n_out = desc.tokens_per_tile
+        got = np.concatenate([out[t * n_out:(t + 1) * n_out].float().cpu().numpy() for t in sample])
+        parity = float(np.abs(got - ref).max() / np.abs(ref).max())
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        cpu = {"value": round(len(sample) / cpu_s, 4), "unit": "tiles/s", "cores": threads,
+               "kind": "oracle",
+               "sample": f"slices {sample} of the same batch at full depth, {cpu_s:.1f} s, numpy fp64"}
+
+    line = {
+        "metric": "image_tiles_per_sec", "value": round(tiles_per_s, 2), "unit": "tiles/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": wk.name, "tiles": T, "requests": wk.n_requests,
+                   "tokens_per_tile": desc.tokens_per_tile, "out_dim": desc.out_dim,
+                   "micro_batch_tiles": desc.max_tiles_per_call},
+        "vision_tokens_per_sec": round(tokens_per_s, 1),
+        "patch_tokens_per_sec": round(tiles_per_s * desc.n_patches, 1),
+        "algorithmic_tflops": round(tflops, 2),
+        "mfma_util_pct_of_peak": round(100.0 * tflops / peak, 2),
+        "parity_max_rel_err_sample": parity,
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

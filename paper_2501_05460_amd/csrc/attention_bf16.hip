@@ -71,19 +71,19 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
       for (int e = 0; e < 8; ++e) qf[s][e] = (bf16_t)0.f;
   }
 
-  uint4 rk[K_LOADS], rv[V_LOADS];
+  u32x4 rk[K_LOADS], rv[V_LOADS];
   auto gload = [&](int kb) {
 #pragma unroll
     for (int i = 0; i < K_LOADS; ++i) {
       const int c = tid + 256 * i;
       const int row = c / KCH, ch = c % KCH;
-      rk[i] = *reinterpret_cast<const uint4*>(kbase + (long)(kb * BKEY + row) * ld_qk + ch * 8);
+      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (long)(kb * BKEY + row) * ld_qk + ch * 8);
     }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) {
       const int c = tid + 256 * i;
       const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
-      rv[i] = *reinterpret_cast<const uint4*>(vbase + (long)row * n_tok + kb * BKEY + ch * 8);
+      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (long)row * n_tok + kb * BKEY + ch * 8);
     }
   };
   auto sstore = [&](int buf) {
@@ -91,13 +91,13 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
     for (int i = 0; i < K_LOADS; ++i) {
       const int c = tid + 256 * i;
       const int row = c / KCH, ch = c % KCH;
-      *reinterpret_cast<uint4*>(sK + buf * SM::K_ELEMS + row * SM::K_LD + ch * 8) = rk[i];
+      *reinterpret_cast<u32x4*>(sK + buf * SM::K_ELEMS + row * SM::K_LD + ch * 8) = rk[i];
     }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) {
       const int c = tid + 256 * i;
       const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
-      *reinterpret_cast<uint4*>(sV + buf * SM::V_ELEMS + row * SM::V_LD + ch * 8) = rv[i];
+      *reinterpret_cast<u32x4*>(sV + buf * SM::V_ELEMS + row * SM::V_LD + ch * 8) = rv[i];
     }
   };
 
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
   __syncthreads();
 
   for (int kb = 0; kb < NB; ++kb) {
-    if (kb + 1 < NB) gload(kb + 1);
+    gload(kb + 1 < NB ? kb + 1 : kb);  // unconditional: staging registers stay out of control flow
     if (active) {
       const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
       const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
           }
         }
     }
-    if (kb + 1 < NB) sstore((kb + 1) & 1);
+    sstore((kb + 1) & 1);
     __syncthreads();
   }
 

@@ -8,6 +8,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define EPD_WAVE 64
 
@@ -18,7 +19,7 @@ enum EpiKind : int {
   EPI_BIAS_GELU_TANH = 2, // out = gelu_tanh(acc + bias)
   EPI_BIAS_RESIDUAL = 3,  // res[r][c] += acc + bias   (fp32 residual stream, in place)
   EPI_BIAS_POS = 4,       // res[r][c]  = acc + bias + pos[r % n_pos][c]
-  EPI_QKV = 5             // q,k row-major bf16; v written transposed per (slice, head)
+  EPI_VT = 5              // out = acc + bias, written transposed per (slice, head): VT[t][h][d][n]
 };
 
 __device__ __forceinline__ float gelu_erf_f(float x) {

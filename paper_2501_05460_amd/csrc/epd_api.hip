@@ -133,7 +133,7 @@ struct Linear {
 
 struct LayerW {
   const float *n1_g = nullptr, *n1_b = nullptr, *n2_g = nullptr, *n2_b = nullptr, *qn_g = nullptr, *kn_g = nullptr;
-  Linear qkv, o, fc1, fc2;
+  Linear qkv, v, o, fc1, fc2;  // bf16 mode: qkv holds q,k only and v the value projection
 };
 
 }  // namespace
@@ -152,7 +152,7 @@ struct epd_ctx {
   std::vector<LayerW> layers;
 
   // bf16 layout
-  int hd_pad = 0, Dq = 0, Dq_k = 0, D_k = 0, F_k = 0, Kp_k = 0, Pin_k = 0, Pmid_k = 0, v_col0 = 0;
+  int hd_pad = 0, Dq = 0, Dq_k = 0, D_k = 0, F_k = 0, Kp_k = 0, Pin_k = 0, Pmid_k = 0;
 
   // workspace (sized for mb slices)
   int mb = 0;
@@ -286,27 +286,22 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         NOMEM_IF(!lw.qn_g || !lw.kn_g);
       }
     } else {
-      // fused QKV: packed rows [q heads | k heads | gap | v heads], heads padded to hd_pad.
-      // The gap aligns the value block to the GEMM's block width.
-      const int qk_cols = 2 * c->Dq;
-      int v0 = round_up(qk_cols, 256);
-      int npad = round_up(v0 + c->Dq, 256);
-      if ((long)(npad - 3 * c->Dq) * 32 > 3L * c->Dq) {  // too much padding: use the 128-wide blocks
-        v0 = round_up(qk_cols, 128);
-        npad = round_up(v0 + c->Dq, 128);
+      // q,k projection (rows [q heads | k heads], heads padded to hd_pad) and the value
+      // projection (stored transposed by its epilogue) are two products over the same input
+      {
+        const int qk_cols = 2 * c->Dq, qk_pad = pad_n(qk_cols), v_pad = pad_n(c->Dq);
+        bf16_t* Wqk = (bf16_t*)dalloc(c, (size_t)qk_pad * c->D_k * sizeof(bf16_t), true, st);
+        float* bqk = (float*)dalloc(c, (size_t)qk_pad * sizeof(float), true, st);
+        bf16_t* Wv = (bf16_t*)dalloc(c, (size_t)v_pad * c->D_k * sizeof(bf16_t), true, st);
+        float* bv = (float*)dalloc(c, (size_t)v_pad * sizeof(float), true, st);
+        NOMEM_IF(!Wqk || !bqk || !Wv || !bv);
+        pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w], 2 * x.D, x.D, Wqk, qk_cols, c->D_k, heads, id, st);
+        pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w] + 2L * x.D * x.D, x.D, x.D, Wv, c->Dq, c->D_k, heads, id, st);
+        pack_vector_f32(w->tensors[li.qkv_b], 1, 2 * x.D, bqk, qk_cols, heads, st);
+        pack_vector_f32((const bf16_t*)w->tensors[li.qkv_b] + 2 * x.D, 1, x.D, bv, c->Dq, heads, st);
+        lw.qkv.W = Wqk; lw.qkv.b = bqk; lw.qkv.N = qk_cols; lw.qkv.K = c->D_k; lw.qkv.Npad = qk_pad;
+        lw.v.W = Wv; lw.v.b = bv; lw.v.N = c->Dq; lw.v.K = c->D_k; lw.v.Npad = v_pad;
       }
-      c->v_col0 = v0;
-      // q,k block and v block are packed by two calls into one matrix
-      bf16_t* Wq = (bf16_t*)dalloc(c, (size_t)npad * c->D_k * sizeof(bf16_t), true, st);
-      float* bq = (float*)dalloc(c, (size_t)npad * sizeof(float), true, st);
-      NOMEM_IF(!Wq || !bq);
-      const PackMap hm = heads;  // always re-index: rows are (block, head, d)
-      pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w], 2 * x.D, x.D, Wq, qk_cols, c->D_k, hm, id, st);
-      pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w] + 2L * x.D * x.D, x.D, x.D,
-                       Wq + (long)v0 * c->D_k, c->Dq, c->D_k, hm, id, st);
-      pack_vector_f32(w->tensors[li.qkv_b], 1, 2 * x.D, bq, qk_cols, hm, st);
-      pack_vector_f32((const bf16_t*)w->tensors[li.qkv_b] + 2 * x.D, 1, x.D, bq + v0, c->Dq, hm, st);
-      lw.qkv.W = Wq; lw.qkv.b = bq; lw.qkv.N = v0 + c->Dq; lw.qkv.K = c->D_k; lw.qkv.Npad = npad;
 
       NOMEM_IF(!make_linear(c, w, li.o_w, li.o_b, x.D, x.D, &lw.o, st, pad_n(x.D), c->Dq_k, id, heads, x.D));
       f_pad = pad_n(x.F);
@@ -461,10 +456,12 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n1_g, w.n1_b, M, x.D, 0, x.g, x.D, d.eps};
       bf16_rowop(r, st); }
     { ProfScope ps(c, 2, st);
-      GemmParams p = gp(EPI_QKV, Xn, c->D_k, w.qkv, M);
-      p.C = QK; p.ldc = ld_qk; p.VT = VT; p.qk_cols = 2 * c->Dq; p.v_col0 = c->v_col0;
-      p.hd_pad = c->hd_pad; p.heads = x.H; p.n_tok = x.N;
-      HIP_TRY(c, bf16_gemm(p, st)); }
+      GemmParams p = gp(EPI_BIAS, Xn, c->D_k, w.qkv, M);
+      p.C = QK; p.ldc = ld_qk;
+      HIP_TRY(c, bf16_gemm(p, st));
+      GemmParams pv = gp(EPI_VT, Xn, c->D_k, w.v, M);
+      pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.N;
+      HIP_TRY(c, bf16_gemm(pv, st)); }
     if (d.qk_norm == EPD_QKNORM_FULL) {
       ProfScope ps(c, 4, st);
       bf16_qknorm(QK, ld_qk, w.qn_g, M, c->Dq, 1, x.D, d.eps, st);

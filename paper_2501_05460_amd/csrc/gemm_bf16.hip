@@ -15,9 +15,9 @@
 // result register i of lane l is D[8*(i/4) + 4*(l/32) + i%4][l % 32].
 // The weight fragment is fed as the LEFT operand, so a lane owns one token
 // and four consecutive output features per register group: 8-byte bf16 /
-// 16-byte fp32 accesses in the epilogue.  For the value columns of the fused
-// QKV GEMM the roles are swapped, so a lane owns four consecutive tokens of
-// one feature, which is what the transposed value layout wants.
+// 16-byte fp32 accesses in the epilogue.  For the attention values (EPI_VT)
+// the roles are swapped, so a lane owns four consecutive tokens of one
+// feature, which is what the transposed value layout wants.
 #include "kernels.h"
 
 namespace epd {
@@ -68,22 +68,22 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
   const bf16_t* gA = p.A + (long)(m0 + ld_row) * p.lda + ld_c * 8;
   const bf16_t* gB = p.W + (long)(n0 + ld_row) * p.K + ld_c * 8;
 
-  uint4 ra[A_LD], rb[B_LD];
+  u32x4 ra[A_LD], rb[B_LD];
   auto gload = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      ra[i] = *reinterpret_cast<const uint4*>(gA + (long)(64 * i) * p.lda + kt * BK);
+      ra[i] = *reinterpret_cast<const u32x4*>(gA + (long)(64 * i) * p.lda + kt * BK);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      rb[i] = *reinterpret_cast<const uint4*>(gB + (long)(64 * i) * p.K + kt * BK);
+      rb[i] = *reinterpret_cast<const u32x4*>(gB + (long)(64 * i) * p.K + kt * BK);
   };
   auto sstore = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      *reinterpret_cast<uint4*>(sA + buf * BM * BK + 64 * i * BK + st_off) = ra[i];
+      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + 64 * i * BK + st_off) = ra[i];
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      *reinterpret_cast<uint4*>(sB + buf * BN * BK + 64 * i * BK + st_off) = rb[i];
+      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + 64 * i * BK + st_off) = rb[i];
   };
 
   f32x16 acc[TM][TN];
@@ -94,8 +94,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // value columns of the fused QKV GEMM: token-major MFMA result
-  const bool tok_major = (EPI == EPI_QKV) && (n0 >= p.v_col0);
+  // attention values: token-major MFMA result, stored transposed
+  constexpr bool tok_major = (EPI == EPI_VT);
 
   const int KT = p.K / BK;
   gload(0);
@@ -104,7 +104,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 
   const int frag_sw = l32 & 7;
   for (int kt = 0; kt < KT; ++kt) {
-    if (kt + 1 < KT) gload(kt + 1);
+    // always issue the next slab's loads (the last iteration re-reads the
+    // final slab into the idle buffer): keeps the staging registers free of
+    // control flow
+    gload(kt + 1 < KT ? kt + 1 : kt);
     const bf16_t* a_s = sA + (kt & 1) * BM * BK + (wm * WM + l32) * BK;
     const bf16_t* b_s = sB + (kt & 1) * BN * BK + (wn * 64 + l32) * BK;
 #pragma unroll
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
       for (int i = 0; i < TM; ++i) xf[i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * BK + coff);
 #pragma unroll
       for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * BK + coff);
-      if (EPI == EPI_QKV && tok_major) {
+      if (tok_major) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -127,18 +130,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
           for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(wf[j], xf[i], acc[i][j]);
       }
     }
-    if (kt + 1 < KT) sstore((kt + 1) & 1);
+    sstore((kt + 1) & 1);
     __syncthreads();
   }
 
   // ------------------------------------------------------------ epilogue ----
-  if (EPI == EPI_QKV && tok_major) {
+  if (tok_major) {
     // lane = feature, register group = 4 consecutive tokens
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int c = n0 + wn * 64 + j * 32 + l32;
-      const int fv = c - p.v_col0;
-      if (fv >= p.heads * p.hd_pad) continue;
+      const int fv = c;
+      if (fv >= p.N) continue;
       const float bv = p.bias[c];
       const int h = fv / p.hd_pad, d = fv % p.hd_pad;
 #pragma unroll
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi) {
         const int c0 = n0 + wn * 64 + j * 32 + gi * 8 + lh * 4;
-        if (c0 >= (EPI == EPI_QKV ? p.qk_cols : p.N)) continue;
+        if (c0 >= p.N) continue;
         const float4 b4 = *reinterpret_cast<const float4*>(p.bias + c0);
         float v[4] = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
                       acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
@@ -211,7 +214,7 @@ hipError_t dispatch(const GemmParams& p, hipStream_t st) {
     case EPI_BIAS_GELU_TANH: return launch<BN, EPI_BIAS_GELU_TANH>(p, st);
     case EPI_BIAS_RESIDUAL: return launch<BN, EPI_BIAS_RESIDUAL>(p, st);
     case EPI_BIAS_POS: return launch<BN, EPI_BIAS_POS>(p, st);
-    case EPI_QKV: return launch<BN, EPI_QKV>(p, st);
+    case EPI_VT: return launch<BN, EPI_VT>(p, st);
   }
   return hipErrorInvalidValue;
 }
@@ -230,7 +233,7 @@ hipError_t set_attr_all() {
   if ((e = set_attr<BN, EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
   if ((e = set_attr<BN, EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
   if ((e = set_attr<BN, EPI_BIAS_POS>()) != hipSuccess) return e;
-  return set_attr<BN, EPI_QKV>();
+  return set_attr<BN, EPI_VT>();
 }
 
 }  // namespace
@@ -243,12 +246,6 @@ hipError_t bf16_gemm_init() {
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (p.K % BK != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
-  // the value block of a fused QKV product must start on a block boundary
-  if (p.epi == EPI_QKV) {
-    const int bn = (p.Npad % 256 == 0 && p.v_col0 % 256 == 0) ? 256 : 128;
-    if (p.v_col0 % bn != 0) return hipErrorInvalidValue;
-    return bn == 256 ? dispatch<256>(p, st) : dispatch<128>(p, st);
-  }
   return (p.Npad % 256 == 0) ? dispatch<256>(p, st) : dispatch<128>(p, st);
 }
 

@@ -25,12 +25,11 @@ struct GemmParams {
   const bf16_t* W;            // packed [Npad, K]
   const float* bias;          // [Npad]
   int M, N, K, Npad;
-  bf16_t* C; long ldc;        // bf16 output (BIAS, GELU_*, q/k part of QKV)
+  bf16_t* C; long ldc;        // bf16 output (BIAS, GELU_*)
   float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS)
   const float* pos; int n_pos;
-  bf16_t* VT;                 // QKV: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
-  int qk_cols;                // QKV: columns [0, qk_cols) are q,k (row-major into C)
-  int v_col0, hd_pad, heads, n_tok;  // QKV: value columns start at v_col0 (block aligned)
+  bf16_t* VT;                 // EPI_VT: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
+  int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
 };
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
 hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (once per process)
