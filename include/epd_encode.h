@@ -164,7 +164,7 @@ epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst /*host*/, int64_t rows,
  * caller provides, bracketed by HIP events on `hip_stream`; returns the mean
  * milliseconds per launch in *ms_per_launch.  A [M,K] bf16, W [N,K] bf16,
  * bias [N] fp32 (may be null), C [M,N] bf16.  M % 256 == 0, N % 128 == 0,
- * K % 64 == 0. */
+ * K % 128 == 0. */
 epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M,
                             int32_t N, int32_t K, int32_t iters, float* ms_per_launch,
                             void* hip_stream);

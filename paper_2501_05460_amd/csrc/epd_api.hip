@@ -114,8 +114,8 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->dtype == EPD_DTYPE_BF16) {
     if (x.N % 64) { set_err(err, len, "bf16 mode needs patches per slice %% 64 == 0, got %d", x.N); return EPD_ERR_UNSUPPORTED; }
     if (x.hd > 128) { set_err(err, len, "bf16 mode supports head dim <= 128, got %d", x.hd); return EPD_ERR_UNSUPPORTED; }
-    if (x.D % 4 || x.F % 4 || x.Pout % 4 || (d->proj_kind == EPD_PROJ_MLP && x.Pmid % 4) || x.hd % 4) {
-      set_err(err, len, "bf16 mode needs hidden, head dim, mlp and projector widths %% 4 == 0"); return EPD_ERR_UNSUPPORTED;
+    if (x.D % 4 || x.hd % 4 || x.F % 8 || x.Pout % 8 || (d->proj_kind == EPD_PROJ_MLP && x.Pmid % 8)) {
+      set_err(err, len, "bf16 mode needs hidden and head dim %% 4 == 0, mlp and projector widths %% 8 == 0"); return EPD_ERR_UNSUPPORTED;
     }
   }
   if (x.N > 16384) { set_err(err, len, "more than 16384 patches per slice is not supported"); return EPD_ERR_UNSUPPORTED; }
@@ -249,10 +249,10 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   if (bf) {
     c->hd_pad = x.hd <= 64 ? 64 : (x.hd <= 96 ? 96 : 128);
     c->Dq = x.H * c->hd_pad;
-    c->Dq_k = round_up(c->Dq, 64);
-    c->D_k = round_up(x.D, 64);
-    c->Kp_k = round_up(x.Kp, 64);
-    c->Pin_k = round_up(x.Pin, 64);
+    c->Dq_k = round_up(c->Dq, 128);
+    c->D_k = round_up(x.D, 128);
+    c->Kp_k = round_up(x.Kp, 128);
+    c->Pin_k = round_up(x.Pin, 128);
     HIP_TRY(c, bf16_gemm_init());
   }
   const PackMap heads{x.hd, c->hd_pad, x.H};
@@ -458,7 +458,8 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
     { ProfScope ps(c, 2, st);
       GemmParams p = gp(EPI_BIAS, Xn, c->D_k, w.qkv, M);
       p.C = QK; p.ldc = ld_qk;
-      HIP_TRY(c, bf16_gemm(p, st));
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 2, st);
       GemmParams pv = gp(EPI_VT, Xn, c->D_k, w.v, M);
       pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.N;
       HIP_TRY(c, bf16_gemm(pv, st)); }
@@ -640,7 +641,7 @@ epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst, int64_t rows, int64_t 
 
 epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M, int32_t N,
                             int32_t K, int32_t iters, float* ms_per_launch, void* hip_stream) {
-  if (!A || !W || !C || M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 128 || K % 64 || iters < 1) {
+  if (!A || !W || !C || M <= 0 || N <= 0 || K <= 0 || M % 256 || N % 128 || K % 128 || iters < 1) {
     set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16: bad argument");
     return EPD_ERR_INVALID_ARG;
   }

@@ -4,10 +4,12 @@
 //
 // Block tile 256 x BN x 64 (BN = 256 or 128), 8 waves of 64 lanes.  Both
 // operands are K-contiguous, staged through LDS as [row][64] bf16 with the
-// 16-byte chunks of a row XOR-swizzled by (row & 7) so that the 32 rows a
-// wave reads for one MFMA operand fall into different banks.  Global loads of
-// k-slab kt+1 are issued before the MFMAs of slab kt and written to the other
-// LDS buffer after them: one barrier per slab.
+// 16-byte chunks of a row XOR-swizzled by the row so that the 32 rows a
+// wave reads for one MFMA operand fall into different banks (64 banks, 16
+// lanes per 128-bit access phase: rows r and r+1 share a chunk column, so the
+// XOR key is (row >> 1) & 7).  Global loads run two slabs ahead in registers
+// (L2 / Infinity-Cache latency is longer than one slab of MFMA work), the
+// slab in between moves to the other LDS buffer: one barrier per slab.
 //
 // v_mfma_f32_32x32x16_bf16 operand layout (checked on the device by
 // mfma_probe): lane l supplies row (l % 32) of the 32 x 16 left operand /
@@ -18,6 +20,8 @@
 // 16-byte fp32 accesses in the epilogue.  For the attention values (EPI_VT)
 // the roles are swapped, so a lane owns four consecutive tokens of one
 // feature, which is what the transposed value layout wants.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace epd {
@@ -27,6 +31,12 @@ namespace {
 constexpr int BM = 256;
 constexpr int BK = 64;
 constexpr int NTHREADS = 512;
+
+#ifndef EPD_SWZ_SHIFT
+#define EPD_SWZ_SHIFT 1
+#endif
+// XOR swizzle of the 16-byte chunk index by the row
+#define SWZ(row) (((row) >> EPD_SWZ_SHIFT) & 7)
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -49,9 +59,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a
   // contiguous run of output tiles (N fastest) so its L2 sees whole panels.
   const int gn = p.Npad / BN;
-  const int nb = gridDim.x;
   int id = blockIdx.x;
   {
+    const int nb = gridDim.x;
     const int x = id & 7, slot = id >> 3;
     const int q = nb >> 3, r = nb & 7;
     id = x * q + (x < r ? x : r) + slot;
@@ -63,53 +73,44 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int l32 = lane & 31, lh = lane >> 5;
 
+  const int KT_ = p.K / BK;  // even (K % 128 == 0)
   const int ld_row = tid >> 3, ld_c = tid & 7;
-  const int st_off = ld_row * BK + ((ld_c ^ (ld_row & 7)) * 8);
+  const int st_off = ld_row * BK + ((ld_c ^ SWZ(ld_row)) * 8);
+
   const bf16_t* gA = p.A + (long)(m0 + ld_row) * p.lda + ld_c * 8;
   const bf16_t* gB = p.W + (long)(n0 + ld_row) * p.K + ld_c * 8;
 
-  u32x4 ra[A_LD], rb[B_LD];
-  auto gload = [&](int kt) {
+  // Two register sets: the loads of slab k+2 are in flight while slab k is
+  // multiplied and slab k+1 (loaded one iteration earlier) moves to LDS.
+  u32x4 ra[2][A_LD], rb[2][B_LD];
+  auto gload = [&](auto set, int kt) {
+    constexpr int S = decltype(set)::value;
+    kt = kt < KT_ ? kt : KT_ - 1;  // past the end: re-read the last slab, result unused
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      ra[i] = *reinterpret_cast<const u32x4*>(gA + (long)(64 * i) * p.lda + kt * BK);
+      ra[S][i] = *reinterpret_cast<const u32x4*>(gA + (long)(64 * i) * p.lda + kt * BK);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      rb[i] = *reinterpret_cast<const u32x4*>(gB + (long)(64 * i) * p.K + kt * BK);
+      rb[S][i] = *reinterpret_cast<const u32x4*>(gB + (long)(64 * i) * p.K + kt * BK);
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](auto set, int buf) {
+    constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + 64 * i * BK + st_off) = ra[i];
+      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + 64 * i * BK + st_off) = ra[S][i];
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + 64 * i * BK + st_off) = rb[i];
+      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + 64 * i * BK + st_off) = rb[S][i];
   };
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // attention values: token-major MFMA result, stored transposed
   constexpr bool tok_major = (EPI == EPI_VT);
 
-  const int KT = p.K / BK;
-  gload(0);
-  sstore(0);
-  __syncthreads();
-
-  const int frag_sw = l32 & 7;
-  for (int kt = 0; kt < KT; ++kt) {
-    // always issue the next slab's loads (the last iteration re-reads the
-    // final slab into the idle buffer): keeps the staging registers free of
-    // control flow
-    gload(kt + 1 < KT ? kt + 1 : kt);
-    const bf16_t* a_s = sA + (kt & 1) * BM * BK + (wm * WM + l32) * BK;
-    const bf16_t* b_s = sB + (kt & 1) * BN * BK + (wn * 64 + l32) * BK;
+  f32x16 acc[TM][TN];
+  const int frag_sw = SWZ(l32);
+  auto compute = [&](int buf) {
+    const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
+    const bf16_t* b_s = sB + buf * BN * BK + (wn * 64 + l32) * BK;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
@@ -130,69 +131,134 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
           for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(wf[j], xf[i], acc[i][j]);
       }
     }
-    sstore((kt + 1) & 1);
+  };
+
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  gload(S0{}, 0);
+  gload(S1{}, 1);
+  sstore(S0{}, 0);
+  __syncthreads();
+  for (int kt = 0; kt < KT_; kt += 2) {
+    gload(S0{}, kt + 2);
+    compute(0);
+    sstore(S1{}, 1);
+    __syncthreads();
+    gload(S1{}, kt + 3);
+    compute(1);
+    sstore(S0{}, 0);
     __syncthreads();
   }
 
   // ------------------------------------------------------------ epilogue ----
-  if (tok_major) {
-    // lane = feature, register group = 4 consecutive tokens
+  // The accumulators go through LDS (the operand buffers are idle now) so
+  // that global memory sees whole 16-byte chunks of consecutive rows: a lane
+  // owns one staging row (l32) and four consecutive columns per register
+  // group; chunk c of staging row r sits at physical chunk c ^ (r & 15), which
+  // spreads the 16 rows of an access phase over all banks.
+  __syncthreads();  // every wave is done reading the operand buffers
+  unsigned char* stage = smem;
+
+  if (EPI == EPI_BIAS_RESIDUAL || EPI == EPI_BIAS_POS) {
+    // fp32 staging, 128 token rows per pass: [128][BN] floats
+    constexpr int ROWB = BN * 4;          // bytes per staging row
+    constexpr int NCH = ROWB / 16;        // 16-byte chunks per row
+    constexpr int PASSES = BM / 128;
+    constexpr int PER_T = 128 * NCH / NTHREADS;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int c = n0 + wn * 64 + j * 32 + l32;
-      const int fv = c;
-      if (fv >= p.N) continue;
-      const float bv = p.bias[c];
-      const int h = fv / p.hd_pad, d = fv % p.hd_pad;
+    for (int pass = 0; pass < PASSES; ++pass) {
+      if (pass > 0) __syncthreads();
+      if ((wm * WM) / 128 == pass) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
+        for (int i = 0; i < TM; ++i) {
+          const int r = (wm * WM) % 128 + i * 32 + l32;
 #pragma unroll
-        for (int gi = 0; gi < 4; ++gi) {
-          const int r0 = m0 + wm * WM + i * 32 + gi * 8 + lh * 4;
-          if (r0 >= p.M) continue;
-          const int t = r0 / p.n_tok, n = r0 % p.n_tok;
-          bf16x4 o;
+          for (int j = 0; j < TN; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(acc[i][j][gi * 4 + e] + bv);
-          *reinterpret_cast<bf16x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = o;
+            for (int gi = 0; gi < 4; ++gi) {
+              const int cl = wn * 64 + j * 32 + gi * 8 + lh * 4;  // column inside the tile
+              const float4 b4 = *reinterpret_cast<const float4*>(p.bias + n0 + cl);
+              f32x4 v = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
+                         acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
+              *reinterpret_cast<f32x4*>(stage + r * ROWB + (((cl >> 2) ^ (r & 15)) << 4)) = v;
+            }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < PER_T; ++i) {
+        const int q = tid + NTHREADS * i;
+        const int r = q / NCH, c = q % NCH;
+        const int row = m0 + pass * 128 + r, col = n0 + c * 4;
+        if (row < p.M && col < p.N) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
+          f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + col);
+          if (EPI == EPI_BIAS_RESIDUAL) {
+            *dst = *dst + v;
+          } else {
+            *dst = v + *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + col);
+          }
         }
       }
     }
-    return;
-  }
-
-  // lane = token, register group = 4 consecutive features
+  } else {
+  // bf16 staging of the whole tile: rows = MFMA lane dimension
+  constexpr int SROWS = tok_major ? BN : BM;   // staging rows
+  constexpr int SCOLS = tok_major ? BM : BN;   // staging columns
+  constexpr int ROWB = SCOLS * 2;
+  constexpr int NCH = ROWB / 16;
+  constexpr int PER_T = SROWS * NCH / NTHREADS;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int r = m0 + wm * WM + i * 32 + l32;
-    if (r >= p.M) continue;
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
+      // lane dimension: feature (tok_major) or token; register dimension: the other one
+      const int r = tok_major ? (wn * 64 + j * 32 + l32) : (wm * WM + i * 32 + l32);
+      float bl = 0.f;
+      if (tok_major) bl = p.bias[n0 + r];
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi) {
-        const int c0 = n0 + wn * 64 + j * 32 + gi * 8 + lh * 4;
-        if (c0 >= p.N) continue;
-        const float4 b4 = *reinterpret_cast<const float4*>(p.bias + c0);
-        float v[4] = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
-                      acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
-        if (EPI == EPI_BIAS_RESIDUAL) {
-          float4* dst = reinterpret_cast<float4*>(p.R + (long)r * p.ldr + c0);
-          float4 x = *dst;
-          x.x += v[0]; x.y += v[1]; x.z += v[2]; x.w += v[3];
-          *dst = x;
-        } else if (EPI == EPI_BIAS_POS) {
-          const float4 ps = *reinterpret_cast<const float4*>(p.pos + (long)(r % p.n_pos) * p.N + c0);
-          float4 x = {v[0] + ps.x, v[1] + ps.y, v[2] + ps.z, v[3] + ps.w};
-          *reinterpret_cast<float4*>(p.R + (long)r * p.ldr + c0) = x;
-        } else {
-          bf16x4 o;
+        const int cl = (tok_major ? (wm * WM + i * 32) : (wn * 64 + j * 32)) + gi * 8 + lh * 4;
+        float v[4];
+        if (tok_major) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act<EPI>(v[e]);
-          *reinterpret_cast<bf16x4*>(p.C + (long)r * p.ldc + c0) = o;
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+        } else {
+          const float4 b4 = *reinterpret_cast<const float4*>(p.bias + n0 + cl);
+          v[0] = acc[i][j][gi * 4 + 0] + b4.x; v[1] = acc[i][j][gi * 4 + 1] + b4.y;
+          v[2] = acc[i][j][gi * 4 + 2] + b4.z; v[3] = acc[i][j][gi * 4 + 3] + b4.w;
         }
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act<EPI>(v[e]);
+        *reinterpret_cast<bf16x4*>(stage + r * ROWB + (((cl >> 3) ^ (r & 15)) << 4) + ((cl & 4) << 1)) = o;
       }
     }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < PER_T; ++i) {
+    const int q = tid + NTHREADS * i;
+    const int r = q / NCH, c = q % NCH;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
+    if (tok_major) {
+      const int f = n0 + r, tok = m0 + c * 8;
+      if (f < p.N && tok < p.M) {
+        const int h = f / p.hd_pad, d = f % p.hd_pad;
+        const int t = tok / p.n_tok, n = tok % p.n_tok;
+        *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v;
+      }
+    } else {
+      const int row = m0 + r, col = n0 + c * 8;
+      if (row < p.M && col < p.N) *reinterpret_cast<u32x4*>(p.C + (long)row * p.ldc + col) = v;
+    }
   }
+  }  // staging kind
 }
 
 template <int BN>
@@ -201,8 +267,9 @@ constexpr size_t smem_bytes() { return (size_t)2 * (BM + BN) * BK * sizeof(bf16_
 template <int BN, int EPI>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
-  if (gm == 0 || gn == 0) return hipSuccess;
-  k_gemm_bf16<BN, EPI><<<dim3(gm * gn), dim3(NTHREADS), smem_bytes<BN>(), st>>>(p);
+  const int n_tiles = gm * gn;
+  if (n_tiles == 0) return hipSuccess;
+  k_gemm_bf16<BN, EPI><<<dim3(n_tiles), dim3(NTHREADS), smem_bytes<BN>(), st>>>(p);
   return hipGetLastError();
 }
 
@@ -245,7 +312,9 @@ hipError_t bf16_gemm_init() {
 }
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
-  if (p.K % BK != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+  if (p.K % (2 * BK) != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+  const bool f32_out = p.epi == EPI_BIAS_RESIDUAL || p.epi == EPI_BIAS_POS;
+  if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
   return (p.Npad % 256 == 0) ? dispatch<256>(p, st) : dispatch<128>(p, st);
 }
 

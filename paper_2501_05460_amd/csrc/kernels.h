@@ -18,7 +18,7 @@ void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t s
 // ---- bf16 mode -------------------------------------------------------------
 // GEMM  C[M,N] = A[M,K] * W[N,K]^T with fused epilogue (gemm_bf16.hip).
 // A must be readable for round_up(M,256) rows, W for Npad rows (zero rows
-// beyond N); K % 64 == 0; N % 4 == 0; Npad % 128 == 0.
+// beyond N); K % 128 == 0; N % 4 == 0 (N % 8 == 0 for bf16 outputs); Npad % 128 == 0.
 struct GemmParams {
   int epi;
   const bf16_t* A; long lda;

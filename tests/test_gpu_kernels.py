@@ -28,7 +28,7 @@ def test_mfma_lane_layout():
     np.testing.assert_allclose(d.cpu().numpy(), want, rtol=1e-5, atol=1e-5)
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 128, 64), (512, 256, 128), (768, 384, 320), (256, 1152, 1152),
+@pytest.mark.parametrize("M,N,K", [(256, 128, 128), (512, 256, 256), (768, 384, 384), (256, 1152, 1152), (2560, 640, 640),
                                    (1024, 4352, 1152), (2048, 1024, 4096)])
 def test_gemm_bf16_vs_oracle_linear(M, N, K):
     rng = np.random.default_rng(M + N + K)
