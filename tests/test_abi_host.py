@@ -1,0 +1,95 @@
+"""Host-only checks of the C boundary: the library loads without a GPU,
+exports every symbol the header declares, and its argument validation
+returns the documented codes without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import workloads as wl
+from paper_2501_05460_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="library not built")
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "epd_encode.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(epd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = header_functions()
+    assert "epd_encode" in names and "epd_encode_range" in names and "epd_create" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_weight_count_matches_generator_order():
+    for name in wl.ALL_WORKLOADS:
+        d = wl.workload(name).desc
+        assert B.weight_count(d) == len(wl.weight_specs(d))
+    d = wl.workload("c4").desc
+    assert B.weight_count(d.replace(qk_norm=wl.QKNORM_PER_HEAD, final_norm=1)) == \
+        len(wl.weight_specs(d.replace(qk_norm=wl.QKNORM_PER_HEAD, final_norm=1)))
+
+
+def test_check_desc_accepts_the_five_configs():
+    for name in wl.ALL_WORKLOADS:
+        s, msg = B.check_desc(wl.workload(name).desc)
+        assert s == B.EPD_OK, (name, msg)
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(dtype=7), B.EPD_ERR_INVALID_ARG),
+    (dict(norm=2), B.EPD_ERR_INVALID_ARG),
+    (dict(act=-1), B.EPD_ERR_INVALID_ARG),
+    (dict(heads=7), B.EPD_ERR_SHAPE),               # 1024 % 7 != 0
+    (dict(tile_size=450), B.EPD_ERR_SHAPE),         # not a multiple of the patch
+    (dict(hidden=0), B.EPD_ERR_SHAPE),
+    (dict(max_tiles_per_call=0), B.EPD_ERR_SHAPE),
+    (dict(tile_size=14 * 15), B.EPD_ERR_SHAPE),     # odd grid with pixel shuffle
+    (dict(tile_size=14 * 6, pixel_shuffle=0, proj_prenorm=0), B.EPD_ERR_UNSUPPORTED),  # 36 patches, bf16
+    (dict(heads=4), B.EPD_ERR_UNSUPPORTED),         # head dim 256 in bf16 mode
+    (dict(proj_out=4100), B.EPD_ERR_UNSUPPORTED),   # not a multiple of 8 in bf16 mode
+])
+def test_check_desc_rejects(change, status):
+    d = wl.workload("c3").desc.replace(**change)
+    s, msg = B.check_desc(d)
+    assert s == status, msg
+    assert msg
+    assert B.weight_count(d) == status
+
+
+def test_check_offsets():
+    assert B.check_offsets([0, 13, 26], 2, 26) == B.EPD_OK
+    assert B.check_offsets([0, 3, 3, 9], 3, 9) == B.EPD_OK          # empty request is legal
+    assert B.check_offsets([0], 0, 0) == B.EPD_OK
+    assert B.check_offsets([1, 3], 1, 3) == B.EPD_ERR_OFFSETS       # must start at 0
+    assert B.check_offsets([0, 5, 4], 2, 4) == B.EPD_ERR_OFFSETS    # decreasing
+    assert B.check_offsets([0, 5], 1, 6) == B.EPD_ERR_OFFSETS       # does not cover the batch
+    assert B.check_offsets(None, 1, 1) == B.EPD_ERR_INVALID_ARG
+    assert B.check_offsets([0, 1], -1, 1) == B.EPD_ERR_OFFSETS
+
+
+def test_create_rejects_bad_arguments_before_touching_a_device():
+    lib = B.lib()
+    d = B.desc_to_c(wl.workload("c1").desc)
+    handle = ctypes.c_void_p(1234)
+    assert lib.epd_create(ctypes.byref(d), None, None, ctypes.byref(handle)) == B.EPD_ERR_INVALID_ARG
+    assert handle.value is None
+    w = B.WeightsC(None, 3)
+    assert lib.epd_create(ctypes.byref(d), ctypes.byref(w), None, ctypes.byref(handle)) == B.EPD_ERR_INVALID_ARG
+    ptrs = (ctypes.c_void_p * 3)(16, 32, 48)
+    w = B.WeightsC(ctypes.cast(ptrs, ctypes.POINTER(ctypes.c_void_p)), 3)       # wrong tensor count
+    assert lib.epd_create(ctypes.byref(d), ctypes.byref(w), None, ctypes.byref(handle)) == B.EPD_ERR_INVALID_ARG
+    assert b"expected" in lib.epd_last_error(None)
+    assert lib.epd_create(ctypes.byref(d), ctypes.byref(w), None, None) == B.EPD_ERR_INVALID_ARG
+    assert lib.epd_encode(None, None, 0, None, 0, None, None) == B.EPD_ERR_INVALID_ARG
+    assert lib.epd_tokens_per_tile(None) == -1
+    lib.epd_destroy(None)   # no-op

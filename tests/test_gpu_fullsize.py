@@ -1,0 +1,99 @@
+"""Parity at the full sizes of the five configurations, in the launch
+configuration bench.py times: the whole batch runs on the GPU, the oracle
+encodes a fixed sample of slices at full depth, and the sampled row blocks
+are compared element by element."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import epd_oracle as O
+from paper_2501_05460_amd import binding as B
+from gpu_util import rel_err, rel_l2, tol
+
+pytestmark = pytest.mark.gpu
+
+
+def build(wk, desc=None):
+    desc = desc or wk.desc
+    bf = desc.dtype == wl.DT_BF16
+    dev = [B.to_device(wl.gen_weight(desc, wk.weight_seed, i), bf) for i in range(len(wl.weight_specs(desc)))]
+    enc = B.Encoder(desc, dev)
+    del dev
+    S = desc.tile_size
+    tiles = torch.empty((wk.n_tiles, 3, S, S), dtype=torch.float32, device="cuda")
+    for t in range(wk.n_tiles):
+        tiles[t] = torch.from_numpy(wl.gen_tile(desc, wk.input_seed, t))
+    return enc, tiles
+
+
+def check_sample(wk, enc, out, sample, desc=None):
+    desc = desc or wk.desc
+    w = wl.gen_weights(desc, wk.weight_seed)
+    n = enc.tokens_per_tile
+    worst = 0.0
+    for t in sample:
+        t0 = time.time()
+        want = O.encode_tile(wl.gen_tile(desc, wk.input_seed, t), w, desc)
+        got = out[t * n:(t + 1) * n].float().cpu().numpy()
+        e = rel_err(got, want)
+        print(f"{wk.name} slice {t}: max_rel_err={e:.3e} rel_l2={rel_l2(got, want):.3e} oracle {time.time() - t0:.1f}s",
+              flush=True)
+        worst = max(worst, e)
+    assert worst < tol(desc)
+
+
+def test_c2_siglip_shape_10_slices():
+    wk = wl.workload("c2")
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (10 * 1024, 3584)
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    enc.close()
+
+
+def test_c3_internvit300m_shape_104_slices():
+    wk = wl.workload("c3")
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (104 * 256, 4096)
+    assert bool(torch.isfinite(out.float()).all())
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    enc.close()
+
+
+def test_c5_mixed_batch_sharded_equals_one_call_and_oracle():
+    wk = wl.workload("c5")
+    enc, tiles = build(wk)
+    off = list(wk.tile_offsets)
+    n = enc.tokens_per_tile
+    full = enc.encode(tiles, off)
+    torch.cuda.synchronize()
+    assert full.shape[0] == wk.n_tiles * n
+    # 4 shards per request, each its own call, rows landing at their final place
+    out = enc.alloc_out(wk.n_tiles)
+    out.fill_(-3.0)
+    for s in range(4):
+        for r in range(wk.n_requests):
+            b, e = wl.shard_range(off[r + 1] - off[r], s, 4)
+            enc.encode_range(tiles, off[r] + b, off[r] + e, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), full.view(torch.int16))
+    del out
+    check_sample(wk, enc, full, wk.oracle_sample_tiles[:3])
+    enc.close()
+
+
+def test_c4_internvit6b_shape_40_slices():
+    wk = wl.workload("c4")
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (40 * 256, 5120)
+    assert bool(torch.isfinite(out.float()).all())
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    enc.close()

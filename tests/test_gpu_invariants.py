@@ -1,0 +1,126 @@
+"""Properties of the HIP path that hold at any size: slices are encoded
+independently (Section 3.2.2), so permuting slices permutes row blocks, one
+slice's pixels touch no other slice's rows, any grouping into calls, shards or
+micro-batches gives the same bits, and runs repeat bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from paper_2501_05460_amd import binding as B
+from gpu_util import make_encoder
+
+pytestmark = pytest.mark.gpu
+
+
+def desc_for(dtype, **kw):
+    base = dict(dtype=dtype, tile_size=224, patch=14, hidden=192, heads=3, mlp=384, layers=2,
+                norm=wl.NORM_LAYERNORM, qk_norm=wl.QKNORM_NONE, act=wl.ACT_GELU_ERF, final_norm=0,
+                pixel_shuffle=1, proj_kind=wl.PROJ_MLP, proj_prenorm=1, proj_mid=256, proj_out=128,
+                eps=1e-6, max_tiles_per_call=8)
+    base.update(kw)
+    return wl.ModelDesc(**base)
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy()
+
+
+@pytest.fixture(scope="module", params=[wl.DT_BF16, wl.DT_FP32], ids=["bf16", "fp32"])
+def setup(request):
+    desc = desc_for(request.param)
+    w = wl.gen_weights(desc, 31, std=0.06)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 31, 7)).cuda()
+    enc = make_encoder(desc, w)
+    full = enc.encode(tiles, [0, 7])
+    torch.cuda.synchronize()
+    yield desc, w, tiles, enc, full
+    enc.close()
+
+
+def test_runs_repeat_bit_for_bit(setup):
+    desc, w, tiles, enc, full = setup
+    again = enc.encode(tiles, [0, 3, 3, 7])      # request structure does not change the rows
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(again), bits(full))
+
+
+def test_permuting_slices_permutes_row_blocks(setup):
+    desc, w, tiles, enc, full = setup
+    perm = [4, 0, 6, 2, 1, 5, 3]
+    out = enc.encode(tiles[perm].contiguous(), [0, 7])
+    torch.cuda.synchronize()
+    n = enc.tokens_per_tile
+    a, b = bits(out), bits(full)
+    for i, src in enumerate(perm):
+        assert np.array_equal(a[i * n:(i + 1) * n], b[src * n:(src + 1) * n])
+
+
+def test_one_slice_does_not_leak_into_another(setup):
+    desc, w, tiles, enc, full = setup
+    t2 = tiles.clone()
+    t2[3] = t2[3] * 0.5 + 0.1
+    out = enc.encode(t2, [0, 7])
+    torch.cuda.synchronize()
+    n = enc.tokens_per_tile
+    a, b = bits(out), bits(full)
+    for t in range(7):
+        same = np.array_equal(a[t * n:(t + 1) * n], b[t * n:(t + 1) * n])
+        assert same == (t != 3), t
+    alone = enc.encode(tiles[5:6].contiguous(), [0, 1])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(alone), b[5 * n:6 * n])
+
+
+def test_shards_write_only_their_rows_and_union_equals_one_call(setup):
+    desc, w, tiles, enc, full = setup
+    offsets = [0, 3, 3, 7]                       # requests of 3, 0 and 4 slices
+    n = enc.tokens_per_tile
+    out = enc.alloc_out(7)
+    sentinel = 12345.0
+    out.fill_(sentinel)
+    covered = np.zeros(7, int)
+    for s in range(4):
+        for r in range(3):
+            cnt = offsets[r + 1] - offsets[r]
+            b, e = wl.shard_range(cnt, s, 4)
+            before = bits(out).copy()
+            enc.encode_range(tiles, offsets[r] + b, offsets[r] + e, out)
+            torch.cuda.synchronize()
+            changed = np.any(bits(out) != before, axis=1).reshape(7, n).any(axis=1)
+            assert set(np.nonzero(changed)[0]) <= set(range(offsets[r] + b, offsets[r] + e))
+            covered[offsets[r] + b:offsets[r] + e] += 1
+    assert np.all(covered == 1)
+    assert np.array_equal(bits(out), bits(full))
+
+
+def test_micro_batch_size_does_not_change_the_bits(setup):
+    desc, w, tiles, enc, full = setup
+    for mb in (1, 2, 3):
+        enc2 = make_encoder(desc.replace(max_tiles_per_call=mb), w)
+        out = enc2.encode(tiles, [0, 7])
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(out), bits(full)), mb
+        enc2.close()
+
+
+def test_empty_batch_and_error_paths_leave_the_cache_untouched(setup):
+    desc, w, tiles, enc, full = setup
+    out = enc.alloc_out(7)
+    out.fill_(7.0)
+    before = bits(out).copy()
+    lib = B.lib()
+    import ctypes
+    off0 = (ctypes.c_int32 * 1)(0)
+    assert lib.epd_encode(enc._h, None, 0, off0, 0, None, None) == B.EPD_OK      # empty batch: no-op
+    bad = (ctypes.c_int32 * 2)(0, 6)
+    st = torch.cuda.current_stream().cuda_stream
+    assert lib.epd_encode(enc._h, tiles.data_ptr(), 7, bad, 1, out.data_ptr(), st) == B.EPD_ERR_OFFSETS
+    assert b"tile_offsets" in lib.epd_last_error(enc._h)
+    assert lib.epd_encode_range(enc._h, tiles.data_ptr(), 7, 5, 9, out.data_ptr(), st) == B.EPD_ERR_OFFSETS
+    assert lib.epd_encode_range(enc._h, tiles.data_ptr(), 7, 4, 2, out.data_ptr(), st) == B.EPD_ERR_OFFSETS
+    assert lib.epd_encode_range(enc._h, tiles.data_ptr(), 7, 2, 2, out.data_ptr(), st) == B.EPD_OK  # empty shard
+    assert lib.epd_encode_range(enc._h, tiles.data_ptr() + 4, 7, 0, 1, out.data_ptr(), st) == B.EPD_ERR_INVALID_ARG
+    assert lib.epd_encode_range(enc._h, None, 7, 0, 1, out.data_ptr(), st) == B.EPD_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out), before)
