@@ -30,7 +30,6 @@ namespace {
 
 constexpr int BM = 256;
 constexpr int BK = 64;
-constexpr int NTHREADS = 512;
 
 #ifndef EPD_SWZ_SHIFT
 #define EPD_SWZ_SHIFT 1
@@ -42,19 +41,40 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int BN, int EPI>
-__global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
-  constexpr int WAVES_N = BN / 64;      // 4 | 2
-  constexpr int WAVES_M = 8 / WAVES_N;  // 2 | 4
-  constexpr int WM = BM / WAVES_M;      // 128 | 64
-  constexpr int TM = WM / 32;           // 4 | 2
-  constexpr int TN = 2;
-  constexpr int A_LD = BM * 8 / NTHREADS;  // 16-byte chunks per thread per slab
+// Configurations (BN, NTHREADS[, WN = 64]):
+//   (256, 512)  256x256 tile, 8 waves, one workgroup per CU, two LDS buffers,
+//               loads two slabs ahead in two register sets;
+//   (128, 512)  256x128 tile, 8 waves (64x64 per wave), same pipeline;
+//   (128, 256)  256x128 tile, 4 waves (128x64 per wave), TWO workgroups per CU:
+//               one LDS buffer and one register set each;
+//   (256, 256, WN = 128)  256x256 tile, 4 waves of 128x128: one wave per SIMD
+//               with the 256 accumulators in AGPRs; a third less LDS read
+//               traffic per MFMA than the 128x64 wave tiles.
+template <int BN, int NT>
+constexpr size_t smem_main_bytes() {
+  // operand slabs, or the epilogue staging tile (256 x BN bf16 / 128 x BN fp32), whichever is larger
+  constexpr size_t operands = (size_t)((NT == 256 && BN == 128) ? 1 : 2) * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t staging = (size_t)BM * BN * sizeof(bf16_t);
+  return operands > staging ? operands : staging;
+}
+
+template <int BN, int NTHREADS, int WN, int EPI>
+__global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) void k_gemm_bf16(const GemmParams p) {
+  constexpr int NWAVES = NTHREADS / 64;
+  constexpr int WAVES_N = BN / WN;           // 4 | 2
+  constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
+  constexpr int WM = BM / WAVES_M;           // 128 | 64 | 128
+  constexpr int TM = WM / 32;                // 4 | 2 | 4
+  constexpr int TN = WN / 32;                // 2 | 4
+  constexpr int A_LD = BM * 8 / NTHREADS;    // 16-byte chunks per thread per slab
   constexpr int B_LD = BN * 8 / NTHREADS;
+  constexpr int NBUF = (NTHREADS == 256 && WN == 64) ? 1 : 2;  // LDS slab buffers = register sets
+  constexpr int ROWS_PER_LD = NTHREADS / 8;      // rows covered by one 16-byte load per thread
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);  // [2][BM][64]
-  bf16_t* sB = sA + 2 * BM * BK;                 // [2][BN][64]
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);  // [NBUF][BM][64]
+  bf16_t* sB = sA + NBUF * BM * BK;              // [NBUF][BN][64]
+  float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());  // [BN]
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a
   // contiguous run of output tiles (N fastest) so its L2 sees whole panels.
@@ -71,9 +91,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  (void)NWAVES;
   const int l32 = lane & 31, lh = lane >> 5;
 
   const int KT_ = p.K / BK;  // even (K % 128 == 0)
+  // the tile's bias values wait in LDS for the epilogue (a global load there
+  // would sit exposed between the last MFMA and the first store)
+  if (tid < BN) sBias[tid] = p.bias[n0 + tid];
   const int ld_row = tid >> 3, ld_c = tid & 7;
   const int st_off = ld_row * BK + ((ld_c ^ SWZ(ld_row)) * 8);
 
@@ -82,25 +106,25 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 
   // Two register sets: the loads of slab k+2 are in flight while slab k is
   // multiplied and slab k+1 (loaded one iteration earlier) moves to LDS.
-  u32x4 ra[2][A_LD], rb[2][B_LD];
+  u32x4 ra[NBUF][A_LD], rb[NBUF][B_LD];
   auto gload = [&](auto set, int kt) {
     constexpr int S = decltype(set)::value;
     kt = kt < KT_ ? kt : KT_ - 1;  // past the end: re-read the last slab, result unused
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      ra[S][i] = *reinterpret_cast<const u32x4*>(gA + (long)(64 * i) * p.lda + kt * BK);
+      ra[S][i] = *reinterpret_cast<const u32x4*>(gA + (long)(ROWS_PER_LD * i) * p.lda + kt * BK);
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      rb[S][i] = *reinterpret_cast<const u32x4*>(gB + (long)(64 * i) * p.K + kt * BK);
+      rb[S][i] = *reinterpret_cast<const u32x4*>(gB + (long)(ROWS_PER_LD * i) * p.K + kt * BK);
   };
   auto sstore = [&](auto set, int buf) {
     constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
-      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + 64 * i * BK + st_off) = ra[S][i];
+      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + ROWS_PER_LD * i * BK + st_off) = ra[S][i];
 #pragma unroll
     for (int i = 0; i < B_LD; ++i)
-      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + 64 * i * BK + st_off) = rb[S][i];
+      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + ROWS_PER_LD * i * BK + st_off) = rb[S][i];
   };
 
   // attention values: token-major MFMA result, stored transposed
@@ -110,7 +134,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
   const int frag_sw = SWZ(l32);
   auto compute = [&](int buf) {
     const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
-    const bf16_t* b_s = sB + buf * BN * BK + (wn * 64 + l32) * BK;
+    const bf16_t* b_s = sB + buf * BN * BK + (wn * WN + l32) * BK;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
@@ -141,19 +165,32 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  gload(S0{}, 0);
-  gload(S1{}, 1);
-  sstore(S0{}, 0);
-  __syncthreads();
-  for (int kt = 0; kt < KT_; kt += 2) {
-    gload(S0{}, kt + 2);
-    compute(0);
-    sstore(S1{}, 1);
-    __syncthreads();
-    gload(S1{}, kt + 3);
-    compute(1);
+  if constexpr (NBUF == 2) {
+    gload(S0{}, 0);
+    gload(S1{}, 1);
     sstore(S0{}, 0);
     __syncthreads();
+    for (int kt = 0; kt < KT_; kt += 2) {
+      gload(S0{}, kt + 2);
+      compute(0);
+      sstore(S1{}, 1);
+      __syncthreads();
+      gload(S1{}, kt + 3);
+      compute(1);
+      sstore(S0{}, 0);
+      __syncthreads();
+    }
+  } else {
+    gload(S0{}, 0);
+    sstore(S0{}, 0);
+    __syncthreads();
+    for (int kt = 0; kt < KT_; ++kt) {
+      gload(S0{}, kt + 1);
+      compute(0);
+      __syncthreads();   // every wave has read the slab
+      sstore(S0{}, 0);
+      __syncthreads();
+    }
   }
 
   // ------------------------------------------------------------ epilogue ----
@@ -182,8 +219,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
           for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int gi = 0; gi < 4; ++gi) {
-              const int cl = wn * 64 + j * 32 + gi * 8 + lh * 4;  // column inside the tile
-              const float4 b4 = *reinterpret_cast<const float4*>(p.bias + n0 + cl);
+              const int cl = wn * WN + j * 32 + gi * 8 + lh * 4;  // column inside the tile
+              const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
               f32x4 v = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
                          acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
               *reinterpret_cast<f32x4*>(stage + r * ROWB + (((cl >> 2) ^ (r & 15)) << 4)) = v;
@@ -219,24 +256,24 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       // lane dimension: feature (tok_major) or token; register dimension: the other one
-      const int r = tok_major ? (wn * 64 + j * 32 + l32) : (wm * WM + i * 32 + l32);
+      const int r = tok_major ? (wn * WN + j * 32 + l32) : (wm * WM + i * 32 + l32);
       float bl = 0.f;
-      if (tok_major) bl = p.bias[n0 + r];
+      if (tok_major) bl = sBias[r];
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi) {
-        const int cl = (tok_major ? (wm * WM + i * 32) : (wn * 64 + j * 32)) + gi * 8 + lh * 4;
+        const int cl = (tok_major ? (wm * WM + i * 32) : (wn * WN + j * 32)) + gi * 8 + lh * 4;
         float v[4];
         if (tok_major) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
         } else {
-          const float4 b4 = *reinterpret_cast<const float4*>(p.bias + n0 + cl);
+          const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
           v[0] = acc[i][j][gi * 4 + 0] + b4.x; v[1] = acc[i][j][gi * 4 + 1] + b4.y;
           v[2] = acc[i][j][gi * 4 + 2] + b4.z; v[3] = acc[i][j][gi * 4 + 3] + b4.w;
         }
         bf16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act<EPI>(v[e]);
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act_fast<EPI>(v[e]);
         *reinterpret_cast<bf16x4*>(stage + r * ROWB + (((cl >> 3) ^ (r & 15)) << 4) + ((cl & 4) << 1)) = o;
       }
     }
@@ -261,61 +298,68 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p) {
   }  // staging kind
 }
 
-template <int BN>
-constexpr size_t smem_bytes() { return (size_t)2 * (BM + BN) * BK * sizeof(bf16_t); }
+template <int BN, int NT>
+constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT>() + BN * sizeof(float); }
 
-template <int BN, int EPI>
+template <int BN, int NT, int WN, int EPI>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
   if (n_tiles == 0) return hipSuccess;
-  k_gemm_bf16<BN, EPI><<<dim3(n_tiles), dim3(NTHREADS), smem_bytes<BN>(), st>>>(p);
+  k_gemm_bf16<BN, NT, WN, EPI><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p);
   return hipGetLastError();
 }
 
-template <int BN>
+template <int BN, int NT, int WN>
 hipError_t dispatch(const GemmParams& p, hipStream_t st) {
   switch (p.epi) {
-    case EPI_BIAS: return launch<BN, EPI_BIAS>(p, st);
-    case EPI_BIAS_GELU_ERF: return launch<BN, EPI_BIAS_GELU_ERF>(p, st);
-    case EPI_BIAS_GELU_TANH: return launch<BN, EPI_BIAS_GELU_TANH>(p, st);
-    case EPI_BIAS_RESIDUAL: return launch<BN, EPI_BIAS_RESIDUAL>(p, st);
-    case EPI_BIAS_POS: return launch<BN, EPI_BIAS_POS>(p, st);
-    case EPI_VT: return launch<BN, EPI_VT>(p, st);
+    case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH>(p, st);
+    case EPI_BIAS_RESIDUAL: return launch<BN, NT, WN, EPI_BIAS_RESIDUAL>(p, st);
+    case EPI_BIAS_POS: return launch<BN, NT, WN, EPI_BIAS_POS>(p, st);
+    case EPI_VT: return launch<BN, NT, WN, EPI_VT>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
-template <int BN, int EPI>
+template <int BN, int NT, int WN, int EPI>
 hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, EPI>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN>());
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, NT>());
 }
 
-template <int BN>
+template <int BN, int NT, int WN>
 hipError_t set_attr_all() {
   hipError_t e;
-  if ((e = set_attr<BN, EPI_BIAS>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, EPI_BIAS_POS>()) != hipSuccess) return e;
-  return set_attr<BN, EPI_VT>();
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS>()) != hipSuccess) return e;
+  return set_attr<BN, NT, WN, EPI_VT>();
 }
 
 }  // namespace
 
 hipError_t bf16_gemm_init() {
-  hipError_t e = set_attr_all<256>();
+  hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
-  return set_attr_all<128>();
+  if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
+  if ((e = set_attr_all<128, 256, 64>()) != hipSuccess) return e;
+  return set_attr_all<256, 256, 128>();
 }
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (p.K % (2 * BK) != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
   const bool f32_out = p.epi == EPI_BIAS_RESIDUAL || p.epi == EPI_BIAS_POS;
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
-  return (p.Npad % 256 == 0) ? dispatch<256>(p, st) : dispatch<128>(p, st);
+  switch (p.cfg) {
+    case 1: return dispatch<128, 512, 64>(p, st);
+    case 2: return dispatch<128, 256, 64>(p, st);
+    case 4: if (p.Npad % 256 == 0) return dispatch<256, 256, 128>(p, st); break;
+  }
+  return p.Npad % 256 == 0 ? dispatch<256, 512, 64>(p, st) : dispatch<128, 512, 64>(p, st);
 }
 
 }  // namespace epd
