@@ -59,7 +59,7 @@ constexpr size_t smem_main_bytes() {
 }
 
 template <int BN, int NTHREADS, int WN, int EPI>
-__global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) void k_gemm_bf16(const GemmParams p) {
+__global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
   constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
@@ -76,8 +76,11 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   bf16_t* sB = sA + NBUF * BM * BK;              // [NBUF][BN][64]
   float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());  // [BN]
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a
-  // contiguous run of output tiles (N fastest) so its L2 sees whole panels.
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
+  // XCD x takes a contiguous run of the tile sequence, and the sequence walks
+  // a band of `gw` tile columns top to bottom before moving to the next
+  // band: the band's weight panel (gw * BN rows) stays L2-resident while the
+  // activation panels stream through once per band.
   const int gn = p.Npad / BN;
   int id = blockIdx.x;
   {
@@ -86,8 +89,10 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     const int q = nb >> 3, r = nb & 7;
     id = x * q + (x < r ? x : r) + slot;
   }
-  const int m0 = (id / gn) * BM;
-  const int n0 = (id % gn) * BN;
+  const int band_tiles = gm_ * gw;
+  const int band = id / band_tiles, in_band = id % band_tiles;
+  const int m0 = (in_band / gw) * BM;
+  const int n0 = (band * gw + in_band % gw) * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -165,7 +170,58 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  if constexpr (NBUF == 2) {
+  if constexpr (NTHREADS == 256 && WN == 128) {
+    // One wave per SIMD: nothing else hides a stall, so the operand
+    // fragments run one k-step ahead of the MFMAs in a second register set,
+    // and the slab hand-over (LDS stores of the next slab + barrier) sits in
+    // front of the LAST k-step, whose 16 MFMAs cover the first fragment reads
+    // from the other buffer.
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto ldfrag = [&](auto set, int buf, int kk) {
+      constexpr int S = decltype(set)::value;
+      const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
+      const bf16_t* b_s = sB + buf * BN * BK + (wn * WN + l32) * BK;
+      const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[S][i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * BK + coff);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[S][j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * BK + coff);
+    };
+    auto mma = [&](auto set) {
+      constexpr int S = decltype(set)::value;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = tok_major ? mfma32(fa[S][i], fb[S][j], acc[i][j]) : mfma32(fb[S][j], fa[S][i], acc[i][j]);
+    };
+    // scheduling hint: after every two MFMAs let one LDS read through
+    auto interleave = [&]() {
+#pragma unroll
+      for (int i = 0; i < TM + TN; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+      }
+    };
+    auto slab = [&](auto lset, auto sset, int buf, int kt) {
+      gload(lset, kt + 2);
+      ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
+      ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
+      ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
+      sstore(sset, buf ^ 1);
+      __syncthreads();
+      ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
+    };
+    gload(S0{}, 0);
+    gload(S1{}, 1);
+    sstore(S0{}, 0);
+    __syncthreads();
+    ldfrag(S0{}, 0, 0);
+    for (int kt = 0; kt < KT_; kt += 2) {
+      slab(S0{}, S1{}, 0, kt);
+      slab(S1{}, S0{}, 1, kt + 1);
+    }
+  } else if constexpr (NBUF == 2) {
     gload(S0{}, 0);
     gload(S1{}, 1);
     sstore(S0{}, 0);
@@ -306,7 +362,11 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
   if (n_tiles == 0) return hipSuccess;
-  k_gemm_bf16<BN, NT, WN, EPI><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p);
+  // band width: the widest divisor of gn whose weight panel fits half of one XCD's 4 MiB L2
+  int gw = gn;
+  while (gw > 1 && ((size_t)gw * BN * p.K * sizeof(bf16_t) > (2u << 20) || gn % gw != 0)) --gw;
+  if (p.band > 0 && gn % p.band == 0) gw = p.band;
+  k_gemm_bf16<BN, NT, WN, EPI><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
   return hipGetLastError();
 }
 

@@ -22,6 +22,7 @@ void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t s
 struct GemmParams {
   int epi;
   int cfg;                    // 0 default; 1: 256x128 / 8 waves; 2: 256x128 / 4 waves, 2 per CU; 3: 256x256 / 8 waves
+  int band;                   // 0: automatic; else tile columns per L2 band (must divide Npad / BN)
   const bf16_t* A; long lda;
   const bf16_t* W;            // packed [Npad, K]
   const float* bias;          // [Npad]
