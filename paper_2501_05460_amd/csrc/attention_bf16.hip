@@ -1,9 +1,11 @@
 // Tile-local flash attention for gfx950 (bf16 MFMA, fp32 online softmax).
 //
-// One workgroup = 128 queries of one (slice, head); 4 waves x 32 queries.
-// Keys and values of the same slice stream through LDS in blocks of 64 keys
-// (double buffered, one barrier per block).  Everything is computed
-// transposed so that a lane always owns ONE query:
+// One workgroup = 4 waves, each owning QT sub-tiles of 32 queries of one
+// (slice, head).  Keys and values of the same slice stream through LDS in
+// blocks of 64 keys (double buffered, one barrier per block); the online
+// softmax advances in steps of 32 keys, software-pipelined so that the S^T
+// MFMAs of step i+1 run under the exponentials of step i.  Everything is computed transposed so
+// that a lane always owns ONE query per sub-tile:
 //     S^T = K Q^T        (left operand: key rows from LDS, right: Q from registers)
 //     O^T += V^T P^T     (left operand: V^T rows from LDS, right: P^T from the S^T registers)
 // With the 32x32 MFMA result layout (register i of lane l = row
@@ -11,15 +13,17 @@
 // per-lane scalars plus one exchange with lane l^32, and the exponentiated
 // S^T registers are already a valid right operand for the second product:
 // registers 8j..8j+7 of a lane hold keys {16j + 4h + 0..3, 16j + 8 + 4h + 0..3}
-// (h = l/32); the V^T fragment is read from LDS in the same key order.
-// Values arrive pre-transposed ([slice, head, hd, token]) from the QKV GEMM.
+// (h = l/32).  The V^T block is stored in LDS with exactly that key order
+// inside every group of 16 keys (positions [0-3, 8-11, 4-7, 12-15]), so the
+// matching left operand is one 16-byte LDS read.  A K / V^T fragment read
+// from LDS feeds all QT sub-tiles of the wave.
+// Values arrive pre-transposed ([slice, head, hd, token]) from the value GEMM.
 #include "kernels.h"
 
 namespace epd {
 
 namespace {
 
-constexpr int BQ = 128;   // queries per workgroup
 constexpr int BKEY = 64;  // keys per LDS block
 
 template <int HD>
@@ -31,13 +35,14 @@ struct AttnSmem {
   static constexpr size_t BYTES = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
 };
 
-template <int HD>
-__global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict__ q,
+template <int HD, int QT>
+__global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
                                                         bf16_t* __restrict__ o, int n_tok, int heads,
                                                         long ld_qk, long ld_o, float scale_log2e) {
   using SM = AttnSmem<HD>;
+  constexpr int BQ = 128 * QT;  // queries per workgroup
   constexpr int KS = HD / 16;   // k-steps of the S^T product
   constexpr int MB = HD / 32;   // 32-row blocks of O^T
   constexpr int KCH = HD / 8;   // 16-byte chunks per key row
@@ -52,23 +57,24 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
   const int l32 = lane & 31, lh = lane >> 5;
   const int qb = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
   const long row0 = (long)t * n_tok;
-  const int q0 = qb * BQ + wave * 32;
-  const bool active = q0 < n_tok;   // n_tok is a multiple of 64, so a wave is all in or all out
+  const int q0 = qb * BQ + wave * 32 * QT;
+  // n_tok is a multiple of 64: a 32-query sub-tile is all in or all out
+  bool act[QT];
+  bool any_act = false;
+#pragma unroll
+  for (int u = 0; u < QT; ++u) { act[u] = q0 + u * 32 < n_tok; any_act = any_act || act[u]; }
 
   const bf16_t* kbase = k + row0 * ld_qk + (long)h * HD;
   const bf16_t* vbase = vt + ((long)t * heads + h) * HD * (long)n_tok;
 
   // Q fragments: lane = query, 8 consecutive head-dim elements per k-step
-  bf16x8 qf[KS];
-  if (active) {
-    const bf16_t* qp = q + (row0 + q0 + l32) * ld_qk + (long)h * HD + lh * 8;
+  bf16x8 qf[QT][KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
-  } else {
+  for (int u = 0; u < QT; ++u) {
+    const int qrow = act[u] ? q0 + u * 32 + l32 : 0;  // inactive sub-tiles read a valid row, result unused
+    const bf16_t* qp = q + (row0 + qrow) * ld_qk + (long)h * HD + lh * 8;
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[s][e] = (bf16_t)0.f;
+    for (int s = 0; s < KS; ++s) qf[u][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
   }
 
   u32x4 rk[K_LOADS], rv[V_LOADS];
@@ -97,116 +103,144 @@ __global__ __launch_bounds__(256) void k_attention_bf16(const bf16_t* __restrict
     for (int i = 0; i < V_LOADS; ++i) {
       const int c = tid + 256 * i;
       const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
-      *reinterpret_cast<u32x4*>(sV + buf * SM::V_ELEMS + row * SM::V_LD + ch * 8) = rv[i];
+      // chunk ch holds keys 8ch..8ch+7; inside a group of 16 keys the LDS order is
+      // [0-3, 8-11, 4-7, 12-15]: keys 8ch+0..3 -> position 16(ch/2) + 4(ch%2),
+      // keys 8ch+4..7 -> position 16(ch/2) + 8 + 4(ch%2)
+      bf16_t* dst = sV + buf * SM::V_ELEMS + row * SM::V_LD + (ch >> 1) * 16 + (ch & 1) * 4;
+      u32x2 lo = {rv[i][0], rv[i][1]}, hi = {rv[i][2], rv[i][3]};
+      *reinterpret_cast<u32x2*>(dst) = lo;
+      *reinterpret_cast<u32x2*>(dst + 8) = hi;
     }
   };
 
-  f32x16 oacc[MB];
+  f32x16 oacc[QT][MB];
+  float m_run[QT], l_run[QT];  // running max (log2 domain) and this lane's share of the running sum
 #pragma unroll
-  for (int b = 0; b < MB; ++b)
+  for (int u = 0; u < QT; ++u) {
+    m_run[u] = -INFINITY;
+    l_run[u] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
-  float m_run = -INFINITY;  // running max of the scaled logits (log2 domain)
-  float l_run = 0.f;        // this lane's share of the running sum
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[u][b][e] = 0.f;
+  }
+
+  // S^T of one 32-key step for all sub-tiles (MFMAs only: they run while the
+  // wave goes on with the softmax arithmetic of the previous step)
+  auto issue_s = [&](f32x16 (&s)[QT], const bf16_t* ks, int kt) {
+#pragma unroll
+    for (int u = 0; u < QT; ++u)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[u][e] = 0.f;
+#pragma unroll
+    for (int st = 0; st < KS; ++st) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * SM::K_LD + st * 16 + lh * 8);
+#pragma unroll
+      for (int u = 0; u < QT; ++u) s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][st], s[u], 0, 0, 0);
+    }
+  };
+  // online softmax of one step, one query per lane (shared with lane ^ 32)
+  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2]) {
+#pragma unroll
+    for (int u = 0; u < QT; ++u) {
+      float mx = fmaxf(s[u][0], s[u][1]);
+#pragma unroll
+      for (int e = 2; e < 16; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);  // three-input max
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[u], mx * scale_log2e);
+      // the running maximum rarely moves after the first blocks: rescale only then
+      if (__builtin_amdgcn_ballot_w64(m_new > m_run[u]) != 0) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run[u] - m_new);
+        l_run[u] *= alpha;
+#pragma unroll
+        for (int b = 0; b < MB; ++b)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[u][b][e] *= alpha;
+        m_run[u] = m_new;
+      }
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pe = __builtin_amdgcn_exp2f(fmaf(s[u][e], scale_log2e, -m_run[u]));
+        psum += pe;
+        pf[u][e >> 3][e & 7] = (bf16_t)pe;
+      }
+      l_run[u] += psum;
+    }
+  };
+  // O^T += V^T P^T for one step
+  auto issue_pv = [&](bf16x8 (&pf)[QT][2], const bf16_t* vs, int kt) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int b = 0; b < MB; ++b) {
+        const bf16x8 vf =
+            *reinterpret_cast<const bf16x8*>(vs + (b * 32 + l32) * SM::V_LD + kt * 32 + j * 16 + lh * 8);
+#pragma unroll
+        for (int u = 0; u < QT; ++u)
+          oacc[u][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u][j], oacc[u][b], 0, 0, 0);
+      }
+  };
 
   const int NB = n_tok / BKEY;
   gload(0);
   sstore(0);
   __syncthreads();
 
+  // Software pipeline over the 32-key steps: the S^T MFMAs of the next step
+  // are in flight while the VALU does the softmax of the current one.  s0 of a
+  // block is issued right after the barrier that published the block.
+  f32x16 s0[QT], s1[QT];
+  bf16x8 p0[QT][2], p1[QT][2];
+  if (any_act) issue_s(s0, sK, 0);
   for (int kb = 0; kb < NB; ++kb) {
     gload(kb + 1 < NB ? kb + 1 : kb);  // unconditional: staging registers stay out of control flow
-    if (active) {
-      const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
-      const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
-      // S^T for the two 32-key halves of the block
-      f32x16 s[2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
-#pragma unroll
-        for (int st = 0; st < KS; ++st) {
-          const bf16x8 kf =
-              *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * SM::K_LD + st * 16 + lh * 8);
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[kt], 0, 0, 0);
-        }
-      }
-      // online softmax, one query per lane (shared with lane ^ 32)
-      float mx = s[0][0];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[kt][e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx * scale_log2e);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float psum = 0.f;
-      bf16x8 pf[2][2];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const float pe = __builtin_amdgcn_exp2f(fmaf(s[kt][e], scale_log2e, -m_new));
-          psum += pe;
-          pf[kt][e >> 3][e & 7] = (bf16_t)pe;
-        }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int b = 0; b < MB; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[b][e] *= alpha;
-      // O^T += V^T P^T
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int key = kt * 32 + j * 16 + lh * 4;
-#pragma unroll
-          for (int b = 0; b < MB; ++b) {
-            const bf16_t* vp = vs + (b * 32 + l32) * SM::V_LD + key;
-            const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp);
-            const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 8);
-            bf16x8 vf;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { vf[e] = lo[e]; vf[4 + e] = hi[e]; }
-            oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kt][j], oacc[b], 0, 0, 0);
-          }
-        }
+    const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
+    const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
+    if (any_act) {
+      issue_s(s1, ks, 1);
+      softmax(s0, p0);
+      issue_pv(p0, vs, 0);
+      softmax(s1, p1);
+      issue_pv(p1, vs, 1);
     }
-    sstore((kb + 1) & 1);
+    sstore((kb + 1) & 1);   // the other buffer: nobody reads it after the previous barrier
     __syncthreads();
+    if (any_act && kb + 1 < NB) issue_s(s0, sK + ((kb + 1) & 1) * SM::K_ELEMS, 0);
   }
 
-  if (!active) return;
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const float inv = 1.0f / l_tot;
-  bf16_t* op = o + (row0 + q0 + l32) * ld_o + (long)h * HD;
 #pragma unroll
-  for (int b = 0; b < MB; ++b)
+  for (int u = 0; u < QT; ++u) {
+    if (!act[u]) continue;
+    const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = o + (row0 + q0 + u * 32 + l32) * ld_o + (long)h * HD;
 #pragma unroll
-    for (int gi = 0; gi < 4; ++gi) {
-      bf16x4 ov;
+    for (int b = 0; b < MB; ++b)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[b][gi * 4 + e] * inv);
-      *reinterpret_cast<bf16x4*>(op + b * 32 + gi * 8 + lh * 4) = ov;
-    }
+      for (int gi = 0; gi < 4; ++gi) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[u][b][gi * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + b * 32 + gi * 8 + lh * 4) = ov;
+      }
+  }
 }
 
-template <int HD>
+template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                        int n_tok, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)AttnSmem<HD>::BYTES);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
+  constexpr int BQ = 128 * QT;
   dim3 grid((n_tok + BQ - 1) / BQ, heads, n_slices);
-  k_attention_bf16<HD><<<grid, dim3(256), AttnSmem<HD>::BYTES, st>>>(
+  k_attention_bf16<HD, QT><<<grid, dim3(256), AttnSmem<HD>::BYTES, st>>>(
       q, k, vt, o, n_tok, heads, ld_qk, ld_o, scale * 1.4426950408889634f);
   return hipGetLastError();
 }
@@ -219,9 +253,9 @@ hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf
   if (n_slices == 0) return hipSuccess;
   if (n_tok % BKEY != 0 || n_tok <= 0) return hipErrorInvalidValue;
   switch (hd_pad) {
-    case 64: return launch_attn<64>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
-    case 96: return launch_attn<96>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
-    case 128: return launch_attn<128>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 64: return launch_attn<64, 2>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
   }
   return hipErrorInvalidValue;
 }
