@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tiles", type=int, default=0, help="slices the oracle encodes (0: bounded default)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -82,6 +84,13 @@ def main():
     offsets = list(wk.tile_offsets)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         enc.encode(tiles, offsets, out)

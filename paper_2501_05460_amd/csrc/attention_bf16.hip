@@ -39,7 +39,7 @@ template <int HD, int QT>
 __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
-                                                        bf16_t* __restrict__ o, int n_tok, int heads,
+                                                        bf16_t* __restrict__ o, int n_tok, int heads, int n_pairs,
                                                         long ld_qk, long ld_o, float scale_log2e) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
@@ -55,7 +55,13 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int qb = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
+  // Workgroups are dealt round-robin to the 8 XCDs: keep the q-blocks of one
+  // (slice, head) on one XCD so that its K / V^T block is fetched into one L2.
+  const int n_qb = (n_tok + BQ - 1) / BQ;
+  const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  const int pair = (seq / n_qb) * 8 + xcd;          // (slice, head) index
+  if (pair >= n_pairs) return;                      // whole workgroup leaves before any barrier
+  const int qb = seq % n_qb, h = pair % heads, t = pair / heads;
   const long row0 = (long)t * n_tok;
   const int q0 = qb * BQ + wave * 32 * QT;
   // n_tok is a multiple of 64: a 32-query sub-tile is all in or all out
@@ -239,9 +245,11 @@ hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_
     attr_done = true;
   }
   constexpr int BQ = 128 * QT;
-  dim3 grid((n_tok + BQ - 1) / BQ, heads, n_slices);
-  k_attention_bf16<HD, QT><<<grid, dim3(256), AttnSmem<HD>::BYTES, st>>>(
-      q, k, vt, o, n_tok, heads, ld_qk, ld_o, scale * 1.4426950408889634f);
+  const int n_qb = (n_tok + BQ - 1) / BQ, n_pairs = n_slices * heads;
+  const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
+  if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
+  k_attention_bf16<HD, QT><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
+      q, k, vt, o, n_tok, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
   return hipGetLastError();
 }
 
