@@ -22,6 +22,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_FP32_TFLOPS = 157.3
 
+# L2 <-> fabric bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain
+# 1 GiB copy kernel gives), averaged over all k_gemm_bf16 launches of one step; measured with
+# rocprofv3 --pmc, summary and commands in profiles/c3_bench_hbm_traffic.txt.
+TRAFFIC_BYTES_PER_GEMM_LAUNCH = {"c3": 1927.9e6}
+
 
 def gemm_flops_per_tile(desc):
     """Dense-contraction flops of the GEMM kernel family per slice, by profile family."""
@@ -126,7 +131,7 @@ def main():
     roofline = {
         "bound": "mfma", "kernel": "k_gemm_bf16 (all epilogue variants)" if bf16 else "k_f32_gemm",
         "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-        "traffic": None,
+        "traffic": TRAFFIC_BYTES_PER_GEMM_LAUNCH.get(args.workload) if desc.max_tiles_per_call == wk.desc.max_tiles_per_call else None,
         "flops_per_launch": gemm_flops / max(gemm_launches, 1),
         "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
         "families_ms_per_step": {k: round(v["ms"] / prof_steps, 3) for k, v in fam.items()},
