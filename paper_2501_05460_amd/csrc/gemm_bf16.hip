@@ -90,9 +90,11 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     id = x * q + (x < r ? x : r) + slot;
   }
   const int band_tiles = gm_ * gw;
-  const int band = id / band_tiles, in_band = id % band_tiles;
-  const int m0 = (in_band / gw) * BM;
-  const int n0 = (band * gw + in_band % gw) * BN;
+  const int full_bands = gn / gw;                 // the last band may be narrower
+  int band = id / band_tiles, in_band = id % band_tiles, bw = gw;
+  if (band >= full_bands) { band = full_bands; in_band = id - full_bands * band_tiles; bw = gn - full_bands * gw; }
+  const int m0 = (in_band / bw) * BM;
+  const int n0 = (band * gw + in_band % bw) * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -362,10 +364,19 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
   if (n_tiles == 0) return hipSuccess;
-  // band width: the widest divisor of gn whose weight panel fits half of one XCD's 4 MiB L2
-  int gw = gn;
-  while (gw > 1 && ((size_t)gw * BN * p.K * sizeof(bf16_t) > (2u << 20) || gn % gw != 0)) --gw;
-  if (p.band > 0 && gn % p.band == 0) gw = p.band;
+  // Band width.  The ~32 workgroups an XCD runs at once cover (32 / gw) tile rows x gw tile
+  // columns and move through K together, so per wave of tiles the L2 pulls 32 / gw activation
+  // panels and gw weight panels (256 x K each) over the fabric; the weight panels are not
+  // pulled again by later waves while a band's whole weight panel fits the 4 MiB L2.
+  const double panel = 256.0 * p.K * sizeof(bf16_t);
+  int gw = 1;
+  double best = 1e30;
+  for (int c = 1; c <= gn && c <= 32; ++c) {
+    const bool resident = c * (double)BN * p.K * sizeof(bf16_t) <= 2.5 * (1 << 20);
+    const double cost = (32.0 / c) * panel + (resident ? 0.0 : c * panel * (BN / 256.0));
+    if (cost < best * 0.999) { best = cost; gw = c; }
+  }
+  if (p.band > 0 && p.band <= gn) gw = p.band;
   k_gemm_bf16<BN, NT, WN, EPI><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
   return hipGetLastError();
 }
