@@ -152,6 +152,62 @@ const char* epd_last_error(const epd_ctx* ctx);
 
 void epd_destroy(epd_ctx* ctx);
 
+/* ---- paged multimodal-token cache ---------------------------------------
+ *
+ * Encode and prefill workers both keep an MM cache; when an encode finishes
+ * its tokens stay in the encode worker's cache until they have been moved to
+ * the prefill worker's cache, then the source entries are released
+ * (Section 3.2.1, "Asynchronous Token Transfer").  The MMBlockManager of that
+ * section pre-allocates cache blocks per request and reassigns them after the
+ * transfer; the paper's settings are blocks of 16 tokens and an MM cache size
+ * of 3000 (Appendix "Hyper-parameters in EPD system").  An epd_mm_cache is one
+ * such cache: a device pool [n_blocks][block_tokens][token_dim] plus the
+ * host-side block manager.  Block lists are host int32 arrays.  One thread at
+ * a time per cache; the manager calls are host-only and immediate, the copies
+ * are enqueued on the given stream. */
+typedef struct epd_mm_cache epd_mm_cache;
+
+/* token_dim 0 creates the manager without a device pool (planning, host tests). */
+epd_status epd_mm_cache_create(int32_t n_blocks, int32_t block_tokens, int32_t token_dim, int32_t dtype,
+                               epd_mm_cache** out);
+void epd_mm_cache_destroy(epd_mm_cache* cache);
+int32_t epd_mm_cache_free_blocks(const epd_mm_cache* cache);
+void* epd_mm_cache_base(const epd_mm_cache* cache); /* dev pointer of the pool */
+const char* epd_mm_last_error(const epd_mm_cache* cache);
+
+/* Pre-allocate the ceil(n_tokens / block_tokens) blocks a request needs (its
+ * token count follows from its slice count: slices * epd_tokens_per_tile).
+ * block_ids (host, max_ids entries) receives them in token order.
+ * EPD_ERR_NOMEM if the cache has too few free blocks (nothing is taken). */
+epd_status epd_mm_alloc(epd_mm_cache* cache, int64_t n_tokens, int32_t* block_ids, int32_t max_ids,
+                        int32_t* n_ids);
+/* Release blocks (after their tokens have been transferred).  A list with an
+ * unallocated, out-of-range or repeated id frees nothing. */
+epd_status epd_mm_free(epd_mm_cache* cache, const int32_t* block_ids, int32_t n_ids);
+
+/* Encode stage with paged output: as epd_encode, but token i of request r is
+ * written to block block_table[block_table_offsets[r] + i / block_tokens],
+ * slot i % block_tokens, of `cache` (token width and dtype must match the
+ * encoder, tokens per slice must be a multiple of block_tokens).
+ * block_table_offsets: host int32 [n_requests + 1], request r owns
+ * (slices of r) * tokens_per_tile / block_tokens entries; every entry must be
+ * an allocated block of `cache`.  No other block is touched. */
+epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles,
+                            const int32_t* tile_offsets_per_request, int32_t n_requests,
+                            epd_mm_cache* cache, const int32_t* block_table,
+                            const int32_t* block_table_offsets, void* hip_stream);
+
+/* Encode-to-prefill migration on one device: copy blocks src_blocks[i] of
+ * `src` to blocks dst_blocks[i] of `dst` (same block shape; all blocks
+ * allocated).  One transfer at a time per destination cache and stream. */
+epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
+                           const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream);
+
+/* Copy blocks[0..n_blocks) of `src`, in that order, into a contiguous dev
+ * buffer (16-byte aligned) of n_blocks * block_tokens tokens. */
+epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blocks, void* dst_contiguous,
+                         void* hip_stream);
+
 /* ---- measurement and test hooks (not needed to serve) ------------------ */
 
 /* Copy the residual stream (float32 [rows, D], the encoder state after the

@@ -227,3 +227,29 @@ def encode_sample(tile_list: Iterable[np.ndarray], w, desc) -> np.ndarray:
     """Tokens of the given slices stacked in the given order (used when only a
     sample of a large batch is affordable on the CPU)."""
     return np.concatenate([encode_tile(t, w, desc) for t in tile_list], axis=0)
+
+
+# ---------------------------------------------------------- paged MM cache ----
+# Section 3.2.1: the tokens of a finished encode wait in the encode worker's
+# multimodal cache, whose blocks a block manager pre-allocated for the request;
+# the paper's setting is blocks of 16 tokens (Appendix "Hyper-parameters in EPD
+# system").  The layout is a pure index map, written here one token at a time.
+
+def paged_scatter(pool: np.ndarray, tokens: np.ndarray, block_ids: Sequence[int], block_tokens: int) -> np.ndarray:
+    """Token i of a request goes to block block_ids[i // block_tokens], slot
+    i % block_tokens.  pool: [n_blocks, block_tokens, dim]; other blocks are
+    left alone."""
+    n = tokens.shape[0]
+    assert len(block_ids) * block_tokens >= n
+    for i in range(n):
+        pool[block_ids[i // block_tokens], i % block_tokens, :] = tokens[i]
+    return pool
+
+
+def paged_gather(pool: np.ndarray, block_ids: Sequence[int], n_tokens: int) -> np.ndarray:
+    """Inverse view: the request's tokens in order, read through its block list."""
+    bt = pool.shape[1]
+    out = np.empty((n_tokens, pool.shape[2]), pool.dtype)
+    for i in range(n_tokens):
+        out[i] = pool[block_ids[i // bt], i % bt]
+    return out

@@ -32,6 +32,8 @@ EXPORTS = (
     "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read",
+    "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
+    "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_gather",
 )
 
 
@@ -97,6 +99,27 @@ def lib() -> ctypes.CDLL:
         L.epd_profile_enable.restype = i32
         L.epd_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.epd_profile_read.restype = i32
+        L.epd_mm_cache_create.argtypes = [i32, i32, i32, i32, ctypes.POINTER(vp)]
+        L.epd_mm_cache_create.restype = i32
+        L.epd_mm_cache_destroy.argtypes = [vp]
+        L.epd_mm_cache_destroy.restype = None
+        L.epd_mm_cache_free_blocks.argtypes = [vp]
+        L.epd_mm_cache_free_blocks.restype = i32
+        L.epd_mm_cache_base.argtypes = [vp]
+        L.epd_mm_cache_base.restype = vp
+        L.epd_mm_last_error.argtypes = [vp]
+        L.epd_mm_last_error.restype = ctypes.c_char_p
+        L.epd_mm_alloc.argtypes = [vp, i64, ctypes.POINTER(i32), i32, ctypes.POINTER(i32)]
+        L.epd_mm_alloc.restype = i32
+        L.epd_mm_free.argtypes = [vp, ctypes.POINTER(i32), i32]
+        L.epd_mm_free.restype = i32
+        L.epd_encode_paged.argtypes = [vp, vp, i32, ctypes.POINTER(i32), i32, vp, ctypes.POINTER(i32),
+                                       ctypes.POINTER(i32), vp]
+        L.epd_encode_paged.restype = i32
+        L.epd_mm_transfer.argtypes = [vp, ctypes.POINTER(i32), vp, ctypes.POINTER(i32), i32, vp]
+        L.epd_mm_transfer.restype = i32
+        L.epd_mm_gather.argtypes = [vp, ctypes.POINTER(i32), i32, vp, vp]
+        L.epd_mm_gather.restype = i32
         _lib = L
     return _lib
 
@@ -217,6 +240,80 @@ class Encoder:
         if s != EPD_OK:
             self._raise(s)
         return {name: {"ms": float(ms[i]), "launches": int(n[i])} for i, name in enumerate(PROF_FAMILIES)}
+
+
+def _i32(values: Sequence[int]):
+    return (ctypes.c_int32 * len(values))(*values)
+
+
+class MMCache:
+    """One paged multimodal-token cache (device pool + block manager)."""
+
+    def __init__(self, n_blocks: int, block_tokens: int, token_dim: int, bf16: bool):
+        h = ctypes.c_void_p()
+        s = lib().epd_mm_cache_create(n_blocks, block_tokens, token_dim, 1 if bf16 else 0, ctypes.byref(h))
+        if s != EPD_OK:
+            raise EpdError(s, lib().epd_mm_last_error(None).decode())
+        self._h = h
+        self.n_blocks, self.block_tokens, self.token_dim, self.bf16 = n_blocks, block_tokens, token_dim, bf16
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().epd_mm_cache_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _raise(self, s):
+        raise EpdError(s, lib().epd_mm_last_error(self._h).decode())
+
+    @property
+    def free_blocks(self) -> int:
+        return lib().epd_mm_cache_free_blocks(self._h)
+
+    def alloc(self, n_tokens: int) -> List[int]:
+        cap = (n_tokens + self.block_tokens - 1) // self.block_tokens
+        ids = (ctypes.c_int32 * max(cap, 1))()
+        n = ctypes.c_int32()
+        s = lib().epd_mm_alloc(self._h, n_tokens, ids, cap, ctypes.byref(n))
+        if s != EPD_OK:
+            self._raise(s)
+        return [ids[i] for i in range(n.value)]
+
+    def free(self, ids: Sequence[int]):
+        s = lib().epd_mm_free(self._h, _i32(ids), len(ids))
+        if s != EPD_OK:
+            self._raise(s)
+
+    def gather(self, ids: Sequence[int]) -> torch.Tensor:
+        dtype = torch.bfloat16 if self.bf16 else torch.float32
+        out = torch.empty((len(ids) * self.block_tokens, self.token_dim), dtype=dtype, device="cuda")
+        s = lib().epd_mm_gather(self._h, _i32(ids), len(ids), out.data_ptr(), _stream_ptr())
+        if s != EPD_OK:
+            self._raise(s)
+        return out
+
+    def transfer_to(self, src_ids: Sequence[int], dst: "MMCache", dst_ids: Sequence[int]):
+        s = lib().epd_mm_transfer(self._h, _i32(src_ids), dst._h, _i32(dst_ids), len(src_ids), _stream_ptr())
+        if s != EPD_OK:
+            dst._raise(s)
+
+
+def encode_paged(enc: "Encoder", tiles: torch.Tensor, tile_offsets: Sequence[int], cache: MMCache,
+                 block_tables: Sequence[Sequence[int]]):
+    """block_tables[r] = block ids of request r in token order."""
+    flat, offs = [], [0]
+    for t in block_tables:
+        flat.extend(t)
+        offs.append(len(flat))
+    s = lib().epd_encode_paged(enc._h, tiles.data_ptr(), int(tiles.shape[0]), _i32(tile_offsets),
+                               len(tile_offsets) - 1, cache._h, _i32(flat or [0]), _i32(offs), _stream_ptr())
+    if s != EPD_OK:
+        enc._raise(s)
 
 
 def op_gemm_bf16(A: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], iters: int = 1):

@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "kernels.h"
+#include "mm_cache.h"
 
 using namespace epd;
 
@@ -164,6 +165,11 @@ struct epd_ctx {
   void* Pin = nullptr;
   void* Pmid = nullptr;
   long last_rows = 0;
+
+  // paged output (epd_encode_paged): device row-block map of the current micro-batch
+  int* d_rowmap = nullptr;       // [mb * N_out] ints (enough for any block size)
+  const int* cur_rowmap = nullptr;  // null: contiguous output
+  int cur_block_tokens = 1;
 
   // profiling
   bool prof = false;
@@ -346,6 +352,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   bool ok = true;
   auto ws = [&](size_t bytes) { void* p = dalloc(c, bytes, true, st); ok = ok && p; return p; };
   c->X = (float*)ws((size_t)c->Mp * x.D * sizeof(float));
+  c->d_rowmap = (int*)ws((size_t)Mo * sizeof(int));
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
     c->QKV = ws((size_t)c->Mp * 2 * c->Dq * 2);
@@ -411,10 +418,12 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
     if (d.proj_prenorm) { f32_norm(0, pin, x.Pin, Pin, x.Pin, c->pn_g, c->pn_b, Mo, x.Pin, 1, d.eps, st); pin = Pin; } }
   { ProfScope ps(c, 9, st);
     if (d.proj_kind == EPD_PROJ_LINEAR) {
-      f32_gemm(EPI_BIAS, pin, x.Pin, (const float*)c->pa.W, c->pa.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pin, st);
+      f32_gemm(EPI_BIAS, pin, x.Pin, (const float*)c->pa.W, c->pa.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pin, st,
+               c->cur_rowmap, c->cur_block_tokens);
     } else {
       f32_gemm(EPI_BIAS_GELU_ERF, pin, x.Pin, (const float*)c->pa.W, c->pa.b, Pmid, x.Pmid, nullptr, 1, Mo, x.Pmid, x.Pin, st);
-      f32_gemm(EPI_BIAS, Pmid, x.Pmid, (const float*)c->pb.W, c->pb.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pmid, st);
+      f32_gemm(EPI_BIAS, Pmid, x.Pmid, (const float*)c->pb.W, c->pb.b, out, x.Pout, nullptr, 1, Mo, x.Pout, x.Pmid, st,
+               c->cur_rowmap, c->cur_block_tokens);
     } }
   HIP_TRY(c, hipGetLastError());
   return EPD_OK;
@@ -494,7 +503,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   if (d.proj_kind == EPD_PROJ_LINEAR) {
       ProfScope ps(c, 9, st);
       GemmParams p = gp(EPI_BIAS, Pin, c->Pin_k, c->pa, Mo);
-      p.C = out; p.ldc = x.Pout;
+      p.C = out; p.ldc = x.Pout; p.row_map = c->cur_rowmap; p.block_tokens = c->cur_block_tokens;
       HIP_TRY(c, bf16_gemm(p, st));
   } else {
     { ProfScope ps(c, 9, st);
@@ -503,15 +512,17 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       HIP_TRY(c, bf16_gemm(p, st)); }
     { ProfScope ps(c, 9, st);
       GemmParams p2 = gp(EPI_BIAS, Pmid, c->Pmid_k, c->pb, Mo);
-      p2.C = out; p2.ldc = x.Pout;
+      p2.C = out; p2.ldc = x.Pout; p2.row_map = c->cur_rowmap; p2.block_tokens = c->cur_block_tokens;
       HIP_TRY(c, bf16_gemm(p2, st)); }
   }
   HIP_TRY(c, hipGetLastError());
   return EPD_OK;
 }
 
+// `block_map` (host, may be null): physical block of every logical block of `block_tokens` output
+// rows of the packed batch; with it `out` is the base of a paged pool instead of a contiguous cache.
 epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, int32_t b, int32_t e, void* out,
-                             hipStream_t st) {
+                             hipStream_t st, const int32_t* block_map = nullptr, int block_tokens = 1) {
   if (b < 0 || e < b || e > n_total) {
     set_err(c->err, sizeof(c->err), "tile range [%d, %d) is not inside [0, %d]", b, e, n_total);
     return EPD_ERR_OFFSETS;
@@ -530,7 +541,18 @@ epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, in
     const int T = (e - t0) < c->mb ? (e - t0) : c->mb;
     const float* tp = tiles + (size_t)t0 * tile_elems;
     char* op = (char*)out + (size_t)t0 * x.N_out * out_row_bytes;
+    c->cur_rowmap = nullptr;
+    c->cur_block_tokens = 1;
+    if (block_map) {
+      // this micro-batch's slice of the map; the copy is stream-ordered behind the previous micro-batch
+      const size_t first = (size_t)t0 * x.N_out / block_tokens, count = (size_t)T * x.N_out / block_tokens;
+      HIP_TRY(c, hipMemcpyAsync(c->d_rowmap, block_map + first, count * sizeof(int), hipMemcpyHostToDevice, st));
+      c->cur_rowmap = c->d_rowmap;
+      c->cur_block_tokens = block_tokens;
+      op = (char*)out;
+    }
     epd_status s = c->bf16 ? run_bf16(c, tp, T, (bf16_t*)op, st) : run_f32(c, tp, T, (float*)op, st);
+    c->cur_rowmap = nullptr;
     if (s != EPD_OK) return s;
     c->last_rows = (long)T * x.N;
   }
@@ -614,6 +636,50 @@ epd_status epd_encode_range(epd_ctx* ctx, const float* tiles, int32_t n_tiles_to
                             int32_t tile_end, void* out, void* hip_stream) {
   if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
   return encode_range_impl(ctx, tiles, n_tiles_total, tile_begin, tile_end, out, (hipStream_t)hip_stream);
+}
+
+epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles, const int32_t* off, int32_t n_requests,
+                            epd_mm_cache* cache, const int32_t* block_table, const int32_t* block_table_offsets,
+                            void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  epd_status s = epd_check_offsets(off, n_requests, n_tiles);
+  if (s != EPD_OK) { strncpy(ctx->err, g_err, sizeof(ctx->err) - 1); return s; }
+  if (n_tiles == 0) return EPD_OK;
+  if (!cache || !block_table || !block_table_offsets) {
+    set_err(ctx->err, sizeof(ctx->err), "cache / block_table / block_table_offsets is null");
+    return EPD_ERR_INVALID_ARG;
+  }
+  const Dims& x = ctx->x;
+  if (!cache->pool || cache->token_dim != x.Pout || cache->dtype != ctx->d.dtype) {
+    set_err(ctx->err, sizeof(ctx->err), "cache token width / dtype (%d, %d) does not match the encoder (%d, %d)",
+            cache->token_dim, cache->dtype, x.Pout, ctx->d.dtype);
+    return EPD_ERR_SHAPE;
+  }
+  if (x.N_out % cache->block_tokens) {
+    set_err(ctx->err, sizeof(ctx->err), "tokens per slice %d is not a multiple of the block size %d", x.N_out,
+            cache->block_tokens);
+    return EPD_ERR_UNSUPPORTED;
+  }
+  const int bpt = x.N_out / cache->block_tokens;  // blocks per slice
+  if (block_table_offsets[0] != 0) { set_err(ctx->err, sizeof(ctx->err), "block_table_offsets[0] must be 0"); return EPD_ERR_OFFSETS; }
+  for (int r = 0; r < n_requests; ++r) {
+    const long want = (long)(off[r + 1] - off[r]) * bpt;
+    if (block_table_offsets[r + 1] - block_table_offsets[r] != want) {
+      set_err(ctx->err, sizeof(ctx->err), "request %d needs %ld blocks, its block table holds %d", r, want,
+              block_table_offsets[r + 1] - block_table_offsets[r]);
+      return EPD_ERR_OFFSETS;
+    }
+  }
+  const long total = (long)n_tiles * bpt;
+  for (long i = 0; i < total; ++i)
+    if (block_table[i] < 0 || block_table[i] >= cache->n_blocks || !cache->used[block_table[i]]) {
+      set_err(ctx->err, sizeof(ctx->err), "block table entry %ld (%d) is out of range or not allocated", i, block_table[i]);
+      return EPD_ERR_OFFSETS;
+    }
+  // requests are contiguous in slice order and own whole blocks, so the concatenated
+  // per-request tables are the logical-block -> physical-block map of the packed batch
+  return encode_range_impl(ctx, tiles, n_tiles, 0, n_tiles, cache->pool, (hipStream_t)hip_stream, block_table,
+                           cache->block_tokens);
 }
 
 int64_t epd_tokens_per_tile(const epd_ctx* ctx) { return ctx ? ctx->x.N_out : -1; }

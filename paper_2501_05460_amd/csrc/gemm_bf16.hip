@@ -350,7 +350,10 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
       }
     } else {
       const int row = m0 + r, col = n0 + c * 8;
-      if (row < p.M && col < p.N) *reinterpret_cast<u32x4*>(p.C + (long)row * p.ldc + col) = v;
+      if (row < p.M && col < p.N) {
+        const long orow = p.row_map ? (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens : row;
+        *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v;
+      }
     }
   }
   }  // staging kind

@@ -8,7 +8,8 @@ namespace epd {
 // ---- fp32 mode (simple_f32.hip) -------------------------------------------
 void f32_im2col(const float* tiles, float* A, int T, int S, int p, hipStream_t st);
 void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
-              const float* pos, int n_pos, int M, int N, int K, hipStream_t st);
+              const float* pos, int n_pos, int M, int N, int K, hipStream_t st,
+              const int* row_map = nullptr, int block_tokens = 1);
 void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, const float* gamma,
               const float* beta, long rows, int dim, int groups, float eps, hipStream_t st);
 void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
@@ -28,6 +29,8 @@ struct GemmParams {
   const float* bias;          // [Npad]
   int M, N, K, Npad;
   bf16_t* C; long ldc;        // bf16 output (BIAS, GELU_*)
+  const int* row_map;         // optional paged output: row r -> row_map[r / block_tokens] * block_tokens + r % block_tokens
+  int block_tokens;
   float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS)
   const float* pos; int n_pos;
   bf16_t* VT;                 // EPI_VT: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
@@ -73,6 +76,11 @@ void pack_matrix_bf16(const bf16_t* src, int rows, int cols, bf16_t* dst, int ro
                       PackMap rmap, PackMap cmap, hipStream_t st);
 void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_pad, PackMap map,
                      hipStream_t st);
+
+// Paged multimodal-token cache: copy `n_blocks` blocks of `block_bytes` (multiple of 16) from
+// src_pool[src_ids[i]] to dst_pool[dst_ids[i]]; a null id array means block i (contiguous side).
+void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, const int* dst_ids,
+                    int n_blocks, long block_bytes, hipStream_t st);
 
 // MFMA lane-layout check: D[32,32] = A[32,16] * B[16,32] with operands loaded
 // and the result stored under the layout the kernels assume.

@@ -1,0 +1,145 @@
+// Paged multimodal-token cache: device pool + host-side block manager, and
+// the block copies that move a request's tokens between two caches (the
+// encode worker's and a stand-in for the prefill worker's) or to / from a
+// contiguous buffer.  See include/epd_encode.h.
+#include "../../include/epd_encode.h"
+
+#include <cstdio>
+#include <cstring>
+
+#include "kernels.h"
+#include "mm_cache.h"
+
+using namespace epd;
+
+namespace {
+thread_local char g_mm_err[256] = "";
+void mm_err(epd_mm_cache* c, const char* msg) {
+  snprintf(g_mm_err, sizeof(g_mm_err), "%s", msg);
+  if (c) snprintf(c->err, sizeof(c->err), "%s", msg);
+}
+bool ids_ok(const epd_mm_cache* c, const int32_t* ids, int32_t n, bool must_be_used) {
+  for (int i = 0; i < n; ++i) {
+    if (ids[i] < 0 || ids[i] >= c->n_blocks) return false;
+    if (must_be_used && !c->used[ids[i]]) return false;
+  }
+  return true;
+}
+}  // namespace
+
+extern "C" {
+
+epd_status epd_mm_cache_create(int32_t n_blocks, int32_t block_tokens, int32_t token_dim, int32_t dtype,
+                               epd_mm_cache** out) {
+  if (!out) return EPD_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (n_blocks <= 0 || block_tokens <= 0 || token_dim < 0 || (dtype != EPD_DTYPE_FP32 && dtype != EPD_DTYPE_BF16)) {
+    mm_err(nullptr, "epd_mm_cache_create: n_blocks, block_tokens must be positive, token_dim >= 0, dtype 0 or 1");
+    return EPD_ERR_INVALID_ARG;
+  }
+  const long elt = dtype == EPD_DTYPE_BF16 ? 2 : 4;
+  const long block_bytes = (long)block_tokens * token_dim * elt;
+  if (block_bytes % 16 != 0) {
+    mm_err(nullptr, "epd_mm_cache_create: a block must be a multiple of 16 bytes");
+    return EPD_ERR_UNSUPPORTED;
+  }
+  epd_mm_cache* c = new epd_mm_cache();
+  c->n_blocks = n_blocks; c->block_tokens = block_tokens; c->token_dim = token_dim; c->dtype = dtype;
+  c->block_bytes = block_bytes;
+  c->used.assign(n_blocks, 0);
+  c->free_list.reserve(n_blocks);
+  for (int i = n_blocks - 1; i >= 0; --i) c->free_list.push_back(i);  // block 0 is handed out first
+  if (block_bytes > 0) {  // token_dim 0: manager only (planning, host tests), no device memory
+    if (hipMalloc(&c->pool, (size_t)n_blocks * block_bytes) != hipSuccess ||
+        hipMalloc((void**)&c->d_ids_a, (size_t)n_blocks * sizeof(int)) != hipSuccess ||
+        hipMalloc((void**)&c->d_ids_b, (size_t)n_blocks * sizeof(int)) != hipSuccess) {
+      mm_err(nullptr, "epd_mm_cache_create: device allocation failed");
+      epd_mm_cache_destroy(c);
+      return EPD_ERR_NOMEM;
+    }
+  }
+  *out = c;
+  return EPD_OK;
+}
+
+void epd_mm_cache_destroy(epd_mm_cache* c) {
+  if (!c) return;
+  if (c->pool) (void)hipFree(c->pool);
+  if (c->d_ids_a) (void)hipFree(c->d_ids_a);
+  if (c->d_ids_b) (void)hipFree(c->d_ids_b);
+  delete c;
+}
+
+int32_t epd_mm_cache_free_blocks(const epd_mm_cache* c) { return c ? (int32_t)c->free_list.size() : -1; }
+void* epd_mm_cache_base(const epd_mm_cache* c) { return c ? c->pool : nullptr; }
+const char* epd_mm_last_error(const epd_mm_cache* c) { return c ? c->err : g_mm_err; }
+
+epd_status epd_mm_alloc(epd_mm_cache* c, int64_t n_tokens, int32_t* block_ids, int32_t max_ids, int32_t* n_ids) {
+  if (!c || !n_ids || n_tokens < 0 || (n_tokens > 0 && !block_ids)) return EPD_ERR_INVALID_ARG;
+  const int64_t need = (n_tokens + c->block_tokens - 1) / c->block_tokens;
+  *n_ids = 0;
+  if (need > max_ids) { mm_err(c, "epd_mm_alloc: block_ids too short for the request"); return EPD_ERR_INVALID_ARG; }
+  if (need > (int64_t)c->free_list.size()) { mm_err(c, "epd_mm_alloc: not enough free blocks"); return EPD_ERR_NOMEM; }
+  for (int64_t i = 0; i < need; ++i) {
+    const int b = c->free_list.back();
+    c->free_list.pop_back();
+    c->used[b] = 1;
+    block_ids[i] = b;
+  }
+  *n_ids = (int32_t)need;
+  return EPD_OK;
+}
+
+epd_status epd_mm_free(epd_mm_cache* c, const int32_t* block_ids, int32_t n_ids) {
+  if (!c || n_ids < 0 || (n_ids > 0 && !block_ids)) return EPD_ERR_INVALID_ARG;
+  // validate everything first: a bad list frees nothing
+  if (!ids_ok(c, block_ids, n_ids, true)) { mm_err(c, "epd_mm_free: id out of range or block not allocated"); return EPD_ERR_INVALID_ARG; }
+  for (int i = 0; i < n_ids; ++i)
+    for (int j = i + 1; j < n_ids; ++j)
+      if (block_ids[i] == block_ids[j]) { mm_err(c, "epd_mm_free: duplicate id in the list"); return EPD_ERR_INVALID_ARG; }
+  for (int i = 0; i < n_ids; ++i) { c->used[block_ids[i]] = 0; c->free_list.push_back(block_ids[i]); }
+  return EPD_OK;
+}
+
+epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
+                           const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream) {
+  if (!src || !dst || n_blocks < 0 || (n_blocks > 0 && (!src_blocks || !dst_blocks))) return EPD_ERR_INVALID_ARG;
+  if (src->block_bytes != dst->block_bytes || src->block_tokens != dst->block_tokens || src->dtype != dst->dtype ||
+      !src->pool || !dst->pool) {
+    mm_err(dst, "epd_mm_transfer: the two caches must have the same block shape and a device pool");
+    return EPD_ERR_SHAPE;
+  }
+  if (n_blocks > src->n_blocks || n_blocks > dst->n_blocks || !ids_ok(src, src_blocks, n_blocks, true) ||
+      !ids_ok(dst, dst_blocks, n_blocks, true)) {
+    mm_err(dst, "epd_mm_transfer: block id out of range or not allocated");
+    return EPD_ERR_OFFSETS;
+  }
+  if (n_blocks == 0) return EPD_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // id lists travel in the destination cache's scratch (one transfer at a time per destination)
+  if (hipMemcpyAsync(dst->d_ids_a, src_blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipMemcpyAsync(dst->d_ids_b, dst_blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) {
+    mm_err(dst, "epd_mm_transfer: id upload failed");
+    return EPD_ERR_HIP;
+  }
+  mm_copy_blocks(src->pool, dst->d_ids_a, dst->pool, dst->d_ids_b, n_blocks, src->block_bytes, st);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+}
+
+epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blocks, void* dst_contiguous,
+                         void* hip_stream) {
+  if (!src || n_blocks < 0 || (n_blocks > 0 && (!blocks || !dst_contiguous))) return EPD_ERR_INVALID_ARG;
+  if (!src->pool) return EPD_ERR_SHAPE;
+  if (((uintptr_t)dst_contiguous & 15) != 0) return EPD_ERR_INVALID_ARG;
+  if (n_blocks > src->n_blocks || !ids_ok(src, blocks, n_blocks, true)) {
+    mm_err(src, "epd_mm_gather: block id out of range or not allocated");
+    return EPD_ERR_OFFSETS;
+  }
+  if (n_blocks == 0) return EPD_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (hipMemcpyAsync(src->d_ids_a, blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) return EPD_ERR_HIP;
+  mm_copy_blocks(src->pool, src->d_ids_a, dst_contiguous, nullptr, n_blocks, src->block_bytes, st);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+}
+
+}  // extern "C"

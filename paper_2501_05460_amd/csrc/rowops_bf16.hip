@@ -225,6 +225,30 @@ void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_
   k_pack_vector<<<dim3((n_pad + 255) / 256), dim3(256), 0, st>>>(src, src_is_bf16, n, dst, n_pad, map);
 }
 
+// ------------------------------------------------- paged cache block copy ----
+// One workgroup row per block; 16 bytes per thread and step.  HBM-bound.
+__global__ __launch_bounds__(256) void k_mm_copy_blocks(const unsigned char* __restrict__ src_pool,
+                                                        const int* __restrict__ src_ids,
+                                                        unsigned char* __restrict__ dst_pool,
+                                                        const int* __restrict__ dst_ids, long block_bytes) {
+  const int b = blockIdx.y;
+  const long sb = src_ids ? src_ids[b] : b, db = dst_ids ? dst_ids[b] : b;
+  const u32x4* s = reinterpret_cast<const u32x4*>(src_pool + sb * block_bytes);
+  u32x4* d = reinterpret_cast<u32x4*>(dst_pool + db * block_bytes);
+  const long n16 = block_bytes >> 4;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256) d[i] = s[i];
+}
+
+void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, const int* dst_ids,
+                    int n_blocks, long block_bytes, hipStream_t st) {
+  if (n_blocks <= 0 || block_bytes <= 0) return;
+  const long n16 = block_bytes >> 4;
+  int gx = (int)((n16 + 255) / 256);
+  if (gx > 8) gx = 8;
+  k_mm_copy_blocks<<<dim3(gx, n_blocks), dim3(256), 0, st>>>((const unsigned char*)src_pool, src_ids,
+                                                             (unsigned char*)dst_pool, dst_ids, block_bytes);
+}
+
 // ------------------------------------------------------------ MFMA probe ----
 __global__ __launch_bounds__(64) void k_mfma_probe(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                    float* __restrict__ D) {

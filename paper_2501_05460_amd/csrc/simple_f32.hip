@@ -38,7 +38,8 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
                                                   const float* __restrict__ W,
                                                   const float* __restrict__ bias, float* C, int ldc,
                                                   const float* __restrict__ pos, int n_pos, int M,
-                                                  int N, int K) {
+                                                  int N, int K, const int* __restrict__ row_map,
+                                                  int block_tokens) {
   __shared__ float sA[16][64 + 1];
   __shared__ float sW[16][64 + 1];
   const int tid = threadIdx.x;
@@ -76,7 +77,9 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
       int c = n0 + tx * 4 + j;
       if (c >= N) continue;
       float v = acc[i][j] + (bias ? bias[c] : 0.f);
-      long o = (long)r * ldc + c;
+      // paged output: row r of the product lives in block row_map[r / block_tokens]
+      const long orow = row_map ? (long)row_map[r / block_tokens] * block_tokens + r % block_tokens : r;
+      long o = orow * ldc + c;
       if (EPI == EPI_BIAS_RESIDUAL) {
         C[o] += v;
       } else if (EPI == EPI_BIAS_POS) {
@@ -89,15 +92,16 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
 }
 
 void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
-              const float* pos, int n_pos, int M, int N, int K, hipStream_t st) {
+              const float* pos, int n_pos, int M, int N, int K, hipStream_t st, const int* row_map,
+              int block_tokens) {
   if (M == 0 || N == 0) return;
   dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
   switch (epi) {
-    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
-    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
-    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
-    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
-    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K); break;
+    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
+    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
+    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
+    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
+    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
   }
 }
 
