@@ -180,8 +180,11 @@ def project(x, w, desc):
     return linear(hmid, w["pb_w"], w["pb_b"])
 
 
-def encode_tile(tile, w, desc, trace: Optional[dict] = None):
-    """Tokens of one slice: [tokens_per_tile, out_dim], float64."""
+def trunk_tile(tile, w, desc, trace: Optional[dict] = None):
+    """Pre-projection tokens of one slice, [N, hidden]: the encoder up to and
+    including its last norm, before pixel shuffle and projector (the part an
+    encode worker runs when projection happens on the prefill side,
+    Section 3.2.2)."""
     x = embed_tile(tile, w, desc)
     if trace is not None:
         trace["embed"] = x.copy()
@@ -191,7 +194,23 @@ def encode_tile(tile, w, desc, trace: Optional[dict] = None):
             trace[f"layer{l}"] = x.copy()
     if desc.final_norm:
         x = _norm(x, w, "fn", desc.norm, desc.eps)
-    return project(x, w, desc)
+    return x
+
+
+def encode_tile(tile, w, desc, trace: Optional[dict] = None):
+    """Tokens of one slice: [tokens_per_tile, out_dim], float64."""
+    return project(trunk_tile(tile, w, desc, trace), w, desc)
+
+
+def project_merge(shards: Sequence[np.ndarray], w, desc) -> np.ndarray:
+    """Prefill side of intra-request parallelism (Section 3.2.2): `shards` are
+    the pre-projection tokens the encode workers sent, each [slices_i * N,
+    hidden], listed in slice order.  They are put one after the other, every
+    slice is projected on its own, and the results are stacked in slice order."""
+    N = (desc.tile_size // desc.patch) ** 2
+    rows = np.concatenate([np.asarray(s, F64) for s in shards], axis=0)
+    assert rows.shape[0] % N == 0
+    return np.concatenate([project(rows[t * N:(t + 1) * N], w, desc) for t in range(rows.shape[0] // N)], axis=0)
 
 
 def tokens_per_tile(desc) -> int:

@@ -221,3 +221,37 @@ def test_bf16_grid_rounding_is_nearest_even():
     bits = wl.bf16_bits(r)
     back = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
     np.testing.assert_array_equal(back, r)
+
+
+@pytest.mark.parametrize("final_norm", [0, 1])
+def test_trunk_is_the_encoder_with_an_identity_projector(final_norm):
+    """With no shuffle, no projector norm and a Linear projector whose weight is
+    the identity, the multimodal tokens are the pre-projection tokens; the
+    library-op composition of that encoder pins trunk_tile on its own."""
+    desc = small_desc(final_norm=final_norm, proj_out=32)
+    w = wl.gen_weights(desc, 21, std=0.08)
+    w["pa_w"] = np.eye(32)
+    w["pa_b"] = np.zeros(32)
+    tile = wl.gen_tiles(desc, 21, 1)[0]
+    ref = torch_second_opinion(tile, w, desc)
+    got = O.trunk_tile(tile, w, desc)
+    assert got.shape == (16, 32)
+    assert np.abs(got - ref).max() < 1e-10 * max(1.0, np.abs(ref).max())
+
+
+def test_project_merge_of_shards_in_slice_order_is_the_encode():
+    """Section 3.2.2: shards of pre-projection tokens, put in slice order, projected and merged,
+    are the request's multimodal tokens; a wrong shard order is not."""
+    desc = small_desc(**VARIANTS["shuffle_ln_mlp"])
+    w = wl.gen_weights(desc, 22, std=0.08)
+    tiles = wl.gen_tiles(desc, 22, 5)
+    ref = np.concatenate([torch_second_opinion(t, w, desc) for t in tiles])
+    pre = [O.trunk_tile(t, w, desc) for t in tiles]
+    shards = [np.concatenate(pre[0:2]), np.concatenate(pre[2:3]), np.concatenate(pre[3:5])]
+    got = O.project_merge(shards, w, desc)
+    assert got.shape == (5 * O.tokens_per_tile(desc), desc.proj_out)
+    assert np.abs(got - ref).max() < 1e-10 * np.abs(ref).max()
+    swapped = O.project_merge([shards[2], shards[1], shards[0]], w, desc)
+    assert np.abs(swapped - ref).max() > 1e-3 * np.abs(ref).max()
+    n = O.tokens_per_tile(desc)
+    assert np.allclose(swapped[:2 * n], ref[3 * n:5 * n], rtol=0, atol=1e-12)
