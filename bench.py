@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mm-cache", action="store_true", help="skip the paged-cache encode / block-transfer leg")
     ap.add_argument("--cpu-tiles", type=int, default=0, help="slices the oracle encodes (0: bounded default)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -139,6 +140,65 @@ def main():
                             for k in gf if fam[k]["ms"] > 0},
     }
 
+    # ---- paged cache: encode into blocks of 16 tokens, then move every block to a second cache ----
+    mm = None
+    if not args.no_mm_cache and desc.tokens_per_tile % 16 == 0:
+        n_blocks = T * desc.tokens_per_tile // 16
+        e_cache = B.MMCache(n_blocks, 16, desc.out_dim, bf16)
+        p_cache = B.MMCache(n_blocks, 16, desc.out_dim, bf16)
+        tables = [e_cache.alloc((offsets[r + 1] - offsets[r]) * desc.tokens_per_tile) for r in range(wk.n_requests)]
+        p_tables = [p_cache.alloc(len(t) * 16) for t in tables]
+        flat_e = [b for t in tables for b in t]
+        flat_p = [b for t in p_tables for b in t][::-1]          # scattered destination order
+        B.encode_paged(enc, tiles, offsets, e_cache, tables)     # warm
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        n_paged = max(1, min(3, args.steps))
+        for _ in range(n_paged):
+            B.encode_paged(enc, tiles, offsets, e_cache, tables)
+        torch.cuda.synchronize()
+        paged_ms = (time.perf_counter() - t2) / n_paged * 1e3
+        e_cache.transfer_to(flat_e, p_cache, flat_p)             # warm
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_xfer = 10
+        ev0.record()
+        for _ in range(n_xfer):
+            e_cache.transfer_to(flat_e, p_cache, flat_p)
+        ev1.record()
+        torch.cuda.synchronize()
+        xfer_ms = ev0.elapsed_time(ev1) / n_xfer
+        nbytes = n_blocks * 16 * desc.out_dim * (2 if bf16 else 4)
+        mm = {"block_tokens": 16, "blocks": n_blocks, "paged_encode_ms_per_step": round(paged_ms, 3),
+              "transfer_ms": round(xfer_ms, 4), "transfer_bytes": nbytes,
+              "transfer_GBps_read_plus_write": round(2 * nbytes / (xfer_ms * 1e-3) / 1e9, 1)}
+        e_cache.close()
+        p_cache.close()
+        # projection on the prefill side: cache and move pre-projection tokens, project after the move
+        if desc.n_patches % 16 == 0:
+            nb = T * desc.n_patches // 16
+            e_pre = B.MMCache(nb, 16, desc.hidden, bf16)
+            p_pre = B.MMCache(nb, 16, desc.hidden, bf16)
+            src, dst = e_pre.alloc(nb * 16), p_pre.alloc(nb * 16)[::-1]
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            out2 = enc.alloc_out(T)
+            for it in range(2):                                   # first pass warms
+                evs[0].record()
+                B.encode_trunk_paged(enc, tiles, 0, T, e_pre, src)
+                evs[1].record()
+                e_pre.transfer_to(src, p_pre, dst)
+                evs[2].record()
+                B.project_merge(enc, p_pre, dst, T, out2)
+                evs[3].record()
+                torch.cuda.synchronize()
+            pre_bytes = nb * 16 * desc.hidden * (2 if bf16 else 4)
+            mm["prefill_side_projection"] = {
+                "trunk_ms": round(evs[0].elapsed_time(evs[1]), 3), "transfer_ms": round(evs[1].elapsed_time(evs[2]), 4),
+                "project_merge_ms": round(evs[2].elapsed_time(evs[3]), 3),
+                "transfer_bytes": pre_bytes, "bytes_vs_projected_tokens": round(pre_bytes / nbytes, 3)}
+            e_pre.close()
+            p_pre.close()
+            del out2
+
     # ---- parity spot check and CPU baseline: the oracle on a bounded sample ----
     cpu = None
     parity = None
@@ -179,6 +239,7 @@ def main():
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "mm_cache": mm,
     }
     print(json.dumps(line))
 

@@ -208,6 +208,36 @@ epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, e
 epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blocks, void* dst_contiguous,
                          void* hip_stream);
 
+/* ---- projection on the prefill side ---------------------------------------
+ *
+ * With intra-request parallelism the slices of one request are encoded on
+ * several encode workers and their tokens sent to the prefill stage, where
+ * they are put in slice order, projected and merged into the request's
+ * multimodal tokens (Section 3.2.2).  These two calls split the path at that
+ * point: the encode side stops after the encoder's last norm and caches the
+ * pre-projection tokens ([patches per slice, hidden] per slice, the encoder's
+ * dtype); the prefill side reads the shards' tokens through one block table
+ * in slice order and runs pixel shuffle (if any) and the projector.  In fp32
+ * mode the result equals epd_encode's bit for bit; in bf16 mode the cached
+ * tokens are rounded to bf16 once more than in the fused path. */
+
+/* Slices [tile_begin, tile_end) of the packed batch -> pre-projection tokens
+ * in `cache` (token_dim == hidden, patches per slice a multiple of
+ * block_tokens).  block_table (host) holds (tile_end - tile_begin) *
+ * patches_per_slice / block_tokens allocated block ids: entry 0 is the first
+ * block of slice tile_begin.  Nothing else in the cache is touched. */
+epd_status epd_encode_trunk_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles_total,
+                                  int32_t tile_begin, int32_t tile_end, epd_mm_cache* cache,
+                                  const int32_t* block_table, void* hip_stream);
+
+/* Pre-projection tokens of n_tiles slices, listed in slice order by
+ * block_table (n_tiles * patches_per_slice / block_tokens ids of `cache`,
+ * whichever shard or transfer filled them) -> out_tokens, a contiguous dev
+ * buffer [n_tiles * epd_tokens_per_tile, epd_out_dim] of the encoder's dtype
+ * (16-byte aligned).  The cache is only read. */
+epd_status epd_project_merge(epd_ctx* ctx, const epd_mm_cache* cache, const int32_t* block_table,
+                             int32_t n_tiles, void* out_tokens, void* hip_stream);
+
 /* ---- measurement and test hooks (not needed to serve) ------------------ */
 
 /* Copy the residual stream (float32 [rows, D], the encoder state after the

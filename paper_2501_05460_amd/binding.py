@@ -34,6 +34,7 @@ EXPORTS = (
     "epd_profile_enable", "epd_profile_read",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_gather",
+    "epd_encode_trunk_paged", "epd_project_merge",
 )
 
 
@@ -120,6 +121,10 @@ def lib() -> ctypes.CDLL:
         L.epd_mm_transfer.restype = i32
         L.epd_mm_gather.argtypes = [vp, ctypes.POINTER(i32), i32, vp, vp]
         L.epd_mm_gather.restype = i32
+        L.epd_encode_trunk_paged.argtypes = [vp, vp, i32, i32, i32, vp, ctypes.POINTER(i32), vp]
+        L.epd_encode_trunk_paged.restype = i32
+        L.epd_project_merge.argtypes = [vp, vp, ctypes.POINTER(i32), i32, vp, vp]
+        L.epd_project_merge.restype = i32
         _lib = L
     return _lib
 
@@ -314,6 +319,26 @@ def encode_paged(enc: "Encoder", tiles: torch.Tensor, tile_offsets: Sequence[int
                                len(tile_offsets) - 1, cache._h, _i32(flat or [0]), _i32(offs), _stream_ptr())
     if s != EPD_OK:
         enc._raise(s)
+
+
+def encode_trunk_paged(enc: "Encoder", tiles: torch.Tensor, tile_begin: int, tile_end: int, cache: MMCache,
+                       block_table: Sequence[int]):
+    """Slices [tile_begin, tile_end) -> pre-projection tokens in `cache`, blocks in slice order."""
+    s = lib().epd_encode_trunk_paged(enc._h, tiles.data_ptr(), int(tiles.shape[0]), tile_begin, tile_end,
+                                     cache._h, _i32(block_table or [0]), _stream_ptr())
+    if s != EPD_OK:
+        enc._raise(s)
+
+
+def project_merge(enc: "Encoder", cache: MMCache, block_table: Sequence[int], n_tiles: int,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Pre-projection tokens listed by `block_table` (slice order) -> merged multimodal tokens."""
+    if out is None:
+        out = enc.alloc_out(n_tiles)
+    s = lib().epd_project_merge(enc._h, cache._h, _i32(block_table or [0]), n_tiles, out.data_ptr(), _stream_ptr())
+    if s != EPD_OK:
+        enc._raise(s)
+    return out
 
 
 def op_gemm_bf16(A: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], iters: int = 1):

@@ -167,9 +167,10 @@ struct epd_ctx {
   long last_rows = 0;
 
   // paged output (epd_encode_paged): device row-block map of the current micro-batch
-  int* d_rowmap = nullptr;       // [mb * N_out] ints (enough for any block size)
+  int* d_rowmap = nullptr;       // [mb * N] ints (enough for any block size, trunk or projector rows)
   const int* cur_rowmap = nullptr;  // null: contiguous output
   int cur_block_tokens = 1;
+  const void* cur_in_pool = nullptr;  // STAGE_PROJECT: cache pool the pre-projection tokens are read from
 
   // profiling
   bool prof = false;
@@ -352,7 +353,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   bool ok = true;
   auto ws = [&](size_t bytes) { void* p = dalloc(c, bytes, true, st); ok = ok && p; return p; };
   c->X = (float*)ws((size_t)c->Mp * x.D * sizeof(float));
-  c->d_rowmap = (int*)ws((size_t)Mo * sizeof(int));
+  c->d_rowmap = (int*)ws((size_t)M * sizeof(int));
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
     c->QKV = ws((size_t)c->Mp * 2 * c->Dq * 2);
@@ -380,7 +381,13 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
 // --------------------------------------------------------------------------
 // one micro-batch, fp32 mode
 // --------------------------------------------------------------------------
-epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_t st) {
+// Which part of the path one call runs.  TRUNK stops after the final norm and writes the
+// pre-projection tokens [N, hidden] of every slice into a paged cache; PROJECT starts from such
+// tokens (read through a block table) and runs pixel shuffle + projector (Section 3.2.2: shards
+// are aligned, projected and merged on the prefill side).
+enum Stage { STAGE_FULL = 0, STAGE_TRUNK = 1, STAGE_PROJECT = 2 };
+
+epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_t st, int stage) {
   const epd_model_desc& d = c->d;
   const Dims& x = c->x;
   const int M = T * x.N, Mo = T * x.N_out;
@@ -389,10 +396,14 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
   const int act_epi = d.act == EPD_ACT_GELU_ERF ? EPI_BIAS_GELU_ERF : EPI_BIAS_GELU_TANH;
   const float scale = 1.0f / sqrtf((float)x.hd);
 
-  { ProfScope ps(c, 0, st);
+  if (stage == STAGE_PROJECT) {
+    ProfScope ps(c, 5, st);
+    blocks_to_stream(c->cur_in_pool, 0, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, M, st);
+  } else {
+    ProfScope ps(c, 0, st);
     f32_im2col(tiles, Ape, T, x.S, x.p, st);
     f32_gemm(EPI_BIAS_POS, Ape, x.Kp, (const float*)c->pe.W, c->pe.b, X, x.D, c->pos, x.N, M, x.D, x.Kp, st); }
-  for (int l = 0; l < x.L; ++l) {
+  for (int l = 0; l < (stage == STAGE_PROJECT ? 0 : x.L); ++l) {
     const LayerW& w = c->layers[l];
     { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n1_g, w.n1_b, M, x.D, 1, d.eps, st); }
     { ProfScope ps(c, 2, st); f32_gemm(EPI_BIAS, Xn, x.D, (const float*)w.qkv.W, w.qkv.b, QKV, 3 * x.D, nullptr, 1, M, 3 * x.D, x.D, st); }
@@ -411,7 +422,13 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
     { ProfScope ps(c, 7, st); f32_gemm(act_epi, Xn, x.D, (const float*)w.fc1.W, w.fc1.b, Hd, x.F, nullptr, 1, M, x.F, x.D, st); }
     { ProfScope ps(c, 8, st); f32_gemm(EPI_BIAS_RESIDUAL, Hd, x.F, (const float*)w.fc2.W, w.fc2.b, X, x.D, nullptr, 1, M, x.D, x.F, st); }
   }
-  if (d.final_norm) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  if (d.final_norm && stage != STAGE_PROJECT) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  if (stage == STAGE_TRUNK) {
+    ProfScope ps(c, 5, st);
+    stream_to_blocks(X, x.D, out, 0, x.D, c->d_rowmap, c->cur_block_tokens, M, st);
+    HIP_TRY(c, hipGetLastError());
+    return EPD_OK;
+  }
   const float* pin = X;
   { ProfScope ps(c, 5, st);
     if (d.pixel_shuffle) { f32_shuffle(X, Pin, T, x.g, x.D, st); pin = Pin; }
@@ -440,7 +457,7 @@ GemmParams gp(int epi, const void* A, long lda, const Linear& lin, int M) {
   return p;
 }
 
-epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStream_t st) {
+epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStream_t st, int stage) {
   const epd_model_desc& d = c->d;
   const Dims& x = c->x;
   const int M = T * x.N, Mo = T * x.N_out;
@@ -451,12 +468,16 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   const float scale = 1.0f / sqrtf((float)x.hd);
   const long ld_qk = 2L * c->Dq;
 
-  { ProfScope ps(c, 0, st);
+  if (stage == STAGE_PROJECT) {
+    ProfScope ps(c, 5, st);
+    blocks_to_stream(c->cur_in_pool, 1, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, M, st);
+  } else {
+    ProfScope ps(c, 0, st);
     bf16_im2col(tiles, Ape, c->Kp_k, T, x.S, x.p, st);
     GemmParams p = gp(EPI_BIAS_POS, Ape, c->Kp_k, c->pe, M);
     p.R = X; p.ldr = x.D; p.pos = c->pos; p.n_pos = x.N;
     HIP_TRY(c, bf16_gemm(p, st)); }
-  for (int l = 0; l < x.L; ++l) {
+  for (int l = 0; l < (stage == STAGE_PROJECT ? 0 : x.L); ++l) {
     const LayerW& w = c->layers[l];
     { ProfScope ps(c, 1, st);
       RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n1_g, w.n1_b, M, x.D, 0, x.g, x.D, d.eps};
@@ -496,7 +517,13 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       p2.R = X; p2.ldr = x.D;
       HIP_TRY(c, bf16_gemm(p2, st)); }
   }
-  if (d.final_norm) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  if (d.final_norm && stage != STAGE_PROJECT) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
+  if (stage == STAGE_TRUNK) {
+    ProfScope ps(c, 5, st);
+    stream_to_blocks(X, x.D, out, 1, x.D, c->d_rowmap, c->cur_block_tokens, M, st);
+    HIP_TRY(c, hipGetLastError());
+    return EPD_OK;
+  }
   { ProfScope ps(c, 5, st);
     RowOpParams r{d.proj_prenorm ? 0 : 2, X, x.D, Pin, c->Pin_k, c->pn_g, c->pn_b, Mo, x.Pin, d.pixel_shuffle, x.g, x.D, d.eps};
     bf16_rowop(r, st); }
@@ -519,16 +546,23 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   return EPD_OK;
 }
 
-// `block_map` (host, may be null): physical block of every logical block of `block_tokens` output
-// rows of the packed batch; with it `out` is the base of a paged pool instead of a contiguous cache.
+// One call over slices [b, e) in micro-batches.
+//   STAGE_FULL, block_map null: `out` is the contiguous token cache of the packed batch.
+//   STAGE_FULL, block_map set:  `out` is a paged pool; block_map[i] is the physical block of logical
+//                               block i of the packed batch's output rows (N_out rows per slice).
+//   STAGE_TRUNK:   `out` is a paged pool of [hidden]-wide tokens; block_map covers the N rows per slice
+//                  of slices [b, e) only, starting at slice b.
+//   STAGE_PROJECT: `tiles` unused; `in_pool` + block_map (N rows per slice, slices [b, e)) are the input
+//                  and `out` is the contiguous merged token buffer (row 0 = first token of slice b).
 epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, int32_t b, int32_t e, void* out,
-                             hipStream_t st, const int32_t* block_map = nullptr, int block_tokens = 1) {
+                             hipStream_t st, const int32_t* block_map = nullptr, int block_tokens = 1,
+                             int stage = STAGE_FULL, const void* in_pool = nullptr) {
   if (b < 0 || e < b || e > n_total) {
     set_err(c->err, sizeof(c->err), "tile range [%d, %d) is not inside [0, %d]", b, e, n_total);
     return EPD_ERR_OFFSETS;
   }
   if (e == b) return EPD_OK;
-  if (!tiles || !out) { set_err(c->err, sizeof(c->err), "tiles / out_token_cache is null"); return EPD_ERR_INVALID_ARG; }
+  if ((stage != STAGE_PROJECT && !tiles) || !out) { set_err(c->err, sizeof(c->err), "tiles / out_token_cache is null"); return EPD_ERR_INVALID_ARG; }
   if (((uintptr_t)tiles & 15) || ((uintptr_t)out & 15)) {
     set_err(c->err, sizeof(c->err), "tiles and out_token_cache must be 16-byte aligned");
     return EPD_ERR_INVALID_ARG;
@@ -536,23 +570,29 @@ epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, in
   const Dims& x = c->x;
   const size_t tile_elems = (size_t)3 * x.S * x.S;
   const size_t out_row_bytes = (size_t)x.Pout * (c->bf16 ? 2 : 4);
+  // rows per slice the block map speaks about, and the slice its entry 0 belongs to
+  const int map_rows = stage == STAGE_FULL ? x.N_out : x.N;
+  const int map_origin = stage == STAGE_FULL ? 0 : b;
+  const int out_origin = stage == STAGE_PROJECT ? b : 0;
   if (c->prof) { c->ev_used = 0; c->ev_family.clear(); }
   for (int t0 = b; t0 < e; t0 += c->mb) {
     const int T = (e - t0) < c->mb ? (e - t0) : c->mb;
-    const float* tp = tiles + (size_t)t0 * tile_elems;
-    char* op = (char*)out + (size_t)t0 * x.N_out * out_row_bytes;
+    const float* tp = tiles ? tiles + (size_t)t0 * tile_elems : nullptr;
+    char* op = (char*)out + (size_t)(t0 - out_origin) * x.N_out * out_row_bytes;
     c->cur_rowmap = nullptr;
     c->cur_block_tokens = 1;
+    c->cur_in_pool = in_pool;
     if (block_map) {
       // this micro-batch's slice of the map; the copy is stream-ordered behind the previous micro-batch
-      const size_t first = (size_t)t0 * x.N_out / block_tokens, count = (size_t)T * x.N_out / block_tokens;
+      const size_t first = (size_t)(t0 - map_origin) * map_rows / block_tokens, count = (size_t)T * map_rows / block_tokens;
       HIP_TRY(c, hipMemcpyAsync(c->d_rowmap, block_map + first, count * sizeof(int), hipMemcpyHostToDevice, st));
-      c->cur_rowmap = c->d_rowmap;
       c->cur_block_tokens = block_tokens;
-      op = (char*)out;
+      if (stage == STAGE_FULL) c->cur_rowmap = c->d_rowmap;   // final GEMM scatters through the map
+      if (stage != STAGE_PROJECT) op = (char*)out;            // paged output: `out` is the pool base
     }
-    epd_status s = c->bf16 ? run_bf16(c, tp, T, (bf16_t*)op, st) : run_f32(c, tp, T, (float*)op, st);
+    epd_status s = c->bf16 ? run_bf16(c, tp, T, (bf16_t*)op, st, stage) : run_f32(c, tp, T, (float*)op, st, stage);
     c->cur_rowmap = nullptr;
+    c->cur_in_pool = nullptr;
     if (s != EPD_OK) return s;
     c->last_rows = (long)T * x.N;
   }
@@ -680,6 +720,60 @@ epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles, c
   // per-request tables are the logical-block -> physical-block map of the packed batch
   return encode_range_impl(ctx, tiles, n_tiles, 0, n_tiles, cache->pool, (hipStream_t)hip_stream, block_table,
                            cache->block_tokens);
+}
+
+namespace {
+// cache shape against a token width, and `count` table entries against the block manager
+epd_status check_cache_table(epd_ctx* ctx, const epd_mm_cache* cache, int token_dim, int rows_per_slice,
+                             const int32_t* table, long count) {
+  if (!cache || !table) { set_err(ctx->err, sizeof(ctx->err), "cache / block_table is null"); return EPD_ERR_INVALID_ARG; }
+  if (!cache->pool || cache->token_dim != token_dim || cache->dtype != ctx->d.dtype) {
+    set_err(ctx->err, sizeof(ctx->err), "cache token width / dtype (%d, %d) does not match the encoder (%d, %d)",
+            cache->token_dim, cache->dtype, token_dim, ctx->d.dtype);
+    return EPD_ERR_SHAPE;
+  }
+  if (rows_per_slice % cache->block_tokens) {
+    set_err(ctx->err, sizeof(ctx->err), "tokens per slice %d is not a multiple of the block size %d", rows_per_slice,
+            cache->block_tokens);
+    return EPD_ERR_UNSUPPORTED;
+  }
+  for (long i = 0; i < count; ++i)
+    if (table[i] < 0 || table[i] >= cache->n_blocks || !cache->used[table[i]]) {
+      set_err(ctx->err, sizeof(ctx->err), "block table entry %ld (%d) is out of range or not allocated", i, table[i]);
+      return EPD_ERR_OFFSETS;
+    }
+  return EPD_OK;
+}
+}  // namespace
+
+epd_status epd_encode_trunk_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles_total, int32_t tile_begin,
+                                  int32_t tile_end, epd_mm_cache* cache, const int32_t* block_table,
+                                  void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  if (tile_begin < 0 || tile_end < tile_begin || tile_end > n_tiles_total) {
+    set_err(ctx->err, sizeof(ctx->err), "tile range [%d, %d) is not inside [0, %d]", tile_begin, tile_end, n_tiles_total);
+    return EPD_ERR_OFFSETS;
+  }
+  if (tile_end == tile_begin) return EPD_OK;
+  const Dims& x = ctx->x;
+  const long count = cache && cache->block_tokens > 0 ? (long)(tile_end - tile_begin) * (x.N / cache->block_tokens) : 0;
+  epd_status s = check_cache_table(ctx, cache, x.D, x.N, block_table, count);
+  if (s != EPD_OK) return s;
+  return encode_range_impl(ctx, tiles, n_tiles_total, tile_begin, tile_end, cache->pool, (hipStream_t)hip_stream,
+                           block_table, cache->block_tokens, STAGE_TRUNK);
+}
+
+epd_status epd_project_merge(epd_ctx* ctx, const epd_mm_cache* cache, const int32_t* block_table, int32_t n_tiles,
+                             void* out_tokens, void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  if (n_tiles < 0) { set_err(ctx->err, sizeof(ctx->err), "n_tiles is negative"); return EPD_ERR_OFFSETS; }
+  if (n_tiles == 0) return EPD_OK;
+  const Dims& x = ctx->x;
+  const long count = cache && cache->block_tokens > 0 ? (long)n_tiles * (x.N / cache->block_tokens) : 0;
+  epd_status s = check_cache_table(ctx, cache, x.D, x.N, block_table, count);
+  if (s != EPD_OK) return s;
+  return encode_range_impl(ctx, nullptr, n_tiles, 0, n_tiles, out_tokens, (hipStream_t)hip_stream, block_table,
+                           cache->block_tokens, STAGE_PROJECT, cache->pool);
 }
 
 int64_t epd_tokens_per_tile(const epd_ctx* ctx) { return ctx ? ctx->x.N_out : -1; }

@@ -82,6 +82,13 @@ void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_
 void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, const int* dst_ids,
                     int n_blocks, long block_bytes, hipStream_t st);
 
+// fp32 residual-stream rows <-> rows of a paged cache of fp32 or bf16 tokens of the same width.
+// Row r of the stream is token r % block_tokens of block row_map[r / block_tokens].
+void stream_to_blocks(const float* X, long ldx, void* pool, int pool_is_bf16, int dim, const int* row_map,
+                      int block_tokens, long rows, hipStream_t st);
+void blocks_to_stream(const void* pool, int pool_is_bf16, int dim, const int* row_map, int block_tokens,
+                      float* X, long ldx, long rows, hipStream_t st);
+
 // MFMA lane-layout check: D[32,32] = A[32,16] * B[16,32] with operands loaded
 // and the result stored under the layout the kernels assume.
 void mfma_probe(const bf16_t* A, const bf16_t* B, float* D, hipStream_t st);

@@ -226,27 +226,85 @@ void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_
 }
 
 // ------------------------------------------------- paged cache block copy ----
-// One workgroup row per block; 16 bytes per thread and step.  HBM-bound.
+// `per_block` consecutive workgroups share one cache block, each moving chunks
+// of 16 KiB: a thread issues four 16-byte loads before the four stores, so a
+// wave keeps 4 KiB in flight.  Streaming (nontemporal) on both sides: nothing
+// is read twice.  HBM-bound: every byte is read once and written once.
 __global__ __launch_bounds__(256) void k_mm_copy_blocks(const unsigned char* __restrict__ src_pool,
                                                         const int* __restrict__ src_ids,
                                                         unsigned char* __restrict__ dst_pool,
-                                                        const int* __restrict__ dst_ids, long block_bytes) {
-  const int b = blockIdx.y;
+                                                        const int* __restrict__ dst_ids, long block_bytes,
+                                                        int per_block) {
+  const int b = blockIdx.x / per_block, part = blockIdx.x % per_block;
   const long sb = src_ids ? src_ids[b] : b, db = dst_ids ? dst_ids[b] : b;
   const u32x4* s = reinterpret_cast<const u32x4*>(src_pool + sb * block_bytes);
   u32x4* d = reinterpret_cast<u32x4*>(dst_pool + db * block_bytes);
   const long n16 = block_bytes >> 4;
-  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256) d[i] = s[i];
+  for (long base = (long)part * 1024; base < n16; base += (long)per_block * 1024) {
+    const long i = base + threadIdx.x;
+    u32x4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (i + j * 256 < n16) v[j] = __builtin_nontemporal_load(s + i + j * 256);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (i + j * 256 < n16) __builtin_nontemporal_store(v[j], d + i + j * 256);
+  }
 }
 
 void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, const int* dst_ids,
                     int n_blocks, long block_bytes, hipStream_t st) {
   if (n_blocks <= 0 || block_bytes <= 0) return;
   const long n16 = block_bytes >> 4;
-  int gx = (int)((n16 + 255) / 256);
-  if (gx > 8) gx = 8;
-  k_mm_copy_blocks<<<dim3(gx, n_blocks), dim3(256), 0, st>>>((const unsigned char*)src_pool, src_ids,
-                                                             (unsigned char*)dst_pool, dst_ids, block_bytes);
+  int per_block = (int)((n16 + 1023) / 1024);  // one 16 KiB chunk per workgroup while the grid stays modest
+  if (per_block < 1) per_block = 1;
+  if (per_block > 8) per_block = 8;
+  k_mm_copy_blocks<<<dim3((unsigned)n_blocks * per_block), dim3(256), 0, st>>>(
+      (const unsigned char*)src_pool, src_ids, (unsigned char*)dst_pool, dst_ids, block_bytes, per_block);
+}
+
+// ------------------------------------- residual stream <-> paged cache rows ----
+// One thread per element; consecutive threads walk one row, so both sides are
+// coalesced.  TO_POOL: stream -> cache (rounding to the cache's type), else the
+// reverse (exact widening).
+template <typename T, bool TO_POOL>
+__global__ __launch_bounds__(256) void k_stream_blocks(float* X, long ldx, T* pool, int dim,
+                                                       const int* __restrict__ row_map, int block_tokens,
+                                                       long total) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+    const long r = i / dim;
+    const int c = (int)(i % dim);
+    const long prow = (long)row_map[r / block_tokens] * block_tokens + r % block_tokens;
+    if (TO_POOL) pool[prow * dim + c] = (T)X[r * ldx + c];
+    else X[r * ldx + c] = (float)pool[prow * dim + c];
+  }
+}
+
+static unsigned stream_blocks_grid(long total) {
+  long g = (total + 255) / 256;
+  return (unsigned)(g > 65536 ? 65536 : g);
+}
+
+void stream_to_blocks(const float* X, long ldx, void* pool, int pool_is_bf16, int dim, const int* row_map,
+                      int block_tokens, long rows, hipStream_t st) {
+  const long total = rows * dim;
+  if (total <= 0) return;
+  const dim3 grid(stream_blocks_grid(total)), block(256);
+  if (pool_is_bf16)
+    k_stream_blocks<bf16_t, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, (bf16_t*)pool, dim, row_map, block_tokens, total);
+  else
+    k_stream_blocks<float, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, (float*)pool, dim, row_map, block_tokens, total);
+}
+
+void blocks_to_stream(const void* pool, int pool_is_bf16, int dim, const int* row_map, int block_tokens,
+                      float* X, long ldx, long rows, hipStream_t st) {
+  const long total = rows * dim;
+  if (total <= 0) return;
+  const dim3 grid(stream_blocks_grid(total)), block(256);
+  if (pool_is_bf16)
+    k_stream_blocks<bf16_t, false><<<grid, block, 0, st>>>(X, ldx, (bf16_t*)pool, dim, row_map, block_tokens, total);
+  else
+    k_stream_blocks<float, false><<<grid, block, 0, st>>>(X, ldx, (float*)pool, dim, row_map, block_tokens, total);
 }
 
 // ------------------------------------------------------------ MFMA probe ----
