@@ -48,11 +48,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mm-cache", action="store_true", help="skip the paged-cache encode / block-transfer leg")
     ap.add_argument("--cpu-tiles", type=int, default=0, help="slices the oracle encodes (0: bounded default)")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also encode the batch in FCFS groups of 1, 2, 4, ... requests per call (maximum encode "
+                         "batch size) and report per-call latency and throughput for each")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -140,6 +143,30 @@ def main():
                             for k in gf if fam[k]["ms"] > 0},
     }
 
+    # ---- maximum encode batch size: latency of one call against throughput ----
+    sweep = None
+    if args.batch_sweep:
+        sweep = []
+        n_out = desc.tokens_per_tile
+        b = 1
+        while True:
+            groups = [(r, min(r + b, wk.n_requests)) for r in range(0, wk.n_requests, b)]
+            lat = []
+            for rep in range(2):                                  # first pass warms
+                evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(groups) + 1)]
+                evs[0].record()
+                for gi, (r0, r1) in enumerate(groups):
+                    t_lo, t_hi = offsets[r0], offsets[r1]
+                    enc.encode(tiles[t_lo:t_hi], [o - t_lo for o in offsets[r0:r1 + 1]], out[t_lo * n_out:t_hi * n_out])
+                    evs[gi + 1].record()
+                torch.cuda.synchronize()
+                lat = [evs[i].elapsed_time(evs[i + 1]) for i in range(len(groups))]
+            sweep.append({"max_batch_requests": b, "calls": len(groups), "mean_call_ms": round(sum(lat) / len(lat), 3),
+                          "max_call_ms": round(max(lat), 3), "tiles_per_s": round(T / (sum(lat) * 1e-3), 1)})
+            if b >= wk.n_requests:
+                break
+            b *= 2
+
     # ---- paged cache: encode into blocks of 16 tokens, then move every block to a second cache ----
     mm = None
     if not args.no_mm_cache and desc.tokens_per_tile % 16 == 0:
@@ -204,7 +231,7 @@ def main():
     parity = None
     if not args.no_cpu_baseline:
         from oracle import epd_oracle as O
-        n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2}[args.workload]
+        n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2, "c6": 2}[args.workload]
         sample = list(wk.oracle_sample_tiles)[:n_cpu]
         w_host = wl.gen_weights(desc, wk.weight_seed)
         host_tiles = [wl.gen_tile(desc, wk.input_seed, t) for t in sample]
@@ -240,6 +267,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "mm_cache": mm,
+        "batch_sweep": sweep,
     }
     print(json.dumps(line))
 

@@ -97,3 +97,23 @@ def test_c4_internvit6b_shape_40_slices():
     assert bool(torch.isfinite(out.float()).all())
     check_sample(wk, enc, out, wk.oracle_sample_tiles)
     enc.close()
+
+
+def test_c6_video_requests_batched_equals_one_request_per_call_and_oracle():
+    """Video workload: 16 requests of 8 to 64 frames, one slice per frame.  Encoding every request in
+    its own call (maximum encode batch size 1) gives the bits of the one batched call."""
+    wk = wl.workload("c6")
+    enc, tiles = build(wk)
+    off = list(wk.tile_offsets)
+    n = enc.tokens_per_tile
+    full = enc.encode(tiles, off)
+    torch.cuda.synchronize()
+    assert full.shape == (480 * 1024, 3584)
+    out = enc.alloc_out(wk.n_tiles)
+    out.fill_(-3.0)
+    for r in range(wk.n_requests):
+        enc.encode(tiles[off[r]:off[r + 1]], [0, off[r + 1] - off[r]], out[off[r] * n:off[r + 1] * n])
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), full.view(torch.int16))
+    check_sample(wk, enc, full, wk.oracle_sample_tiles)
+    enc.close()

@@ -131,6 +131,13 @@ DESC_C4 = _desc(hidden=3200, heads=25, mlp=12800, layers=45, norm=NORM_RMSNORM,
                 proj_mid=5120, proj_out=5120, max_tiles_per_call=40)
 
 
+def _video_structure(seed: int, per_length: int = 4) -> Tuple[int, ...]:
+    """Frames per request: `per_length` requests of each of 8, 16, 32 and 64 frames, in a seeded order."""
+    frames = np.repeat(np.array([8, 16, 32, 64]), per_length)
+    np.random.default_rng([seed, 0]).shuffle(frames)
+    return tuple(int(f) for f in frames)
+
+
 def _prefix(counts) -> Tuple[int, ...]:
     off = [0]
     for c in counts:
@@ -176,10 +183,18 @@ def workload(name: str) -> Workload:
         desc = DESC_C2.replace(max_tiles_per_call=128)
         return Workload("c5_mixed_siglip_32req", desc, 1002, 1005, off, image_tiles,
                         tuple(sorted(sample)))
+    if name == "c6":
+        # Video requests (Section 4.2, the table of latency versus number of frames): 8, 16, 32 or 64
+        # sampled frames per request, every frame one 448x448 slice of a SigLIP-shaped encoder.
+        frames = _video_structure(1006)
+        off = _prefix(frames)
+        desc = DESC_C2.replace(max_tiles_per_call=128)
+        return Workload("c6_video_siglip_16req", desc, 1002, 1006, off, tuple((1,) * f for f in frames),
+                        (0, off[len(frames) // 2], off[-1] - 1))
     raise KeyError(name)
 
 
-ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5")
+ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c6")
 
 
 def shard_range(n_tiles: int, shard: int, n_shards: int) -> Tuple[int, int]:
