@@ -111,18 +111,67 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   const bf16_t* gA = p.A + (long)(m0 + ld_row) * p.lda + ld_c * 8;
   const bf16_t* gB = p.W + (long)(n0 + ld_row) * p.K + ld_c * 8;
 
+  // Residual epilogue: the tile's fp32 rows are added in passes of 64 token
+  // rows; the rows of pass p wait in register set p % 2, loaded two passes
+  // ahead (the first two while the last slabs are multiplied), so the
+  // read-modify-write never waits for memory with the MFMA pipe idle.
+  constexpr int XROWS = 64;                          // token rows per fp32 epilogue pass
+  constexpr int XNCH = BN * 4 / 16;                  // 16-byte chunks per staging row
+  constexpr int XPER_T = XROWS * XNCH / NTHREADS;    // chunks per thread and pass
+  constexpr int XSTEP = NTHREADS / XNCH;             // rows between a thread's consecutive chunks
+  static_assert(NTHREADS % XNCH == 0, "a thread keeps one chunk column");
+  // chunk i of a thread: tile row tid / XNCH + XSTEP * i (the same for a whole
+  // wave), column chunk tid % XNCH: one lane offset serves every access, the
+  // row part of the address is wave-uniform
+  const int x_r0 = XNCH % 64 == 0 ? __builtin_amdgcn_readfirstlane(tid / XNCH) : tid / XNCH;  // wave-uniform when a row is >= 64 chunks
+  const int x_col = n0 + (tid % XNCH) * 4;
+  const bool x_col_ok = x_col < p.N;
+  const unsigned x_voff = (unsigned)x_r0 * (unsigned)p.ldr + (unsigned)x_col;
+  // the operand register sets can carry the first two passes when the counts match
+  constexpr bool X_IN_LOOP = EPI == EPI_BIAS_RESIDUAL && NBUF == 2 && !(NTHREADS == 256 && WN == 128) &&
+                             XPER_T == A_LD + B_LD;
+  f32x4 xr[2][X_IN_LOOP ? XPER_T : 1];
+  auto xload = [&](auto set, int pass) {
+    if constexpr (X_IN_LOOP) {
+      constexpr int S = decltype(set)::value;
+      if (x_col_ok) {
+#pragma unroll
+        for (int i = 0; i < XPER_T; ++i) {
+          const int row0 = m0 + pass * XROWS + XSTEP * i;            // uniform
+          if (row0 + x_r0 < p.M) xr[S][i] = *reinterpret_cast<const f32x4*>(p.R + (long)row0 * p.ldr + x_voff);
+        }
+      }
+    }
+  };
+
+
   // Two register sets: the loads of slab k+2 are in flight while slab k is
   // multiplied and slab k+1 (loaded one iteration earlier) moves to LDS.
   u32x4 ra[NBUF][A_LD], rb[NBUF][B_LD];
   auto gload = [&](auto set, int kt) {
     constexpr int S = decltype(set)::value;
-    kt = kt < KT_ ? kt : KT_ - 1;  // past the end: re-read the last slab, result unused
+    // Residual epilogue: the two loads past the last slab (kt == KT_ into set
+    // 0, KT_ + 1 into set 1) fetch the fp32 rows of the first two epilogue
+    // passes into the same registers instead of re-reading operands.
+    const bool past = kt >= KT_;
+    const int xpass = kt - KT_;
+    kt = past ? KT_ - 1 : kt;  // past the end (other epilogues): re-read the last slab, result unused
+    // branch-free choice between the operand chunk and residual chunk i of pass xpass
+    auto pick = [&](const bf16_t* operand, int i) -> const u32x4* {
+      if constexpr (X_IN_LOOP) {
+        const int row0 = m0 + xpass * XROWS + XSTEP * i;
+        const bool take = past & x_col_ok & (row0 + x_r0 < p.M);
+        const uintptr_t a = reinterpret_cast<uintptr_t>(operand);
+        const uintptr_t x = reinterpret_cast<uintptr_t>(p.R + (long)row0 * p.ldr + x_voff);
+        return reinterpret_cast<const u32x4*>(a ^ ((a ^ x) & (uintptr_t)0 - (uintptr_t)take));
+      } else {
+        return reinterpret_cast<const u32x4*>(operand);
+      }
+    };
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i)
-      ra[S][i] = *reinterpret_cast<const u32x4*>(gA + (long)(ROWS_PER_LD * i) * p.lda + kt * BK);
+    for (int i = 0; i < A_LD; ++i) ra[S][i] = *pick(gA + (long)(ROWS_PER_LD * i) * p.lda + kt * BK, i);
 #pragma unroll
-    for (int i = 0; i < B_LD; ++i)
-      rb[S][i] = *reinterpret_cast<const u32x4*>(gB + (long)(ROWS_PER_LD * i) * p.K + kt * BK);
+    for (int i = 0; i < B_LD; ++i) rb[S][i] = *pick(gB + (long)(ROWS_PER_LD * i) * p.K + kt * BK, A_LD + i);
   };
   auto sstore = [&](auto set, int buf) {
     constexpr int S = decltype(set)::value;
@@ -166,6 +215,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
 
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
+
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -229,14 +279,22 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     sstore(S0{}, 0);
     __syncthreads();
     for (int kt = 0; kt < KT_; kt += 2) {
-      gload(S0{}, kt + 2);
+      gload(S0{}, kt + 2);   // past the last slab: residual rows of epilogue pass 0 (see gload)
       compute(0);
       sstore(S1{}, 1);
       __syncthreads();
-      gload(S1{}, kt + 3);
+      gload(S1{}, kt + 3);   // ... and of pass 1
       compute(1);
+      if (X_IN_LOOP && kt + 2 >= KT_) break;   // nothing left to hand over
       sstore(S0{}, 0);
       __syncthreads();
+    }
+    if constexpr (X_IN_LOOP) {
+#pragma unroll
+      for (int i = 0; i < XPER_T; ++i) {
+        xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
+        xr[1][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[1][i < A_LD ? i : 0] : rb[1][i < A_LD ? 0 : i - A_LD]);
+      }
     }
   } else {
     gload(S0{}, 0);
@@ -261,46 +319,54 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   unsigned char* stage = smem;
 
   if (EPI == EPI_BIAS_RESIDUAL || EPI == EPI_BIAS_POS) {
-    // fp32 staging, 128 token rows per pass: [128][BN] floats
+    // fp32 staging, XROWS token rows per pass: [XROWS][BN] floats
     constexpr int ROWB = BN * 4;          // bytes per staging row
-    constexpr int NCH = ROWB / 16;        // 16-byte chunks per row
-    constexpr int PASSES = BM / 128;
-    constexpr int PER_T = 128 * NCH / NTHREADS;
-#pragma unroll
-    for (int pass = 0; pass < PASSES; ++pass) {
+    constexpr int PASSES = BM / XROWS;
+    auto fp32_pass = [&](auto set, int pass) {
+      constexpr int S = decltype(set)::value;
       if (pass > 0) __syncthreads();
-      if ((wm * WM) / 128 == pass) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int r = (wm * WM) % 128 + i * 32 + l32;
+      for (int i = 0; i < TM; ++i) {
+        const int base = wm * WM + i * 32;            // first tile row of this 32-row group
+        if (base / XROWS != pass) continue;            // wave-uniform
+        const int r = base % XROWS + l32;
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int gi = 0; gi < 4; ++gi) {
-              const int cl = wn * WN + j * 32 + gi * 8 + lh * 4;  // column inside the tile
-              const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
-              f32x4 v = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
-                         acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
-              *reinterpret_cast<f32x4*>(stage + r * ROWB + (((cl >> 2) ^ (r & 15)) << 4)) = v;
-            }
-        }
+          for (int gi = 0; gi < 4; ++gi) {
+            const int cl = wn * WN + j * 32 + gi * 8 + lh * 4;  // column inside the tile
+            const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
+            f32x4 v = {acc[i][j][gi * 4 + 0] + b4.x, acc[i][j][gi * 4 + 1] + b4.y,
+                       acc[i][j][gi * 4 + 2] + b4.z, acc[i][j][gi * 4 + 3] + b4.w};
+            *reinterpret_cast<f32x4*>(stage + r * ROWB + (((cl >> 2) ^ (r & 15)) << 4)) = v;
+          }
       }
       __syncthreads();
+      if (x_col_ok) {
+        const int c = tid % XNCH;
 #pragma unroll
-      for (int i = 0; i < PER_T; ++i) {
-        const int q = tid + NTHREADS * i;
-        const int r = q / NCH, c = q % NCH;
-        const int row = m0 + pass * 128 + r, col = n0 + c * 4;
-        if (row < p.M && col < p.N) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
-          f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + col);
-          if (EPI == EPI_BIAS_RESIDUAL) {
-            *dst = *dst + v;
-          } else {
-            *dst = v + *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + col);
+        for (int i = 0; i < XPER_T; ++i) {
+          const int r = x_r0 + XSTEP * i;
+          const int row0 = m0 + pass * XROWS + XSTEP * i;              // uniform
+          if (row0 + x_r0 < p.M) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
+            f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)row0 * p.ldr + x_voff);
+            if (EPI == EPI_BIAS_RESIDUAL) {
+              if constexpr (X_IN_LOOP) *dst = xr[S][i] + v;
+              else *dst = *dst + v;      // other tile shapes: plain read-modify-write
+            } else {
+              const int row = row0 + x_r0;
+              *dst = v + *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + x_col);
+            }
           }
         }
       }
+      if (pass + 2 < PASSES) xload(set, pass + 2);
+    };
+#pragma unroll
+    for (int pass = 0; pass < PASSES; pass += 2) {
+      fp32_pass(S0{}, pass);
+      fp32_pass(S1{}, pass + 1);
     }
   } else {
   // bf16 staging of the whole tile: rows = MFMA lane dimension
