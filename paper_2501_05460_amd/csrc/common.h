@@ -33,24 +33,24 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
 }
 
 // GELU for the bf16 epilogues: branch-free, one exp and one reciprocal each.
-// erf form: x * Phi(x) with erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2),
-// t = 1 / (1 + p z), z >= 0 (Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7, far
-// below one bf16 ulp of the result).
+// erf form: x * Phi(x) with Phi(x) ~= 1 / (1 + exp(-x (a + b x^2 + c x^4))), the
+// logistic shape of the tanh form with a third term and all three coefficients
+// fitted (minimax over |x| <= 7) to x * Phi(x) itself: |error| <= 2.6e-5, a
+// fortieth of half a bf16 ulp at 0.5.  The polynomial's argument is clamped to
+// +-7, where Phi is 0 or 1 to 1e-12 (c < 0 would turn the exponent around
+// beyond |x| ~ 10).  The coefficients carry the factor -log2(e) of exp2.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float z = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));
-  float poly = fmaf(t, 1.061405429f, -1.453152027f);
-  poly = fmaf(t, poly, 1.421413741f);
-  poly = fmaf(t, poly, -0.284496736f);
-  poly = fmaf(t, poly, 0.254829592f);
-  const float erfc_z = poly * t * __builtin_amdgcn_exp2f(-1.4426950408889634f * z * z);  // erfc(|x|/sqrt 2)
-  const float phi_neg = 0.5f * erfc_z;                   // Phi(-|x|)
-  return x >= 0.f ? x - x * phi_neg : x * phi_neg;       // x Phi(x)
+  const float xc = __builtin_amdgcn_fmed3f(x, -7.0f, 7.0f);
+  const float x2 = xc * xc;
+  float p = fmaf(x2, 1.0142650e-3f, -1.0677574e-1f);   // -log2e * (c x^2 + b)
+  p = fmaf(x2, p, -2.3011213f);                         // -log2e * a
+  const float e = __builtin_amdgcn_exp2f(xc * p);
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
-// tanh form: 0.5 x (1 + tanh u) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3)
+// tanh form: 0.5 x (1 + tanh u) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3);
+// -2 log2(e) sqrt(2/pi) is folded into the two coefficients of exp2's argument.
 __device__ __forceinline__ float gelu_tanh_fast(float x) {
-  const float u = 0.79788456080286535588f * fmaf(0.044715f * x * x, x, x);
-  const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
+  const float e = __builtin_amdgcn_exp2f(x * fmaf(x * x, -1.029432396e-01f, -2.302208198e+00f));
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
