@@ -259,7 +259,7 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
  * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
  * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
  * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
- * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 96, 128}, n_tokens % 64 == 0;
+ * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0;
  * `scale` multiplies the logits. */
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
                                  int32_t n_slices, int32_t n_tokens, int32_t heads, int32_t hd_pad,

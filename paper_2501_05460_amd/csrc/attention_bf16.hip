@@ -26,12 +26,17 @@ namespace {
 
 constexpr int BKEY = 64;  // keys per LDS block
 
+// HD = head dim as stored in q, k, v^T (a multiple of 8).  The products run
+// over HD rounded up to the MFMA shapes (16 for q.k, 32 rows of O^T); the
+// extra head-dim positions exist only in LDS and registers, as zeros.
 template <int HD>
 struct AttnSmem {
-  static constexpr int K_LD = HD + 8;      // bf16 elements per key row (16 B pad)
+  static constexpr int HDK = (HD + 15) / 16 * 16;   // contraction length of S^T
+  static constexpr int HDV = (HD + 31) / 32 * 32;   // rows of V^T / O^T
+  static constexpr int K_LD = HDK + 8;     // bf16 elements per key row (16 B pad)
   static constexpr int V_LD = BKEY + 8;    // bf16 elements per V^T row
   static constexpr int K_ELEMS = BKEY * K_LD;
-  static constexpr int V_ELEMS = HD * V_LD;
+  static constexpr int V_ELEMS = HDV * V_LD;
   static constexpr size_t BYTES = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
 };
 
@@ -43,11 +48,13 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
                                                         long ld_qk, long ld_o, float scale_log2e) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
-  constexpr int KS = HD / 16;   // k-steps of the S^T product
-  constexpr int MB = HD / 32;   // 32-row blocks of O^T
-  constexpr int KCH = HD / 8;   // 16-byte chunks per key row
-  constexpr int K_LOADS = BKEY * KCH / 256;
-  constexpr int V_LOADS = HD * (BKEY / 8) / 256;
+  constexpr int KS = SM::HDK / 16;   // k-steps of the S^T product
+  constexpr int MB = SM::HDV / 32;   // 32-row blocks of O^T
+  constexpr int KCH = HD / 8;        // 16-byte chunks per key row in memory
+  constexpr int K_TOTAL = BKEY * KCH, V_TOTAL = HD * (BKEY / 8);   // chunks per block
+  constexpr int K_LOADS = (K_TOTAL + 255) / 256;
+  constexpr int V_LOADS = (V_TOTAL + 255) / 256;
+  constexpr bool K_EXACT = K_TOTAL % 256 == 0, V_EXACT = V_TOTAL % 256 == 0;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem);       // [2][BKEY][K_LD]
@@ -80,20 +87,29 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
     const int qrow = act[u] ? q0 + u * 32 + l32 : 0;  // inactive sub-tiles read a valid row, result unused
     const bf16_t* qp = q + (row0 + qrow) * ld_qk + (long)h * HD + lh * 8;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) qf[u][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+    for (int s = 0; s < KS; ++s) {
+      if (s * 16 + 8 < HD || lh == 0) {
+        qf[u][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+      } else {   // head-dim positions past HD (last k-step of a head dim that is not a multiple of 16)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[u][s][e] = (bf16_t)0.f;
+      }
+    }
   }
 
   u32x4 rk[K_LOADS], rv[V_LOADS];
   auto gload = [&](int kb) {
 #pragma unroll
     for (int i = 0; i < K_LOADS; ++i) {
-      const int c = tid + 256 * i;
+      int c = tid + 256 * i;
+      if (!K_EXACT) c = c < K_TOTAL ? c : 0;   // spare threads of the last round re-read chunk 0, never stored
       const int row = c / KCH, ch = c % KCH;
       rk[i] = *reinterpret_cast<const u32x4*>(kbase + (long)(kb * BKEY + row) * ld_qk + ch * 8);
     }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) {
-      const int c = tid + 256 * i;
+      int c = tid + 256 * i;
+      if (!V_EXACT) c = c < V_TOTAL ? c : 0;
       const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
       rv[i] = *reinterpret_cast<const u32x4*>(vbase + (long)row * n_tok + kb * BKEY + ch * 8);
     }
@@ -102,12 +118,14 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
 #pragma unroll
     for (int i = 0; i < K_LOADS; ++i) {
       const int c = tid + 256 * i;
+      if (!K_EXACT && c >= K_TOTAL) continue;
       const int row = c / KCH, ch = c % KCH;
       *reinterpret_cast<u32x4*>(sK + buf * SM::K_ELEMS + row * SM::K_LD + ch * 8) = rk[i];
     }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) {
       const int c = tid + 256 * i;
+      if (!V_EXACT && c >= V_TOTAL) continue;
       const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
       // chunk ch holds keys 8ch..8ch+7; inside a group of 16 keys the LDS order is
       // [0-3, 8-11, 4-7, 12-15]: keys 8ch+0..3 -> position 16(ch/2) + 4(ch%2),
@@ -190,6 +208,20 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
 
   const int NB = n_tok / BKEY;
   gload(0);
+  // head-dim positions that exist only in LDS stay zero for the whole kernel:
+  // columns HD .. HDK-1 of every key row, rows HD .. HDV-1 of V^T, both buffers
+  if constexpr (SM::HDK > HD) {
+    for (int r = tid; r < 2 * BKEY; r += 256) {
+      bf16_t* dst = sK + (r / BKEY) * SM::K_ELEMS + (r % BKEY) * SM::K_LD + HD;
+#pragma unroll
+      for (int e = 0; e < SM::HDK - HD; ++e) dst[e] = (bf16_t)0.f;
+    }
+  }
+  if constexpr (SM::HDV > HD) {
+    constexpr int PAD_ELEMS = (SM::HDV - HD) * SM::V_LD;
+    for (int e = tid; e < 2 * PAD_ELEMS; e += 256)
+      sV[(e / PAD_ELEMS) * SM::V_ELEMS + HD * SM::V_LD + e % PAD_ELEMS] = (bf16_t)0.f;
+  }
   sstore(0);
   __syncthreads();
 
@@ -225,10 +257,12 @@ __global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restr
     for (int b = 0; b < MB; ++b)
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi) {
+        const int d0 = b * 32 + gi * 8 + lh * 4;
+        if (SM::HDV > HD && d0 >= HD) continue;   // rows of O^T past the head dim
         bf16x4 ov;
 #pragma unroll
         for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[u][b][gi * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + b * 32 + gi * 8 + lh * 4) = ov;
+        *reinterpret_cast<bf16x4*>(op + d0) = ov;
       }
   }
 }
@@ -262,6 +296,7 @@ hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf
   if (n_tok % BKEY != 0 || n_tok <= 0) return hipErrorInvalidValue;
   switch (hd_pad) {
     case 64: return launch_attn<64, 2>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
     case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
     case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
   }

@@ -251,7 +251,8 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   const bool bf = c->bf16;
 
   if (bf) {
-    c->hd_pad = x.hd <= 64 ? 64 : (x.hd <= 96 ? 96 : 128);
+    // head dims the attention kernel is built for; others are zero-padded up to the next one
+    c->hd_pad = x.hd <= 64 ? 64 : (x.hd == 72 ? 72 : (x.hd <= 96 ? 96 : 128));
     c->Dq = x.H * c->hd_pad;
     c->Dq_k = round_up(c->Dq, 128);
     c->D_k = round_up(x.D, 128);

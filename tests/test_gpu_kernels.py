@@ -75,7 +75,8 @@ def _attention_case(n_slices, n_tok, heads, hd, hd_pad, qk_scale, seed):
 
 @pytest.mark.parametrize("n_slices,n_tok,heads,hd,hd_pad", [
     (1, 64, 1, 64, 64), (2, 256, 3, 64, 64), (3, 1024, 2, 64, 64), (2, 1024, 2, 72, 96),
-    (2, 1024, 2, 128, 128), (1, 192, 2, 32, 64)])
+    (2, 1024, 2, 128, 128), (1, 192, 2, 32, 64), (2, 1024, 2, 72, 72), (1, 128, 3, 72, 72),
+    (1, 256, 2, 80, 96)])
 @pytest.mark.parametrize("qk_scale", [0.25, 1.0])
 def test_attention_bf16_vs_oracle(n_slices, n_tok, heads, hd, hd_pad, qk_scale):
     # N(0,1) q/k give logits with std ~ 1..3 after scaling by 1/sqrt(hd) * hd^0.5:
