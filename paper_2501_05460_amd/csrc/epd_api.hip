@@ -353,7 +353,8 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   c->Mp_out = (Mo + 255) / 256 * 256;
   bool ok = true;
   auto ws = [&](size_t bytes) { void* p = dalloc(c, bytes, true, st); ok = ok && p; return p; };
-  c->X = (float*)ws((size_t)c->Mp * x.D * sizeof(float));
+  // the residual GEMM prefetches whole 256-column tile rows: one padded row of slack behind the last
+  c->X = (float*)ws(((size_t)c->Mp * x.D + 256) * sizeof(float));
   c->d_rowmap = (int*)ws((size_t)M * sizeof(int));
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);

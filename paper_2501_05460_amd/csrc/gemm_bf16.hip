@@ -20,6 +20,7 @@
 // 16-byte fp32 accesses in the epilogue.  For the attention values (EPI_VT)
 // the roles are swapped, so a lane owns four consecutive tokens of one
 // feature, which is what the transposed value layout wants.
+#include <cstdlib>
 #include <type_traits>
 
 #include "kernels.h"
@@ -58,7 +59,7 @@ constexpr size_t smem_main_bytes() {
   return operands > staging ? operands : staging;
 }
 
-template <int BN, int NTHREADS, int WN, int EPI>
+template <int BN, int NTHREADS, int WN, int EPI, int PIPE>
 __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
@@ -72,8 +73,10 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   constexpr int ROWS_PER_LD = NTHREADS / 8;      // rows covered by one 16-byte load per thread
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem);  // [NBUF][BM][64]
-  bf16_t* sB = sA + NBUF * BM * BK;              // [NBUF][BN][64]
+  // weight slabs first: their LDS addresses (<= 64 KiB) also serve as the 16-bit base of the
+  // direct global-to-LDS loads
+  bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [NBUF][BN][64]
+  bf16_t* sA = sB + NBUF * BN * BK;              // [NBUF][BM][64]
   float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());  // [BN]
 
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
@@ -108,8 +111,9 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   const int ld_row = tid >> 3, ld_c = tid & 7;
   const int st_off = ld_row * BK + ((ld_c ^ SWZ(ld_row)) * 8);
 
-  const bf16_t* gA = p.A + (long)(m0 + ld_row) * p.lda + ld_c * 8;
-  const bf16_t* gB = p.W + (long)(n0 + ld_row) * p.K + ld_c * 8;
+  // global addresses = wave-uniform base (scalar registers) + one 32-bit lane offset per operand
+  const unsigned a_voff = ((unsigned)ld_row * (unsigned)p.lda + ld_c * 8) * 2;   // bytes
+  const unsigned b_voff = ((unsigned)ld_row * (unsigned)p.K + ld_c * 8) * 2;
 
   // Residual epilogue: the tile's fp32 rows are added in passes of 64 token
   // rows; the rows of pass p wait in register set p % 2, loaded two passes
@@ -127,9 +131,14 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   const int x_col = n0 + (tid % XNCH) * 4;
   const bool x_col_ok = x_col < p.N;
   const unsigned x_voff = (unsigned)x_r0 * (unsigned)p.ldr + (unsigned)x_col;
-  // the operand register sets can carry the first two passes when the counts match
+  // PIPE == 1: the weight slab goes from global memory straight into LDS (no
+  // staging registers), one slab ahead; only the activation slab is staged in
+  // registers, two slabs ahead.
+  constexpr bool B_DIRECT = PIPE == 1;
+  // the operand register sets can carry residual rows of the first passes when the counts match:
+  // both sets = passes 0 and 1 (A and B staged), or both sets = the two halves of pass 0 (A staged only)
   constexpr bool X_IN_LOOP = EPI == EPI_BIAS_RESIDUAL && NBUF == 2 && !(NTHREADS == 256 && WN == 128) &&
-                             XPER_T == A_LD + B_LD;
+                             (B_DIRECT ? XPER_T == 2 * A_LD : XPER_T == A_LD + B_LD);
   f32x4 xr[2][X_IN_LOOP ? XPER_T : 1];
   auto xload = [&](auto set, int pass) {
     if constexpr (X_IN_LOOP) {
@@ -145,42 +154,95 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   };
 
 
+  // Global operands are read through buffer descriptors: descriptor + scalar offset + one lane
+  // offset per operand, so no per-load address arithmetic touches vector registers, and a read
+  // past the end of a matrix returns zero.  The host launcher checks that every extent fits 32 bits.
+  __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(p.A), 0, (int)(unsigned)(((long)(p.M - 1) * p.lda + p.K) * 2), 0x00020000);
+  __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(p.W), 0, (int)(unsigned)((long)p.Npad * p.K * 2), 0x00020000);
+  __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+      p.R, 0, EPI == EPI_BIAS_RESIDUAL ? (int)(unsigned)(((long)(p.M - 1) * p.ldr + p.N) * 4) : 0, 0x00020000);
+
   // Two register sets: the loads of slab k+2 are in flight while slab k is
   // multiplied and slab k+1 (loaded one iteration earlier) moves to LDS.
-  u32x4 ra[NBUF][A_LD], rb[NBUF][B_LD];
+  u32x4 ra[NBUF][A_LD], rb[NBUF][B_DIRECT ? 1 : B_LD];
   auto gload = [&](auto set, int kt) {
     constexpr int S = decltype(set)::value;
     // Residual epilogue: the two loads past the last slab (kt == KT_ into set
-    // 0, KT_ + 1 into set 1) fetch the fp32 rows of the first two epilogue
-    // passes into the same registers instead of re-reading operands.
+    // 0, KT_ + 1 into set 1) fetch fp32 rows of the first epilogue passes into
+    // the same registers instead of re-reading operands.  Chunk c of a pass =
+    // rows XSTEP * c + x_r0 of the pass, this lane's 16-byte column chunk.
+    // Staged A and B: set s holds pass s, chunks 0 .. XPER_T-1; staged A only:
+    // set s holds chunks s * A_LD .. of pass 0.
     const bool past = kt >= KT_;
     const int xpass = kt - KT_;
     kt = past ? KT_ - 1 : kt;  // past the end (other epilogues): re-read the last slab, result unused
-    // branch-free choice between the operand chunk and residual chunk i of pass xpass
-    auto pick = [&](const bf16_t* operand, int i) -> const u32x4* {
-      if constexpr (X_IN_LOOP) {
-        const int row0 = m0 + xpass * XROWS + XSTEP * i;
-        const bool take = past & x_col_ok & (row0 + x_r0 < p.M);
-        const uintptr_t a = reinterpret_cast<uintptr_t>(operand);
-        const uintptr_t x = reinterpret_cast<uintptr_t>(p.R + (long)row0 * p.ldr + x_voff);
-        return reinterpret_cast<const u32x4*>(a ^ ((a ^ x) & (uintptr_t)0 - (uintptr_t)take));
-      } else {
-        return reinterpret_cast<const u32x4*>(operand);
+    if (X_IN_LOOP && past) {   // one uniform branch per slab, taken for the last two slabs of a tile
+      auto so_x = [&](int c) {
+        const int pass = B_DIRECT ? 0 : xpass, ci = B_DIRECT ? xpass * A_LD + c : c;
+        return (unsigned)(m0 + pass * XROWS + XSTEP * ci) * (unsigned)p.ldr * 4u;
+      };
+#pragma unroll
+      for (int i = 0; i < A_LD; ++i) ra[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(i), 0);
+      if constexpr (!B_DIRECT) {
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+          rb[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(A_LD + i), 0);
       }
-    };
+    } else {
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i) ra[S][i] = *pick(gA + (long)(ROWS_PER_LD * i) * p.lda + kt * BK, i);
+      for (int i = 0; i < A_LD; ++i) {
+        const unsigned so = ((unsigned)(m0 + ROWS_PER_LD * i) * (unsigned)p.lda + (unsigned)(kt * BK)) * 2u;
+        ra[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, a_voff, so, 0);
+      }
+      if constexpr (!B_DIRECT) {
 #pragma unroll
-    for (int i = 0; i < B_LD; ++i) rb[S][i] = *pick(gB + (long)(ROWS_PER_LD * i) * p.K + kt * BK, A_LD + i);
+        for (int i = 0; i < B_LD; ++i) {
+          const unsigned so = ((unsigned)(n0 + ROWS_PER_LD * i) * (unsigned)p.K + (unsigned)(kt * BK)) * 2u;
+          rb[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, b_voff, so, 0);
+        }
+      }
+    }
+  };
+  // Weight slab kt -> LDS buffer buf without passing through registers.  The
+  // hardware puts lane l's 16 bytes at (wave-uniform LDS base) + 16 l, so a
+  // wave fills 1 KiB = 8 slab rows linearly; the swizzle is applied on the
+  // global side instead: the lane that lands on physical chunk ld_c of its row
+  // fetches logical chunk ld_c ^ SWZ(row).
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const unsigned bd_voff = ((unsigned)ld_row * (unsigned)p.K + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  auto bload = [&](int buf, int kt) {
+    if constexpr (B_DIRECT) {
+#pragma unroll
+      for (int i = 0; i < B_LD; ++i) {
+        const bf16_t* g = p.W + (long)(n0 + ROWS_PER_LD * i) * p.K + kt * BK;   // uniform
+        bf16_t* l = sB + buf * BN * BK + (wave_u * 64 + NTHREADS * i) * 8;
+        // Written as assembly on purpose: for the builtin form the compiler makes every later
+        // LDS read wait for ALL outstanding vector-memory loads (it cannot tell the two LDS
+        // buffers apart), which would serialise the pipeline.  Completion is awaited
+        // explicitly (wait_vm) in front of the barrier that publishes the buffer.
+        const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(bd_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+      }
+    }
+  };
+  // wait until at most n of this wave's vector-memory loads are outstanding (they complete in order)
+  auto wait_vm = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
   };
   auto sstore = [&](auto set, int buf) {
     constexpr int S = decltype(set)::value;
 #pragma unroll
     for (int i = 0; i < A_LD; ++i)
       *reinterpret_cast<u32x4*>(sA + buf * BM * BK + ROWS_PER_LD * i * BK + st_off) = ra[S][i];
+    if constexpr (!B_DIRECT) {
 #pragma unroll
-    for (int i = 0; i < B_LD; ++i)
-      *reinterpret_cast<u32x4*>(sB + buf * BN * BK + ROWS_PER_LD * i * BK + st_off) = rb[S][i];
+      for (int i = 0; i < B_LD; ++i)
+        *reinterpret_cast<u32x4*>(sB + buf * BN * BK + ROWS_PER_LD * i * BK + st_off) = rb[S][i];
+    }
   };
 
   // attention values: token-major MFMA result, stored transposed
@@ -222,12 +284,12 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  if constexpr (NTHREADS == 256 && WN == 128) {
-    // One wave per SIMD: nothing else hides a stall, so the operand
-    // fragments run one k-step ahead of the MFMAs in a second register set,
-    // and the slab hand-over (LDS stores of the next slab + barrier) sits in
-    // front of the LAST k-step, whose 16 MFMAs cover the first fragment reads
-    // from the other buffer.
+  if constexpr (NBUF == 2 && (PIPE >= 1 || (NTHREADS == 256 && WN == 128))) {
+    // The operand fragments run one k-step ahead of the MFMAs in a second
+    // register set, so a wave issues its MFMAs back to back instead of
+    // waiting for LDS in front of every k-step; the slab hand-over (LDS
+    // stores of the next slab + barrier) sits in front of the LAST k-step,
+    // whose MFMAs cover the first fragment reads from the other buffer.
     bf16x8 fa[2][TM], fb[2][TN];
     auto ldfrag = [&](auto set, int buf, int kk) {
       constexpr int S = decltype(set)::value;
@@ -247,31 +309,53 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
         for (int j = 0; j < TN; ++j)
           acc[i][j] = tok_major ? mfma32(fa[S][i], fb[S][j], acc[i][j]) : mfma32(fb[S][j], fa[S][i], acc[i][j]);
     };
-    // scheduling hint: after every two MFMAs let one LDS read through
+    // scheduling hint: spread the TM + TN LDS reads of the next k-step over the TM * TN MFMAs of this one
     auto interleave = [&]() {
+      constexpr int PER = (TM * TN) / (TM + TN) > 0 ? (TM * TN) / (TM + TN) : 1;
 #pragma unroll
       for (int i = 0; i < TM + TN; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read
       }
     };
     auto slab = [&](auto lset, auto sset, int buf, int kt) {
-      gload(lset, kt + 2);
+      if (kt + 1 < KT_) bload(buf ^ 1, kt + 1);  // the other buffer is free since the last barrier
+      gload(lset, kt + 2);   // past the last slab: residual rows of the first epilogue passes (see gload)
+      // the loads stay in front of the slab's arithmetic: moved down by the scheduler they would
+      // share registers with the fragments and lose half of their head start
+      __builtin_amdgcn_sched_barrier(0);
       ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
       ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
       ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
-      sstore(sset, buf ^ 1);
-      __syncthreads();
-      ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
+      if (kt + 1 < KT_) {
+        sstore(sset, buf ^ 1);
+        if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, A_LD>{});  // all but the newest A loads: the weight slab has landed
+        __syncthreads();
+        ldfrag(S0{}, buf ^ 1, 0);
+      }
+      mma(S1{}); interleave();
     };
+    bload(0, 0);
     gload(S0{}, 0);
     gload(S1{}, 1);
     sstore(S0{}, 0);
+    if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, 0>{});
     __syncthreads();
     ldfrag(S0{}, 0, 0);
     for (int kt = 0; kt < KT_; kt += 2) {
       slab(S0{}, S1{}, 0, kt);
       slab(S1{}, S0{}, 1, kt + 1);
+    }
+    if constexpr (X_IN_LOOP && B_DIRECT) {
+#pragma unroll
+      for (int i = 0; i < XPER_T; ++i) xr[0][i] = __builtin_bit_cast(f32x4, ra[i / A_LD][i % A_LD]);
+      xload(S1{}, 1);   // into the registers the operand fragments have left
+    } else if constexpr (X_IN_LOOP) {
+#pragma unroll
+      for (int i = 0; i < XPER_T; ++i) {
+        xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
+        xr[1][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[1][i < A_LD ? i : 0] : rb[1][i < A_LD ? 0 : i - A_LD]);
+      }
     }
   } else if constexpr (NBUF == 2) {
     gload(S0{}, 0);
@@ -428,7 +512,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
 template <int BN, int NT>
 constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT>() + BN * sizeof(float); }
 
-template <int BN, int NT, int WN, int EPI>
+template <int BN, int NT, int WN, int EPI, int PIPE>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
@@ -446,38 +530,38 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     if (cost < best * 0.999) { best = cost; gw = c; }
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
-  k_gemm_bf16<BN, NT, WN, EPI><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
+  k_gemm_bf16<BN, NT, WN, EPI, PIPE><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
   return hipGetLastError();
 }
 
-template <int BN, int NT, int WN>
+template <int BN, int NT, int WN, int PIPE = 0>
 hipError_t dispatch(const GemmParams& p, hipStream_t st) {
   switch (p.epi) {
-    case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS>(p, st);
-    case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF>(p, st);
-    case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH>(p, st);
-    case EPI_BIAS_RESIDUAL: return launch<BN, NT, WN, EPI_BIAS_RESIDUAL>(p, st);
-    case EPI_BIAS_POS: return launch<BN, NT, WN, EPI_BIAS_POS>(p, st);
-    case EPI_VT: return launch<BN, NT, WN, EPI_VT>(p, st);
+    case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS, PIPE>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE>(p, st);
+    case EPI_BIAS_RESIDUAL: return launch<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE>(p, st);
+    case EPI_BIAS_POS: return launch<BN, NT, WN, EPI_BIAS_POS, PIPE>(p, st);
+    case EPI_VT: return launch<BN, NT, WN, EPI_VT, PIPE>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
-template <int BN, int NT, int WN, int EPI>
+template <int BN, int NT, int WN, int EPI, int PIPE>
 hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI, PIPE>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, NT>());
 }
 
-template <int BN, int NT, int WN>
+template <int BN, int NT, int WN, int PIPE = 0>
 hipError_t set_attr_all() {
   hipError_t e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS>()) != hipSuccess) return e;
-  return set_attr<BN, NT, WN, EPI_VT>();
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS, PIPE>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS, PIPE>()) != hipSuccess) return e;
+  return set_attr<BN, NT, WN, EPI_VT, PIPE>();
 }
 
 }  // namespace
@@ -485,6 +569,7 @@ hipError_t set_attr_all() {
 hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
+  if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 256, 64>()) != hipSuccess) return e;
   return set_attr_all<256, 256, 128>();
@@ -492,14 +577,29 @@ hipError_t bf16_gemm_init() {
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (p.K % (2 * BK) != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+  // operands are addressed through 32-bit buffer offsets
+  if ((long)p.M * p.lda * 2 >= (1L << 32) || (long)p.Npad * p.K * 2 >= (1L << 32) ||
+      (p.R && (long)p.M * p.ldr * 4 >= (1L << 32)))
+    return hipErrorInvalidValue;
   const bool f32_out = p.epi == EPI_BIAS_RESIDUAL || p.epi == EPI_BIAS_POS;
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
   switch (p.cfg) {
     case 1: return dispatch<128, 512, 64>(p, st);
     case 2: return dispatch<128, 256, 64>(p, st);
     case 4: if (p.Npad % 256 == 0) return dispatch<256, 256, 128>(p, st); break;
+    case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
+    case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
   }
-  return p.Npad % 256 == 0 ? dispatch<256, 512, 64>(p, st) : dispatch<128, 512, 64>(p, st);
+  if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
+  // the residual epilogue keeps the register-staged loop: with both operand sets in registers it can
+  // prefetch two epilogue passes of the fp32 stream inside the loop, which measured faster in place
+  if (p.epi == EPI_BIAS_RESIDUAL) {
+    static const int res_pipe = getenv("EPD_RES_PIPE") ? atoi(getenv("EPD_RES_PIPE")) : 1;
+    return res_pipe == 1 ? dispatch<256, 512, 64, 1>(p, st) : dispatch<256, 512, 64, 0>(p, st);
+  }
+  static const int main_pipe = getenv("EPD_MAIN_PIPE") ? atoi(getenv("EPD_MAIN_PIPE")) : 1;
+  if (main_pipe == 0) return dispatch<256, 512, 64, 0>(p, st);
+  return dispatch<256, 512, 64, 1>(p, st);
 }
 
 }  // namespace epd

@@ -31,7 +31,8 @@ struct GemmParams {
   bf16_t* C; long ldc;        // bf16 output (BIAS, GELU_*)
   const int* row_map;         // optional paged output: row r -> row_map[r / block_tokens] * block_tokens + r % block_tokens
   int block_tokens;
-  float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS)
+  float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS); RESIDUAL reads whole tiles: R must hold
+                              // round_up(M, 256) rows plus (Npad - N) floats behind the last one
   const float* pos; int n_pos;
   bf16_t* VT;                 // EPI_VT: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
   int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
