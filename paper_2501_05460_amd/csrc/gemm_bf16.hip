@@ -318,8 +318,10 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read
       }
     };
+    // The hand-over is unconditional so that a slab is straight-line code: behind the last slab it
+    // re-reads the last weight slab and parks stale registers in the idle buffer, nobody reads them.
     auto slab = [&](auto lset, auto sset, int buf, int kt) {
-      if (kt + 1 < KT_) bload(buf ^ 1, kt + 1);  // the other buffer is free since the last barrier
+      bload(buf ^ 1, kt + 1 < KT_ ? kt + 1 : KT_ - 1);  // the other buffer is free since the last barrier
       gload(lset, kt + 2);   // past the last slab: residual rows of the first epilogue passes (see gload)
       // the loads stay in front of the slab's arithmetic: moved down by the scheduler they would
       // share registers with the fragments and lose half of their head start
@@ -327,13 +329,11 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
       ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
       ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
       ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
-      if (kt + 1 < KT_) {
-        sstore(sset, buf ^ 1);
-        if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, A_LD>{});  // all but the newest A loads: the weight slab has landed
-        __syncthreads();
-        ldfrag(S0{}, buf ^ 1, 0);
-      }
-      mma(S1{}); interleave();
+      __builtin_amdgcn_sched_barrier(0);   // the LDS stores wait for loads issued a slab ago: keep them late
+      sstore(sset, buf ^ 1);
+      if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, A_LD>{});  // all but the newest A loads: the weight slab has landed
+      __syncthreads();
+      ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
     };
     bload(0, 0);
     gload(S0{}, 0);
