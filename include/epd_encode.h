@@ -69,7 +69,9 @@ typedef struct {
   int32_t proj_out;      /* D_out: width of a token in the cache                         */
   float   eps;           /* epsilon of every norm                                        */
   int32_t max_tiles_per_call; /* workspace is sized for this many slices at once; larger
-                                 calls are processed in micro-batches of at most this    */
+                                 calls are processed in micro-batches of at most this.
+                                 bf16 mode: every activation buffer of a micro-batch must
+                                 stay below 4 GiB (epd_create: EPD_ERR_UNSUPPORTED)      */
 } epd_model_desc;
 
 /* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix

@@ -3,6 +3,7 @@
 #include "../../include/epd_encode.h"
 
 #include <cstdarg>
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <cmath>
@@ -351,6 +352,15 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   const long M = (long)c->mb * x.N, Mo = (long)c->mb * x.N_out;
   c->Mp = (M + 255) / 256 * 256;
   c->Mp_out = (Mo + 255) / 256 * 256;
+  if (bf) {
+    // the MFMA GEMM addresses its operands through 32-bit buffer offsets
+    const long widest = std::max({(long)c->F_k, 2L * c->Dq, (long)c->Dq_k, (long)c->D_k, (long)c->Kp_k, 2L * x.D});
+    if (c->Mp * widest * 2 >= (1L << 32) || c->Mp_out * (long)std::max(c->Pin_k, c->Pmid_k) * 2 >= (1L << 32)) {
+      set_err(c->err, sizeof(c->err), "max_tiles_per_call %d makes an activation buffer of 4 GiB or more; use a smaller value "
+              "(a call is cut into micro-batches of that many slices anyway)", c->mb);
+      return EPD_ERR_UNSUPPORTED;
+    }
+  }
   bool ok = true;
   auto ws = [&](size_t bytes) { void* p = dalloc(c, bytes, true, st); ok = ok && p; return p; };
   // the residual GEMM prefetches whole 256-column tile rows: one padded row of slack behind the last

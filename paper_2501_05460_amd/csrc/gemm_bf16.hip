@@ -7,9 +7,17 @@
 // 16-byte chunks of a row XOR-swizzled by the row so that the 32 rows a
 // wave reads for one MFMA operand fall into different banks (64 banks, 16
 // lanes per 128-bit access phase: rows r and r+1 share a chunk column, so the
-// XOR key is (row >> 1) & 7).  Global loads run two slabs ahead in registers
-// (L2 / Infinity-Cache latency is longer than one slab of MFMA work), the
-// slab in between moves to the other LDS buffer: one barrier per slab.
+// XOR key is (row >> 1) & 7).  One barrier per slab, two LDS buffers.
+//
+// Main loop of the default shape (PIPE = 1): the activation slab is read two
+// slabs ahead into registers through a buffer descriptor (L2 / Infinity-Cache
+// latency is longer than one slab of MFMA work) and stored to the other LDS
+// buffer a slab later; the weight slab, which sits in L2, goes from global
+// memory straight into the other LDS buffer one slab ahead (global_load_lds,
+// no staging registers).  The MFMA operand fragments of k-step kk+1 are read
+// from LDS into a second register set while the MFMAs of k-step kk issue back
+// to back.  PIPE = 0 is the plain form (both operands staged in registers,
+// fragment reads left to the compiler), kept for the other tile shapes.
 //
 // v_mfma_f32_32x32x16_bf16 operand layout (checked on the device by
 // mfma_probe): lane l supplies row (l % 32) of the 32 x 16 left operand /
@@ -20,7 +28,6 @@
 // 16-byte fp32 accesses in the epilogue.  For the attention values (EPI_VT)
 // the roles are swapped, so a lane owns four consecutive tokens of one
 // feature, which is what the transposed value layout wants.
-#include <cstdlib>
 #include <type_traits>
 
 #include "kernels.h"
@@ -32,20 +39,18 @@ namespace {
 constexpr int BM = 256;
 constexpr int BK = 64;
 
-#ifndef EPD_SWZ_SHIFT
-#define EPD_SWZ_SHIFT 1
-#endif
 // XOR swizzle of the 16-byte chunk index by the row
-#define SWZ(row) (((row) >> EPD_SWZ_SHIFT) & 7)
+#define SWZ(row) (((row) >> 1) & 7)
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 // Configurations (BN, NTHREADS[, WN = 64]):
-//   (256, 512)  256x256 tile, 8 waves, one workgroup per CU, two LDS buffers,
-//               loads two slabs ahead in two register sets;
-//   (128, 512)  256x128 tile, 8 waves (64x64 per wave), same pipeline;
+//   (256, 512)  256x256 tile, 8 waves, one workgroup per CU, two LDS buffers
+//               (PIPE = 1: the default; PIPE = 0: both operands two slabs ahead
+//               in two register sets);
+//   (128, 512)  256x128 tile, 8 waves (64x64 per wave), PIPE = 0;
 //   (128, 256)  256x128 tile, 4 waves (128x64 per wave), TWO workgroups per CU:
 //               one LDS buffer and one register set each;
 //   (256, 256, WN = 128)  256x256 tile, 4 waves of 128x128: one wave per SIMD
@@ -591,14 +596,6 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
   }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
-  // the residual epilogue keeps the register-staged loop: with both operand sets in registers it can
-  // prefetch two epilogue passes of the fp32 stream inside the loop, which measured faster in place
-  if (p.epi == EPI_BIAS_RESIDUAL) {
-    static const int res_pipe = getenv("EPD_RES_PIPE") ? atoi(getenv("EPD_RES_PIPE")) : 1;
-    return res_pipe == 1 ? dispatch<256, 512, 64, 1>(p, st) : dispatch<256, 512, 64, 0>(p, st);
-  }
-  static const int main_pipe = getenv("EPD_MAIN_PIPE") ? atoi(getenv("EPD_MAIN_PIPE")) : 1;
-  if (main_pipe == 0) return dispatch<256, 512, 64, 0>(p, st);
   return dispatch<256, 512, 64, 1>(p, st);
 }
 
