@@ -40,8 +40,11 @@ struct AttnSmem {
   static constexpr size_t BYTES = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
 };
 
+// Registers: head dim 64 with one sub-tile per wave fits 168 registers, i.e. three workgroups per
+// CU; measured faster than two sub-tiles per wave at two workgroups (more waves hide the
+// MFMA -> exp -> MFMA dependency chain better than fragment reuse saves LDS reads).
 template <int HD, int QT>
-__global__ __launch_bounds__(256, 2) void k_attention_bf16(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
                                                         bf16_t* __restrict__ o, int n_tok, int heads, int n_pairs,
@@ -295,7 +298,7 @@ hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf
   if (n_slices == 0) return hipSuccess;
   if (n_tok % BKEY != 0 || n_tok <= 0) return hipErrorInvalidValue;
   switch (hd_pad) {
-    case 64: return launch_attn<64, 2>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
     case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
     case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
     case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);

@@ -344,7 +344,8 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     gload(S0{}, 0);
     gload(S1{}, 1);
     sstore(S0{}, 0);
-    if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, 0>{});
+    // loads complete in order: once all but the newest A_LD (slab 1's) are done, weight slab 0 has landed
+    if constexpr (B_DIRECT) wait_vm(std::integral_constant<int, A_LD>{});
     __syncthreads();
     ldfrag(S0{}, 0, 0);
     for (int kt = 0; kt < KT_; kt += 2) {
