@@ -72,6 +72,9 @@ typedef struct {
                                  calls are processed in micro-batches of at most this.
                                  bf16 mode: every activation buffer of a micro-batch must
                                  stay below 4 GiB (epd_create: EPD_ERR_UNSUPPORTED)      */
+  int32_t layer_scale;   /* 1: each residual branch is multiplied by a learned per-channel
+                            vector before it is added (x += ls1 * attn(..), x += ls2 * mlp(..)),
+                            as in the InternViT encoders                                  */
 } epd_model_desc;
 
 /* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix
@@ -81,8 +84,8 @@ typedef struct {
  *     n1_g [D], n1_b [D] (n1_b only for LayerNorm),
  *     qkv_w [3D, D] (row blocks q, k, v; head h = rows h*hd..(h+1)*hd-1 of a block), qkv_b [3D],
  *     qn_g, kn_g ([D] for QKNORM_FULL, [hd] for QKNORM_PER_HEAD, absent for NONE),
- *     o_w [D, D], o_b [D], n2_g [D], n2_b [D] (LayerNorm only),
- *     fc1_w [F, D], fc1_b [F], fc2_w [D, F], fc2_b [D];
+ *     o_w [D, D], o_b [D], ls1 [D] (if layer_scale), n2_g [D], n2_b [D] (LayerNorm only),
+ *     fc1_w [F, D], fc1_b [F], fc2_w [D, F], fc2_b [D], ls2 [D] (if layer_scale);
  *   fn_g [D], fn_b [D]            (if final_norm; fn_b only for LayerNorm)
  *   pn_g [Din], pn_b [Din]        (if proj_prenorm; Din = 4D with pixel shuffle else D)
  *   pa_w [Dmid or D_out, Din], pa_b;  pb_w [D_out, Dmid], pb_b   (pb_* only for MLP)

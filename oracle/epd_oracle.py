@@ -154,10 +154,16 @@ def encoder_layer(x, w, desc, l: int):
         q = rms_norm(q.reshape(-1, H, hd), w[p + "qn_g"], desc.eps).reshape(-1, D)
         k = rms_norm(k.reshape(-1, H, hd), w[p + "kn_g"], desc.eps).reshape(-1, D)
     o = attention(q, k, v, H)
-    x = x + linear(o, w[p + "o_w"], w[p + "o_b"])
+    branch = linear(o, w[p + "o_w"], w[p + "o_b"])
+    if getattr(desc, "layer_scale", 0):
+        branch = branch * np.asarray(w[p + "ls1"], F64)     # per-channel layer scale
+    x = x + branch
     u = _norm(x, w, p + "n2", desc.norm, desc.eps)
     hmid = _act(linear(u, w[p + "fc1_w"], w[p + "fc1_b"]), desc.act)
-    x = x + linear(hmid, w[p + "fc2_w"], w[p + "fc2_b"])
+    branch = linear(hmid, w[p + "fc2_w"], w[p + "fc2_b"])
+    if getattr(desc, "layer_scale", 0):
+        branch = branch * np.asarray(w[p + "ls2"], F64)
+    x = x + branch
     return x
 
 

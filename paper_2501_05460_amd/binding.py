@@ -42,7 +42,7 @@ class ModelDescC(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "dtype", "tile_size", "patch", "hidden", "heads", "mlp", "layers", "norm", "qk_norm", "act",
         "final_norm", "pixel_shuffle", "proj_kind", "proj_prenorm", "proj_mid", "proj_out")] + [
-        ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32)]
+        ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32), ("layer_scale", ctypes.c_int32)]
 
 
 class WeightsC(ctypes.Structure):

@@ -37,7 +37,7 @@ inline int pad_n(int n) { return n > 128 ? round_up(n, 256) : round_up(n, 128); 
 // --------------------------------------------------------------------------
 struct TensorSpec { long rows, cols; };  // vectors: rows = 1
 
-struct LayerIdx { int n1_g, n1_b, qkv_w, qkv_b, qn_g, kn_g, o_w, o_b, n2_g, n2_b, fc1_w, fc1_b, fc2_w, fc2_b; };
+struct LayerIdx { int n1_g, n1_b, qkv_w, qkv_b, qn_g, kn_g, o_w, o_b, ls1, n2_g, n2_b, fc1_w, fc1_b, fc2_w, fc2_b, ls2; };
 
 struct WeightIndex {
   int pe_w, pe_b, pos;
@@ -75,9 +75,11 @@ WeightIndex build_index(const epd_model_desc& d) {
     if (d.qk_norm == EPD_QKNORM_FULL) { i.qn_g = add(1, x.D); i.kn_g = add(1, x.D); }
     if (d.qk_norm == EPD_QKNORM_PER_HEAD) { i.qn_g = add(1, x.hd); i.kn_g = add(1, x.hd); }
     i.o_w = add(x.D, x.D); i.o_b = add(1, x.D);
+    i.ls1 = d.layer_scale ? add(1, x.D) : -1;
     i.n2_g = add(1, x.D); i.n2_b = ln ? add(1, x.D) : -1;
     i.fc1_w = add(x.F, x.D); i.fc1_b = add(1, x.F);
     i.fc2_w = add(x.D, x.F); i.fc2_b = add(1, x.D);
+    i.ls2 = d.layer_scale ? add(1, x.D) : -1;
     w.layers.push_back(i);
   }
   w.fn_g = w.fn_b = w.pn_g = w.pn_b = w.pb_w = w.pb_b = -1;
@@ -97,7 +99,8 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->dtype != EPD_DTYPE_FP32 && d->dtype != EPD_DTYPE_BF16) { set_err(err, len, "dtype must be 0 (fp32) or 1 (bf16)"); return EPD_ERR_INVALID_ARG; }
   if (d->norm < 0 || d->norm > 1 || d->qk_norm < 0 || d->qk_norm > 2 || d->act < 0 || d->act > 1 ||
       d->final_norm < 0 || d->final_norm > 1 || d->pixel_shuffle < 0 || d->pixel_shuffle > 1 ||
-      d->proj_kind < 0 || d->proj_kind > 1 || d->proj_prenorm < 0 || d->proj_prenorm > 1) {
+      d->proj_kind < 0 || d->proj_kind > 1 || d->proj_prenorm < 0 || d->proj_prenorm > 1 ||
+      d->layer_scale < 0 || d->layer_scale > 1) {
     set_err(err, len, "an enum field of the description is out of range"); return EPD_ERR_INVALID_ARG;
   }
   if (d->tile_size <= 0 || d->patch <= 0 || d->hidden <= 0 || d->heads <= 0 || d->mlp <= 0 ||
@@ -322,6 +325,14 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         lw.kn_g = make_vec(c, w, li.kn_g, x.hd, c->hd_pad, id, st);
         NOMEM_IF(!lw.qn_g || !lw.kn_g);
       }
+    }
+    if (d.layer_scale) {
+      // layer scale is folded into the branch's last Linear: rows of W and the bias times ls
+      const float* ls1 = make_vec(c, w, li.ls1, x.D, x.D, id, st);
+      const float* ls2 = make_vec(c, w, li.ls2, x.D, x.D, id, st);
+      NOMEM_IF(!ls1 || !ls2);
+      scale_rows(const_cast<void*>(lw.o.W), bf ? 1 : 0, x.D, lw.o.K, lw.o.K, const_cast<float*>(lw.o.b), ls1, st);
+      scale_rows(const_cast<void*>(lw.fc2.W), bf ? 1 : 0, x.D, lw.fc2.K, lw.fc2.K, const_cast<float*>(lw.fc2.b), ls2, st);
     }
     c->layers.push_back(lw);
   }

@@ -78,6 +78,10 @@ void pack_matrix_bf16(const bf16_t* src, int rows, int cols, bf16_t* dst, int ro
 void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_pad, PackMap map,
                      hipStream_t st);
 
+// Layer scale folded into a packed Linear: W[r][0..cols) *= s[r] for r < rows (row stride ld), and
+// b[r] *= s[r].  W is bf16 or fp32, s and b fp32.
+void scale_rows(void* W, int w_is_bf16, int rows, int cols, long ld, float* b, const float* s, hipStream_t st);
+
 // Paged multimodal-token cache: copy `n_blocks` blocks of `block_bytes` (multiple of 16) from
 // src_pool[src_ids[i]] to dst_pool[dst_ids[i]]; a null id array means block i (contiguous side).
 void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, const int* dst_ids,

@@ -225,6 +225,24 @@ void pack_vector_f32(const void* src, int src_is_bf16, int n, float* dst, int n_
   k_pack_vector<<<dim3((n_pad + 255) / 256), dim3(256), 0, st>>>(src, src_is_bf16, n, dst, n_pad, map);
 }
 
+template <typename T>
+__global__ void k_scale_rows(T* __restrict__ W, int rows, int cols, long ld, float* __restrict__ b,
+                             const float* __restrict__ s) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)rows * cols) return;
+  const int r = (int)(i / cols), c = (int)(i % cols);
+  W[(long)r * ld + c] = (T)((float)W[(long)r * ld + c] * s[r]);
+  if (c == 0) b[r] *= s[r];
+}
+
+void scale_rows(void* W, int w_is_bf16, int rows, int cols, long ld, float* b, const float* s, hipStream_t st) {
+  const long total = (long)rows * cols;
+  if (total == 0) return;
+  const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (w_is_bf16) k_scale_rows<bf16_t><<<grid, block, 0, st>>>((bf16_t*)W, rows, cols, ld, b, s);
+  else k_scale_rows<float><<<grid, block, 0, st>>>((float*)W, rows, cols, ld, b, s);
+}
+
 // ------------------------------------------------- paged cache block copy ----
 // `per_block` consecutive workgroups share one cache block, each moving chunks
 // of 16 KiB: a thread issues four 16-byte loads before the four stores, so a

@@ -37,6 +37,9 @@ def test_weight_count_matches_generator_order():
     d = wl.workload("c4").desc
     assert B.weight_count(d.replace(qk_norm=wl.QKNORM_PER_HEAD, final_norm=1)) == \
         len(wl.weight_specs(d.replace(qk_norm=wl.QKNORM_PER_HEAD, final_norm=1)))
+    scaled = d.replace(layer_scale=1)                      # two more vectors per layer
+    assert B.weight_count(scaled) == B.weight_count(d) + 2 * d.layers == len(wl.weight_specs(scaled))
+    assert B.weight_count(d.replace(layer_scale=2)) == B.EPD_ERR_INVALID_ARG
 
 
 def test_check_desc_accepts_the_five_configs():

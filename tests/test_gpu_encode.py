@@ -30,6 +30,8 @@ VARIANTS = {
     "hd72": dict(hidden=144, heads=2),
     "hd128_3heads": dict(hidden=384, heads=3, mlp=512),
     "hd32": dict(hidden=96, heads=3),
+    "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=136),
+    "layer_scale_hd72": dict(layer_scale=1, hidden=144, heads=2, act=wl.ACT_GELU_TANH),
 }
 
 

@@ -29,6 +29,7 @@ VARIANTS = {
                        proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
     "rms_qkhead_final": dict(norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_PER_HEAD, final_norm=1),
     "ln_final": dict(final_norm=1, heads=4),
+    "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
 }
 
 
@@ -60,11 +61,13 @@ def torch_second_opinion(tile, w, desc):
             k = F.rms_norm(k, (hd,), t[pre + "kn_g"], desc.eps)
         o = F.scaled_dot_product_attention(q[None], k[None], v[None])[0]    # [H,N,hd]
         o = o.transpose(0, 1).reshape(-1, D)
-        x = x + F.linear(o, t[pre + "o_w"], t[pre + "o_b"])
+        ls1 = t[pre + "ls1"] if desc.layer_scale else 1.0
+        ls2 = t[pre + "ls2"] if desc.layer_scale else 1.0
+        x = torch.addcmul(x, F.linear(o, t[pre + "o_w"], t[pre + "o_b"]), torch.as_tensor(ls1, dtype=x.dtype).expand(D))
         u = norm(x, pre + "n2", desc.norm)
         hmid = F.gelu(F.linear(u, t[pre + "fc1_w"], t[pre + "fc1_b"]),
                       approximate="tanh" if desc.act == wl.ACT_GELU_TANH else "none")
-        x = x + F.linear(hmid, t[pre + "fc2_w"], t[pre + "fc2_b"])
+        x = torch.addcmul(x, F.linear(hmid, t[pre + "fc2_w"], t[pre + "fc2_b"]), torch.as_tensor(ls2, dtype=x.dtype).expand(D))
     if desc.final_norm:
         x = norm(x, "fn", desc.norm)
     if desc.pixel_shuffle:
@@ -255,3 +258,45 @@ def test_project_merge_of_shards_in_slice_order_is_the_encode():
     assert np.abs(swapped - ref).max() > 1e-3 * np.abs(ref).max()
     n = O.tokens_per_tile(desc)
     assert np.allclose(swapped[:2 * n], ref[3 * n:5 * n], rtol=0, atol=1e-12)
+
+
+def test_layer_scale_of_ones_changes_nothing_and_of_zeros_removes_the_layers():
+    plain = small_desc(final_norm=1)
+    scaled = small_desc(final_norm=1, layer_scale=1)
+    w = wl.gen_weights(scaled, 23, std=0.08)
+    tile = wl.gen_tiles(scaled, 23, 1)[0]
+    got = O.encode_tile(tile, w, scaled)
+    w_plain = {k: v for k, v in w.items() if not k.endswith(("ls1", "ls2"))}
+    base = O.encode_tile(tile, w_plain, plain)
+    assert np.abs(got - base).max() > 1e-3 * np.abs(base).max()          # the factors are in use
+    for k in w:
+        if k.endswith(("ls1", "ls2")):
+            w[k] = np.ones_like(w[k])
+    assert np.array_equal(O.encode_tile(tile, w, scaled), base)
+    for k in w:
+        if k.endswith(("ls1", "ls2")):
+            w[k] = np.zeros_like(w[k])
+    no_layers = O.encode_tile(tile, w_plain, small_desc(final_norm=1, layers=0))
+    assert np.allclose(O.encode_tile(tile, w, scaled), no_layers, rtol=0, atol=1e-13)
+
+
+def test_layer_scale_acts_per_channel_on_the_branch_not_on_the_stream():
+    """x + ls * f(x): doubling one channel of ls2 of the last layer moves exactly that channel of
+    the pre-projection tokens, by exactly the branch value."""
+    desc = small_desc(layer_scale=1)
+    w = wl.gen_weights(desc, 24, std=0.08)
+    tile = wl.gen_tiles(desc, 24, 1)[0]
+    a = O.trunk_tile(tile, w, desc)
+    w2 = dict(w)
+    ls = np.array(w["l1_ls2"], np.float64).copy()
+    ls[5] *= 2.0
+    w2["l1_ls2"] = ls
+    b = O.trunk_tile(tile, w2, desc)
+    diff = b - a
+    assert np.abs(np.delete(diff, 5, axis=1)).max() == 0.0
+    w3 = dict(w)
+    z = np.array(w["l1_ls2"], np.float64).copy()
+    z[5] = 0.0
+    w3["l1_ls2"] = z
+    branch5 = (a - O.trunk_tile(tile, w3, desc))[:, 5]                   # ls2[5] * mlp(x)[:, 5]
+    assert np.allclose(diff[:, 5], branch5, rtol=1e-12, atol=1e-14)

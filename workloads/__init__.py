@@ -58,6 +58,7 @@ class ModelDesc:
     proj_out: int
     eps: float
     max_tiles_per_call: int
+    layer_scale: int = 0
 
     # ---- shape bookkeeping only (counts, no arithmetic on data) ----
     @property
@@ -210,7 +211,7 @@ def shard_range(n_tiles: int, shard: int, n_shards: int) -> Tuple[int, int]:
 
 def weight_specs(desc: ModelDesc) -> List[Tuple[str, Tuple[int, ...], str]]:
     """(name, shape, kind) in boundary order.  kind: 'w' matrix/bias/pos-emb,
-    'g' norm gain, 'b' norm shift."""
+    'g' norm gain, 'b' norm shift, 's' layer-scale vector."""
     D, F, N = desc.hidden, desc.mlp, desc.n_patches
     specs: List[Tuple[str, Tuple[int, ...], str]] = []
 
@@ -235,11 +236,15 @@ def weight_specs(desc: ModelDesc) -> List[Tuple[str, Tuple[int, ...], str]]:
             specs.append((p + "kn_g", (desc.head_dim,), "g"))
         specs.append((p + "o_w", (D, D), "w"))
         specs.append((p + "o_b", (D,), "w"))
+        if desc.layer_scale:
+            specs.append((p + "ls1", (D,), "s"))
         norm(p + "n2", D, desc.norm)
         specs.append((p + "fc1_w", (F, D), "w"))
         specs.append((p + "fc1_b", (F,), "w"))
         specs.append((p + "fc2_w", (D, F), "w"))
         specs.append((p + "fc2_b", (D,), "w"))
+        if desc.layer_scale:
+            specs.append((p + "ls2", (D,), "s"))
     if desc.final_norm:
         norm("fn", D, desc.norm)
     if desc.proj_prenorm:
@@ -287,6 +292,8 @@ def gen_weight(desc: ModelDesc, seed: int, index: int, std: float = 0.02,
     w = rng.standard_normal(size=shape, dtype=np.float32) * np.float32(std)
     if kind == "g":
         w = w + np.float32(1.0)
+    if kind == "s":   # layer scale: spread over 0.1 .. 1, so a missing or misplaced factor shows
+        w = np.float32(0.1) + np.float32(0.9) * rng.random(size=shape, dtype=np.float32)
     if scale:
         for key, s in scale.items():
             if name.endswith(key):
