@@ -515,6 +515,237 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   }  // staging kind
 }
 
+
+// ---------------------------------------------------------------------------
+// Persistent form of the default shape (256 x 256 x 64 tile, 8 waves, pipelined
+// loop) for the epilogues with bf16 output.  One workgroup per CU walks the
+// tile sequence with stride gridDim.x.  The loads that would run past the last
+// slab of a tile fetch the first two slabs of the workgroup's NEXT tile instead
+// (slab 0 into LDS buffer 0, slab 1 into a register set), and the epilogue
+// stages the finished tile through LDS buffer 1 only, in two passes of 128
+// rows: the next tile's main loop starts right behind the last store, without
+// the launch gap and the exposed first-slab latency a fresh workgroup pays.
+// ---------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p, const int gm_, const int gw,
+                                                              const int n_tiles) {
+  constexpr int BN = 256, NTHREADS = 512, WN = 64, WAVES_N = 4, WM = 128, TM = 4, TN = 2;
+  constexpr int A_LD = 4, B_LD = 4, ROWS_PER_LD = 64;
+  constexpr bool tok_major = (EPI == EPI_VT);
+  static_assert(EPI != EPI_BIAS_RESIDUAL && EPI != EPI_BIAS_POS, "bf16-output epilogues only");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [2][BN][64]: bytes 0 .. 64 Ki
+  bf16_t* sA = sB + 2 * BN * BK;                 // [2][BM][64]: bytes 64 Ki .. 128 Ki
+  float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int KT_ = p.K / BK;  // even
+  const int gn = p.Npad / BN;
+
+  // position in the launch order -> tile (same XCD-aware band order as the one-tile kernel; a
+  // persistent workgroup keeps pos % 8, i.e. its XCD)
+  auto tile_of = [&](int pos, int& m0, int& n0) {
+    const int x = pos & 7, slot = pos >> 3;
+    const int q = n_tiles >> 3, r = n_tiles & 7;
+    const int id = x * q + (x < r ? x : r) + slot;
+    const int band_tiles = gm_ * gw;
+    const int full_bands = gn / gw;
+    int band = id / band_tiles, in_band = id % band_tiles, bw = gw;
+    if (band >= full_bands) { band = full_bands; in_band = id - full_bands * band_tiles; bw = gn - full_bands * gw; }
+    m0 = (in_band / bw) * BM;
+    n0 = (band * gw + in_band % bw) * BN;
+  };
+
+  const int ld_row = tid >> 3, ld_c = tid & 7;
+  const int st_off = ld_row * BK + ((ld_c ^ SWZ(ld_row)) * 8);
+  const unsigned a_voff = ((unsigned)ld_row * (unsigned)p.lda + ld_c * 8) * 2;
+  const unsigned bd_voff = ((unsigned)ld_row * (unsigned)p.K + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<bf16_t*>(p.A), 0, (int)(unsigned)(((long)(p.M - 1) * p.lda + p.K) * 2), 0x00020000);
+
+  u32x4 ra[2][A_LD];
+  auto gload = [&](auto set, int mrow0, int kt) {   // activation slab kt of the tile rows mrow0 ..
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+      const unsigned so = ((unsigned)(mrow0 + ROWS_PER_LD * i) * (unsigned)p.lda + (unsigned)(kt * BK)) * 2u;
+      ra[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, a_voff, so, 0);
+    }
+  };
+  auto bload = [&](int buf, int ncol0, int kt) {    // weight slab kt of the tile columns ncol0 .. -> LDS
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+      const bf16_t* g = p.W + (long)(ncol0 + ROWS_PER_LD * i) * p.K + kt * BK;   // uniform
+      bf16_t* l = sB + buf * BN * BK + (wave_u * 64 + NTHREADS * i) * 8;
+      const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(bd_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+    }
+  };
+  auto sstore = [&](auto set, int buf) {
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i)
+      *reinterpret_cast<u32x4*>(sA + buf * BM * BK + ROWS_PER_LD * i * BK + st_off) = ra[S][i];
+  };
+  auto wait_vm = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
+  };
+
+  f32x16 acc[TM][TN];
+  bf16x8 fa[2][TM], fb[2][TN];
+  const int frag_sw = SWZ(l32);
+  auto ldfrag = [&](auto set, int buf, int kk) {
+    constexpr int S = decltype(set)::value;
+    const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
+    const bf16_t* b_s = sB + buf * BN * BK + (wn * WN + l32) * BK;
+    const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[S][i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * BK + coff);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[S][j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * BK + coff);
+  };
+  auto mma = [&](auto set) {
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = tok_major ? mfma32(fa[S][i], fb[S][j], acc[i][j]) : mfma32(fb[S][j], fa[S][i], acc[i][j]);
+  };
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  using VM_A = std::integral_constant<int, A_LD>;
+
+  int pos = blockIdx.x, m0, n0, m0n, n0n;
+  tile_of(pos, m0, n0);
+  if (tid < BN) sBias[tid] = p.bias[n0 + tid];
+  bload(0, n0, 0);
+  gload(S0{}, m0, 0);
+  gload(S1{}, m0, 1);
+  sstore(S0{}, 0);
+  wait_vm(VM_A{});   // loads complete in order: all but slab 1's are done, weight slab 0 has landed
+  __syncthreads();
+
+  for (;;) {
+    ldfrag(S0{}, 0, 0);   // (the copy the last hand-over of the previous tile read is not kept across the epilogue)
+    const int nxt = pos + (int)gridDim.x;
+    const bool has_next = nxt < n_tiles;
+    if (has_next) tile_of(nxt, m0n, n0n); else { m0n = m0; n0n = n0; }   // no next tile: harmless re-reads
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // slab kt sits in LDS buffer `buf` with its first fragments in set 0; slab kt+1 in the register
+    // set `sset`.  Slab indices past the tile's end name the first slabs of the next tile.
+    auto slab = [&](auto lset, auto sset, int buf, int kt) {
+      const bool w_own = kt + 1 < KT_, a_own = kt + 2 < KT_;
+      bload(buf ^ 1, w_own ? n0 : n0n, w_own ? kt + 1 : kt + 1 - KT_);
+      gload(lset, a_own ? m0 : m0n, a_own ? kt + 2 : kt + 2 - KT_);
+      __builtin_amdgcn_sched_barrier(0);
+      ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
+      ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
+      ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      sstore(sset, buf ^ 1);
+      wait_vm(VM_A{});
+      __syncthreads();
+      ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
+    };
+    for (int kt = 0; kt < KT_; kt += 2) {
+      slab(S0{}, S1{}, 0, kt);
+      slab(S1{}, S0{}, 1, kt + 1);
+    }
+    // Here LDS buffer 0 holds slab 0 of the next tile and register set 1 holds its slab 1; nobody reads buffer 1 any more (the reads of the last slab were
+    // complete at the barrier inside its hand-over).
+
+    // ---- epilogue through LDS buffer 1: staging rows 0..63 of a pass in sB[1], 64..127 in sA[1] ----
+    constexpr int ROWB = 512, NCH = 32;
+    auto stage_row = [&](int r) -> unsigned char* {   // r = 0..127 inside the pass
+      return reinterpret_cast<unsigned char*>(r < 64 ? sB + BN * BK : sA + BM * BK) + (r & 63) * ROWB;
+    };
+    // Every wave stages half of its own sub-tiles per pass (token-major result: its 32-row group
+    // j == pass of both halves i; otherwise its groups i = 2 pass, 2 pass + 1), so a pass holds 128
+    // staging rows: slot (r / G) * G + r % G  <->  tile row (slot / G) * 2G + pass * G + slot % G,
+    // G = 32 (token-major) or 64.
+    constexpr int G = tok_major ? 32 : 64;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      if (pass > 0) __syncthreads();   // pass 0 has been read out
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if ((tok_major ? j : i / 2) != pass) continue;
+          // lane dimension: feature (tok_major) or token; register dimension: the other one
+          const int rg = tok_major ? (wn * WN + j * 32 + l32) : (wm * WM + i * 32 + l32);
+          const int r = (rg / (2 * G)) * G + rg % G;
+          float bl = 0.f;
+          if (tok_major) bl = sBias[rg];
+          unsigned char* srow = stage_row(r);
+#pragma unroll
+          for (int gi = 0; gi < 4; ++gi) {
+            const int cl = (tok_major ? (wm * WM + i * 32) : (wn * WN + j * 32)) + gi * 8 + lh * 4;
+            float v[4];
+            if (tok_major) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+            } else {
+              const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
+              v[0] = acc[i][j][gi * 4 + 0] + b4.x; v[1] = acc[i][j][gi * 4 + 1] + b4.y;
+              v[2] = acc[i][j][gi * 4 + 2] + b4.z; v[3] = acc[i][j][gi * 4 + 3] + b4.w;
+            }
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act_fast<EPI>(v[e]);
+            *reinterpret_cast<bf16x4*>(srow + (((cl >> 3) ^ (r & 15)) << 4) + ((cl & 4) << 1)) = o;
+          }
+        }
+      __syncthreads();
+      if (pass == 1 && has_next && tid < BN) sBias[tid] = p.bias[n0n + tid];   // every bias read is behind us
+#pragma unroll
+      for (int i = 0; i < 128 * NCH / NTHREADS; ++i) {
+        const int q = tid + NTHREADS * i;
+        const int r = q / NCH, c = q % NCH;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
+        const int rg = (r / G) * 2 * G + pass * G + r % G;
+        if (tok_major) {
+          const int f = n0 + rg, tok = m0 + c * 8;
+          if (f < p.N && tok < p.M) {
+            const int h = f / p.hd_pad, d = f % p.hd_pad;
+            const int t = tok / p.n_tok, n = tok % p.n_tok;
+            *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v;
+          }
+        } else {
+          const int row = m0 + rg, col = n0 + c * 8;
+          if (row < p.M && col < p.N) {
+            const long orow = p.row_map ? (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens : row;
+            *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v;
+          }
+        }
+      }
+    }
+    if (!has_next) break;
+    __syncthreads();   // buffer 1 has been read out: the next tile's first hand-over may fill it
+    pos = nxt; m0 = m0n; n0 = n0n;
+  }
+}
+
 template <int BN, int NT>
 constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT>() + BN * sizeof(float); }
 
@@ -538,6 +769,54 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
   if (p.band > 0 && p.band <= gn) gw = p.band;
   k_gemm_bf16<BN, NT, WN, EPI, PIPE><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
   return hipGetLastError();
+}
+
+int cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
+}
+
+template <int EPI>
+hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
+  const int gm = (p.M + BM - 1) / BM, gn = p.Npad / 256;
+  const int n_tiles = gm * gn;
+  if (n_tiles == 0) return hipSuccess;
+  const double panel = 256.0 * p.K * sizeof(bf16_t);
+  int gw = 1;
+  double best = 1e30;
+  for (int c = 1; c <= gn && c <= 32; ++c) {
+    const bool resident = c * 256.0 * p.K * sizeof(bf16_t) <= 2.5 * (1 << 20);
+    const double cost = (32.0 / c) * panel + (resident ? 0.0 : c * panel);
+    if (cost < best * 0.999) { best = cost; gw = c; }
+  }
+  if (p.band > 0 && p.band <= gn) gw = p.band;
+  const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
+  k_gemm_bf16_persist<EPI><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  return hipGetLastError();
+}
+
+hipError_t dispatch_persist(const GemmParams& p, hipStream_t st) {
+  switch (p.epi) {
+    case EPI_BIAS: return launch_persist<EPI_BIAS>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch_persist<EPI_BIAS_GELU_ERF>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch_persist<EPI_BIAS_GELU_TANH>(p, st);
+    case EPI_VT: return launch_persist<EPI_VT>(p, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int EPI>
+hipError_t set_attr_persist() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist<EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>());
 }
 
 template <int BN, int NT, int WN, int PIPE = 0>
@@ -576,6 +855,10 @@ hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_VT>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 256, 64>()) != hipSuccess) return e;
   return set_attr_all<256, 256, 128>();
@@ -595,8 +878,10 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 4: if (p.Npad % 256 == 0) return dispatch<256, 256, 128>(p, st); break;
     case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
+    case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
   }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
+  if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st);
   return dispatch<256, 512, 64, 1>(p, st);
 }
 
