@@ -46,26 +46,23 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// Configurations (BN, NTHREADS[, WN = 64]):
-//   (256, 512)  256x256 tile, 8 waves, one workgroup per CU, two LDS buffers
-//               (PIPE = 1: the default; PIPE = 0: both operands two slabs ahead
-//               in two register sets);
-//   (128, 512)  256x128 tile, 8 waves (64x64 per wave), PIPE = 0;
-//   (128, 256)  256x128 tile, 4 waves (128x64 per wave), TWO workgroups per CU:
-//               one LDS buffer and one register set each;
-//   (256, 256, WN = 128)  256x256 tile, 4 waves of 128x128: one wave per SIMD
-//               with the 256 accumulators in AGPRs; a third less LDS read
-//               traffic per MFMA than the 128x64 wave tiles.
+// Configurations (BN, 512 threads, 64-wide wave tiles), one workgroup per CU, two LDS buffers:
+//   BN = 256  256x256 tile, 128x64 per wave (PIPE = 1: pipelined loop, the default; PIPE = 0:
+//             both operands two slabs ahead in two register sets, fragment reads left to the
+//             compiler: the reference the pipelined loop is checked against bit for bit);
+//   BN = 128  256x128 tile, 64x64 per wave, PIPE = 0: outputs narrower than 256 columns.
+// (Tried and dropped, none faster on the six workloads: 4 waves of 128x128 with AGPR
+// accumulators, 256x128 tiles with two 4-wave workgroups per CU, 32-deep slabs.)
 template <int BN, int NT>
 constexpr size_t smem_main_bytes() {
-  // operand slabs, or the epilogue staging tile (256 x BN bf16 / 128 x BN fp32), whichever is larger
-  constexpr size_t operands = (size_t)((NT == 256 && BN == 128) ? 1 : 2) * (BM + BN) * BK * sizeof(bf16_t);
+  // operand slabs, or the epilogue staging tile (256 x BN bf16 / 64 x BN fp32), whichever is larger
+  constexpr size_t operands = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
   constexpr size_t staging = (size_t)BM * BN * sizeof(bf16_t);
   return operands > staging ? operands : staging;
 }
 
 template <int BN, int NTHREADS, int WN, int EPI, int PIPE>
-__global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
+__global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
   constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
@@ -74,7 +71,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   constexpr int TN = WN / 32;                // 2 | 4
   constexpr int A_LD = BM * 8 / NTHREADS;    // 16-byte chunks per thread per slab
   constexpr int B_LD = BN * 8 / NTHREADS;
-  constexpr int NBUF = (NTHREADS == 256 && WN == 64) ? 1 : 2;  // LDS slab buffers = register sets
+  constexpr int NBUF = 2;  // LDS slab buffers = register sets
   constexpr int ROWS_PER_LD = NTHREADS / 8;      // rows covered by one 16-byte load per thread
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -142,7 +139,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
   constexpr bool B_DIRECT = PIPE == 1;
   // the operand register sets can carry residual rows of the first passes when the counts match:
   // both sets = passes 0 and 1 (A and B staged), or both sets = the two halves of pass 0 (A staged only)
-  constexpr bool X_IN_LOOP = EPI == EPI_BIAS_RESIDUAL && NBUF == 2 && !(NTHREADS == 256 && WN == 128) &&
+  constexpr bool X_IN_LOOP = EPI == EPI_BIAS_RESIDUAL &&
                              (B_DIRECT ? XPER_T == 2 * A_LD : XPER_T == A_LD + B_LD);
   f32x4 xr[2][X_IN_LOOP ? XPER_T : 1];
   auto xload = [&](auto set, int pass) {
@@ -289,7 +286,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  if constexpr (NBUF == 2 && (PIPE >= 1 || (NTHREADS == 256 && WN == 128))) {
+  if constexpr (PIPE == 1) {
     // The operand fragments run one k-step ahead of the MFMAs in a second
     // register set, so a wave issues its MFMAs back to back instead of
     // waiting for LDS in front of every k-step; the slab hand-over (LDS
@@ -363,7 +360,7 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
         xr[1][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[1][i < A_LD ? i : 0] : rb[1][i < A_LD ? 0 : i - A_LD]);
       }
     }
-  } else if constexpr (NBUF == 2) {
+  } else {
     gload(S0{}, 0);
     gload(S1{}, 1);
     sstore(S0{}, 0);
@@ -385,17 +382,6 @@ __global__ __launch_bounds__(NTHREADS, (NTHREADS == 256 && WN == 64) ? 2 : 1) vo
         xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
         xr[1][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[1][i < A_LD ? i : 0] : rb[1][i < A_LD ? 0 : i - A_LD]);
       }
-    }
-  } else {
-    gload(S0{}, 0);
-    sstore(S0{}, 0);
-    __syncthreads();
-    for (int kt = 0; kt < KT_; ++kt) {
-      gload(S0{}, kt + 1);
-      compute(0);
-      __syncthreads();   // every wave has read the slab
-      sstore(S0{}, 0);
-      __syncthreads();
     }
   }
 
@@ -860,8 +846,7 @@ hipError_t bf16_gemm_init() {
   if ((e = set_attr_persist<EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_VT>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
-  if ((e = set_attr_all<128, 256, 64>()) != hipSuccess) return e;
-  return set_attr_all<256, 256, 128>();
+  return hipSuccess;
 }
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
@@ -874,8 +859,6 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
   switch (p.cfg) {
     case 1: return dispatch<128, 512, 64>(p, st);
-    case 2: return dispatch<128, 256, 64>(p, st);
-    case 4: if (p.Npad % 256 == 0) return dispatch<256, 256, 128>(p, st); break;
     case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;

@@ -22,7 +22,8 @@ void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t s
 // beyond N); K % 128 == 0; N % 4 == 0 (N % 8 == 0 for bf16 outputs); Npad % 128 == 0.
 struct GemmParams {
   int epi;
-  int cfg;                    // 0 default; 1: 256x128 / 8 waves; 2: 256x128 / 4 waves, 2 per CU; 3: 256x256 / 8 waves
+  int cfg;                    // 0: chosen by shape and epilogue; tests / timing: 1 = 256x128 tile, 6 = 256x256 plain loop,
+                              // 7 = 256x256 pipelined loop, 9 = 256x256 persistent (bf16-output epilogues)
   int band;                   // 0: automatic; else tile columns per L2 band (must divide Npad / BN)
   const bf16_t* A; long lda;
   const bf16_t* W;            // packed [Npad, K]
