@@ -260,6 +260,15 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
                             int32_t N, int32_t K, int32_t iters, float* ms_per_launch,
                             void* hip_stream);
 
+/* One launch of the bf16 MFMA GEMM in a chosen form, for tests that hold the forms against each
+ * other: epi 0 bias, 1 bias + GELU(erf), 2 bias + GELU(tanh) -> C [M,N] bf16; epi 3 -> R [M,N]
+ * fp32 += A W^T + bias (C unused).  form 0 = what the library would pick, 1 = 256x128 tile,
+ * 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
+ * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 9), K % 128 == 0; bias [N] fp32. */
+epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias, void* C, float* R,
+                                 int32_t M, int32_t N, int32_t K, int32_t epi, int32_t form,
+                                 void* hip_stream);
+
 /* Tile-local non-causal attention on packed slices, bf16:  for every slice t
  * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
  * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk

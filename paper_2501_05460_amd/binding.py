@@ -30,7 +30,7 @@ PROF_FAMILIES = ("embed", "norm", "gemm_qkv", "attention", "qk_norm", "proj_inpu
 EXPORTS = (
     "epd_weight_count", "epd_check_desc", "epd_check_offsets", "epd_create", "epd_encode",
     "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
-    "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_attention_bf16", "epd_op_mfma_probe",
+    "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_gather",
@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.epd_debug_read_stream.restype = i32
         L.epd_op_gemm_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.epd_op_gemm_bf16.restype = i32
+        L.epd_op_gemm_bf16_form.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.epd_op_gemm_bf16_form.restype = i32
         L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.epd_op_attention_bf16.restype = i32
         L.epd_op_mfma_probe.argtypes = [vp, vp, vp, vp]
@@ -352,6 +354,19 @@ def op_gemm_bf16(A: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor],
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())
     return C, ms.value
+
+
+def op_gemm_bf16_form(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, epi: int, form: int,
+                      R: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One GEMM launch in the given form; returns C (bf16) or, for epi 3, the updated R (fp32, in place)."""
+    M, K = A.shape
+    N = W.shape[0]
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device) if epi != 3 else None
+    s = lib().epd_op_gemm_bf16_form(A.data_ptr(), W.data_ptr(), bias.data_ptr(), C.data_ptr() if C is not None else None,
+                                    R.data_ptr() if R is not None else None, M, N, K, epi, form, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return C if epi != 3 else R
 
 
 def op_attention_bf16(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int,

@@ -852,6 +852,26 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
   return EPD_OK;
 }
 
+epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias, void* C, float* R, int32_t M,
+                                 int32_t N, int32_t K, int32_t epi, int32_t form, void* hip_stream) {
+  const bool residual = epi == EPI_BIAS_RESIDUAL;
+  if (!A || !W || !bias || (residual ? !R : !C) || M <= 0 || N <= 0 || K <= 0 || N % 128 || K % 128 ||
+      !(epi == EPI_BIAS || epi == EPI_BIAS_GELU_ERF || epi == EPI_BIAS_GELU_TANH || residual) ||
+      !(form == 0 || form == 1 || form == 6 || form == 7 || form == 9) || (form >= 6 && N % 256) ||
+      (form == 9 && residual)) {
+    set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16_form: bad argument");
+    return EPD_ERR_INVALID_ARG;
+  }
+  if (bf16_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = epi; p.cfg = form; p.A = (const bf16_t*)A; p.lda = K; p.W = (const bf16_t*)W; p.bias = bias;
+  p.M = M; p.N = N; p.K = K; p.Npad = N; p.C = (bf16_t*)C; p.ldc = N; p.R = R; p.ldr = N; p.n_pos = 1;
+  const hipError_t err = bf16_gemm(p, (hipStream_t)hip_stream);
+  if (err != hipSuccess) { set_err(g_err, sizeof(g_err), "gemm launch failed: %s", hipGetErrorString(err)); return EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o, int32_t n_slices,
                                  int32_t n_tokens, int32_t heads, int32_t hd_pad, int32_t ld_qk, float scale,
                                  void* hip_stream) {

@@ -83,3 +83,31 @@ def test_attention_bf16_vs_oracle(n_slices, n_tok, heads, hd, hd_pad, qk_scale):
     # sharp softmax rows, so a wrong key set or a cross-slice leak is visible
     got, want = _attention_case(n_slices, n_tok, heads, hd, hd_pad, qk_scale, seed=n_tok + hd)
     assert rel_err(got, want) < 1.5e-2
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 128), (1000, 512, 256), (2304, 1024, 1024), (77, 256, 384)])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3])
+def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
+    """The plain loop, the pipelined loop (weights straight into LDS, fragments one k-step ahead) and
+    the persistent kernel order every sum the same way: identical bits, ragged M included; the
+    256x128 tile too."""
+    rng = np.random.default_rng(M + N + K + epi)
+    A = B.to_device(_bf16_grid(rng, (M, K), 0.5), True)
+    W = B.to_device(_bf16_grid(rng, (N, K), 0.05), True)
+    bias = torch.from_numpy(rng.standard_normal(N).astype(np.float32) * 0.1).cuda()
+    r0 = torch.from_numpy(rng.standard_normal((M, N)).astype(np.float32)).cuda()
+
+    def run(form):
+        R = r0.clone() if epi == 3 else None
+        out = B.op_gemm_bf16_form(A, W, bias, epi, form, R)
+        torch.cuda.synchronize()
+        return out.view(torch.int16 if epi != 3 else torch.int32).cpu().numpy()
+
+    ref = run(6)
+    forms = [0, 1, 7] + ([9] if epi != 3 else [])
+    for form in forms:
+        assert np.array_equal(run(form), ref), form
+    if epi == 0:   # and the value itself, against the oracle
+        want = O.linear(A.float().cpu().numpy(), W.float().cpu().numpy(), bias.cpu().numpy())
+        got = B.op_gemm_bf16_form(A, W, bias, 0, 0).float().cpu().numpy()
+        assert rel_err(got, want) < 6e-3
