@@ -553,6 +553,9 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
   __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(p.A), 0, (int)(unsigned)(((long)(p.M - 1) * p.lda + p.K) * 2), 0x00020000);
 
+  __amdgpu_buffer_rsrc_t rsrc_c = __builtin_amdgcn_make_buffer_rsrc(
+      p.C, 0, (tok_major || !p.C) ? 0 : (int)(unsigned)(((long)(p.M - 1) * p.ldc + p.N) * 2), 0x00020000);
+
   u32x4 ra[2][A_LD];
   auto gload = [&](auto set, int mrow0, int kt) {   // activation slab kt of the tile rows mrow0 ..
     constexpr int S = decltype(set)::value;
@@ -704,25 +707,47 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
         }
       __syncthreads();
       if (pass == 1 && has_next && tid < BN) sBias[tid] = p.bias[n0n + tid];   // every bias read is behind us
+      // read-out: all LDS reads first, then the stores.  Thread tid owns 16-byte chunk tid % 32 of
+      // staging rows tid / 32 + 16 i.
+      constexpr int PER_T = 128 * NCH / NTHREADS;   // 8
+      u32x4 v[PER_T];
+      const int c = tid % NCH;
 #pragma unroll
-      for (int i = 0; i < 128 * NCH / NTHREADS; ++i) {
-        const int q = tid + NTHREADS * i;
-        const int r = q / NCH, c = q % NCH;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
-        const int rg = (r / G) * 2 * G + pass * G + r % G;
-        if (tok_major) {
+      for (int i = 0; i < PER_T; ++i) {
+        const int r = tid / NCH + (NTHREADS / NCH) * i;
+        v[i] = *reinterpret_cast<const u32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
+      }
+      if (tok_major) {
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+          const int r = tid / NCH + (NTHREADS / NCH) * i;
+          const int rg = (r / G) * 2 * G + pass * G + r % G;
           const int f = n0 + rg, tok = m0 + c * 8;
           if (f < p.N && tok < p.M) {
             const int h = f / p.hd_pad, d = f % p.hd_pad;
             const int t = tok / p.n_tok, n = tok % p.n_tok;
-            *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v;
+            *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v[i];
           }
-        } else {
-          const int row = m0 + rg, col = n0 + c * 8;
+        }
+      } else if (p.row_map) {   // paged output: rows go through the block map
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+          const int r = tid / NCH + (NTHREADS / NCH) * i;
+          const int row = m0 + (r / G) * 2 * G + pass * G + r % G, col = n0 + c * 8;
           if (row < p.M && col < p.N) {
-            const long orow = p.row_map ? (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens : row;
-            *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v;
+            const long orow = (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens;
+            *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v[i];
           }
+        }
+      } else if (n0 + c * 8 < p.N) {
+        // buffer stores: uniform row part in the scalar offset, one lane offset for all eight;
+        // rows past M fall outside the descriptor and are dropped by the hardware
+        const unsigned voff = ((unsigned)(tid / NCH) * (unsigned)p.ldc + (unsigned)(n0 + c * 8)) * 2u;
+#pragma unroll
+        for (int i = 0; i < PER_T; ++i) {
+          const int r0 = (NTHREADS / NCH) * i;                                  // staging row of lane row 0
+          const int row0 = m0 + (r0 / G) * 2 * G + pass * G + r0 % G;           // uniform (G % 16 == 0)
+          __builtin_amdgcn_raw_buffer_store_b128(v[i], rsrc_c, voff, (unsigned)row0 * (unsigned)p.ldc * 2u, 0);
         }
       }
     }
@@ -853,7 +878,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (p.K % (2 * BK) != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
   // operands are addressed through 32-bit buffer offsets
   if ((long)p.M * p.lda * 2 >= (1L << 32) || (long)p.Npad * p.K * 2 >= (1L << 32) ||
-      (p.R && (long)p.M * p.ldr * 4 >= (1L << 32)))
+      (p.R && (long)p.M * p.ldr * 4 >= (1L << 32)) || (p.C && !p.row_map && (long)p.M * p.ldc * 2 >= (1L << 32)))
     return hipErrorInvalidValue;
   const bool f32_out = p.epi == EPI_BIAS_RESIDUAL || p.epi == EPI_BIAS_POS;
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
