@@ -418,22 +418,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
           }
       }
       __syncthreads();
-      if (X_IN_LOOP && x_col_ok) {
-        // prefetched rows: all LDS reads first, then stores through the descriptor (rows past M are
-        // dropped by the hardware, the row part of the address is a scalar offset)
-        const int c = tid % XNCH;
-        f32x4 vv[XPER_T];
-#pragma unroll
-        for (int i = 0; i < XPER_T; ++i) {
-          const int r = x_r0 + XSTEP * i;
-          vv[i] = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
-        }
-#pragma unroll
-        for (int i = 0; i < XPER_T; ++i) {
-          const unsigned so = (unsigned)(m0 + pass * XROWS + XSTEP * i) * (unsigned)p.ldr * 4u;
-          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, xr[S][i] + vv[i]), rsrc_x, x_voff * 4u, so, 0);
-        }
-      } else if (x_col_ok) {
+      if (x_col_ok) {
         const int c = tid % XNCH;
 #pragma unroll
         for (int i = 0; i < XPER_T; ++i) {
