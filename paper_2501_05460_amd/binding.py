@@ -358,15 +358,35 @@ def op_gemm_bf16(A: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor],
 
 def op_gemm_bf16_form(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, epi: int, form: int,
                       R: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """One GEMM launch in the given form; returns C (bf16) or, for epi 3, the updated R (fp32, in place)."""
+    """One GEMM launch in the given form; returns C (bf16) or, for epi 3, the updated R (fp32, in place).
+
+    The kernels read whole 256-row tiles of A and R, so both are handed over in buffers of
+    round_up(M, 256) rows; the output buffer carries the same rows as a guard, and a call that
+    writes any row past M raises."""
     M, K = A.shape
     N = W.shape[0]
-    C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device) if epi != 3 else None
-    s = lib().epd_op_gemm_bf16_form(A.data_ptr(), W.data_ptr(), bias.data_ptr(), C.data_ptr() if C is not None else None,
-                                    R.data_ptr() if R is not None else None, M, N, K, epi, form, _stream_ptr())
+    Mp = (M + 255) // 256 * 256
+    Ap = torch.zeros((Mp, K), dtype=A.dtype, device=A.device)
+    Ap[:M] = A
+    guard = 12345.0
+    if epi != 3:
+        Cp = torch.full((Mp, N), guard, dtype=torch.bfloat16, device=A.device)
+        Rp = None
+    else:
+        Cp = None
+        Rp = torch.full((Mp * N + 256,), guard, dtype=torch.float32, device=A.device)
+        Rp[:M * N] = R.reshape(-1)
+    s = lib().epd_op_gemm_bf16_form(Ap.data_ptr(), W.data_ptr(), bias.data_ptr(), Cp.data_ptr() if Cp is not None else None,
+                                    Rp.data_ptr() if Rp is not None else None, M, N, K, epi, form, _stream_ptr())
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())
-    return C if epi != 3 else R
+    tail = Cp[M:] if epi != 3 else Rp[M * N:]
+    if not bool((tail == guard).all()):
+        raise RuntimeError("GEMM form %d wrote rows past M=%d" % (form, M))
+    if epi != 3:
+        return Cp[:M]
+    R.copy_(Rp[:M * N].view(M, N))
+    return R
 
 
 def op_attention_bf16(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int,

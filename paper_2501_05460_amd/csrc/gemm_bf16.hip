@@ -157,8 +157,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
 
 
   // Global operands are read through buffer descriptors: descriptor + scalar offset + one lane
-  // offset per operand, so no per-load address arithmetic touches vector registers, and a read
-  // past the end of a matrix returns zero.  The host launcher checks that every extent fits 32 bits.
+  // offset per operand, so no per-load address arithmetic touches vector registers.  The range
+  // check of a descriptor covers the lane offset only, not the scalar one: the rows of a ragged
+  // last tile past M are read like any other (A and R hold round_up(M, 256) rows) and their
+  // results never stored.  The host launcher checks that every extent fits 32 bits.
   __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(p.A), 0, (int)(unsigned)(((long)(p.M - 1) * p.lda + p.K) * 2), 0x00020000);
   __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc(
@@ -418,6 +420,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
           }
       }
       __syncthreads();
+      // The sums leave through global stores.  The 128-bit buffer store with a scalar offset is no
+      // alternative here: the compiler puts no wait state behind that form, and with the next chunk's
+      // additions rewriting its data registers in the following cycle a stored row was wrong once in
+      // about 1e8 stores on gfx950 (gone with one s_nop behind each store, no faster than this form).
       if (x_col_ok) {
         const int c = tid % XNCH;
 #pragma unroll
@@ -740,14 +746,15 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
           }
         }
       } else if (n0 + c * 8 < p.N) {
-        // buffer stores: uniform row part in the scalar offset, one lane offset for all eight;
-        // rows past M fall outside the descriptor and are dropped by the hardware
+        // buffer stores: the whole byte offset is the lane offset (the only part the descriptor's range
+        // check sees; a scalar offset is outside it), so a row past M is dropped by the hardware.  The
+        // data registers are not written again before the next barrier.
         const unsigned voff = ((unsigned)(tid / NCH) * (unsigned)p.ldc + (unsigned)(n0 + c * 8)) * 2u;
 #pragma unroll
         for (int i = 0; i < PER_T; ++i) {
           const int r0 = (NTHREADS / NCH) * i;                                  // staging row of lane row 0
           const int row0 = m0 + (r0 / G) * 2 * G + pass * G + r0 % G;           // uniform (G % 16 == 0)
-          __builtin_amdgcn_raw_buffer_store_b128(v[i], rsrc_c, voff, (unsigned)row0 * (unsigned)p.ldc * 2u, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(v[i], rsrc_c, voff + (unsigned)row0 * (unsigned)p.ldc * 2u, 0, 0);
         }
       }
     }

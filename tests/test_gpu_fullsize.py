@@ -117,3 +117,23 @@ def test_c6_video_requests_batched_equals_one_request_per_call_and_oracle():
     assert torch.equal(out.view(torch.int16), full.view(torch.int16))
     check_sample(wk, enc, full, wk.oracle_sample_tiles)
     enc.close()
+
+
+@pytest.mark.parametrize("name,reps", [("c2", 300), ("c3", 30)])
+def test_full_size_runs_repeat_bit_for_bit(name, reps):
+    """The same batch encoded again and again gives the same bits at the full GEMM shapes, where every
+    compute unit holds a tile and the chip is at its power limit: a data hazard in a kernel (a register
+    rewritten while a store still reads it, a missing wait) shows up here as an occasional run that differs
+    in whole slices, never in the small cases."""
+    wk = wl.workload(name)
+    enc, tiles = build(wk)
+    off = list(wk.tile_offsets)
+    ref = enc.encode(tiles, off).clone()
+    torch.cuda.synchronize()
+    differing = 0
+    for _ in range(reps):
+        out = enc.encode(tiles, off)
+        torch.cuda.synchronize()
+        differing += int(not torch.equal(out.view(torch.int16), ref.view(torch.int16)))
+    assert differing == 0, f"{differing} of {reps} runs differ from the first"
+    enc.close()
