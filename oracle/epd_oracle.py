@@ -168,9 +168,16 @@ def encoder_layer(x, w, desc, l: int):
 
 
 def embed_tile(tile, w, desc):
-    """Patch embedding + learned position embedding; no class token."""
+    """Patch embedding + learned position embedding.  With a class token the
+    sequence is [cls, patch 0, patch 1, ...]: the learned vector `cls` is put in
+    front of the embedded patches and the position table has one more row,
+    row 0 for the class token (the usual ViT input; Section 3.1 takes the
+    encoder as given)."""
     a = patchify(tile, desc.patch)
-    return linear(a, w["pe_w"], w["pe_b"]) + np.asarray(w["pos"], F64)
+    x = linear(a, w["pe_w"], w["pe_b"])
+    if getattr(desc, "class_token", 0):
+        x = np.concatenate([np.asarray(w["cls"], F64).reshape(1, -1), x], axis=0)
+    return x + np.asarray(w["pos"], F64)
 
 
 def project(x, w, desc):
@@ -187,10 +194,10 @@ def project(x, w, desc):
 
 
 def trunk_tile(tile, w, desc, trace: Optional[dict] = None):
-    """Pre-projection tokens of one slice, [N, hidden]: the encoder up to and
-    including its last norm, before pixel shuffle and projector (the part an
-    encode worker runs when projection happens on the prefill side,
-    Section 3.2.2)."""
+    """Pre-projection tokens of one slice, [N, hidden] (N patches): the encoder
+    up to and including its last norm, before pixel shuffle and projector (the
+    part an encode worker runs when projection happens on the prefill side,
+    Section 3.2.2).  The traced streams keep the class token's row, if any."""
     x = embed_tile(tile, w, desc)
     if trace is not None:
         trace["embed"] = x.copy()
@@ -200,6 +207,10 @@ def trunk_tile(tile, w, desc, trace: Optional[dict] = None):
             trace[f"layer{l}"] = x.copy()
     if desc.final_norm:
         x = _norm(x, w, "fn", desc.norm, desc.eps)
+    if getattr(desc, "class_token", 0):
+        # reading: the class token takes part in every attention layer and is dropped
+        # after the last norm; pixel shuffle and projector see the patch tokens only
+        x = x[1:]
     return x
 
 

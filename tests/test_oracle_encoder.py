@@ -30,6 +30,9 @@ VARIANTS = {
     "rms_qkhead_final": dict(norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_PER_HEAD, final_norm=1),
     "ln_final": dict(final_norm=1, heads=4),
     "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
+    "class_token": dict(class_token=1, final_norm=1),
+    "class_token_shuffle_scale": dict(class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
+                                      proj_kind=wl.PROJ_MLP, proj_mid=48),
 }
 
 
@@ -40,7 +43,13 @@ def torch_second_opinion(tile, w, desc):
     g = desc.tile_size // p
     img = torch.from_numpy(np.asarray(tile, np.float64))[None]            # [1,3,S,S]
     x = F.conv2d(img, t["pe_w"].reshape(D, 3, p, p), t["pe_b"], stride=p)  # [1,D,g,g]
-    x = x.flatten(2).transpose(1, 2)[0] + t["pos"]                         # [N,D]
+    x = x.flatten(2).transpose(1, 2)[0]                                    # [N,D]
+    if desc.class_token:
+        # attention does not care where a token sits in the sequence: here the class token goes LAST
+        # (with its own position row, row 0 of the table) and is cut off at the end
+        x = torch.cat([x + t["pos"][1:], (t["cls"] + t["pos"][0])[None]], dim=0)
+    else:
+        x = x + t["pos"]
 
     def norm(x, prefix, kind):
         if kind == wl.NORM_LAYERNORM:
@@ -70,6 +79,8 @@ def torch_second_opinion(tile, w, desc):
         x = torch.addcmul(x, F.linear(hmid, t[pre + "fc2_w"], t[pre + "fc2_b"]), torch.as_tensor(ls2, dtype=x.dtype).expand(D))
     if desc.final_norm:
         x = norm(x, "fn", desc.norm)
+    if desc.class_token:
+        x = x[:-1]
     if desc.pixel_shuffle:
         # pixel_unshuffle emits channel c*4 + dy*2 + dx; the encoder's order is (dy*2+dx)*D + c
         y = F.pixel_unshuffle(x.T.reshape(1, D, g, g), 2)                    # [1, 4D, g/2, g/2]
@@ -300,3 +311,47 @@ def test_layer_scale_acts_per_channel_on_the_branch_not_on_the_stream():
     w3["l1_ls2"] = z
     branch5 = (a - O.trunk_tile(tile, w3, desc))[:, 5]                   # ls2[5] * mlp(x)[:, 5]
     assert np.allclose(diff[:, 5], branch5, rtol=1e-12, atol=1e-14)
+
+
+def test_class_token_without_layers_only_shifts_the_position_rows():
+    """No layers: the class token cannot reach any patch, so token n is the affine map of patch n with
+    position row n + 1 (row 0 belongs to the class token), and the class token's own row is not emitted."""
+    desc = small_desc(layers=0, class_token=1)
+    w = wl.gen_weights(desc, 13, std=0.2)
+    tile = wl.gen_tile(desc, 13, 0)
+    got = O.encode_tile(tile, w, desc)
+    g, p = desc.grid, desc.patch
+    assert got.shape == (g * g, desc.out_dim)
+    for n in (0, 1, g, g * g - 1):
+        y, x = divmod(n, g)
+        a = np.array([tile[c, p * y + dy, p * x + dx] for c in range(3) for dy in range(p) for dx in range(p)],
+                     dtype=np.float64)
+        e = w["pe_w"].astype(np.float64) @ a + w["pe_b"] + w["pos"][n + 1]
+        np.testing.assert_allclose(got[n], w["pa_w"].astype(np.float64) @ e + w["pa_b"], rtol=1e-11, atol=1e-12)
+
+
+def test_class_token_is_one_more_key_for_every_patch():
+    """One layer, brute force for one patch query: its attention runs over the g*g patch keys AND the class
+    token's key; leaving that key out (or the class vector, or its position row) changes the result."""
+    desc = small_desc(layers=1, class_token=1, heads=1)
+    w = wl.gen_weights(desc, 17, std=0.3)
+    tile = wl.gen_tile(desc, 17, 0)
+    trace = {}
+    O.trunk_tile(tile, w, desc, trace)
+    x0 = trace["embed"]
+    assert x0.shape == (desc.n_patches + 1, desc.hidden)
+    np.testing.assert_allclose(x0[0], w["cls"].astype(np.float64) + w["pos"][0], rtol=0, atol=1e-15)
+    D = desc.hidden
+    u = O.layer_norm(x0, w["l0_n1_g"], w["l0_n1_b"], desc.eps)
+    qkv = u @ w["l0_qkv_w"].astype(np.float64).T + w["l0_qkv_b"]
+    q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
+    n = 5                                                    # sequence row of patch 4
+    logits = np.array([sum(q[n, d] * k[j, d] for d in range(D)) for j in range(x0.shape[0])]) / np.sqrt(D)
+    pr = np.exp(logits - logits.max()); pr /= pr.sum()
+    o = sum(pr[j] * v[j] for j in range(x0.shape[0]))
+    x1 = x0[n] + w["l0_o_w"].astype(np.float64) @ o + w["l0_o_b"]
+    u2 = O.layer_norm(x1[None], w["l0_n2_g"], w["l0_n2_b"], desc.eps)[0]
+    h = O.gelu_erf(w["l0_fc1_w"].astype(np.float64) @ u2 + w["l0_fc1_b"])
+    x2 = x1 + w["l0_fc2_w"].astype(np.float64) @ h + w["l0_fc2_b"]
+    np.testing.assert_allclose(trace["layer0"][n], x2, rtol=1e-10, atol=1e-12)
+    assert pr[0] > 1e-4      # the class key carries weight, so dropping it would show

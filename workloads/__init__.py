@@ -59,6 +59,7 @@ class ModelDesc:
     eps: float
     max_tiles_per_call: int
     layer_scale: int = 0
+    class_token: int = 0
 
     # ---- shape bookkeeping only (counts, no arithmetic on data) ----
     @property
@@ -68,6 +69,11 @@ class ModelDesc:
     @property
     def n_patches(self) -> int:
         return self.grid * self.grid
+
+    @property
+    def seq_len(self) -> int:
+        """Tokens per slice inside the encoder: the patches plus the class token."""
+        return self.n_patches + self.class_token
 
     @property
     def patch_dim(self) -> int:
@@ -222,7 +228,9 @@ def weight_specs(desc: ModelDesc) -> List[Tuple[str, Tuple[int, ...], str]]:
 
     specs.append(("pe_w", (D, desc.patch_dim), "w"))
     specs.append(("pe_b", (D,), "w"))
-    specs.append(("pos", (N, D), "w"))
+    specs.append(("pos", (N + desc.class_token, D), "w"))
+    if desc.class_token:
+        specs.append(("cls", (D,), "w"))
     for l in range(desc.layers):
         p = f"l{l}_"
         norm(p + "n1", D, desc.norm)
