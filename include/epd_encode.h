@@ -75,11 +75,16 @@ typedef struct {
   int32_t layer_scale;   /* 1: each residual branch is multiplied by a learned per-channel
                             vector before it is added (x += ls1 * attn(..), x += ls2 * mlp(..)),
                             as in the InternViT encoders                                  */
+  int32_t class_token;   /* 1: a learned class vector is put in front of the patch tokens
+                            (position row 0 is its own); it takes part in every attention
+                            layer and is dropped after the last norm: pixel shuffle,
+                            projector and the emitted tokens cover the N patches only     */
 } epd_model_desc;
 
 /* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix
  * W[out, in] row-major, every tensor of type desc.dtype (fp32 or bf16):
- *   pe_w [D, 3*p*p] (patch vector ordered channel, dy, dx), pe_b [D], pos [N, D];
+ *   pe_w [D, 3*p*p] (patch vector ordered channel, dy, dx), pe_b [D], pos [N, D]
+ *   (class_token: pos [N + 1, D] with row 0 for the class token, followed by cls [D]);
  *   per layer l = 0..L-1:
  *     n1_g [D], n1_b [D] (n1_b only for LayerNorm),
  *     qkv_w [3D, D] (row blocks q, k, v; head h = rows h*hd..(h+1)*hd-1 of a block), qkv_b [3D],
@@ -276,10 +281,11 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
  * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
  * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
  * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0;
- * `scale` multiplies the logits. */
+ * `scale` multiplies the logits.  Only the first n_keys (1 .. n_tokens) rows of a slice are tokens:
+ * the others are left out of every softmax as keys, and their rows of o hold unused values. */
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
-                                 int32_t n_slices, int32_t n_tokens, int32_t heads, int32_t hd_pad,
-                                 int32_t ld_qk, float scale, void* hip_stream);
+                                 int32_t n_slices, int32_t n_tokens, int32_t n_keys, int32_t heads,
+                                 int32_t hd_pad, int32_t ld_qk, float scale, void* hip_stream);
 
 /* Check of the MFMA operand / result lane layout the kernels assume:
  * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one

@@ -42,7 +42,8 @@ class ModelDescC(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "dtype", "tile_size", "patch", "hidden", "heads", "mlp", "layers", "norm", "qk_norm", "act",
         "final_norm", "pixel_shuffle", "proj_kind", "proj_prenorm", "proj_mid", "proj_out")] + [
-        ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32), ("layer_scale", ctypes.c_int32)]
+        ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32), ("layer_scale", ctypes.c_int32),
+        ("class_token", ctypes.c_int32)]
 
 
 class WeightsC(ctypes.Structure):
@@ -94,7 +95,7 @@ def lib() -> ctypes.CDLL:
         L.epd_op_gemm_bf16.restype = i32
         L.epd_op_gemm_bf16_form.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.epd_op_gemm_bf16_form.restype = i32
-        L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
         L.epd_op_attention_bf16.restype = i32
         L.epd_op_mfma_probe.argtypes = [vp, vp, vp, vp]
         L.epd_op_mfma_probe.restype = i32
@@ -390,10 +391,11 @@ def op_gemm_bf16_form(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, epi:
 
 
 def op_attention_bf16(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int,
-                      heads: int, hd_pad: int, ld_qk: int, scale: float) -> torch.Tensor:
+                      heads: int, hd_pad: int, ld_qk: int, scale: float, n_keys: Optional[int] = None) -> torch.Tensor:
     o = torch.empty((n_slices * n_tokens, heads * hd_pad), dtype=torch.bfloat16, device=q.device)
     s = lib().epd_op_attention_bf16(q.data_ptr(), k.data_ptr(), vt.data_ptr(), o.data_ptr(), n_slices,
-                                    n_tokens, heads, hd_pad, ld_qk, scale, _stream_ptr())
+                                    n_tokens, n_tokens if n_keys is None else n_keys, heads, hd_pad, ld_qk, scale,
+                                    _stream_ptr())
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())
     return o

@@ -47,8 +47,8 @@ template <int HD, int QT>
 __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
-                                                        bf16_t* __restrict__ o, int n_tok, int heads, int n_pairs,
-                                                        long ld_qk, long ld_o, float scale_log2e) {
+                                                        bf16_t* __restrict__ o, int n_tok, int n_keys, int heads,
+                                                        int n_pairs, long ld_qk, long ld_o, float scale_log2e) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
   constexpr int KS = SM::HDK / 16;   // k-steps of the S^T product
@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   const int qb = seq % n_qb, h = pair % heads, t = pair / heads;
   const long row0 = (long)t * n_tok;
   const int q0 = qb * BQ + wave * 32 * QT;
-  // n_tok is a multiple of 64: a 32-query sub-tile is all in or all out
+  // n_tok is a multiple of 64: a 32-query sub-tile is all in or all out (rows past n_keys are computed like
+  // any other and never used)
   bool act[QT];
   bool any_act = false;
 #pragma unroll
@@ -167,9 +168,16 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     }
   };
   // online softmax of one step, one query per lane (shared with lane ^ 32)
-  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2]) {
+  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0) {
 #pragma unroll
     for (int u = 0; u < QT; ++u) {
+      if (key0 + 32 > n_keys) {   // uniform; only the last steps of a slice whose rows are padded
+        // rows past n_keys are no tokens: logit -inf, weight 0 (the first step always holds a real key,
+        // so the running maximum is finite by the time a step is masked entirely)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
+      }
       float mx = fmaxf(s[u][0], s[u][1]);
 #pragma unroll
       for (int e = 2; e < 16; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);  // three-input max
@@ -240,9 +248,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
     if (any_act) {
       issue_s(s1, ks, 1);
-      softmax(s0, p0);
+      softmax(s0, p0, kb * BKEY);
       issue_pv(p0, vs, 0);
-      softmax(s1, p1);
+      softmax(s1, p1, kb * BKEY + 32);
       issue_pv(p1, vs, 1);
     }
     sstore((kb + 1) & 1);   // the other buffer: nobody reads it after the previous barrier
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 
 template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                       int n_tok, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
+                       int n_tok, int n_keys, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT>),
@@ -286,22 +294,22 @@ hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
   k_attention_bf16<HD, QT><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
-      q, k, vt, o, n_tok, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
+      q, k, vt, o, n_tok, n_keys, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                          int n_tok, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
+                          int n_tok, int n_keys, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
                           hipStream_t st) {
   if (n_slices == 0) return hipSuccess;
-  if (n_tok % BKEY != 0 || n_tok <= 0) return hipErrorInvalidValue;
+  if (n_tok % BKEY != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok) return hipErrorInvalidValue;
   switch (hd_pad) {
-    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
-    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
-    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
-    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, heads, ld_qk, ld_o, scale, st);
+    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
+    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
+    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
+    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
   }
   return hipErrorInvalidValue;
 }

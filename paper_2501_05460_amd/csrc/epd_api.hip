@@ -40,14 +40,18 @@ struct TensorSpec { long rows, cols; };  // vectors: rows = 1
 struct LayerIdx { int n1_g, n1_b, qkv_w, qkv_b, qn_g, kn_g, o_w, o_b, ls1, n2_g, n2_b, fc1_w, fc1_b, fc2_w, fc2_b, ls2; };
 
 struct WeightIndex {
-  int pe_w, pe_b, pos;
+  int pe_w, pe_b, pos, cls;
   std::vector<LayerIdx> layers;
   int fn_g, fn_b, pn_g, pn_b, pa_w, pa_b, pb_w, pb_b;
   std::vector<TensorSpec> specs;
 };
 
+// N = patches per slice; Nt = tokens per slice inside the encoder (patches + class token); Ns = rows a
+// slice owns in the activation buffers (bf16 mode: Nt rounded up to the attention kernel's 64-key block,
+// the extra rows are masked as keys and never read as tokens; fp32 mode: Nt).
 struct Dims {
-  int S, p, g, N, Kp, D, H, hd, F, L, N_out, Pin, Pmid, Pout;
+  int S, p, g, N, Kp, D, H, hd, F, L, N_out, Pin, Pmid, Pout, cls, Nt, Ns;
+  SliceRows xrows() const { return (Ns == N) ? SliceRows{0, 0, 0} : SliceRows{N, Ns, cls}; }
 };
 
 Dims dims_of(const epd_model_desc& d) {
@@ -58,6 +62,9 @@ Dims dims_of(const epd_model_desc& d) {
   x.N_out = d.pixel_shuffle ? x.N / 4 : x.N;
   x.Pin = d.pixel_shuffle ? 4 * x.D : x.D;
   x.Pmid = d.proj_mid; x.Pout = d.proj_out;
+  x.cls = d.class_token ? 1 : 0;
+  x.Nt = x.N + x.cls;
+  x.Ns = d.dtype == EPD_DTYPE_BF16 ? round_up(x.Nt, 64) : x.Nt;
   return x;
 }
 
@@ -66,7 +73,8 @@ WeightIndex build_index(const epd_model_desc& d) {
   WeightIndex w;
   auto add = [&](long r, long c) { w.specs.push_back({r, c}); return (int)w.specs.size() - 1; };
   const bool ln = d.norm == EPD_NORM_LAYERNORM;
-  w.pe_w = add(x.D, x.Kp); w.pe_b = add(1, x.D); w.pos = add(x.N, x.D);
+  w.pe_w = add(x.D, x.Kp); w.pe_b = add(1, x.D); w.pos = add(x.Nt, x.D);
+  w.cls = x.cls ? add(1, x.D) : -1;
   for (int l = 0; l < x.L; ++l) {
     LayerIdx i;
     i.n1_g = add(1, x.D); i.n1_b = ln ? add(1, x.D) : -1;
@@ -100,7 +108,7 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->norm < 0 || d->norm > 1 || d->qk_norm < 0 || d->qk_norm > 2 || d->act < 0 || d->act > 1 ||
       d->final_norm < 0 || d->final_norm > 1 || d->pixel_shuffle < 0 || d->pixel_shuffle > 1 ||
       d->proj_kind < 0 || d->proj_kind > 1 || d->proj_prenorm < 0 || d->proj_prenorm > 1 ||
-      d->layer_scale < 0 || d->layer_scale > 1) {
+      d->layer_scale < 0 || d->layer_scale > 1 || d->class_token < 0 || d->class_token > 1) {
     set_err(err, len, "an enum field of the description is out of range"); return EPD_ERR_INVALID_ARG;
   }
   if (d->tile_size <= 0 || d->patch <= 0 || d->hidden <= 0 || d->heads <= 0 || d->mlp <= 0 ||
@@ -112,9 +120,8 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->proj_kind == EPD_PROJ_MLP && d->proj_mid <= 0) { set_err(err, len, "proj_mid must be positive for an MLP projector"); return EPD_ERR_SHAPE; }
   const Dims x = dims_of(*d);
   if (d->pixel_shuffle && (x.g % 2)) { set_err(err, len, "pixel shuffle needs an even patch grid, got %d", x.g); return EPD_ERR_SHAPE; }
-  if ((long)x.N * d->max_tiles_per_call > (1L << 30)) { set_err(err, len, "max_tiles_per_call too large"); return EPD_ERR_UNSUPPORTED; }
+  if ((long)x.Ns * d->max_tiles_per_call > (1L << 30)) { set_err(err, len, "max_tiles_per_call too large"); return EPD_ERR_UNSUPPORTED; }
   if (d->dtype == EPD_DTYPE_BF16) {
-    if (x.N % 64) { set_err(err, len, "bf16 mode needs patches per slice %% 64 == 0, got %d", x.N); return EPD_ERR_UNSUPPORTED; }
     if (x.hd > 128) { set_err(err, len, "bf16 mode supports head dim <= 128, got %d", x.hd); return EPD_ERR_UNSUPPORTED; }
     if (x.D % 4 || x.hd % 4 || x.F % 8 || x.Pout % 8 || (d->proj_kind == EPD_PROJ_MLP && x.Pmid % 8)) {
       set_err(err, len, "bf16 mode needs hidden and head dim %% 4 == 0, mlp and projector widths %% 8 == 0"); return EPD_ERR_UNSUPPORTED;
@@ -149,7 +156,8 @@ struct epd_ctx {
 
   // weights
   Linear pe, pa, pb;
-  const float* pos = nullptr;
+  const float* pos = nullptr;   // [Nt, D]; row 0 is the class token's when there is one
+  const float* cls = nullptr;   // [D], null without a class token
   const float *fn_g = nullptr, *fn_b = nullptr, *pn_g = nullptr, *pn_b = nullptr;
   std::vector<LayerW> layers;
 
@@ -271,8 +279,9 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
 
   // patch embedding and position embedding
   NOMEM_IF(!make_linear(c, w, wi.pe_w, wi.pe_b, x.D, x.Kp, &c->pe, st, pad_n(x.D), c->Kp_k, id, id, x.D));
-  c->pos = make_vec(c, w, wi.pos, (long)x.N * x.D, x.N * x.D, id, st);
+  c->pos = make_vec(c, w, wi.pos, (long)x.Nt * x.D, x.Nt * x.D, id, st);
   NOMEM_IF(!c->pos);
+  if (x.cls) { c->cls = make_vec(c, w, wi.cls, x.D, x.D, id, st); NOMEM_IF(!c->cls); }
 
   int f_pad = 0;
   for (int l = 0; l < x.L; ++l) {
@@ -360,7 +369,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
 
   // ---- workspace ----
   c->mb = d.max_tiles_per_call;
-  const long M = (long)c->mb * x.N, Mo = (long)c->mb * x.N_out;
+  const long M = (long)c->mb * x.Ns, Mo = (long)c->mb * x.N_out;
   c->Mp = (M + 255) / 256 * 256;
   c->Mp_out = (Mo + 255) / 256 * 256;
   if (bf) {
@@ -380,7 +389,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
     c->QKV = ws((size_t)c->Mp * 2 * c->Dq * 2);
-    c->VT = ws((size_t)c->mb * x.H * c->hd_pad * x.N * 2);
+    c->VT = ws((size_t)c->mb * x.H * c->hd_pad * x.Ns * 2);
     c->O = ws((size_t)c->Mp * c->Dq_k * 2);
     c->Hd = ws((size_t)c->Mp * c->F_k * 2);
     c->Ape = ws((size_t)c->Mp * c->Kp_k * 2);
@@ -413,7 +422,8 @@ enum Stage { STAGE_FULL = 0, STAGE_TRUNK = 1, STAGE_PROJECT = 2 };
 epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_t st, int stage) {
   const epd_model_desc& d = c->d;
   const Dims& x = c->x;
-  const int M = T * x.N, Mo = T * x.N_out;
+  const int M = T * x.Ns, Mo = T * x.N_out, Mpatch = T * x.N;
+  const SliceRows xr = x.xrows();
   float* X = c->X; float* Xn = (float*)c->Xn; float* QKV = (float*)c->QKV; float* O = (float*)c->O;
   float* Hd = (float*)c->Hd; float* Ape = (float*)c->Ape; float* Pin = (float*)c->Pin; float* Pmid = (float*)c->Pmid;
   const int act_epi = d.act == EPD_ACT_GELU_ERF ? EPI_BIAS_GELU_ERF : EPI_BIAS_GELU_TANH;
@@ -421,11 +431,13 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
 
   if (stage == STAGE_PROJECT) {
     ProfScope ps(c, 5, st);
-    blocks_to_stream(c->cur_in_pool, 0, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, M, st);
+    blocks_to_stream(c->cur_in_pool, 0, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, xr, Mpatch, st);
   } else {
     ProfScope ps(c, 0, st);
     f32_im2col(tiles, Ape, T, x.S, x.p, st);
-    f32_gemm(EPI_BIAS_POS, Ape, x.Kp, (const float*)c->pe.W, c->pe.b, X, x.D, c->pos, x.N, M, x.D, x.Kp, st); }
+    f32_gemm(EPI_BIAS_POS, Ape, x.Kp, (const float*)c->pe.W, c->pe.b, X, x.D, c->pos + (long)x.cls * x.D, x.N, Mpatch, x.D, x.Kp, st,
+             nullptr, 1, xr);
+    if (x.Ns != x.N) fill_slice_rows(X, x.D, T, x.Ns, x.Nt, c->cls, c->pos, st); }
   for (int l = 0; l < (stage == STAGE_PROJECT ? 0 : x.L); ++l) {
     const LayerW& w = c->layers[l];
     { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n1_g, w.n1_b, M, x.D, 1, d.eps, st); }
@@ -439,7 +451,7 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
       f32_norm(1, QKV, 3 * x.D, QKV, 3 * x.D, w.qn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
       f32_norm(1, QKV + x.D, 3 * x.D, QKV + x.D, 3 * x.D, w.kn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
     }
-    { ProfScope ps(c, 3, st); f32_attention(QKV, QKV + x.D, QKV + 2 * x.D, 3 * x.D, O, x.D, T, x.N, x.H, x.hd, scale, st); }
+    { ProfScope ps(c, 3, st); f32_attention(QKV, QKV + x.D, QKV + 2 * x.D, 3 * x.D, O, x.D, T, x.Ns, x.H, x.hd, scale, st); }
     { ProfScope ps(c, 6, st); f32_gemm(EPI_BIAS_RESIDUAL, O, x.D, (const float*)w.o.W, w.o.b, X, x.D, nullptr, 1, M, x.D, x.D, st); }
     { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n2_g, w.n2_b, M, x.D, 1, d.eps, st); }
     { ProfScope ps(c, 7, st); f32_gemm(act_epi, Xn, x.D, (const float*)w.fc1.W, w.fc1.b, Hd, x.F, nullptr, 1, M, x.F, x.D, st); }
@@ -448,13 +460,14 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
   if (d.final_norm && stage != STAGE_PROJECT) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
   if (stage == STAGE_TRUNK) {
     ProfScope ps(c, 5, st);
-    stream_to_blocks(X, x.D, out, 0, x.D, c->d_rowmap, c->cur_block_tokens, M, st);
+    stream_to_blocks(X, x.D, xr, out, 0, x.D, c->d_rowmap, c->cur_block_tokens, Mpatch, st);
     HIP_TRY(c, hipGetLastError());
     return EPD_OK;
   }
   const float* pin = X;
   { ProfScope ps(c, 5, st);
-    if (d.pixel_shuffle) { f32_shuffle(X, Pin, T, x.g, x.D, st); pin = Pin; }
+    if (d.pixel_shuffle) { f32_shuffle(X, xr, Pin, T, x.g, x.D, st); pin = Pin; }
+    else if (xr.n) { f32_take_rows(X, xr, Pin, Mpatch, x.D, st); pin = Pin; }
     if (d.proj_prenorm) { f32_norm(0, pin, x.Pin, Pin, x.Pin, c->pn_g, c->pn_b, Mo, x.Pin, 1, d.eps, st); pin = Pin; } }
   { ProfScope ps(c, 9, st);
     if (d.proj_kind == EPD_PROJ_LINEAR) {
@@ -483,7 +496,8 @@ GemmParams gp(int epi, const void* A, long lda, const Linear& lin, int M) {
 epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStream_t st, int stage) {
   const epd_model_desc& d = c->d;
   const Dims& x = c->x;
-  const int M = T * x.N, Mo = T * x.N_out;
+  const int M = T * x.Ns, Mo = T * x.N_out, Mpatch = T * x.N;
+  const SliceRows xr = x.xrows();
   float* X = c->X;
   bf16_t* Xn = (bf16_t*)c->Xn; bf16_t* QK = (bf16_t*)c->QKV; bf16_t* VT = (bf16_t*)c->VT; bf16_t* O = (bf16_t*)c->O;
   bf16_t* Hd = (bf16_t*)c->Hd; bf16_t* Ape = (bf16_t*)c->Ape; bf16_t* Pin = (bf16_t*)c->Pin; bf16_t* Pmid = (bf16_t*)c->Pmid;
@@ -493,13 +507,14 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
 
   if (stage == STAGE_PROJECT) {
     ProfScope ps(c, 5, st);
-    blocks_to_stream(c->cur_in_pool, 1, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, M, st);
+    blocks_to_stream(c->cur_in_pool, 1, x.D, c->d_rowmap, c->cur_block_tokens, X, x.D, xr, Mpatch, st);
   } else {
     ProfScope ps(c, 0, st);
     bf16_im2col(tiles, Ape, c->Kp_k, T, x.S, x.p, st);
-    GemmParams p = gp(EPI_BIAS_POS, Ape, c->Kp_k, c->pe, M);
-    p.R = X; p.ldr = x.D; p.pos = c->pos; p.n_pos = x.N;
-    HIP_TRY(c, bf16_gemm(p, st)); }
+    GemmParams p = gp(EPI_BIAS_POS, Ape, c->Kp_k, c->pe, Mpatch);
+    p.R = X; p.ldr = x.D; p.pos = c->pos + (long)x.cls * x.D; p.n_pos = x.N; p.xrows = xr;
+    HIP_TRY(c, bf16_gemm(p, st));
+    if (x.Ns != x.N) fill_slice_rows(X, x.D, T, x.Ns, x.Nt, c->cls, c->pos, st); }
   for (int l = 0; l < (stage == STAGE_PROJECT ? 0 : x.L); ++l) {
     const LayerW& w = c->layers[l];
     { ProfScope ps(c, 1, st);
@@ -511,7 +526,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       HIP_TRY(c, bf16_gemm(p, st)); }
     { ProfScope ps(c, 2, st);
       GemmParams pv = gp(EPI_VT, Xn, c->D_k, w.v, M);
-      pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.N;
+      pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.Ns;
       HIP_TRY(c, bf16_gemm(pv, st)); }
     if (d.qk_norm == EPD_QKNORM_FULL) {
       ProfScope ps(c, 4, st);
@@ -523,7 +538,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
     }
     { ProfScope ps(c, 3, st);
-      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.N, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
+      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
     { ProfScope ps(c, 6, st);
       GemmParams p = gp(EPI_BIAS_RESIDUAL, O, c->Dq_k, w.o, M);
       p.R = X; p.ldr = x.D;
@@ -543,12 +558,12 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   if (d.final_norm && stage != STAGE_PROJECT) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
   if (stage == STAGE_TRUNK) {
     ProfScope ps(c, 5, st);
-    stream_to_blocks(X, x.D, out, 1, x.D, c->d_rowmap, c->cur_block_tokens, M, st);
+    stream_to_blocks(X, x.D, xr, out, 1, x.D, c->d_rowmap, c->cur_block_tokens, Mpatch, st);
     HIP_TRY(c, hipGetLastError());
     return EPD_OK;
   }
   { ProfScope ps(c, 5, st);
-    RowOpParams r{d.proj_prenorm ? 0 : 2, X, x.D, Pin, c->Pin_k, c->pn_g, c->pn_b, Mo, x.Pin, d.pixel_shuffle, x.g, x.D, d.eps};
+    RowOpParams r{d.proj_prenorm ? 0 : 2, X, x.D, Pin, c->Pin_k, c->pn_g, c->pn_b, Mo, x.Pin, d.pixel_shuffle, x.g, x.D, d.eps, xr};
     bf16_rowop(r, st); }
   if (d.proj_kind == EPD_PROJ_LINEAR) {
       ProfScope ps(c, 9, st);
@@ -617,7 +632,7 @@ epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, in
     c->cur_rowmap = nullptr;
     c->cur_in_pool = nullptr;
     if (s != EPD_OK) return s;
-    c->last_rows = (long)T * x.N;
+    c->last_rows = (long)T * x.Nt;
   }
   return EPD_OK;
 }
@@ -815,7 +830,15 @@ epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst, int64_t rows, int64_t 
   const int64_t bytes = rows * ctx->x.D * 4;
   if (rows < 0 || rows > ctx->Mp || bytes > dst_bytes) return EPD_ERR_INVALID_ARG;
   HIP_TRY(ctx, hipDeviceSynchronize());
-  HIP_TRY(ctx, hipMemcpy(dst, ctx->X, bytes, hipMemcpyDeviceToHost));
+  // the stream keeps Ns rows per slice, the caller gets the Nt token rows of each slice back to back
+  const Dims& x = ctx->x;
+  const size_t tok_bytes = (size_t)x.Nt * x.D * 4, slice_bytes = (size_t)x.Ns * x.D * 4;
+  const int64_t whole = rows / x.Nt, rest = rows % x.Nt;
+  if (whole * x.Ns + rest > ctx->Mp) return EPD_ERR_INVALID_ARG;
+  if (whole > 0) HIP_TRY(ctx, hipMemcpy2D(dst, tok_bytes, ctx->X, slice_bytes, tok_bytes, (size_t)whole, hipMemcpyDeviceToHost));
+  if (rest > 0)
+    HIP_TRY(ctx, hipMemcpy((char*)dst + whole * tok_bytes, (const char*)ctx->X + whole * slice_bytes, (size_t)rest * x.D * 4,
+                           hipMemcpyDeviceToHost));
   return EPD_OK;
 }
 
@@ -873,11 +896,11 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
 }
 
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o, int32_t n_slices,
-                                 int32_t n_tokens, int32_t heads, int32_t hd_pad, int32_t ld_qk, float scale,
-                                 void* hip_stream) {
+                                 int32_t n_tokens, int32_t n_keys, int32_t heads, int32_t hd_pad, int32_t ld_qk,
+                                 float scale, void* hip_stream) {
   if (!q || !k || !vt || !o) return EPD_ERR_INVALID_ARG;
   hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, (bf16_t*)o, n_slices,
-                                n_tokens, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
+                                n_tokens, n_keys, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
   if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }
   return EPD_OK;
 }

@@ -436,9 +436,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
             if (EPI == EPI_BIAS_RESIDUAL) {
               if constexpr (X_IN_LOOP) *dst = xr[S][i] + v;
               else *dst = *dst + v;      // other tile shapes: plain read-modify-write
-            } else {
+            } else {   // patch embedding: position row by patch index, output row through the slice layout
               const int row = row0 + x_r0;
-              *dst = v + *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + x_col);
+              *reinterpret_cast<f32x4*>(p.R + p.xrows.row(row) * p.ldr + x_col) =
+                  v + *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + x_col);
             }
           }
         }

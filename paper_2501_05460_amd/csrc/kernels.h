@@ -5,16 +5,26 @@
 
 namespace epd {
 
+// Where the patch tokens of a slice sit in the residual stream: slice t owns `stride` rows and its
+// patch token i is row t * stride + off + i (off = 1 behind a class token; stride > off + n when a
+// slice's rows are padded to the attention kernel's key block).  n == 0: the rows are contiguous.
+struct SliceRows {
+  int n, stride, off;
+  __host__ __device__ long row(long r) const { return n ? (r / n) * stride + off + r % n : r; }
+};
+
 // ---- fp32 mode (simple_f32.hip) -------------------------------------------
 void f32_im2col(const float* tiles, float* A, int T, int S, int p, hipStream_t st);
 void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
               const float* pos, int n_pos, int M, int N, int K, hipStream_t st,
-              const int* row_map = nullptr, int block_tokens = 1);
+              const int* row_map = nullptr, int block_tokens = 1, SliceRows xrows = SliceRows{0, 0, 0});
 void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, const float* gamma,
               const float* beta, long rows, int dim, int groups, float eps, hipStream_t st);
 void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
                    int N, int H, int hd, float scale, hipStream_t st);
-void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t st);
+void f32_shuffle(const float* in, SliceRows src, float* out, int T, int g, int D, hipStream_t st);
+// out[r] = in[src.row(r)], rows of D floats
+void f32_take_rows(const float* in, SliceRows src, float* out, long rows, int D, hipStream_t st);
 
 // ---- bf16 mode -------------------------------------------------------------
 // GEMM  C[M,N] = A[M,K] * W[N,K]^T with fused epilogue (gemm_bf16.hip).
@@ -34,7 +44,8 @@ struct GemmParams {
   int block_tokens;
   float* R; long ldr;         // fp32 residual stream (RESIDUAL, POS); RESIDUAL reads whole tiles: R must hold
                               // round_up(M, 256) rows plus (Npad - N) floats behind the last one
-  const float* pos; int n_pos;
+  const float* pos; int n_pos;   // POS: product row r gets pos[r % n_pos] and lands in row xrows.row(r) of R
+  SliceRows xrows;
   bf16_t* VT;                 // EPI_VT: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
   int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
 };
@@ -56,6 +67,7 @@ struct RowOpParams {
   int shuffle;                    // 1: gather 2x2 grid neighbours, dim == 4*D
   int g, D;                       // grid side and source row length (shuffle only)
   float eps;
+  SliceRows src;                  // source row of patch token r (shuffle: of grid cell r) = src.row(r)
 };
 void bf16_rowop(const RowOpParams& p, hipStream_t st);
 
@@ -66,9 +78,16 @@ void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, i
                  float eps, hipStream_t st);
 
 // Tile-local flash attention (attention_bf16.hip).
+// Slice t owns rows t * n_tok .. of q, k, o and columns 0 .. n_tok of its V^T rows (n_tok % 64 == 0);
+// only its first n_keys rows are real tokens: later keys are masked out, later queries give unused rows.
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                          int n_tok, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
+                          int n_tok, int n_keys, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
                           hipStream_t st);
+
+// Rows of the residual stream no product writes: the class token's row of every slice
+// (cls + pos[0]; cls null = no class token) and the padding rows n_real .. stride - 1 (zeros).
+void fill_slice_rows(float* X, int D, int T, int stride, int n_real, const float* cls, const float* pos0,
+                     hipStream_t st);
 
 // Weight packing (pack.hip): dst[r][c] for r < rows_pad, c < cols_pad, zero
 // outside the source.  row_hd/col_hd > 0: the packed index runs over heads
@@ -89,11 +108,11 @@ void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, co
                     int n_blocks, long block_bytes, hipStream_t st);
 
 // fp32 residual-stream rows <-> rows of a paged cache of fp32 or bf16 tokens of the same width.
-// Row r of the stream is token r % block_tokens of block row_map[r / block_tokens].
-void stream_to_blocks(const float* X, long ldx, void* pool, int pool_is_bf16, int dim, const int* row_map,
+// Patch token r (stream row xr.row(r)) is token r % block_tokens of block row_map[r / block_tokens].
+void stream_to_blocks(const float* X, long ldx, SliceRows xr, void* pool, int pool_is_bf16, int dim, const int* row_map,
                       int block_tokens, long rows, hipStream_t st);
 void blocks_to_stream(const void* pool, int pool_is_bf16, int dim, const int* row_map, int block_tokens,
-                      float* X, long ldx, long rows, hipStream_t st);
+                      float* X, long ldx, SliceRows xr, long rows, hipStream_t st);
 
 // MFMA lane-layout check: D[32,32] = A[32,16] * B[16,32] with operands loaded
 // and the result stored under the layout the kernels assume.

@@ -59,10 +59,11 @@ __global__ __launch_bounds__(256) void k_bf16_rowop(const RowOpParams p) {
     const int m = (int)(R % tok_per);
     Y = m / hgrid;
     X = m % hgrid;
-    base_t = t * p.g * p.g;
+    base_t = p.src.row(t * p.g * p.g);   // stream row of the slice's patch 0; a slice's patch rows are consecutive
   }
+  const long plain_row = p.shuffle ? 0 : p.src.row(R);
   auto src = [&](int c) -> const float4* {
-    if (!p.shuffle) return reinterpret_cast<const float4*>(p.in + R * p.ld_in) + c;
+    if (!p.shuffle) return reinterpret_cast<const float4*>(p.in + plain_row * p.ld_in) + c;
     const int e = c << 2;
     const int blk = e / p.D, ch = e % p.D;
     const long srow = base_t + (long)(2 * Y + (blk >> 1)) * p.g + (2 * X + (blk & 1));
@@ -286,16 +287,41 @@ void mm_copy_blocks(const void* src_pool, const int* src_ids, void* dst_pool, co
 // coalesced.  TO_POOL: stream -> cache (rounding to the cache's type), else the
 // reverse (exact widening).
 template <typename T, bool TO_POOL>
-__global__ __launch_bounds__(256) void k_stream_blocks(float* X, long ldx, T* pool, int dim,
+__global__ __launch_bounds__(256) void k_stream_blocks(float* X, long ldx, SliceRows xr, T* pool, int dim,
                                                        const int* __restrict__ row_map, int block_tokens,
                                                        long total) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
     const long r = i / dim;
     const int c = (int)(i % dim);
     const long prow = (long)row_map[r / block_tokens] * block_tokens + r % block_tokens;
-    if (TO_POOL) pool[prow * dim + c] = (T)X[r * ldx + c];
-    else X[r * ldx + c] = (float)pool[prow * dim + c];
+    const long xrow = xr.row(r);
+    if (TO_POOL) pool[prow * dim + c] = (T)X[xrow * ldx + c];
+    else X[xrow * ldx + c] = (float)pool[prow * dim + c];
   }
+}
+
+// ------------------------------- class-token and padding rows of the stream ----
+// One thread per element of a row that no product writes.
+__global__ __launch_bounds__(256) void k_fill_slice_rows(float* X, int D, int stride, int n_real, int extra,
+                                                         const float* __restrict__ cls,
+                                                         const float* __restrict__ pos0, long total) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % D);
+  const long rr = i / D;
+  const long t = rr / extra;
+  const int e = (int)(rr % extra);       // 0: class row (when there is one), then the padding rows
+  const bool is_cls = cls && e == 0;
+  const int row = is_cls ? 0 : n_real + e - (cls ? 1 : 0);
+  X[(t * stride + row) * (long)D + c] = is_cls ? cls[c] + pos0[c] : 0.f;
+}
+
+void fill_slice_rows(float* X, int D, int T, int stride, int n_real, const float* cls, const float* pos0,
+                     hipStream_t st) {
+  const int extra = (cls ? 1 : 0) + (stride - n_real);
+  const long total = (long)T * extra * D;
+  if (total <= 0) return;
+  k_fill_slice_rows<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(X, D, stride, n_real, extra, cls, pos0, total);
 }
 
 static unsigned stream_blocks_grid(long total) {
@@ -303,26 +329,26 @@ static unsigned stream_blocks_grid(long total) {
   return (unsigned)(g > 65536 ? 65536 : g);
 }
 
-void stream_to_blocks(const float* X, long ldx, void* pool, int pool_is_bf16, int dim, const int* row_map,
+void stream_to_blocks(const float* X, long ldx, SliceRows xr, void* pool, int pool_is_bf16, int dim, const int* row_map,
                       int block_tokens, long rows, hipStream_t st) {
   const long total = rows * dim;
   if (total <= 0) return;
   const dim3 grid(stream_blocks_grid(total)), block(256);
   if (pool_is_bf16)
-    k_stream_blocks<bf16_t, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, (bf16_t*)pool, dim, row_map, block_tokens, total);
+    k_stream_blocks<bf16_t, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, xr, (bf16_t*)pool, dim, row_map, block_tokens, total);
   else
-    k_stream_blocks<float, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, (float*)pool, dim, row_map, block_tokens, total);
+    k_stream_blocks<float, true><<<grid, block, 0, st>>>(const_cast<float*>(X), ldx, xr, (float*)pool, dim, row_map, block_tokens, total);
 }
 
 void blocks_to_stream(const void* pool, int pool_is_bf16, int dim, const int* row_map, int block_tokens,
-                      float* X, long ldx, long rows, hipStream_t st) {
+                      float* X, long ldx, SliceRows xr, long rows, hipStream_t st) {
   const long total = rows * dim;
   if (total <= 0) return;
   const dim3 grid(stream_blocks_grid(total)), block(256);
   if (pool_is_bf16)
-    k_stream_blocks<bf16_t, false><<<grid, block, 0, st>>>(X, ldx, (bf16_t*)pool, dim, row_map, block_tokens, total);
+    k_stream_blocks<bf16_t, false><<<grid, block, 0, st>>>(X, ldx, xr, (bf16_t*)pool, dim, row_map, block_tokens, total);
   else
-    k_stream_blocks<float, false><<<grid, block, 0, st>>>(X, ldx, (float*)pool, dim, row_map, block_tokens, total);
+    k_stream_blocks<float, false><<<grid, block, 0, st>>>(X, ldx, xr, (float*)pool, dim, row_map, block_tokens, total);
 }
 
 // ------------------------------------------------------------ MFMA probe ----

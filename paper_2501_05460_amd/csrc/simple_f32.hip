@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
                                                   const float* __restrict__ bias, float* C, int ldc,
                                                   const float* __restrict__ pos, int n_pos, int M,
                                                   int N, int K, const int* __restrict__ row_map,
-                                                  int block_tokens) {
+                                                  int block_tokens, SliceRows xrows) {
   __shared__ float sA[16][64 + 1];
   __shared__ float sW[16][64 + 1];
   const int tid = threadIdx.x;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
       if (EPI == EPI_BIAS_RESIDUAL) {
         C[o] += v;
       } else if (EPI == EPI_BIAS_POS) {
-        C[o] = v + pos[(long)(r % n_pos) * N + c];
+        C[xrows.row(r) * ldc + c] = v + pos[(long)(r % n_pos) * N + c];   // patch embedding: through the slice layout
       } else {
         C[o] = apply_act<EPI>(v);
       }
@@ -93,15 +93,15 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
 
 void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
               const float* pos, int n_pos, int M, int N, int K, hipStream_t st, const int* row_map,
-              int block_tokens) {
+              int block_tokens, SliceRows xrows) {
   if (M == 0 || N == 0) return;
   dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
   switch (epi) {
-    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
-    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
-    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
-    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
-    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens); break;
+    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
   }
 }
 
@@ -199,8 +199,8 @@ void f32_attention(const float* q, const float* k, const float* v, long ld, floa
 }
 
 // --------------------------------------------------------- pixel shuffle ----
-// out[t*N/4 + Y*(g/2) + X][(dy*2 + dx)*D + c] = in[t*N + (2Y+dy)*g + (2X+dx)][c]
-__global__ void k_f32_shuffle(const float* __restrict__ in, float* __restrict__ out, int g, int D,
+// out[t*N/4 + Y*(g/2) + X][(dy*2 + dx)*D + c] = in[row of patch t*N + (2Y+dy)*g + (2X+dx)][c]
+__global__ void k_f32_shuffle(const float* __restrict__ in, SliceRows srows, float* __restrict__ out, int g, int D,
                               long total) {
   long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
@@ -213,14 +213,26 @@ __global__ void k_f32_shuffle(const float* __restrict__ in, float* __restrict__ 
   int Y = mm / h, X = mm % h;
   int blk = e / D, c = e % D;
   int dy = blk / 2, dx = blk % 2;
-  long src = t * g * g + (long)(2 * Y + dy) * g + (2 * X + dx);
+  long src = srows.row(t * g * g + (long)(2 * Y + dy) * g + (2 * X + dx));
   out[i] = in[src * D + c];
 }
 
-void f32_shuffle(const float* in, float* out, int T, int g, int D, hipStream_t st) {
+void f32_shuffle(const float* in, SliceRows src, float* out, int T, int g, int D, hipStream_t st) {
   long total = (long)T * (g * g / 4) * 4 * D;
   if (total == 0) return;
-  k_f32_shuffle<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(in, out, g, D, total);
+  k_f32_shuffle<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(in, src, out, g, D, total);
+}
+
+__global__ void k_f32_take_rows(const float* __restrict__ in, SliceRows srows, float* __restrict__ out, int D, long total) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  out[i] = in[srows.row(i / D) * D + i % D];
+}
+
+void f32_take_rows(const float* in, SliceRows src, float* out, long rows, int D, hipStream_t st) {
+  long total = rows * D;
+  if (total == 0) return;
+  k_f32_take_rows<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(in, src, out, D, total);
 }
 
 }  // namespace epd

@@ -40,12 +40,25 @@ def test_weight_count_matches_generator_order():
     scaled = d.replace(layer_scale=1)                      # two more vectors per layer
     assert B.weight_count(scaled) == B.weight_count(d) + 2 * d.layers == len(wl.weight_specs(scaled))
     assert B.weight_count(d.replace(layer_scale=2)) == B.EPD_ERR_INVALID_ARG
+    with_cls = d.replace(class_token=1)                    # the class vector; pos grows by a row
+    assert B.weight_count(with_cls) == B.weight_count(d) + 1 == len(wl.weight_specs(with_cls))
+    assert wl.weight_specs(with_cls)[2][1] == (d.n_patches + 1, d.hidden)
+    assert B.weight_count(d.replace(class_token=2)) == B.EPD_ERR_INVALID_ARG
 
 
 def test_check_desc_accepts_the_five_configs():
     for name in wl.ALL_WORKLOADS:
         s, msg = B.check_desc(wl.workload(name).desc)
         assert s == B.EPD_OK, (name, msg)
+
+
+def test_check_desc_accepts_any_patch_grid_and_a_class_token():
+    d = wl.workload("c3").desc
+    for change in (dict(tile_size=14 * 6, pixel_shuffle=0, proj_prenorm=0),      # 36 patches per slice
+                   dict(tile_size=14 * 27, pixel_shuffle=0, proj_prenorm=0),     # 729
+                   dict(class_token=1), dict(class_token=1, dtype=wl.DT_FP32)):
+        s, msg = B.check_desc(d.replace(**change))
+        assert s == B.EPD_OK, (change, msg)
 
 
 @pytest.mark.parametrize("change,status", [
@@ -57,7 +70,6 @@ def test_check_desc_accepts_the_five_configs():
     (dict(hidden=0), B.EPD_ERR_SHAPE),
     (dict(max_tiles_per_call=0), B.EPD_ERR_SHAPE),
     (dict(tile_size=14 * 15), B.EPD_ERR_SHAPE),     # odd grid with pixel shuffle
-    (dict(tile_size=14 * 6, pixel_shuffle=0, proj_prenorm=0), B.EPD_ERR_UNSUPPORTED),  # 36 patches, bf16
     (dict(heads=4), B.EPD_ERR_UNSUPPORTED),         # head dim 256 in bf16 mode
     (dict(proj_out=4100), B.EPD_ERR_UNSUPPORTED),   # not a multiple of 8 in bf16 mode
 ])

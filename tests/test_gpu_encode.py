@@ -32,6 +32,15 @@ VARIANTS = {
     "hd32": dict(hidden=96, heads=3),
     "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=136),
     "layer_scale_hd72": dict(layer_scale=1, hidden=144, heads=2, act=wl.ACT_GELU_TANH),
+    # class token: 65 tokens per slice (bf16 mode pads a slice's rows to 128 and masks the extra keys)
+    "class_token": dict(class_token=1, final_norm=1),
+    "class_token_shuffle_scale_hd72": dict(class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
+                                           proj_kind=wl.PROJ_MLP, proj_mid=136, hidden=144, heads=2),
+    "class_token_rms_qkhead": dict(class_token=1, norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_PER_HEAD),
+    # patch grids whose token count is no multiple of the key block: 7 x 7 = 49 and 6 x 6 + 1 = 37
+    "grid7": dict(tile_size=98),
+    "grid6_class_token_shuffle": dict(tile_size=84, class_token=1, pixel_shuffle=1, proj_prenorm=1,
+                                      proj_kind=wl.PROJ_MLP, proj_mid=136),
 }
 
 
@@ -64,6 +73,25 @@ def test_sharp_attention_encoder_vs_oracle(dtype):
     uniform, so a wrong key range or a leak across slices would move the output."""
     desc = small_desc(dtype, layers=3)
     got, want = run_case(desc, 22, 2, [0, 2], scale={"qkv_w": 2.0})
+    assert rel_err(got, want) < tol(desc)
+
+
+@pytest.mark.parametrize("dtype", [wl.DT_FP32, wl.DT_BF16])
+def test_sharp_attention_with_class_token_vs_oracle(dtype):
+    """Sharp softmax rows and a class token of large norm: its key takes a visible share of every
+    patch's attention, and a padding row leaking in as a key would too."""
+    desc = small_desc(dtype, layers=3, class_token=1)
+    got, want = run_case(desc, 23, 5, [0, 2, 5], scale={"qkv_w": 2.0, "cls": 8.0})
+    assert rel_err(got, want) < tol(desc)
+
+
+def test_class_token_at_a_257_token_sequence_vs_oracle():
+    """224-pixel slices with a class token: 257 tokens per slice, padded to 320 rows; more slices than
+    one micro-batch holds."""
+    desc = small_desc(wl.DT_BF16, tile_size=224, class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
+                      proj_kind=wl.PROJ_MLP, proj_mid=136, max_tiles_per_call=3)
+    got, want = run_case(desc, 24, 5, [0, 5])
+    assert got.shape == (5 * 64, 96)
     assert rel_err(got, want) < tol(desc)
 
 

@@ -85,6 +85,44 @@ def test_attention_bf16_vs_oracle(n_slices, n_tok, heads, hd, hd_pad, qk_scale):
     assert rel_err(got, want) < 1.5e-2
 
 
+@pytest.mark.parametrize("n_tok,n_keys,heads,hd,hd_pad", [
+    (128, 65, 2, 64, 64), (320, 257, 1, 64, 64), (1088, 1025, 2, 64, 64), (64, 1, 1, 64, 64),
+    (128, 96, 2, 72, 72), (256, 197, 2, 128, 128), (192, 129, 1, 80, 96)])
+def test_attention_bf16_ignores_rows_past_n_keys(n_tok, n_keys, heads, hd, hd_pad):
+    """A slice owns n_tok rows but only n_keys of them are tokens (class token + patches, padded to the
+    key block): the real queries see exactly the real keys, whatever the padding rows hold (here: large
+    values that would take all the softmax weight if they leaked in)."""
+    rng = np.random.default_rng(n_tok + n_keys + hd)
+    n_slices = 2
+    M = n_slices * n_tok
+    D, Dq = heads * hd, heads * hd_pad
+    q = _bf16_grid(rng, (M, D), 0.5)
+    k = _bf16_grid(rng, (M, D), 0.5)
+    v = _bf16_grid(rng, (M, D))
+    real = (np.arange(M) % n_tok) < n_keys
+    k[~real] *= 16.0
+    v[~real] = 100.0
+
+    def pad_heads(x):
+        out = np.zeros((M, Dq), np.float32)
+        for h in range(heads):
+            out[:, h * hd_pad:h * hd_pad + hd] = x[:, h * hd:(h + 1) * hd]
+        return out
+
+    qk = np.concatenate([pad_heads(q), pad_heads(k)], axis=1)
+    vt = pad_heads(v).reshape(n_slices, n_tok, heads, hd_pad).transpose(0, 2, 3, 1).copy()
+    qk_d = B.to_device(qk, True)
+    o = B.op_attention_bf16(qk_d, qk_d[:, Dq:], B.to_device(vt, True), n_slices, n_tok, heads, hd_pad,
+                            2 * Dq, 1.0 / math.sqrt(hd), n_keys=n_keys)
+    torch.cuda.synchronize()
+    got = o.float().cpu().numpy().reshape(M, heads, hd_pad)[:, :, :hd].reshape(M, D)
+    assert np.isfinite(got).all()
+    for s in range(n_slices):
+        r = slice(s * n_tok, s * n_tok + n_keys)
+        want = O.attention(q[r], k[r], v[r], heads)
+        assert rel_err(got[r], want) < 1.5e-2, s
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (1000, 512, 256), (2304, 1024, 1024), (77, 256, 384)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
