@@ -43,7 +43,9 @@ struct AttnSmem {
 // Registers: head dim 64 with one sub-tile per wave fits 168 registers, i.e. three workgroups per
 // CU; measured faster than two sub-tiles per wave at two workgroups (more waves hide the
 // MFMA -> exp -> MFMA dependency chain better than fragment reuse saves LDS reads).
-template <int HD, int QT>
+// MASK: the slices carry rows past n_keys (compiled apart: the unmasked kernel keeps its registers and
+// its step free of the key-index compare).
+template <int HD, int QT, bool MASK>
 __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0) {
 #pragma unroll
     for (int u = 0; u < QT; ++u) {
-      if (key0 + 32 > n_keys) {   // uniform; only the last steps of a slice whose rows are padded
+      if (MASK && key0 + 32 > n_keys) {   // uniform; only the last steps of a slice whose rows are padded
         // rows past n_keys are no tokens: logit -inf, weight 0 (the first step always holds a real key,
         // so the running maximum is finite by the time a step is masked entirely)
 #pragma unroll
@@ -278,12 +280,12 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   }
 }
 
-template <int HD, int QT>
-hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
+template <int HD, int QT, bool MASK>
+hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                        int n_tok, int n_keys, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)AttnSmem<HD>::BYTES);
     if (e != hipSuccess) return e;
@@ -293,9 +295,16 @@ hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_
   const int n_qb = (n_tok + BQ - 1) / BQ, n_pairs = n_slices * heads;
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
-  k_attention_bf16<HD, QT><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
+  k_attention_bf16<HD, QT, MASK><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
       q, k, vt, o, n_tok, n_keys, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
   return hipGetLastError();
+}
+
+template <int HD, int QT>
+hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
+                       int n_tok, int n_keys, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
+  return n_keys < n_tok ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st)
+                        : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
 }
 
 }  // namespace

@@ -99,6 +99,22 @@ def test_c4_internvit6b_shape_40_slices():
     enc.close()
 
 
+def test_c7_internvit300m_shape_with_class_token_and_layer_scale():
+    """1025 tokens per slice in rows padded to 1088: every GEMM has a ragged last tile, the last key
+    block of every slice is masked from its second key on."""
+    wk = wl.workload("c7")
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (104 * 256, 4096)
+    assert bool(torch.isfinite(out.float()).all())
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    again = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), out.view(torch.int16))
+    enc.close()
+
+
 def test_c6_video_requests_batched_equals_one_request_per_call_and_oracle():
     """Video workload: 16 requests of 8 to 64 frames, one slice per frame.  Encoding every request in
     its own call (maximum encode batch size 1) gives the bits of the one batched call."""

@@ -165,7 +165,7 @@ def _mixed_structure(seed: int, n_requests: int = 32):
 
 
 def workload(name: str) -> Workload:
-    """The five named configurations."""
+    """The named configurations."""
     if name == "c1":
         return Workload("c1_tiny_fp32", DESC_C1, 1001, 1001, (0, 1), ((1,),), (0,))
     if name == "c2":
@@ -198,10 +198,16 @@ def workload(name: str) -> Workload:
         desc = DESC_C2.replace(max_tiles_per_call=128)
         return Workload("c6_video_siglip_16req", desc, 1002, 1006, off, tuple((1,) * f for f in frames),
                         (0, off[len(frames) // 2], off[-1] - 1))
+    if name == "c7":
+        # The C3 batch through the encoder shape of the InternViT-300M checkpoints themselves: class token
+        # (1025 tokens per slice) and layer scale on both residual branches.
+        img = tuple((13,) for _ in range(8))
+        desc = DESC_C3.replace(class_token=1, layer_scale=1)
+        return Workload("c7_internvit300m_cls_ls_8x13tiles", desc, 1007, 1003, _prefix([13] * 8), img, (0, 51, 103))
     raise KeyError(name)
 
 
-ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c6")
+ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c6", "c7")
 
 
 def shard_range(n_tiles: int, shard: int, n_shards: int) -> Tuple[int, int]:
@@ -339,8 +345,8 @@ def gen_tiles(desc: ModelDesc, seed: int, n_tiles: int, first: int = 0) -> np.nd
 
 def flops_per_tile(desc: ModelDesc) -> int:
     """Multiply-add = 2 flops; dense contractions only, no padding."""
-    N, D, F, L = desc.n_patches, desc.hidden, desc.mlp, desc.layers
-    f = 2 * N * desc.patch_dim * D
+    N, D, F, L = desc.seq_len, desc.hidden, desc.mlp, desc.layers
+    f = 2 * desc.n_patches * desc.patch_dim * D
     f += L * (2 * N * D * 3 * D + 2 * N * D * D + 4 * N * D * F + 4 * N * N * D)
     No, Pi = desc.tokens_per_tile, desc.proj_in
     if desc.proj_kind == PROJ_LINEAR:
