@@ -44,7 +44,7 @@ F64 = np.float64
 NORM_LAYERNORM, NORM_RMSNORM = 0, 1
 QKNORM_NONE, QKNORM_FULL, QKNORM_PER_HEAD = 0, 1, 2
 ACT_GELU_ERF, ACT_GELU_TANH = 0, 1
-PROJ_LINEAR, PROJ_MLP = 0, 1
+PROJ_LINEAR, PROJ_MLP, PROJ_RESAMPLER = 0, 1, 2
 
 
 # ---------------------------------------------------------------- steps ----
@@ -100,8 +100,9 @@ def softmax_rows(s):
 
 
 def attention(q, k, v, heads: int):
-    """Non-causal softmax attention inside one slice.  q, k, v: [N, D]; head h
-    owns columns h*hd .. (h+1)*hd-1; logits are scaled by 1/sqrt(hd)."""
+    """Non-causal softmax attention inside one slice.  q: [Nq, D], k, v: [Nk, D]
+    (Nq = Nk in the encoder layers); head h owns columns h*hd .. (h+1)*hd-1;
+    logits are scaled by 1/sqrt(hd)."""
     q, k, v = (np.asarray(a, F64) for a in (q, k, v))
     N, D = q.shape
     hd = D // heads
@@ -180,9 +181,35 @@ def embed_tile(tile, w, desc):
     return x + np.asarray(w["pos"], F64)
 
 
+def resampler(x, w, desc):
+    """Cross-attention projector of the MiniCPM-V family (one of the three models
+    of Section 4): `proj_mid` learned queries read the N patch tokens of a slice,
+    so a slice yields that many tokens whatever its patch count.
+        kv  = LayerNorm_kv(x Wkv^T)                      x: [N, hidden] -> [N, E], no bias
+        q   = LayerNorm_q(query)                         [Q, E], the same for every slice
+        o   = MHA(q, kv + pos, kv)                       keys carry the position table, values do not;
+                                                         in-projections Wq, Wk, Wv = row blocks of in_w
+                                                         [3E, E] with bias in_b, `proj_heads` heads,
+                                                         logits / sqrt(E / heads), then out_w, out_b
+        out = LayerNorm_post(o) Wp^T                     [Q, E], no bias
+    reading: the position table `r_pos [N, E]` is a weight tensor (the checkpoints
+    compute a 2-D sin-cos table of that shape; its values do not matter here)."""
+    E = desc.proj_out
+    kv = layer_norm(linear(x, w["r_kv_w"], None), w["r_lnkv_g"], w["r_lnkv_b"], desc.eps)
+    q = layer_norm(np.asarray(w["r_query"], F64), w["r_lnq_g"], w["r_lnq_b"], desc.eps)
+    in_w, in_b = np.asarray(w["r_in_w"], F64), np.asarray(w["r_in_b"], F64)
+    qp = linear(q, in_w[:E], in_b[:E])
+    kp = linear(kv + np.asarray(w["r_pos"], F64), in_w[E:2 * E], in_b[E:2 * E])
+    vp = linear(kv, in_w[2 * E:], in_b[2 * E:])
+    o = linear(attention(qp, kp, vp, desc.proj_heads), w["r_out_w"], w["r_out_b"])
+    return linear(layer_norm(o, w["r_lnp_g"], w["r_lnp_b"], desc.eps), w["r_proj_w"], None)
+
+
 def project(x, w, desc):
-    """Optional pixel shuffle, optional LayerNorm, then Linear or
-    Linear-GELU(erf)-Linear."""
+    """Optional pixel shuffle, optional LayerNorm, then Linear,
+    Linear-GELU(erf)-Linear, or the cross-attention resampler."""
+    if desc.proj_kind == PROJ_RESAMPLER:
+        return resampler(x, w, desc)
     if desc.pixel_shuffle:
         x = pixel_shuffle_half(x, desc.tile_size // desc.patch)
     if desc.proj_prenorm:
@@ -231,6 +258,8 @@ def project_merge(shards: Sequence[np.ndarray], w, desc) -> np.ndarray:
 
 
 def tokens_per_tile(desc) -> int:
+    if desc.proj_kind == PROJ_RESAMPLER:
+        return desc.proj_mid            # one token per learned query
     n = (desc.tile_size // desc.patch) ** 2
     return n // 4 if desc.pixel_shuffle else n
 

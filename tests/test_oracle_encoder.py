@@ -31,6 +31,8 @@ VARIANTS = {
     "ln_final": dict(final_norm=1, heads=4),
     "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=48),
     "class_token": dict(class_token=1, final_norm=1),
+    "resampler": dict(final_norm=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=5, proj_heads=3, act=wl.ACT_GELU_TANH),
+    "resampler_class_token": dict(class_token=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=7, proj_heads=2),
     "class_token_shuffle_scale": dict(class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
                                       proj_kind=wl.PROJ_MLP, proj_mid=48),
 }
@@ -88,6 +90,18 @@ def torch_second_opinion(tile, w, desc):
         x = y
     if desc.proj_prenorm:
         x = F.layer_norm(x, (x.shape[-1],), t["pn_g"], t["pn_b"], desc.eps)
+    if desc.proj_kind == wl.PROJ_RESAMPLER:
+        # the library's multi-head attention module does the in-projections, head split, softmax and out-projection
+        E = desc.proj_out
+        mha = torch.nn.MultiheadAttention(E, desc.proj_heads, bias=True, batch_first=False, dtype=torch.float64)
+        with torch.no_grad():
+            mha.in_proj_weight.copy_(t["r_in_w"]); mha.in_proj_bias.copy_(t["r_in_b"])
+            mha.out_proj.weight.copy_(t["r_out_w"]); mha.out_proj.bias.copy_(t["r_out_b"])
+            kv = F.layer_norm(x @ t["r_kv_w"].T, (E,), t["r_lnkv_g"], t["r_lnkv_b"], desc.eps)
+            q = F.layer_norm(t["r_query"], (E,), t["r_lnq_g"], t["r_lnq_b"], desc.eps)
+            o = mha(q[:, None], (kv + t["r_pos"])[:, None], kv[:, None], need_weights=False)[0][:, 0]
+            x = F.layer_norm(o, (E,), t["r_lnp_g"], t["r_lnp_b"], desc.eps) @ t["r_proj_w"].T
+        return x.numpy()
     if desc.proj_kind == wl.PROJ_LINEAR:
         x = F.linear(x, t["pa_w"], t["pa_b"])
     else:
@@ -355,3 +369,43 @@ def test_class_token_is_one_more_key_for_every_patch():
     x2 = x1 + w["l0_fc2_w"].astype(np.float64) @ h + w["l0_fc2_b"]
     np.testing.assert_allclose(trace["layer0"][n], x2, rtol=1e-10, atol=1e-12)
     assert pr[0] > 1e-4      # the class key carries weight, so dropping it would show
+
+
+def test_resampler_one_query_one_head_by_hand():
+    """One learned query, one head: the output token is LayerNorm_post(out_w (sum_j p_j v_j) + out_b) Wp^T with
+    p = softmax over the N patch keys of q . k_j / sqrt(E), keys built from LayerNorm_kv(x Wkv^T) + pos and
+    values without pos, all written as explicit loops."""
+    desc = small_desc(layers=0, proj_kind=wl.PROJ_RESAMPLER, proj_mid=1, proj_heads=1, proj_out=8)
+    w = {k: v.astype(np.float64) for k, v in wl.gen_weights(desc, 19, std=0.4).items()}
+    tile = wl.gen_tile(desc, 19, 0)
+    x = O.trunk_tile(tile, w, desc)
+    got = O.project(x, w, desc)
+    assert got.shape == (1, 8)
+    N, E = x.shape[0], 8
+
+    def ln(v, g, b):
+        mu = sum(v) / len(v)
+        var = sum((a - mu) ** 2 for a in v) / len(v)
+        return np.array([(a - mu) / np.sqrt(var + desc.eps) for a in v]) * g + b
+
+    kv = np.array([ln([sum(w["r_kv_w"][e, d] * x[j, d] for d in range(desc.hidden)) for e in range(E)],
+                      w["r_lnkv_g"], w["r_lnkv_b"]) for j in range(N)])
+    q = ln(list(w["r_query"][0]), w["r_lnq_g"], w["r_lnq_b"])
+    Wq, Wk, Wv = w["r_in_w"][:E], w["r_in_w"][E:2 * E], w["r_in_w"][2 * E:]
+    bq, bk, bv = w["r_in_b"][:E], w["r_in_b"][E:2 * E], w["r_in_b"][2 * E:]
+    qp = Wq @ q + bq
+    logits = np.array([qp @ (Wk @ (kv[j] + w["r_pos"][j]) + bk) for j in range(N)]) / np.sqrt(E)
+    pr = np.exp(logits - logits.max()); pr /= pr.sum()
+    o = sum(pr[j] * (Wv @ kv[j] + bv) for j in range(N))
+    o = w["r_out_w"] @ o + w["r_out_b"]
+    want = w["r_proj_w"] @ ln(list(o), w["r_lnp_g"], w["r_lnp_b"])
+    np.testing.assert_allclose(got[0], want, rtol=1e-10, atol=1e-12)
+    assert pr.max() < 0.9 and pr.max() > 1.5 / N     # neither uniform nor one-hot: the key side matters
+
+
+def test_resampler_emits_one_token_per_query_for_any_patch_count():
+    for tile_size in (56, 84):
+        desc = small_desc(tile_size=tile_size, proj_kind=wl.PROJ_RESAMPLER, proj_mid=6, proj_heads=2)
+        w = wl.gen_weights(desc, 23, std=0.2)
+        out = O.encode([wl.gen_tile(desc, 23, t) for t in range(2)], [0, 2], w, desc)
+        assert out.shape == (2 * 6, desc.proj_out) and O.tokens_per_tile(desc) == desc.tokens_per_tile == 6

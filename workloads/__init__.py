@@ -35,6 +35,7 @@ ACT_GELU_TANH = 1
 
 PROJ_LINEAR = 0
 PROJ_MLP = 1
+PROJ_RESAMPLER = 2   # proj_mid learned queries cross-attend to the patch tokens (proj_heads heads)
 
 
 @dataclass(frozen=True)
@@ -60,6 +61,7 @@ class ModelDesc:
     max_tiles_per_call: int
     layer_scale: int = 0
     class_token: int = 0
+    proj_heads: int = 0
 
     # ---- shape bookkeeping only (counts, no arithmetic on data) ----
     @property
@@ -85,6 +87,8 @@ class ModelDesc:
 
     @property
     def tokens_per_tile(self) -> int:
+        if self.proj_kind == PROJ_RESAMPLER:
+            return self.proj_mid
         return self.n_patches // 4 if self.pixel_shuffle else self.n_patches
 
     @property
@@ -263,7 +267,20 @@ def weight_specs(desc: ModelDesc) -> List[Tuple[str, Tuple[int, ...], str]]:
         norm("fn", D, desc.norm)
     if desc.proj_prenorm:
         norm("pn", desc.proj_in, NORM_LAYERNORM)
-    if desc.proj_kind == PROJ_LINEAR:
+    if desc.proj_kind == PROJ_RESAMPLER:
+        E, Q = desc.proj_out, desc.proj_mid
+        specs.append(("r_kv_w", (E, D), "w"))
+        specs.append(("r_query", (Q, E), "w"))
+        specs.append(("r_pos", (N, E), "w"))
+        norm("r_lnq", E, NORM_LAYERNORM)
+        norm("r_lnkv", E, NORM_LAYERNORM)
+        specs.append(("r_in_w", (3 * E, E), "w"))
+        specs.append(("r_in_b", (3 * E,), "w"))
+        specs.append(("r_out_w", (E, E), "w"))
+        specs.append(("r_out_b", (E,), "w"))
+        norm("r_lnp", E, NORM_LAYERNORM)
+        specs.append(("r_proj_w", (E, E), "w"))
+    elif desc.proj_kind == PROJ_LINEAR:
         specs.append(("pa_w", (desc.proj_out, desc.proj_in), "w"))
         specs.append(("pa_b", (desc.proj_out,), "w"))
     else:
@@ -349,7 +366,10 @@ def flops_per_tile(desc: ModelDesc) -> int:
     f = 2 * desc.n_patches * desc.patch_dim * D
     f += L * (2 * N * D * 3 * D + 2 * N * D * D + 4 * N * D * F + 4 * N * N * D)
     No, Pi = desc.tokens_per_tile, desc.proj_in
-    if desc.proj_kind == PROJ_LINEAR:
+    if desc.proj_kind == PROJ_RESAMPLER:
+        E, Np = desc.proj_out, desc.n_patches
+        f += 2 * Np * D * E + 4 * Np * E * E + 4 * No * Np * E + 4 * No * E * E   # kv, k/v in-proj, attention, out + proj
+    elif desc.proj_kind == PROJ_LINEAR:
         f += 2 * No * Pi * desc.proj_out
     else:
         f += 2 * No * Pi * desc.proj_mid + 2 * No * desc.proj_mid * desc.proj_out
