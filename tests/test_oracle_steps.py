@@ -231,10 +231,12 @@ def test_patch_and_token_counts():
     assert O.patchify(np.zeros((3, 224, 224)), 14).shape == (256, 588)
 
     class D:  # minimal description
-        tile_size, patch, pixel_shuffle = 448, 14, 1
+        tile_size, patch, pixel_shuffle, proj_kind, proj_mid = 448, 14, 1, O.PROJ_MLP, 4096
     assert O.tokens_per_tile(D) == 256
     D.pixel_shuffle = 0
     assert O.tokens_per_tile(D) == 1024
+    D.proj_kind, D.proj_mid = O.PROJ_RESAMPLER, 64     # one token per learned query
+    assert O.tokens_per_tile(D) == 64
 
 
 # ------------------------------------------------------ pixel shuffle ----
