@@ -45,7 +45,7 @@ enum { EPD_DTYPE_FP32 = 0, EPD_DTYPE_BF16 = 1 };
 enum { EPD_NORM_LAYERNORM = 0, EPD_NORM_RMSNORM = 1 };
 enum { EPD_QKNORM_NONE = 0, EPD_QKNORM_FULL = 1, EPD_QKNORM_PER_HEAD = 2 };
 enum { EPD_ACT_GELU_ERF = 0, EPD_ACT_GELU_TANH = 1 };
-enum { EPD_PROJ_LINEAR = 0, EPD_PROJ_MLP = 1 };
+enum { EPD_PROJ_LINEAR = 0, EPD_PROJ_MLP = 1, EPD_PROJ_RESAMPLER = 2 };
 
 /* Encoder description.  The paper takes the encoder as given (SigLIP-400M,
  * InternViT-300M / 6B; Appendix "LMM Details"); this struct states which
@@ -63,9 +63,11 @@ typedef struct {
   int32_t act;           /* EPD_ACT_*: activation of the layer MLP                       */
   int32_t final_norm;    /* 1: a norm of kind `norm` after the last layer                */
   int32_t pixel_shuffle; /* 1: space-to-depth by 2 on the g x g grid: N/4 tokens of 4D   */
-  int32_t proj_kind;     /* EPD_PROJ_*: Linear, or Linear - GELU(erf) - Linear           */
+  int32_t proj_kind;     /* EPD_PROJ_*: Linear, Linear - GELU(erf) - Linear, or the
+                            cross-attention resampler (see proj_heads)                    */
   int32_t proj_prenorm;  /* 1: LayerNorm over the projector input                        */
-  int32_t proj_mid;      /* width of the MLP projector's hidden layer (ignored if Linear) */
+  int32_t proj_mid;      /* MLP: width of the hidden layer; resampler: number of learned
+                            queries = tokens per slice (ignored if Linear)                */
   int32_t proj_out;      /* D_out: width of a token in the cache                         */
   float   eps;           /* epsilon of every norm                                        */
   int32_t max_tiles_per_call; /* workspace is sized for this many slices at once; larger
@@ -79,6 +81,14 @@ typedef struct {
                             (position row 0 is its own); it takes part in every attention
                             layer and is dropped after the last norm: pixel shuffle,
                             projector and the emitted tokens cover the N patches only     */
+  int32_t proj_heads;    /* EPD_PROJ_RESAMPLER (the MiniCPM-V family's projector): proj_mid
+                            learned queries read the N patch tokens of a slice,
+                              kv = LN_kv(x Wkv^T), q = LN_q(query),
+                              o = MHA(q, kv + pos, kv) with proj_heads heads over width
+                              E = proj_out (in-projections with bias, logits / sqrt(E/heads),
+                              out-projection with bias), out = LN_post(o) Wp^T;
+                            needs pixel_shuffle = 0, proj_prenorm = 0, E % proj_heads == 0;
+                            bf16 mode: N % 64 == 0 and E / proj_heads <= 128             */
 } epd_model_desc;
 
 /* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix
@@ -94,6 +104,10 @@ typedef struct {
  *   fn_g [D], fn_b [D]            (if final_norm; fn_b only for LayerNorm)
  *   pn_g [Din], pn_b [Din]        (if proj_prenorm; Din = 4D with pixel shuffle else D)
  *   pa_w [Dmid or D_out, Din], pa_b;  pb_w [D_out, Dmid], pb_b   (pb_* only for MLP)
+ *   resampler instead of pa / pb (E = proj_out, Q = proj_mid): kv_w [E, D], query [Q, E],
+ *     pos [N, E] (position table added to the keys), lnq_g, lnq_b, lnkv_g, lnkv_b [E],
+ *     in_w [3E, E] (row blocks q, k, v), in_b [3E], out_w [E, E], out_b [E], lnp_g, lnp_b [E],
+ *     proj_w [E, E] (out = LN_post(o) proj_w^T)
  * The tensors are copied / repacked during epd_create and may be freed by the
  * caller once it returns. */
 typedef struct {

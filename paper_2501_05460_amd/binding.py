@@ -43,7 +43,7 @@ class ModelDescC(ctypes.Structure):
         "dtype", "tile_size", "patch", "hidden", "heads", "mlp", "layers", "norm", "qk_norm", "act",
         "final_norm", "pixel_shuffle", "proj_kind", "proj_prenorm", "proj_mid", "proj_out")] + [
         ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32), ("layer_scale", ctypes.c_int32),
-        ("class_token", ctypes.c_int32)]
+        ("class_token", ctypes.c_int32), ("proj_heads", ctypes.c_int32)]
 
 
 class WeightsC(ctypes.Structure):

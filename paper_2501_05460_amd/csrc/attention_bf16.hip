@@ -49,8 +49,9 @@ template <int HD, int QT, bool MASK>
 __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
-                                                        bf16_t* __restrict__ o, int n_tok, int n_keys, int heads,
-                                                        int n_pairs, long ld_qk, long ld_o, float scale_log2e) {
+                                                        bf16_t* __restrict__ o, int n_tok, int n_keys, int n_q,
+                                                        int q_shared, int heads, int n_pairs, long ld_qk,
+                                                        long ld_o, float scale_log2e) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
   constexpr int KS = SM::HDK / 16;   // k-steps of the S^T product
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   const int l32 = lane & 31, lh = lane >> 5;
   // Workgroups are dealt round-robin to the 8 XCDs: keep the q-blocks of one
   // (slice, head) on one XCD so that its K / V^T block is fetched into one L2.
-  const int n_qb = (n_tok + BQ - 1) / BQ;
+  const int n_qb = (n_q + BQ - 1) / BQ;
   const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
   const int pair = (seq / n_qb) * 8 + xcd;          // (slice, head) index
   if (pair >= n_pairs) return;                      // whole workgroup leaves before any barrier
@@ -81,7 +82,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   bool act[QT];
   bool any_act = false;
 #pragma unroll
-  for (int u = 0; u < QT; ++u) { act[u] = q0 + u * 32 < n_tok; any_act = any_act || act[u]; }
+  for (int u = 0; u < QT; ++u) { act[u] = q0 + u * 32 < n_q; any_act = any_act || act[u]; }
+  const long q_row0 = q_shared ? 0 : row0;   // learned queries: the same rows for every slice
 
   const bf16_t* kbase = k + row0 * ld_qk + (long)h * HD;
   const bf16_t* vbase = vt + ((long)t * heads + h) * HD * (long)n_tok;
@@ -91,7 +93,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     const int qrow = act[u] ? q0 + u * 32 + l32 : 0;  // inactive sub-tiles read a valid row, result unused
-    const bf16_t* qp = q + (row0 + qrow) * ld_qk + (long)h * HD + lh * 8;
+    const bf16_t* qp = q + (q_row0 + qrow) * ld_qk + (long)h * HD + lh * 8;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s * 16 + 8 < HD || lh == 0) {
@@ -262,10 +264,10 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
-    if (!act[u]) continue;
+    if (!act[u] || q0 + u * 32 + l32 >= n_q) continue;   // a shared query set need not fill its last 32 rows
     const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
     const float inv = 1.0f / l_tot;
-    bf16_t* op = o + (row0 + q0 + u * 32 + l32) * ld_o + (long)h * HD;
+    bf16_t* op = o + ((long)t * n_q + q0 + u * 32 + l32) * ld_o + (long)h * HD;
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
@@ -282,7 +284,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 
 template <int HD, int QT, bool MASK>
 hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                       int n_tok, int n_keys, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
+                         int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
+                         hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
@@ -292,33 +295,36 @@ hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf1
     attr_done = true;
   }
   constexpr int BQ = 128 * QT;
-  const int n_qb = (n_tok + BQ - 1) / BQ, n_pairs = n_slices * heads;
+  const int n_qb = (n_q + BQ - 1) / BQ, n_pairs = n_slices * heads;
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
   k_attention_bf16<HD, QT, MASK><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
-      q, k, vt, o, n_tok, n_keys, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
+      q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
   return hipGetLastError();
 }
 
 template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                       int n_tok, int n_keys, int heads, long ld_qk, long ld_o, float scale, hipStream_t st) {
-  return n_keys < n_tok ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st)
-                        : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
+                       int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
+                       hipStream_t st) {
+  return n_keys < n_tok
+             ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st)
+             : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
 }
 
 }  // namespace
 
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                          int n_tok, int n_keys, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
-                          hipStream_t st) {
+                          int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
+                          long ld_o, float scale, hipStream_t st) {
   if (n_slices == 0) return hipSuccess;
-  if (n_tok % BKEY != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok) return hipErrorInvalidValue;
+  if (n_tok % BKEY != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok || n_q < 1) return hipErrorInvalidValue;
+  if (!q_shared && n_q != n_tok) return hipErrorInvalidValue;   // a slice's own rows: one query per row
   switch (hd_pad) {
-    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
-    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
-    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
-    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, heads, ld_qk, ld_o, scale, st);
+    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
+    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
+    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
+    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
   }
   return hipErrorInvalidValue;
 }

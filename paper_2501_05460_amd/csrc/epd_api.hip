@@ -43,6 +43,7 @@ struct WeightIndex {
   int pe_w, pe_b, pos, cls;
   std::vector<LayerIdx> layers;
   int fn_g, fn_b, pn_g, pn_b, pa_w, pa_b, pb_w, pb_b;
+  int r_kv_w, r_query, r_pos, r_lnq_g, r_lnq_b, r_lnkv_g, r_lnkv_b, r_in_w, r_in_b, r_out_w, r_out_b, r_lnp_g, r_lnp_b, r_proj_w;
   std::vector<TensorSpec> specs;
 };
 
@@ -59,7 +60,7 @@ Dims dims_of(const epd_model_desc& d) {
   x.S = d.tile_size; x.p = d.patch; x.g = d.tile_size / d.patch; x.N = x.g * x.g;
   x.Kp = 3 * d.patch * d.patch; x.D = d.hidden; x.H = d.heads; x.hd = d.hidden / d.heads;
   x.F = d.mlp; x.L = d.layers;
-  x.N_out = d.pixel_shuffle ? x.N / 4 : x.N;
+  x.N_out = d.proj_kind == EPD_PROJ_RESAMPLER ? d.proj_mid : (d.pixel_shuffle ? x.N / 4 : x.N);
   x.Pin = d.pixel_shuffle ? 4 * x.D : x.D;
   x.Pmid = d.proj_mid; x.Pout = d.proj_out;
   x.cls = d.class_token ? 1 : 0;
@@ -90,10 +91,16 @@ WeightIndex build_index(const epd_model_desc& d) {
     i.ls2 = d.layer_scale ? add(1, x.D) : -1;
     w.layers.push_back(i);
   }
-  w.fn_g = w.fn_b = w.pn_g = w.pn_b = w.pb_w = w.pb_b = -1;
+  w.fn_g = w.fn_b = w.pn_g = w.pn_b = w.pa_w = w.pa_b = w.pb_w = w.pb_b = -1;
   if (d.final_norm) { w.fn_g = add(1, x.D); w.fn_b = ln ? add(1, x.D) : -1; }
   if (d.proj_prenorm) { w.pn_g = add(1, x.Pin); w.pn_b = add(1, x.Pin); }
-  if (d.proj_kind == EPD_PROJ_LINEAR) {
+  if (d.proj_kind == EPD_PROJ_RESAMPLER) {
+    const long E = x.Pout, Q = x.Pmid;
+    w.r_kv_w = add(E, x.D); w.r_query = add(Q, E); w.r_pos = add(x.N, E);
+    w.r_lnq_g = add(1, E); w.r_lnq_b = add(1, E); w.r_lnkv_g = add(1, E); w.r_lnkv_b = add(1, E);
+    w.r_in_w = add(3 * E, E); w.r_in_b = add(1, 3 * E); w.r_out_w = add(E, E); w.r_out_b = add(1, E);
+    w.r_lnp_g = add(1, E); w.r_lnp_b = add(1, E); w.r_proj_w = add(E, E);
+  } else if (d.proj_kind == EPD_PROJ_LINEAR) {
     w.pa_w = add(x.Pout, x.Pin); w.pa_b = add(1, x.Pout);
   } else {
     w.pa_w = add(x.Pmid, x.Pin); w.pa_b = add(1, x.Pmid);
@@ -107,7 +114,7 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->dtype != EPD_DTYPE_FP32 && d->dtype != EPD_DTYPE_BF16) { set_err(err, len, "dtype must be 0 (fp32) or 1 (bf16)"); return EPD_ERR_INVALID_ARG; }
   if (d->norm < 0 || d->norm > 1 || d->qk_norm < 0 || d->qk_norm > 2 || d->act < 0 || d->act > 1 ||
       d->final_norm < 0 || d->final_norm > 1 || d->pixel_shuffle < 0 || d->pixel_shuffle > 1 ||
-      d->proj_kind < 0 || d->proj_kind > 1 || d->proj_prenorm < 0 || d->proj_prenorm > 1 ||
+      d->proj_kind < 0 || d->proj_kind > 2 || d->proj_prenorm < 0 || d->proj_prenorm > 1 ||
       d->layer_scale < 0 || d->layer_scale > 1 || d->class_token < 0 || d->class_token > 1) {
     set_err(err, len, "an enum field of the description is out of range"); return EPD_ERR_INVALID_ARG;
   }
@@ -118,6 +125,12 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->tile_size % d->patch) { set_err(err, len, "tile_size %d is not a multiple of patch %d", d->tile_size, d->patch); return EPD_ERR_SHAPE; }
   if (d->hidden % d->heads) { set_err(err, len, "hidden %d is not a multiple of heads %d", d->hidden, d->heads); return EPD_ERR_SHAPE; }
   if (d->proj_kind == EPD_PROJ_MLP && d->proj_mid <= 0) { set_err(err, len, "proj_mid must be positive for an MLP projector"); return EPD_ERR_SHAPE; }
+  if (d->proj_kind == EPD_PROJ_RESAMPLER) {
+    if (d->proj_mid <= 0 || d->proj_heads <= 0 || d->proj_out % d->proj_heads) {
+      set_err(err, len, "resampler needs proj_mid (queries) > 0 and proj_heads > 0 dividing proj_out"); return EPD_ERR_SHAPE;
+    }
+    if (d->pixel_shuffle || d->proj_prenorm) { set_err(err, len, "resampler excludes pixel_shuffle and proj_prenorm"); return EPD_ERR_INVALID_ARG; }
+  }
   const Dims x = dims_of(*d);
   if (d->pixel_shuffle && (x.g % 2)) { set_err(err, len, "pixel shuffle needs an even patch grid, got %d", x.g); return EPD_ERR_SHAPE; }
   if ((long)x.Ns * d->max_tiles_per_call > (1L << 30)) { set_err(err, len, "max_tiles_per_call too large"); return EPD_ERR_UNSUPPORTED; }
@@ -125,6 +138,13 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
     if (x.hd > 128) { set_err(err, len, "bf16 mode supports head dim <= 128, got %d", x.hd); return EPD_ERR_UNSUPPORTED; }
     if (x.D % 4 || x.hd % 4 || x.F % 8 || x.Pout % 8 || (d->proj_kind == EPD_PROJ_MLP && x.Pmid % 8)) {
       set_err(err, len, "bf16 mode needs hidden and head dim %% 4 == 0, mlp and projector widths %% 8 == 0"); return EPD_ERR_UNSUPPORTED;
+    }
+    if (d->proj_kind == EPD_PROJ_RESAMPLER) {
+      const int hdr = d->proj_out / d->proj_heads;
+      if (x.N % 64 || hdr > 128 || hdr % 4) {
+        set_err(err, len, "bf16 resampler needs patches per slice %% 64 == 0 and a head dim <= 128, %% 4 == 0 (got %d, %d)", x.N, hdr);
+        return EPD_ERR_UNSUPPORTED;
+      }
     }
   }
   if (x.N > 16384) { set_err(err, len, "more than 16384 patches per slice is not supported"); return EPD_ERR_UNSUPPORTED; }
@@ -138,6 +158,17 @@ struct Linear {
   const void* W = nullptr;  // fp32 mode: float [N,K]; bf16 mode: packed bf16 [Npad,K]
   const float* b = nullptr; // fp32 (padded to Npad in bf16 mode)
   int N = 0, K = 0, Npad = 0;
+};
+
+// Cross-attention resampler projector: weights, the projected learned queries, and its workspace.
+struct Resampler {
+  Linear kv, k, v, o, proj;     // kv: hidden -> E; k, v: in-projections of keys / values; o: out-projection; proj: last matrix
+  const float *lnkv_g = nullptr, *lnkv_b = nullptr, *lnp_g = nullptr, *lnp_b = nullptr;
+  const float* pos = nullptr;   // [N, E] fp32
+  void* qp = nullptr;           // in-projected LN_q(query): bf16 [>= round_up(Q, 256), Eq_k] / fp32 [Q, E]
+  int Q = 0, E = 0, H = 0, hd = 0, hd_pad = 0, Eq = 0, Eq_k = 0, E_k = 0;
+  void *xin = nullptr, *kvraw = nullptr, *kin = nullptr, *vin = nullptr, *K = nullptr, *V = nullptr, *O = nullptr,
+       *o2 = nullptr, *o3 = nullptr;   // V: bf16 [mb, H, hd_pad, N] (transposed) / fp32 [M, E]
 };
 
 struct LayerW {
@@ -156,6 +187,7 @@ struct epd_ctx {
 
   // weights
   Linear pe, pa, pb;
+  Resampler rs;
   const float* pos = nullptr;   // [Nt, D]; row 0 is the class token's when there is one
   const float* cls = nullptr;   // [D], null without a class token
   const float *fn_g = nullptr, *fn_b = nullptr, *pn_g = nullptr, *pn_b = nullptr;
@@ -235,25 +267,46 @@ const float* make_vec(epd_ctx* c, const epd_weights* w, int idx, long n, int n_p
   return dst;
 }
 
-bool make_linear(epd_ctx* c, const epd_weights* w, int wi, int bi, int N, int K, Linear* out, hipStream_t st,
-                 int Npad, int Kpad, PackMap rmap, PackMap cmap, int n_packed) {
+// elements of the weight dtype further into a caller tensor
+const void* tensor_at(const epd_ctx* c, const void* base, long elems) {
+  return (const char*)base + elems * (c->bf16 ? 2 : 4);
+}
+
+// fp32 copy of n values at src (weight dtype), zero-padded / head-reindexed to n_pad; src null: zeros
+const float* make_vec_p(epd_ctx* c, const void* src, long n, int n_pad, PackMap map, hipStream_t st) {
+  float* dst = (float*)dalloc(c, (size_t)n_pad * sizeof(float), src == nullptr, st);
+  if (!dst) return nullptr;
+  if (src) pack_vector_f32(src, c->bf16 ? 1 : 0, (int)n, dst, n_pad, map, st);
+  return dst;
+}
+
+// Linear from a [N, K] matrix at Wsrc and a bias at bsrc (null: no bias, a zero vector is kept)
+bool make_linear_p(epd_ctx* c, const void* Wsrc, const void* bsrc, int N, int K, Linear* out, hipStream_t st,
+                   int Npad, int Kpad, PackMap rmap, PackMap cmap, int n_packed) {
   out->N = n_packed; out->K = Kpad; out->Npad = Npad;
   if (!c->bf16) {
     const size_t bytes = (size_t)N * K * sizeof(float);
     void* dst = dalloc(c, bytes, false, st);
     if (!dst) return false;
-    if (hipMemcpyAsync(dst, w->tensors[wi], bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return false;
+    if (hipMemcpyAsync(dst, Wsrc, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return false;
     out->W = dst; out->N = N; out->K = K; out->Npad = N;
-    out->b = make_vec(c, w, bi, N, N, PackMap{0, 0, 0}, st);
+    out->b = make_vec_p(c, bsrc, N, N, PackMap{0, 0, 0}, st);
     return out->b != nullptr;
   }
   bf16_t* dst = (bf16_t*)dalloc(c, (size_t)Npad * Kpad * sizeof(bf16_t), false, st);
   if (!dst) return false;
-  pack_matrix_bf16((const bf16_t*)w->tensors[wi], N, K, dst, Npad, Kpad, rmap, cmap, st);
+  pack_matrix_bf16((const bf16_t*)Wsrc, N, K, dst, Npad, Kpad, rmap, cmap, st);
   out->W = dst;
-  out->b = make_vec(c, w, bi, N, Npad, rmap, st);
+  out->b = make_vec_p(c, bsrc, N, Npad, rmap, st);
   return out->b != nullptr;
 }
+
+bool make_linear(epd_ctx* c, const epd_weights* w, int wi, int bi, int N, int K, Linear* out, hipStream_t st,
+                 int Npad, int Kpad, PackMap rmap, PackMap cmap, int n_packed) {
+  return make_linear_p(c, w->tensors[wi], bi >= 0 ? w->tensors[bi] : nullptr, N, K, out, st, Npad, Kpad, rmap, cmap, n_packed);
+}
+
+GemmParams gp(int epi, const void* A, long lda, const Linear& lin, int M);
 
 epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   const epd_model_desc& d = c->d;
@@ -358,7 +411,50 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     c->pn_b = make_vec(c, w, wi.pn_b, x.Pin, x.Pin, id, st);
     NOMEM_IF(!c->pn_g || !c->pn_b);
   }
-  if (d.proj_kind == EPD_PROJ_LINEAR) {
+  if (d.proj_kind == EPD_PROJ_RESAMPLER) {
+    Resampler& r = c->rs;
+    r.Q = x.Pmid; r.E = x.Pout; r.H = d.proj_heads; r.hd = r.E / r.H;
+    const int E = r.E;
+    r.hd_pad = bf ? (r.hd <= 64 ? 64 : (r.hd == 72 ? 72 : (r.hd <= 96 ? 96 : 128))) : r.hd;
+    r.Eq = r.H * r.hd_pad;
+    r.Eq_k = bf ? round_up(r.Eq, 128) : r.Eq;
+    r.E_k = bf ? round_up(E, 128) : E;
+    const PackMap rh = (bf && r.hd_pad != r.hd) ? PackMap{r.hd, r.hd_pad, r.H} : id;
+    const void* in_w = w->tensors[wi.r_in_w];
+    const void* in_b = w->tensors[wi.r_in_b];
+    Linear lq;
+    NOMEM_IF(!make_linear(c, w, wi.r_kv_w, -1, E, x.D, &r.kv, st, pad_n(E), c->D_k, id, id, E));
+    NOMEM_IF(!make_linear_p(c, in_w, in_b, E, E, &lq, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
+    NOMEM_IF(!make_linear_p(c, tensor_at(c, in_w, (long)E * E), tensor_at(c, in_b, E), E, E, &r.k, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
+    NOMEM_IF(!make_linear_p(c, tensor_at(c, in_w, 2L * E * E), tensor_at(c, in_b, 2L * E), E, E, &r.v, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
+    NOMEM_IF(!make_linear(c, w, wi.r_out_w, wi.r_out_b, E, E, &r.o, st, pad_n(E), r.Eq_k, id, rh, E));
+    NOMEM_IF(!make_linear(c, w, wi.r_proj_w, -1, E, E, &r.proj, st, pad_n(E), r.E_k, id, id, E));
+    r.lnkv_g = make_vec(c, w, wi.r_lnkv_g, E, E, id, st); r.lnkv_b = make_vec(c, w, wi.r_lnkv_b, E, E, id, st);
+    r.lnp_g = make_vec(c, w, wi.r_lnp_g, E, E, id, st); r.lnp_b = make_vec(c, w, wi.r_lnp_b, E, E, id, st);
+    r.pos = make_vec(c, w, wi.r_pos, (long)x.N * E, x.N * E, id, st);
+    const float* query = make_vec(c, w, wi.r_query, (long)r.Q * E, r.Q * E, id, st);
+    const float* lnq_g = make_vec(c, w, wi.r_lnq_g, E, E, id, st);
+    const float* lnq_b = make_vec(c, w, wi.r_lnq_b, E, E, id, st);
+    NOMEM_IF(!r.lnkv_g || !r.lnkv_b || !r.lnp_g || !r.lnp_b || !r.pos || !query || !lnq_g || !lnq_b);
+    // the queries are the same for every slice: LN_q and their in-projection run once, here
+    const long Qp = round_up(r.Q, 256);
+    if (bf) {
+      bf16_t* qn = (bf16_t*)dalloc(c, (size_t)Qp * r.E_k * 2, true, st);
+      r.qp = dalloc(c, (size_t)Qp * r.Eq_k * 2, true, st);
+      NOMEM_IF(!qn || !r.qp);
+      RowOpParams ro{0, query, E, qn, r.E_k, lnq_g, lnq_b, r.Q, E, 0, x.g, x.D, d.eps, SliceRows{0, 0, 0}};
+      bf16_rowop(ro, st);
+      GemmParams p = gp(EPI_BIAS, qn, r.E_k, lq, r.Q);
+      p.C = (bf16_t*)r.qp; p.ldc = r.Eq_k;
+      HIP_TRY(c, bf16_gemm(p, st));
+    } else {
+      float* qn = (float*)dalloc(c, (size_t)r.Q * E * 4, false, st);
+      r.qp = dalloc(c, (size_t)r.Q * E * 4, false, st);
+      NOMEM_IF(!qn || !r.qp);
+      f32_norm(0, query, E, qn, E, lnq_g, lnq_b, r.Q, E, 1, d.eps, st);
+      f32_gemm(EPI_BIAS, qn, E, (const float*)lq.W, lq.b, (float*)r.qp, E, nullptr, 1, r.Q, E, E, st);
+    }
+  } else if (d.proj_kind == EPD_PROJ_LINEAR) {
     NOMEM_IF(!make_linear(c, w, wi.pa_w, wi.pa_b, x.Pout, x.Pin, &c->pa, st, pad_n(x.Pout), c->Pin_k, id, id, x.Pout));
   } else {
     const int mid_pad = pad_n(x.Pmid);
@@ -403,6 +499,24 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     c->Ape = ws((size_t)M * x.Kp * 4);
     c->Pin = ws((size_t)Mo * x.Pin * 4);
     c->Pmid = ws((size_t)Mo * (x.Pmid > 0 ? x.Pmid : 1) * 4);
+  }
+  if (d.proj_kind == EPD_PROJ_RESAMPLER) {
+    Resampler& r = c->rs;
+    const long Mr = round_up(c->mb * x.N, 256), Mq = c->Mp_out;   // patch rows, query rows
+    if (bf) {
+      if (Mr * (long)std::max(r.E_k, r.Eq_k) * 2 >= (1L << 32)) {
+        set_err(c->err, sizeof(c->err), "max_tiles_per_call %d makes a resampler buffer of 4 GiB or more", c->mb);
+        return EPD_ERR_UNSUPPORTED;
+      }
+      r.xin = ws((size_t)Mr * c->D_k * 2); r.kvraw = ws((size_t)Mr * r.E_k * 2);
+      r.kin = ws((size_t)Mr * r.E_k * 2); r.vin = ws((size_t)Mr * r.E_k * 2);
+      r.K = ws((size_t)Mr * r.Eq_k * 2); r.V = ws((size_t)c->mb * r.H * r.hd_pad * x.N * 2);
+      r.O = ws((size_t)Mq * r.Eq_k * 2); r.o2 = ws((size_t)Mq * r.E_k * 2); r.o3 = ws((size_t)Mq * r.E_k * 2);
+    } else {
+      const size_t e4 = (size_t)c->mb * x.N * r.E * 4, q4 = (size_t)c->mb * r.Q * r.E * 4;
+      r.xin = ws((size_t)c->mb * x.N * x.D * 4); r.kvraw = ws(e4); r.kin = ws(e4); r.vin = ws(e4); r.K = ws(e4); r.V = ws(e4);
+      r.O = ws(q4); r.o2 = ws(q4); r.o3 = ws(q4);
+    }
   }
   if (!ok) { set_err(c->err, sizeof(c->err), "device allocation failed (workspace for %d slices)", c->mb); return EPD_ERR_NOMEM; }
   HIP_TRY(c, hipStreamSynchronize(st));
@@ -451,7 +565,7 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
       f32_norm(1, QKV, 3 * x.D, QKV, 3 * x.D, w.qn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
       f32_norm(1, QKV + x.D, 3 * x.D, QKV + x.D, 3 * x.D, w.kn_g, nullptr, (long)M * x.H, x.hd, x.H, d.eps, st);
     }
-    { ProfScope ps(c, 3, st); f32_attention(QKV, QKV + x.D, QKV + 2 * x.D, 3 * x.D, O, x.D, T, x.Ns, x.H, x.hd, scale, st); }
+    { ProfScope ps(c, 3, st); f32_attention(QKV, 3 * x.D, x.Ns, 0, QKV + x.D, QKV + 2 * x.D, 3 * x.D, O, x.D, T, x.Ns, x.H, x.hd, scale, st); }
     { ProfScope ps(c, 6, st); f32_gemm(EPI_BIAS_RESIDUAL, O, x.D, (const float*)w.o.W, w.o.b, X, x.D, nullptr, 1, M, x.D, x.D, st); }
     { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, Xn, x.D, w.n2_g, w.n2_b, M, x.D, 1, d.eps, st); }
     { ProfScope ps(c, 7, st); f32_gemm(act_epi, Xn, x.D, (const float*)w.fc1.W, w.fc1.b, Hd, x.F, nullptr, 1, M, x.F, x.D, st); }
@@ -461,6 +575,33 @@ epd_status run_f32(epd_ctx* c, const float* tiles, int T, float* out, hipStream_
   if (stage == STAGE_TRUNK) {
     ProfScope ps(c, 5, st);
     stream_to_blocks(X, x.D, xr, out, 0, x.D, c->d_rowmap, c->cur_block_tokens, Mpatch, st);
+    HIP_TRY(c, hipGetLastError());
+    return EPD_OK;
+  }
+  if (d.proj_kind == EPD_PROJ_RESAMPLER) {
+    const Resampler& r = c->rs;
+    const int E = r.E;
+    float *kvraw = (float*)r.kvraw, *kin = (float*)r.kin, *vin = (float*)r.vin, *K = (float*)r.K, *V = (float*)r.V;
+    float *Oq = (float*)r.O, *o2 = (float*)r.o2, *o3 = (float*)r.o3;
+    const float* xin = X;
+    { ProfScope ps(c, 5, st);
+      if (xr.n) { f32_take_rows(X, xr, (float*)r.xin, Mpatch, x.D, st); xin = (const float*)r.xin; } }
+    { ProfScope ps(c, 9, st);
+      f32_gemm(EPI_BIAS, xin, x.D, (const float*)r.kv.W, nullptr, kvraw, E, nullptr, 1, Mpatch, E, x.D, st); }
+    { ProfScope ps(c, 5, st);
+      f32_norm(0, kvraw, E, vin, E, r.lnkv_g, r.lnkv_b, Mpatch, E, 1, d.eps, st);
+      f32_add_rows(vin, r.pos, x.N, kin, Mpatch, E, st); }
+    { ProfScope ps(c, 9, st);
+      f32_gemm(EPI_BIAS, kin, E, (const float*)r.k.W, r.k.b, K, E, nullptr, 1, Mpatch, E, E, st);
+      f32_gemm(EPI_BIAS, vin, E, (const float*)r.v.W, r.v.b, V, E, nullptr, 1, Mpatch, E, E, st); }
+    { ProfScope ps(c, 3, st);
+      f32_attention((const float*)r.qp, E, r.Q, 1, K, V, E, Oq, E, T, x.N, r.H, r.hd, 1.0f / sqrtf((float)r.hd), st); }
+    { ProfScope ps(c, 9, st);
+      f32_gemm(EPI_BIAS, Oq, E, (const float*)r.o.W, r.o.b, o2, E, nullptr, 1, Mo, E, E, st); }
+    { ProfScope ps(c, 5, st); f32_norm(0, o2, E, o3, E, r.lnp_g, r.lnp_b, Mo, E, 1, d.eps, st); }
+    { ProfScope ps(c, 9, st);
+      f32_gemm(EPI_BIAS, o3, E, (const float*)r.proj.W, nullptr, out, x.Pout, nullptr, 1, Mo, E, E, st,
+               c->cur_rowmap, c->cur_block_tokens); }
     HIP_TRY(c, hipGetLastError());
     return EPD_OK;
   }
@@ -538,7 +679,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
     }
     { ProfScope ps(c, 3, st);
-      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
+      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
     { ProfScope ps(c, 6, st);
       GemmParams p = gp(EPI_BIAS_RESIDUAL, O, c->Dq_k, w.o, M);
       p.R = X; p.ldr = x.D;
@@ -559,6 +700,42 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   if (stage == STAGE_TRUNK) {
     ProfScope ps(c, 5, st);
     stream_to_blocks(X, x.D, xr, out, 1, x.D, c->d_rowmap, c->cur_block_tokens, Mpatch, st);
+    HIP_TRY(c, hipGetLastError());
+    return EPD_OK;
+  }
+  if (d.proj_kind == EPD_PROJ_RESAMPLER) {
+    const Resampler& r = c->rs;
+    bf16_t *xin = (bf16_t*)r.xin, *kvraw = (bf16_t*)r.kvraw, *kin = (bf16_t*)r.kin, *vin = (bf16_t*)r.vin, *K = (bf16_t*)r.K;
+    bf16_t *Oq = (bf16_t*)r.O, *o2 = (bf16_t*)r.o2, *o3 = (bf16_t*)r.o3;
+    { ProfScope ps(c, 5, st);   // the patch rows of the stream as bf16
+      RowOpParams ro{2, X, x.D, xin, c->D_k, nullptr, nullptr, Mpatch, x.D, 0, x.g, x.D, d.eps, xr};
+      bf16_rowop(ro, st); }
+    { ProfScope ps(c, 9, st);
+      GemmParams p = gp(EPI_BIAS, xin, c->D_k, r.kv, Mpatch);
+      p.C = kvraw; p.ldc = r.E_k;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 5, st);   // values LN_kv(kv), keys LN_kv(kv) + pos
+      bf16_ln_rows(kvraw, r.E_k, r.lnkv_g, r.lnkv_b, d.eps, vin, r.E_k, kin, r.pos, x.N, Mpatch, r.E, st); }
+    { ProfScope ps(c, 9, st);
+      GemmParams pk = gp(EPI_BIAS, kin, r.E_k, r.k, Mpatch);
+      pk.C = K; pk.ldc = r.Eq_k;
+      HIP_TRY(c, bf16_gemm(pk, st));
+      GemmParams pv = gp(EPI_VT, vin, r.E_k, r.v, Mpatch);
+      pv.VT = (bf16_t*)r.V; pv.hd_pad = r.hd_pad; pv.heads = r.H; pv.n_tok = x.N;
+      HIP_TRY(c, bf16_gemm(pv, st)); }
+    { ProfScope ps(c, 3, st);
+      HIP_TRY(c, bf16_attention((const bf16_t*)r.qp, K, (const bf16_t*)r.V, Oq, T, x.N, x.N, r.Q, 1, r.H, r.hd_pad, r.Eq_k, r.Eq_k,
+                                1.0f / sqrtf((float)r.hd), st)); }
+    { ProfScope ps(c, 9, st);
+      GemmParams p = gp(EPI_BIAS, Oq, r.Eq_k, r.o, Mo);
+      p.C = o2; p.ldc = r.E_k;
+      HIP_TRY(c, bf16_gemm(p, st)); }
+    { ProfScope ps(c, 5, st);
+      bf16_ln_rows(o2, r.E_k, r.lnp_g, r.lnp_b, d.eps, o3, r.E_k, nullptr, nullptr, 1, Mo, r.E, st); }
+    { ProfScope ps(c, 9, st);
+      GemmParams p = gp(EPI_BIAS, o3, r.E_k, r.proj, Mo);
+      p.C = out; p.ldc = x.Pout; p.row_map = c->cur_rowmap; p.block_tokens = c->cur_block_tokens;
+      HIP_TRY(c, bf16_gemm(p, st)); }
     HIP_TRY(c, hipGetLastError());
     return EPD_OK;
   }
@@ -900,7 +1077,7 @@ epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, v
                                  float scale, void* hip_stream) {
   if (!q || !k || !vt || !o) return EPD_ERR_INVALID_ARG;
   hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, (bf16_t*)o, n_slices,
-                                n_tokens, n_keys, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
+                                n_tokens, n_keys, n_tokens, 0, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
   if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }
   return EPD_OK;
 }

@@ -20,8 +20,13 @@ void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bia
               const int* row_map = nullptr, int block_tokens = 1, SliceRows xrows = SliceRows{0, 0, 0});
 void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, const float* gamma,
               const float* beta, long rows, int dim, int groups, float eps, hipStream_t st);
-void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
-                   int N, int H, int hd, float scale, hipStream_t st);
+// Slice t: keys / values rows t*N .. t*N+N-1 (row stride ld).  Encoder layers: n_q = N queries from the
+// slice's own rows.  q_shared: the n_q query rows (stride ld_q) are the same for every slice (resampler).
+// Output row t*n_q + i.
+void f32_attention(const float* q, long ld_q, int n_q, int q_shared, const float* k, const float* v, long ld,
+                   float* o, long ldo, int T, int N, int H, int hd, float scale, hipStream_t st);
+// out[r][c] = in[r][c] + add[r % add_rows][c], rows of dim floats
+void f32_add_rows(const float* in, const float* add, int add_rows, float* out, long rows, int dim, hipStream_t st);
 void f32_shuffle(const float* in, SliceRows src, float* out, int T, int g, int D, hipStream_t st);
 // out[r] = in[src.row(r)], rows of D floats
 void f32_take_rows(const float* in, SliceRows src, float* out, long rows, int D, hipStream_t st);
@@ -80,9 +85,17 @@ void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, i
 // Tile-local flash attention (attention_bf16.hip).
 // Slice t owns rows t * n_tok .. of q, k, o and columns 0 .. n_tok of its V^T rows (n_tok % 64 == 0);
 // only its first n_keys rows are real tokens: later keys are masked out, later queries give unused rows.
+// n_q queries per slice (multiple of 64 unless q_shared); q_shared: the query rows are rows 0 .. n_q-1 of q
+// for every slice (learned queries of the resampler; q must be readable for round_up(n_q, 32) rows) instead
+// of the slice's own rows.  Row t * n_q + i of o is query i of slice t.
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                          int n_tok, int n_keys, int heads, int hd_pad, long ld_qk, long ld_o, float scale,
-                          hipStream_t st);
+                          int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
+                          long ld_o, float scale, hipStream_t st);
+
+// LayerNorm of bf16 rows (statistics in fp32 over `dim` elements, dim % 4 == 0): out = LN(in) and, when
+// out_plus is set, out_plus = LN(in) + add[row % add_rows] (fp32 table [add_rows, dim]).
+void bf16_ln_rows(const bf16_t* in, long ld_in, const float* gamma, const float* beta, float eps, bf16_t* out,
+                  long ld_out, bf16_t* out_plus, const float* add, int add_rows, long rows, int dim, hipStream_t st);
 
 // Rows of the residual stream no product writes: the class token's row of every slice
 // (cls + pos[0]; cls null = no class token) and the padding rows n_real .. stride - 1 (zeros).

@@ -182,6 +182,59 @@ void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, i
                                                                        count, eps);
 }
 
+// ---------------------------------------------- LayerNorm of bf16 rows ------
+// One wave per row; the row is read twice (statistics, then output).
+__global__ __launch_bounds__(256) void k_bf16_ln_rows(const bf16_t* __restrict__ in, long ld_in,
+                                                      const float* __restrict__ gamma,
+                                                      const float* __restrict__ beta, float eps,
+                                                      bf16_t* __restrict__ out, long ld_out,
+                                                      bf16_t* __restrict__ out_plus,
+                                                      const float* __restrict__ add, int add_rows, long rows,
+                                                      int dim) {
+  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const bf16x4* x = reinterpret_cast<const bf16x4*>(in + R * ld_in);
+  const int nchunk = dim >> 2;
+  float s = 0.f;
+  for (int c = lane; c < nchunk; c += 64) {
+    const bf16x4 a = x[c];
+    s += (float)a[0] + (float)a[1] + (float)a[2] + (float)a[3];
+  }
+  const float mean = wave_sum(s) / dim;
+  float qs = 0.f;
+  for (int c = lane; c < nchunk; c += 64) {
+    const bf16x4 a = x[c];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { const float d = (float)a[e] - mean; qs += d * d; }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(qs) / dim + eps);
+  const float* arow = out_plus ? add + (R % add_rows) * (long)dim : nullptr;
+  for (int c = lane; c < nchunk; c += 64) {
+    const bf16x4 a = x[c];
+    const float4 gm = reinterpret_cast<const float4*>(gamma)[c], bt = reinterpret_cast<const float4*>(beta)[c];
+    const float r[4] = {((float)a[0] - mean) * rstd * gm.x + bt.x, ((float)a[1] - mean) * rstd * gm.y + bt.y,
+                        ((float)a[2] - mean) * rstd * gm.z + bt.z, ((float)a[3] - mean) * rstd * gm.w + bt.w};
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)r[e];
+    reinterpret_cast<bf16x4*>(out + R * ld_out)[c] = o;
+    if (out_plus) {
+      const float4 ad = reinterpret_cast<const float4*>(arow)[c];
+      bf16x4 p;
+      p[0] = (bf16_t)(r[0] + ad.x); p[1] = (bf16_t)(r[1] + ad.y); p[2] = (bf16_t)(r[2] + ad.z); p[3] = (bf16_t)(r[3] + ad.w);
+      reinterpret_cast<bf16x4*>(out_plus + R * ld_out)[c] = p;
+    }
+  }
+}
+
+void bf16_ln_rows(const bf16_t* in, long ld_in, const float* gamma, const float* beta, float eps, bf16_t* out,
+                  long ld_out, bf16_t* out_plus, const float* add, int add_rows, long rows, int dim, hipStream_t st) {
+  if (rows == 0) return;
+  k_bf16_ln_rows<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(in, ld_in, gamma, beta, eps, out, ld_out,
+                                                                        out_plus, add, add_rows, rows, dim);
+}
+
 // --------------------------------------------------------------- packing ----
 __device__ __forceinline__ int unpad_index(int i, PackMap m, int limit) {
   if (m.hd == 0) return i < limit ? i : -1;

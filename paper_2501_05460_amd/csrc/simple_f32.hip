@@ -146,7 +146,7 @@ void f32_norm(int kind, const float* in, long ld_in, float* out, long ld_out, co
 // ------------------------------------------------------------- attention ----
 // One block per (query, head, slice): logits of the slice's N keys in LDS,
 // block-wide max and sum, then one thread per output channel.
-__global__ __launch_bounds__(128) void k_f32_attention(const float* __restrict__ q,
+__global__ __launch_bounds__(128) void k_f32_attention(const float* __restrict__ q, long ld_q, int q_shared,
                                                        const float* __restrict__ k,
                                                        const float* __restrict__ v, long ld,
                                                        float* __restrict__ o, long ldo, int N, int hd,
@@ -158,7 +158,9 @@ __global__ __launch_bounds__(128) void k_f32_attention(const float* __restrict__
   const int tid = threadIdx.x;
   const int qi = blockIdx.x, h = blockIdx.y, t = blockIdx.z;
   const long row0 = (long)t * N;
-  for (int d = tid; d < hd; d += 128) sq[d] = q[(row0 + qi) * ld + h * hd + d];
+  const long qrow = q_shared ? qi : row0 + qi;
+  const long orow = (long)t * gridDim.x + qi;
+  for (int d = tid; d < hd; d += 128) sq[d] = q[qrow * ld_q + h * hd + d];
   __syncthreads();
   float mx = -INFINITY;
   for (int j = tid; j < N; j += 128) {
@@ -187,15 +189,28 @@ __global__ __launch_bounds__(128) void k_f32_attention(const float* __restrict__
   for (int d = tid; d < hd; d += 128) {
     float acc = 0.f;
     for (int j = 0; j < N; ++j) acc = fmaf(sc[j], v[(row0 + j) * ld + h * hd + d], acc);
-    o[(row0 + qi) * ldo + h * hd + d] = acc * inv;
+    o[orow * ldo + h * hd + d] = acc * inv;
   }
 }
 
-void f32_attention(const float* q, const float* k, const float* v, long ld, float* o, long ldo, int T,
-                   int N, int H, int hd, float scale, hipStream_t st) {
+void f32_attention(const float* q, long ld_q, int n_q, int q_shared, const float* k, const float* v, long ld,
+                   float* o, long ldo, int T, int N, int H, int hd, float scale, hipStream_t st) {
   if (T == 0) return;
   size_t smem = (size_t)(N + hd) * sizeof(float);
-  k_f32_attention<<<dim3(N, H, T), dim3(128), smem, st>>>(q, k, v, ld, o, ldo, N, hd, scale);
+  k_f32_attention<<<dim3(n_q, H, T), dim3(128), smem, st>>>(q, ld_q, q_shared, k, v, ld, o, ldo, N, hd, scale);
+}
+
+__global__ void k_f32_add_rows(const float* __restrict__ in, const float* __restrict__ add, int add_rows,
+                               float* __restrict__ out, int dim, long total) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  out[i] = in[i] + add[((i / dim) % add_rows) * dim + i % dim];
+}
+
+void f32_add_rows(const float* in, const float* add, int add_rows, float* out, long rows, int dim, hipStream_t st) {
+  long total = rows * dim;
+  if (total == 0) return;
+  k_f32_add_rows<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(in, add, add_rows, out, dim, total);
 }
 
 // --------------------------------------------------------- pixel shuffle ----

@@ -44,6 +44,11 @@ def test_weight_count_matches_generator_order():
     assert B.weight_count(with_cls) == B.weight_count(d) + 1 == len(wl.weight_specs(with_cls))
     assert wl.weight_specs(with_cls)[2][1] == (d.n_patches + 1, d.hidden)
     assert B.weight_count(d.replace(class_token=2)) == B.EPD_ERR_INVALID_ARG
+    rs = wl.workload("c2").desc.replace(final_norm=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=64, proj_heads=28)
+    assert B.weight_count(rs) == len(wl.weight_specs(rs))
+    assert B.weight_count(rs.replace(proj_heads=27)) == B.EPD_ERR_SHAPE          # 3584 % 27 != 0
+    assert B.weight_count(rs.replace(proj_heads=7)) == B.EPD_ERR_UNSUPPORTED     # head dim 512 in bf16 mode
+    assert B.weight_count(rs.replace(pixel_shuffle=1)) < 0
 
 
 def test_check_desc_accepts_the_five_configs():

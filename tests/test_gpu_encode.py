@@ -37,6 +37,11 @@ VARIANTS = {
     "class_token_shuffle_scale_hd72": dict(class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
                                            proj_kind=wl.PROJ_MLP, proj_mid=136, hidden=144, heads=2),
     "class_token_rms_qkhead": dict(class_token=1, norm=wl.NORM_RMSNORM, qk_norm=wl.QKNORM_PER_HEAD),
+    # cross-attention resampler projector: 8 / 5 learned queries per slice, head dims 48 (padded to 64) and 128
+    "resampler": dict(final_norm=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=8, proj_heads=2, act=wl.ACT_GELU_TANH),
+    "resampler_hd128_class_token": dict(class_token=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=5, proj_heads=2,
+                                        proj_out=256),
+    "resampler_hd72": dict(proj_kind=wl.PROJ_RESAMPLER, proj_mid=40, proj_heads=3, proj_out=216),
     # patch grids whose token count is no multiple of the key block: 7 x 7 = 49 and 6 x 6 + 1 = 37
     "grid7": dict(tile_size=98),
     "grid6_class_token_shuffle": dict(tile_size=84, class_token=1, pixel_shuffle=1, proj_prenorm=1,
@@ -92,6 +97,16 @@ def test_class_token_at_a_257_token_sequence_vs_oracle():
                       proj_kind=wl.PROJ_MLP, proj_mid=136, max_tiles_per_call=3)
     got, want = run_case(desc, 24, 5, [0, 5])
     assert got.shape == (5 * 64, 96)
+    assert rel_err(got, want) < tol(desc)
+
+
+def test_resampler_at_a_1024_patch_slice_vs_oracle():
+    """448-pixel slices (1024 keys per query, 16 key blocks), 64 learned queries, more slices than one
+    micro-batch holds; logits sharpened so the key side (LayerNorm, position table, in-projection) shows."""
+    desc = small_desc(wl.DT_BF16, tile_size=448, final_norm=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=64,
+                      proj_heads=2, proj_out=256, layers=1, max_tiles_per_call=2)
+    got, want = run_case(desc, 25, 3, [0, 3], scale={"r_in_w": 1.5})
+    assert got.shape == (3 * 64, 256)
     assert rel_err(got, want) < tol(desc)
 
 

@@ -21,6 +21,9 @@ def desc_for(dtype, variant):
     common = dict(dtype=dtype, tile_size=224, patch=14, hidden=128, heads=2, mlp=256, layers=2,
                   norm=wl.NORM_LAYERNORM, qk_norm=wl.QKNORM_NONE, act=wl.ACT_GELU_ERF, eps=1e-6,
                   max_tiles_per_call=2)
+    if variant == "resampler":   # 16 learned queries per slice: one cache block of projected tokens
+        return wl.ModelDesc(final_norm=1, pixel_shuffle=0, proj_kind=wl.PROJ_RESAMPLER, proj_prenorm=0, proj_mid=16,
+                            proj_out=96, proj_heads=2, **common)
     if variant == "class_token_shuffle_mlp":   # the class token never reaches the cache: 256 patch tokens per slice
         return wl.ModelDesc(final_norm=0, pixel_shuffle=1, proj_kind=wl.PROJ_MLP, proj_prenorm=1, proj_mid=128,
                             proj_out=96, class_token=1, **common)
@@ -35,7 +38,7 @@ def bits(t):
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy()
 
 
-@pytest.mark.parametrize("variant", ["shuffle_mlp", "postnorm_linear", "class_token_shuffle_mlp"])
+@pytest.mark.parametrize("variant", ["shuffle_mlp", "postnorm_linear", "class_token_shuffle_mlp", "resampler"])
 @pytest.mark.parametrize("dtype", [wl.DT_BF16, wl.DT_FP32], ids=["bf16", "fp32"])
 def test_shards_cached_transferred_projected_and_merged(dtype, variant):
     desc = desc_for(dtype, variant)
