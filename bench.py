@@ -32,8 +32,13 @@ def gemm_flops_per_tile(desc):
     """Dense-contraction flops of the GEMM kernel family per slice, by profile family."""
     N, D, F, L = desc.seq_len, desc.hidden, desc.mlp, desc.layers   # real tokens, the row padding is not counted
     No, Pi = desc.tokens_per_tile, desc.proj_in
-    proj = 2 * No * Pi * desc.proj_out if desc.proj_kind == 0 else \
-        2 * No * Pi * desc.proj_mid + 2 * No * desc.proj_mid * desc.proj_out
+    if desc.proj_kind == 2:   # resampler: kv projection, key / value in-projections, out-projection + last matrix
+        E, Np = desc.proj_out, desc.n_patches
+        proj = 2 * Np * D * E + 4 * Np * E * E + 4 * No * E * E
+    elif desc.proj_kind == 0:
+        proj = 2 * No * Pi * desc.proj_out
+    else:
+        proj = 2 * No * Pi * desc.proj_mid + 2 * No * desc.proj_mid * desc.proj_out
     return {
         "gemm_qkv": L * 2 * N * D * 3 * D,
         "gemm_out": L * 2 * N * D * D,
@@ -48,7 +53,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6", "c7"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8"])
     ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mm-cache", action="store_true", help="skip the paged-cache encode / block-transfer leg")
@@ -231,7 +236,7 @@ def main():
     parity = None
     if not args.no_cpu_baseline:
         from oracle import epd_oracle as O
-        n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2, "c6": 2, "c7": 3}[args.workload]
+        n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2, "c6": 2, "c7": 3, "c8": 2}[args.workload]
         sample = list(wk.oracle_sample_tiles)[:n_cpu]
         w_host = wl.gen_weights(desc, wk.weight_seed)
         host_tiles = [wl.gen_tile(desc, wk.input_seed, t) for t in sample]

@@ -115,6 +115,16 @@ def test_c7_internvit300m_shape_with_class_token_and_layer_scale():
     enc.close()
 
 
+def test_c8_siglip_shape_with_resampler_10_slices():
+    wk = wl.workload("c8")
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (10 * 64, 3584)
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    enc.close()
+
+
 def test_c6_video_requests_batched_equals_one_request_per_call_and_oracle():
     """Video workload: 16 requests of 8 to 64 frames, one slice per frame.  Encoding every request in
     its own call (maximum encode batch size 1) gives the bits of the one batched call."""

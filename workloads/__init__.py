@@ -208,10 +208,16 @@ def workload(name: str) -> Workload:
         img = tuple((13,) for _ in range(8))
         desc = DESC_C3.replace(class_token=1, layer_scale=1)
         return Workload("c7_internvit300m_cls_ls_8x13tiles", desc, 1007, 1003, _prefix([13] * 8), img, (0, 51, 103))
+    if name == "c8":
+        # The C2 batch through the MiniCPM-V-shaped encoder: SigLIP trunk with its post norm, then the
+        # resampler (64 learned queries, width 3584, 28 heads of 128) in place of the MLP projector:
+        # 64 tokens per slice.
+        desc = DESC_C2.replace(final_norm=1, proj_kind=PROJ_RESAMPLER, proj_mid=64, proj_out=3584, proj_heads=28)
+        return Workload("c8_siglip_resampler_10tiles", desc, 1008, 1002, (0, 10), ((10,),), (0, 9))
     raise KeyError(name)
 
 
-ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c6", "c7")
+ALL_WORKLOADS = ("c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8")
 
 
 def shard_range(n_tiles: int, shard: int, n_shards: int) -> Tuple[int, int]:
