@@ -326,7 +326,6 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     HIP_TRY(c, bf16_gemm_init());
   }
   const PackMap heads{x.hd, c->hd_pad, x.H};
-  const PackMap hmap = (bf && c->hd_pad != x.hd) ? heads : id;
 
 #define NOMEM_IF(cond) do { if (cond) { set_err(c->err, sizeof(c->err), "device allocation failed (weights)"); return EPD_ERR_NOMEM; } } while (0)
 
@@ -399,7 +398,6 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     c->layers.push_back(lw);
   }
   c->F_k = bf ? (x.L ? f_pad : pad_n(x.F)) : x.F;
-  (void)hmap;
 
   if (d.final_norm) {
     c->fn_g = make_vec(c, w, wi.fn_g, x.D, x.D, id, st);
