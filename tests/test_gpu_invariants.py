@@ -124,3 +124,24 @@ def test_empty_batch_and_error_paths_leave_the_cache_untouched(setup):
     assert lib.epd_encode_range(enc._h, None, 7, 0, 1, out.data_ptr(), st) == B.EPD_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert np.array_equal(bits(out), before)
+
+
+def test_a_slice_alone_has_the_bits_it_has_inside_a_large_batch():
+    """The GEMM picks its tile width by how many tiles the launch has (narrow tiles when half of the
+    chip would idle), the persistent form for long tile sequences: all forms order their sums alike, so
+    a slice encoded alone (4 tiles per product) carries the bits it has inside a 70-slice batch."""
+    desc = desc_for(wl.DT_BF16, hidden=512, heads=8, mlp=1024, layers=2, max_tiles_per_call=72, proj_out=256)
+    w = wl.gen_weights(desc, 37, std=0.05)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 37, 70)).cuda()
+    enc = make_encoder(desc, w)
+    full = enc.encode(tiles, [0, 70])
+    torch.cuda.synchronize()
+    n = enc.tokens_per_tile
+    for t in (0, 5, 69):
+        alone = enc.encode(tiles[t:t + 1], [0, 1])
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(alone), bits(full[t * n:(t + 1) * n])), t
+    few = enc.encode(tiles[3:7], [0, 4])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(few), bits(full[3 * n:7 * n]))
+    enc.close()
