@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
             const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
             f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)row0 * p.ldr + x_voff);
             if (EPI == EPI_BIAS_RESIDUAL) {
-              if constexpr (X_IN_LOOP) *dst = xr[S][i] + v;
+              if constexpr (X_IN_LOOP) __builtin_nontemporal_store(xr[S][i] + v, dst);   // streamed: read next by a row kernel, not by this launch
               else *dst = *dst + v;      // other tile shapes: plain read-modify-write
             } else {   // patch embedding: position row by patch index, output row through the slice layout
               const int row = row0 + x_r0;

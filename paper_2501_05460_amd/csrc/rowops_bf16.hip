@@ -76,7 +76,12 @@ __global__ __launch_bounds__(256) void k_bf16_rowop(const RowOpParams p) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
       const int c = lane + 64 * i;
-      v[i] = (c < nchunk) ? *src(c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < nchunk) {
+        const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src(c)));
+        v[i] = make_float4(t[0], t[1], t[2], t[3]);
+      } else {
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
       s += v[i].x + v[i].y + v[i].z + v[i].w;
     }
   } else {
