@@ -755,7 +755,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
         for (int i = 0; i < PER_T; ++i) {
           const int r0 = (NTHREADS / NCH) * i;                                  // staging row of lane row 0
           const int row0 = m0 + (r0 / G) * 2 * G + pass * G + r0 % G;           // uniform (G % 16 == 0)
-          __builtin_amdgcn_raw_buffer_store_b128(v[i], rsrc_c, voff + (unsigned)row0 * (unsigned)p.ldc * 2u, 0, 0);
+          __builtin_amdgcn_raw_buffer_store_b128(v[i], rsrc_c, voff + (unsigned)row0 * (unsigned)p.ldc * 2u, 0, 2);   // streamed (nt): read by a later launch
         }
       }
     }
