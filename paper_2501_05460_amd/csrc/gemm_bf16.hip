@@ -495,13 +495,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
       if (f < p.N && tok < p.M) {
         const int h = f / p.hd_pad, d = f % p.hd_pad;
         const int t = tok / p.n_tok, n = tok % p.n_tok;
-        *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n));
       }
     } else {
       const int row = m0 + r, col = n0 + c * 8;
       if (row < p.M && col < p.N) {
         const long orow = p.row_map ? (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens : row;
-        *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col));
       }
     }
   }
@@ -733,7 +733,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
           if (f < p.N && tok < p.M) {
             const int h = f / p.hd_pad, d = f % p.hd_pad;
             const int t = tok / p.n_tok, n = tok % p.n_tok;
-            *reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = v[i];
+            __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n));
           }
         }
       } else if (p.row_map) {   // paged output: rows go through the block map
@@ -743,7 +743,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
           const int row = m0 + (r / G) * 2 * G + pass * G + r % G, col = n0 + c * 8;
           if (row < p.M && col < p.N) {
             const long orow = (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens;
-            *reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col) = v[i];
+            __builtin_nontemporal_store(v[i], reinterpret_cast<u32x4*>(p.C + orow * p.ldc + col));
           }
         }
       } else if (n0 + c * 8 < p.N) {
