@@ -149,7 +149,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
 #pragma unroll
         for (int i = 0; i < XPER_T; ++i) {
           const int row0 = m0 + pass * XROWS + XSTEP * i;            // uniform
-          if (row0 + x_r0 < p.M) xr[S][i] = *reinterpret_cast<const f32x4*>(p.R + (long)row0 * p.ldr + x_voff);
+          if (row0 + x_r0 < p.M) xr[S][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.R + (long)row0 * p.ldr + x_voff));
         }
       }
     }
@@ -188,11 +188,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
         return (unsigned)(m0 + pass * XROWS + XSTEP * ci) * (unsigned)p.ldr * 4u;
       };
 #pragma unroll
-      for (int i = 0; i < A_LD; ++i) ra[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(i), 0);
+      for (int i = 0; i < A_LD; ++i) ra[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(i), 2);
       if constexpr (!B_DIRECT) {
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-          rb[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(A_LD + i), 0);
+          rb[S][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, x_voff * 4u, so_x(A_LD + i), 2);
       }
     } else {
 #pragma unroll
