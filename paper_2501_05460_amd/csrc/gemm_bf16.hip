@@ -897,6 +897,23 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
   }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
+  // A width like 3200 leaves the last 256-wide tile column half used.  When that column is also what
+  // spills the launch into a nearly empty last round (at most a quarter of the CUs busy), the residual
+  // product is cut by columns: the whole 256-wide tile columns, and the last 128 columns as a launch of
+  // 128-wide tiles (weight rows, bias and residual columns are pointer offsets).  Same bits.  A 128-wide
+  // tile takes about as long as a 256-wide one, so the cut pays only then: -4 % on the 6B shape's FC2,
+  // +1 % on a SigLIP-shaped batch of 480 slices whose 2560 tiles are ten full rounds anyway.
+  const long tiles_all = (long)((p.M + BM - 1) / BM) * (p.Npad / 256), cus = cu_count();
+  if (p.cfg == 0 && p.epi == EPI_BIAS_RESIDUAL && p.N > 256 && p.N % 256 != 0 && p.N % 256 <= 128 &&
+      tiles_all >= cus && tiles_all % cus != 0 && (tiles_all % cus) * 4 <= cus) {
+    const int n_a = p.N / 256 * 256;
+    GemmParams a = p, b = p;
+    a.N = n_a; a.Npad = n_a;
+    b.N = p.N - n_a; b.Npad = 128;
+    b.W = p.W + (long)n_a * p.K; b.bias = p.bias + n_a; b.R = p.R + n_a;
+    const hipError_t e = bf16_gemm(a, st);
+    return e != hipSuccess ? e : bf16_gemm(b, st);
+  }
   // Small batches: when 256-wide tiles would leave half of the CUs without one, the 128-wide tile
   // doubles the number of workgroups and halves the time of the one round there is.  Same bits.
   // (Measured and not kept for this regime: the pipelined loop on this tile, 8 % slower, and operands
