@@ -7,34 +7,34 @@
 namespace epd {
 
 // ---------------------------------------------------------------- im2col ----
-// One thread per (row, channel, dy): 14 consecutive pixels -> 14 bf16.  The
-// 43rd thread of a row zero-fills the K padding.
+// One thread per 16-byte chunk of the output: 8 consecutive elements of a patch
+// vector (order channel, dy, dx), zeros in the K padding; lda % 8 == 0.
 __global__ __launch_bounds__(256) void k_bf16_im2col(const float* __restrict__ tiles,
                                                      bf16_t* __restrict__ A, int lda, int S, int p,
                                                      int g, long total) {
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
-  const int per_row = 3 * p + 1;
-  const int j = (int)(i % per_row);
+  const int per_row = lda >> 3;
+  const int e0 = (int)(i % per_row) << 3;
   const long row = i / per_row;
-  const int N = g * g;
+  const int N = g * g, pp = p * p, kp = 3 * pp;
   const long t = row / N;
   const int n = (int)(row % N);
   const int y = n / g, x = n % g;
-  bf16_t* dst = A + row * (long)lda;
-  if (j == 3 * p) {
-    for (int e = 3 * p * p; e < lda; ++e) dst[e] = (bf16_t)0.f;
-    return;
+  const float* base = tiles + (t * 3 * S + (long)p * y) * S + p * x;   // channel 0, dy 0, dx 0 of the patch
+  bf16x8 out;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int e = e0 + k;
+    const int c = e / pp, r = e % pp;
+    out[k] = (bf16_t)(e < kp ? base[((long)c * S + r / p) * S + r % p] : 0.f);
   }
-  const int c = j / p, dy = j % p;
-  const float* src = tiles + ((t * 3 + c) * S + (p * y + dy)) * (long)S + p * x;
-  dst += (c * p + dy) * p;
-  for (int dx = 0; dx < p; ++dx) dst[dx] = (bf16_t)src[dx];
+  *reinterpret_cast<bf16x8*>(A + row * (long)lda + e0) = out;
 }
 
 void bf16_im2col(const float* tiles, bf16_t* A, int lda, int T, int S, int p, hipStream_t st) {
   const int g = S / p;
-  const long total = (long)T * g * g * (3 * p + 1);
+  const long total = (long)T * g * g * (lda >> 3);
   if (total == 0) return;
   k_bf16_im2col<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(tiles, A, lda, S, p, g, total);
 }
