@@ -15,20 +15,25 @@ pytestmark = pytest.mark.gpu
 BT = 16   # tokens per block, the paper's setting
 
 
-def desc_for(dtype):
-    return wl.ModelDesc(dtype=dtype, tile_size=224, patch=14, hidden=128, heads=2, mlp=256, layers=1,
-                        norm=wl.NORM_LAYERNORM, qk_norm=wl.QKNORM_NONE, act=wl.ACT_GELU_ERF, final_norm=0,
-                        pixel_shuffle=1, proj_kind=wl.PROJ_MLP, proj_prenorm=1, proj_mid=128, proj_out=96,
-                        eps=1e-6, max_tiles_per_call=2)     # 5 slices -> 3 micro-batches
+def desc_for(dtype, tail="shuffle_mlp"):
+    common = dict(dtype=dtype, tile_size=224, patch=14, hidden=128, heads=2, mlp=256, layers=1,
+                  norm=wl.NORM_LAYERNORM, qk_norm=wl.QKNORM_NONE, act=wl.ACT_GELU_ERF, eps=1e-6,
+                  max_tiles_per_call=2)     # 5 slices -> 3 micro-batches
+    if tail == "resampler_class_token":   # 64 learned queries per slice (4 blocks), class token in the trunk
+        return wl.ModelDesc(final_norm=1, pixel_shuffle=0, proj_kind=wl.PROJ_RESAMPLER, proj_prenorm=0, proj_mid=64,
+                            proj_out=96, proj_heads=2, class_token=1, **common)
+    return wl.ModelDesc(final_norm=0, pixel_shuffle=1, proj_kind=wl.PROJ_MLP, proj_prenorm=1, proj_mid=128,
+                        proj_out=96, **common)
 
 
 def bits(t):
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).cpu().numpy()
 
 
+@pytest.mark.parametrize("tail", ["shuffle_mlp", "resampler_class_token"])
 @pytest.mark.parametrize("dtype", [wl.DT_BF16, wl.DT_FP32], ids=["bf16", "fp32"])
-def test_paged_encode_transfer_and_release(dtype):
-    desc = desc_for(dtype)
+def test_paged_encode_transfer_and_release(dtype, tail):
+    desc = desc_for(dtype, tail)
     w = wl.gen_weights(desc, 41, std=0.06)
     tiles_np = wl.gen_tiles(desc, 41, 5)
     tiles = torch.from_numpy(tiles_np).cuda()
