@@ -409,3 +409,32 @@ def test_resampler_emits_one_token_per_query_for_any_patch_count():
         w = wl.gen_weights(desc, 23, std=0.2)
         out = O.encode([wl.gen_tile(desc, 23, t) for t in range(2)], [0, 2], w, desc)
         assert out.shape == (2 * 6, desc.proj_out) and O.tokens_per_tile(desc) == desc.tokens_per_tile == 6
+
+
+def test_resampler_does_not_care_about_patch_order_when_the_position_rows_move_along():
+    """Cross attention sums over the keys: feeding the patch tokens in another order, with the rows of the
+    key position table permuted the same way, gives the same tokens; permuting only one of the two does not."""
+    desc = small_desc(layers=0, proj_kind=wl.PROJ_RESAMPLER, proj_mid=4, proj_heads=2)
+    w = {k: v.astype(np.float64) for k, v in wl.gen_weights(desc, 29, std=0.4).items()}
+    x = O.trunk_tile(wl.gen_tile(desc, 29, 0), w, desc)
+    base = O.project(x, w, desc)
+    perm = np.random.default_rng(0).permutation(x.shape[0])
+    w2 = dict(w)
+    w2["r_pos"] = w["r_pos"][perm]
+    np.testing.assert_allclose(O.project(x[perm], w2, desc), base, rtol=1e-11, atol=1e-13)
+    assert np.abs(O.project(x[perm], w, desc) - base).max() > 1e-3
+
+
+def test_resampler_with_zero_value_projection_returns_the_bias_path_only():
+    """Zero value in-projection weights: every query's attention output is the value bias b_v whatever the
+    patches hold, so the tokens equal LayerNorm_post(out_w b_v + out_b) proj_w^T for every query and slice."""
+    desc = small_desc(layers=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=3, proj_heads=2)
+    w = {k: v.astype(np.float64) for k, v in wl.gen_weights(desc, 31, std=0.3).items()}
+    E = desc.proj_out
+    w["r_in_w"] = w["r_in_w"].copy()
+    w["r_in_w"][2 * E:] = 0.0
+    got = O.encode_tile(wl.gen_tile(desc, 31, 0), w, desc)
+    o = w["r_out_w"] @ w["r_in_b"][2 * E:] + w["r_out_b"]
+    want = w["r_proj_w"] @ O.layer_norm(o[None], w["r_lnp_g"], w["r_lnp_b"], desc.eps)[0]
+    for q in range(3):
+        np.testing.assert_allclose(got[q], want, rtol=1e-10, atol=1e-12)
