@@ -27,7 +27,10 @@ attention on tiny shapes, closed forms for the norms and softmax, tabulated
 values of the normal CDF for GELU, index arithmetic for patchify and pixel
 shuffle, an affine special case (zero layers), an identity special case (zero
 output projections), a composition of PyTorch CPU library ops for the whole
-tiny encoder, and the independence / permutation / shard invariants.
+tiny encoder (class token placed last there, the library's multi-head
+attention module for the resampler), explicit loops for one resampler query
+and for one patch query next to a class token, and the independence /
+permutation / shard invariants.
 Parity unpinned: fidelity to the *trained* SigLIP / InternViT checkpoints (no
 weights or reference activations exist here; the target does not need them).
 """
