@@ -125,6 +125,19 @@ def test_c8_siglip_shape_with_resampler_10_slices():
     enc.close()
 
 
+def test_siglip_shape_at_378_pixels_729_patches_per_slice():
+    """The C2 encoder at 378-pixel slices: a 27 x 27 patch grid, 729 tokens per slice in rows padded to
+    768 with the last 39 keys masked; more slices than a micro-batch holds."""
+    desc = wl.workload("c2").desc.replace(tile_size=378, max_tiles_per_call=4)
+    wk = wl.Workload("siglip_378", desc, 1012, 1012, (0, 6), ((6,),), (0, 5))
+    enc, tiles = build(wk)
+    out = enc.encode(tiles, [0, 6])
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (6 * 729, 3584)
+    check_sample(wk, enc, out, wk.oracle_sample_tiles)
+    enc.close()
+
+
 def test_c6_video_requests_batched_equals_one_request_per_call_and_oracle():
     """Video workload: 16 requests of 8 to 64 frames, one slice per frame.  Encoding every request in
     its own call (maximum encode batch size 1) gives the bits of the one batched call."""
