@@ -123,3 +123,40 @@ def test_c1_tiny_fp32_vs_oracle():
     e = rel_err(got, want)
     print("c1 rel_err", e)
     assert e < 1e-4
+
+
+def _random_desc(rng, dtype):
+    """A small encoder description drawn within the documented limits (bf16 mode: hidden and head dim
+    % 4, mlp and projector widths % 8, head dim <= 128; resampler: patches % 64)."""
+    heads = int(rng.choice([1, 2, 3, 4]))
+    hd = int(rng.choice([16, 32, 36, 64, 72, 80, 128]))
+    proj_kind = int(rng.choice([wl.PROJ_LINEAR, wl.PROJ_MLP, wl.PROJ_RESAMPLER]))
+    if proj_kind == wl.PROJ_RESAMPLER:
+        tile = int(rng.choice([112, 224]))                 # 64 or 256 patches
+        shuffle, prenorm = 0, 0
+    else:
+        tile = int(rng.choice([70, 84, 98, 112, 140]))     # grids of 5 .. 10: any token count
+        shuffle = int(rng.integers(0, 2)) if (tile // 14) % 2 == 0 else 0
+        prenorm = int(rng.integers(0, 2))
+    r_heads = int(rng.choice([1, 2, 4]))
+    return wl.ModelDesc(
+        dtype=dtype, tile_size=tile, patch=14, hidden=heads * hd, heads=heads, mlp=8 * int(rng.integers(8, 60)),
+        layers=int(rng.integers(1, 4)), norm=int(rng.integers(0, 2)), qk_norm=int(rng.integers(0, 3)),
+        act=int(rng.integers(0, 2)), final_norm=int(rng.integers(0, 2)), pixel_shuffle=shuffle, proj_kind=proj_kind,
+        proj_prenorm=prenorm, proj_mid=8 * int(rng.integers(1, 20)), proj_out=r_heads * 8 * int(rng.integers(2, 12)),
+        eps=1e-6, max_tiles_per_call=int(rng.integers(1, 4)), layer_scale=int(rng.integers(0, 2)),
+        class_token=int(rng.integers(0, 2)), proj_heads=r_heads)
+
+
+@pytest.mark.parametrize("dtype", [wl.DT_FP32, wl.DT_BF16])
+@pytest.mark.parametrize("case", range(14))
+def test_seeded_random_descriptions_vs_oracle(case, dtype):
+    rng = np.random.default_rng([77, case])
+    desc = _random_desc(rng, dtype)
+    n_tiles = int(rng.integers(1, 6))
+    cut = int(rng.integers(0, n_tiles + 1))
+    got, want = run_case(desc, 100 + case, n_tiles, [0, cut, n_tiles], std=0.06)
+    e = rel_err(got, want)
+    print(f"case {case} dtype={dtype} {desc} tiles={n_tiles} rel_err={e:.3e}")
+    assert got.shape == want.shape
+    assert e < tol(desc)
