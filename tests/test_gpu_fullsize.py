@@ -1,4 +1,4 @@
-"""Parity at the full sizes of the five configurations, in the launch
+"""Parity at the full sizes of the named configurations, in the launch
 configuration bench.py times: the whole batch runs on the GPU, the oracle
 encodes a fixed sample of slices at full depth, and the sampled row blocks
 are compared element by element."""
