@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       }
   };
 
-  const int NB = n_tok / BKEY;
+  const int NB = (n_tok + BKEY - 1) / BKEY;   // a last block may reach past the slice: those keys are masked
   gload(0);
   // head-dim positions that exist only in LDS stay zero for the whole kernel:
   // columns HD .. HDK-1 of every key row, rows HD .. HDV-1 of V^T, both buffers
@@ -307,7 +307,7 @@ template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                        int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
                        hipStream_t st) {
-  return n_keys < n_tok
+  return (n_keys < n_tok || n_tok % BKEY != 0)
              ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st)
              : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
 }
@@ -318,7 +318,9 @@ hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf
                           int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
                           long ld_o, float scale, hipStream_t st) {
   if (n_slices == 0) return hipSuccess;
-  if (n_tok % BKEY != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok || n_q < 1) return hipErrorInvalidValue;
+  // n_tok % 8: V^T rows are read in 16-byte chunks.  A slice whose rows are no multiple of the key block is
+  // read up to 63 rows (q, k) / 63 elements (v^T) past its end: the caller's buffers must reach that far.
+  if (n_tok % 8 != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok || n_q < 1) return hipErrorInvalidValue;
   if (!q_shared && n_q != n_tok) return hipErrorInvalidValue;   // a slice's own rows: one query per row
   switch (hd_pad) {
     case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);

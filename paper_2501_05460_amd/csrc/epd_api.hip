@@ -48,8 +48,8 @@ struct WeightIndex {
 };
 
 // N = patches per slice; Nt = tokens per slice inside the encoder (patches + class token); Ns = rows a
-// slice owns in the activation buffers (bf16 mode: Nt rounded up to the attention kernel's 64-key block,
-// the extra rows are masked as keys and never read as tokens; fp32 mode: Nt).
+// slice owns in the activation buffers (bf16 mode: Nt rounded up to 8, the unit of the transposed value
+// store; the extra rows are masked as keys and never read as tokens; fp32 mode: Nt).
 struct Dims {
   int S, p, g, N, Kp, D, H, hd, F, L, N_out, Pin, Pmid, Pout, cls, Nt, Ns;
   SliceRows xrows() const { return (Ns == N) ? SliceRows{0, 0, 0} : SliceRows{N, Ns, cls}; }
@@ -65,7 +65,7 @@ Dims dims_of(const epd_model_desc& d) {
   x.Pmid = d.proj_mid; x.Pout = d.proj_out;
   x.cls = d.class_token ? 1 : 0;
   x.Nt = x.N + x.cls;
-  x.Ns = d.dtype == EPD_DTYPE_BF16 ? round_up(x.Nt, 64) : x.Nt;
+  x.Ns = d.dtype == EPD_DTYPE_BF16 ? round_up(x.Nt, 8) : x.Nt;
   return x;
 }
 
@@ -482,8 +482,9 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   c->d_rowmap = (int*)ws((size_t)M * sizeof(int));
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
-    c->QKV = ws((size_t)c->Mp * 2 * c->Dq * 2);
-    c->VT = ws((size_t)c->mb * x.H * c->hd_pad * x.Ns * 2);
+    // the attention kernel reads whole 64-key blocks: up to 63 rows / elements past the last slice
+    c->QKV = ws((size_t)(c->Mp + 64) * 2 * c->Dq * 2);
+    c->VT = ws(((size_t)c->mb * x.H * c->hd_pad * x.Ns + 64) * 2);
     c->O = ws((size_t)c->Mp * c->Dq_k * 2);
     c->Hd = ws((size_t)c->Mp * c->F_k * 2);
     c->Ape = ws((size_t)c->Mp * c->Kp_k * 2);
@@ -1074,6 +1075,7 @@ epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, v
                                  int32_t n_tokens, int32_t n_keys, int32_t heads, int32_t hd_pad, int32_t ld_qk,
                                  float scale, void* hip_stream) {
   if (!q || !k || !vt || !o) return EPD_ERR_INVALID_ARG;
+  if (n_tokens % 64) { set_err(g_err, sizeof(g_err), "epd_op_attention_bf16: n_tokens %% 64 != 0"); return EPD_ERR_UNSUPPORTED; }
   hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, (bf16_t*)o, n_slices,
                                 n_tokens, n_keys, n_tokens, 0, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
   if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }

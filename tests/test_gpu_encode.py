@@ -32,7 +32,7 @@ VARIANTS = {
     "hd32": dict(hidden=96, heads=3),
     "layer_scale": dict(layer_scale=1, pixel_shuffle=1, proj_prenorm=1, proj_kind=wl.PROJ_MLP, proj_mid=136),
     "layer_scale_hd72": dict(layer_scale=1, hidden=144, heads=2, act=wl.ACT_GELU_TANH),
-    # class token: 65 tokens per slice (bf16 mode pads a slice's rows to 128 and masks the extra keys)
+    # class token: 65 tokens per slice (bf16 mode pads a slice's rows to 72 and masks the keys past 65)
     "class_token": dict(class_token=1, final_norm=1),
     "class_token_shuffle_scale_hd72": dict(class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
                                            proj_kind=wl.PROJ_MLP, proj_mid=136, hidden=144, heads=2),
@@ -91,7 +91,7 @@ def test_sharp_attention_with_class_token_vs_oracle(dtype):
 
 
 def test_class_token_at_a_257_token_sequence_vs_oracle():
-    """224-pixel slices with a class token: 257 tokens per slice, padded to 320 rows; more slices than
+    """224-pixel slices with a class token: 257 tokens per slice in 264 rows; more slices than
     one micro-batch holds."""
     desc = small_desc(wl.DT_BF16, tile_size=224, class_token=1, layer_scale=1, pixel_shuffle=1, proj_prenorm=1,
                       proj_kind=wl.PROJ_MLP, proj_mid=136, max_tiles_per_call=3)

@@ -100,8 +100,8 @@ def test_c4_internvit6b_shape_40_slices():
 
 
 def test_c7_internvit300m_shape_with_class_token_and_layer_scale():
-    """1025 tokens per slice in rows padded to 1088: every GEMM has a ragged last tile, the last key
-    block of every slice is masked from its second key on."""
+    """1025 tokens per slice in rows padded to 1032: every GEMM has a ragged last tile, the last key
+    block of every slice reaches into the next slice and is masked from its second key on."""
     wk = wl.workload("c7")
     enc, tiles = build(wk)
     out = enc.encode(tiles, list(wk.tile_offsets))
@@ -127,7 +127,7 @@ def test_c8_siglip_shape_with_resampler_10_slices():
 
 def test_siglip_shape_at_378_pixels_729_patches_per_slice():
     """The C2 encoder at 378-pixel slices: a 27 x 27 patch grid, 729 tokens per slice in rows padded to
-    768 with the last 39 keys masked; more slices than a micro-batch holds."""
+    736, the last key block masked from key 729 on; more slices than a micro-batch holds."""
     desc = wl.workload("c2").desc.replace(tile_size=378, max_tiles_per_call=4)
     wk = wl.Workload("siglip_378", desc, 1012, 1012, (0, 6), ((6,),), (0, 5))
     enc, tiles = build(wk)
