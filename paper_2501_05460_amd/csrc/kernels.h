@@ -7,7 +7,7 @@ namespace epd {
 
 // Where the patch tokens of a slice sit in the residual stream: slice t owns `stride` rows and its
 // patch token i is row t * stride + off + i (off = 1 behind a class token; stride > off + n when a
-// slice's rows are padded to the attention kernel's key block).  n == 0: the rows are contiguous.
+// slice's rows are padded to a multiple of 8).  n == 0: the rows are contiguous.
 struct SliceRows {
   int n, stride, off;
   __host__ __device__ long row(long r) const { return n ? (r / n) * stride + off + r % n : r; }
@@ -83,9 +83,11 @@ void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, i
                  float eps, hipStream_t st);
 
 // Tile-local flash attention (attention_bf16.hip).
-// Slice t owns rows t * n_tok .. of q, k, o and columns 0 .. n_tok of its V^T rows (n_tok % 64 == 0);
+// Slice t owns rows t * n_tok .. of q, k, o and columns 0 .. n_tok of its V^T rows (n_tok % 8 == 0);
 // only its first n_keys rows are real tokens: later keys are masked out, later queries give unused rows.
-// n_q queries per slice (multiple of 64 unless q_shared); q_shared: the query rows are rows 0 .. n_q-1 of q
+// Keys are read in blocks of 64: when n_tok % 64 != 0 the last block reaches up to 63 rows of q / k and
+// 63 elements of v^T past the slice (the next slice's, or slack the caller keeps behind the buffers).
+// n_q queries per slice (n_tok unless q_shared); q_shared: the query rows are rows 0 .. n_q-1 of q
 // for every slice (learned queries of the resampler; q must be readable for round_up(n_q, 32) rows) instead
 // of the slice's own rows.  Row t * n_q + i of o is query i of slice t.
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
