@@ -670,12 +670,10 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       HIP_TRY(c, bf16_gemm(pv, st)); }
     if (d.qk_norm == EPD_QKNORM_FULL) {
       ProfScope ps(c, 4, st);
-      bf16_qknorm(QK, ld_qk, w.qn_g, M, c->Dq, 1, x.D, d.eps, st);
-      bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, M, c->Dq, 1, x.D, d.eps, st);
+      bf16_qknorm(QK, ld_qk, c->Dq, w.qn_g, w.kn_g, M, c->Dq, 1, x.D, d.eps, st);
     } else if (d.qk_norm == EPD_QKNORM_PER_HEAD) {
       ProfScope ps(c, 4, st);
-      bf16_qknorm(QK, ld_qk, w.qn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
-      bf16_qknorm(QK + c->Dq, ld_qk, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
+      bf16_qknorm(QK, ld_qk, c->Dq, w.qn_g, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
     }
     { ProfScope ps(c, 3, st);
       HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }

@@ -76,13 +76,12 @@ struct RowOpParams {
 };
 void bf16_rowop(const RowOpParams& p, hipStream_t st);
 
-// In-place RMSNorm of bf16 rows (q or k inside the QK buffer).  Logical row R
-// of `dim` (padded) elements at buf + (R / groups) * ld + (R % groups) * dim;
+// In-place RMSNorm of the q rows and the k rows of the QK buffer in one launch (k = q + k_off elements,
+// its own gain).  Logical row R of `dim` (padded) elements at buf + (R / groups) * ld + (R % groups) * dim;
 // `count` = number of real elements the mean runs over.
-void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, int groups, int count,
-                 float eps, hipStream_t st);
+void bf16_qknorm(bf16_t* buf, long ld, long k_off, const float* gamma_q, const float* gamma_k, long rows, int dim,
+                 int groups, int count, float eps, hipStream_t st);
 
-// Tile-local flash attention (attention_bf16.hip).
 // Slice t owns rows t * n_tok .. of q, k, o and columns 0 .. n_tok of its V^T rows (n_tok % 8 == 0);
 // only its first n_keys rows are real tokens: later keys are masked out, later queries give unused rows.
 // Keys are read in blocks of 64: when n_tok % 64 != 0 the last block reaches up to 63 rows of q / k and

@@ -153,38 +153,70 @@ void bf16_rowop(const RowOpParams& p, hipStream_t st) {
 }
 
 // --------------------------------------------------------- q/k RMSNorm ------
-__global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld,
-                                                     const float* __restrict__ gamma, long rows,
+// One wave per logical row, q rows first, then k rows (k = q + k_off elements, its own gain).  The
+// row waits in registers between the sum of squares and the scaling when it fits (NV 8-byte chunks per
+// lane), otherwise it is read twice.
+template <int NV>
+__global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld, long k_off,
+                                                     const float* __restrict__ gamma_q,
+                                                     const float* __restrict__ gamma_k, long rows,
                                                      int dim, int groups, int count, float eps) {
-  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (R >= rows) return;
+  long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= 2 * rows) return;
+  const bool is_k = R >= rows;
+  if (is_k) R -= rows;
+  const float* gamma = is_k ? gamma_k : gamma_q;
   const int lane = threadIdx.x & 63;
-  bf16_t* x = buf + (R / groups) * ld + (R % groups) * (long)dim;
+  bf16x4* x = reinterpret_cast<bf16x4*>(buf + (is_k ? k_off : 0) + (R / groups) * ld + (R % groups) * (long)dim);
   const int nchunk = dim >> 2;
+  bf16x4 v[NV > 0 ? NV : 1];
   float qs = 0.f;
-  for (int c = lane; c < nchunk; c += 64) {
-    const bf16x4 a = *(reinterpret_cast<const bf16x4*>(x) + c);
+  if (NV > 0) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) qs += (float)a[e] * (float)a[e];
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        v[i] = x[c];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) qs += (float)v[i][e] * (float)v[i][e];
+      }
+    }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) {
+      const bf16x4 a = x[c];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) qs += (float)a[e] * (float)a[e];
+    }
   }
   const float rstd = 1.0f / sqrtf(wave_sum(qs) / count + eps);
-  for (int c = lane; c < nchunk; c += 64) {
-    const bf16x4 a = *(reinterpret_cast<const bf16x4*>(x) + c);
+  auto emit = [&](int c, bf16x4 a) {
     const float4 gm = *(reinterpret_cast<const float4*>(gamma) + c);
     bf16x4 o;
     o[0] = (bf16_t)((float)a[0] * rstd * gm.x);
     o[1] = (bf16_t)((float)a[1] * rstd * gm.y);
     o[2] = (bf16_t)((float)a[2] * rstd * gm.z);
     o[3] = (bf16_t)((float)a[3] * rstd * gm.w);
-    *(reinterpret_cast<bf16x4*>(x) + c) = o;
+    x[c] = o;
+  };
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) emit(c, v[i]);
+    }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) emit(c, x[c]);
   }
 }
 
-void bf16_qknorm(bf16_t* buf, long ld, const float* gamma, long rows, int dim, int groups, int count,
-                 float eps, hipStream_t st) {
+void bf16_qknorm(bf16_t* buf, long ld, long k_off, const float* gamma_q, const float* gamma_k, long rows, int dim,
+                 int groups, int count, float eps, hipStream_t st) {
   if (rows == 0) return;
-  k_bf16_qknorm<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(buf, ld, gamma, rows, dim, groups,
-                                                                       count, eps);
+  const dim3 grid((unsigned)((2 * rows + 3) / 4)), block(256);
+  const int per_lane = (dim / 4 + 63) / 64;
+  if (per_lane <= 2) k_bf16_qknorm<2><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  else if (per_lane <= 16) k_bf16_qknorm<16><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  else k_bf16_qknorm<0><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
 }
 
 // ---------------------------------------------- LayerNorm of bf16 rows ------
