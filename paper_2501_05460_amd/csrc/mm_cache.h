@@ -7,8 +7,10 @@ struct epd_mm_cache {
   int n_blocks = 0, block_tokens = 0, token_dim = 0, dtype = 0;
   long block_bytes = 0;
   void* pool = nullptr;        // device: [n_blocks][block_tokens][token_dim]
-  int* d_ids_a = nullptr;      // device scratch for block id lists (n_blocks each)
-  int* d_ids_b = nullptr;
+  int* d_ids = nullptr;        // device scratch for block id lists (2 * n_blocks ints)
+  int* h_ids = nullptr;        // pinned host staging of the same size: one asynchronous upload per call
+  hipEvent_t ev_ids = nullptr; // recorded behind the upload; the staging is rewritten only after it
+  bool ev_pending = false;
   std::vector<int> free_list;  // LIFO of free block ids
   std::vector<unsigned char> used;
   char err[256] = "";

@@ -51,8 +51,9 @@ epd_status epd_mm_cache_create(int32_t n_blocks, int32_t block_tokens, int32_t t
   for (int i = n_blocks - 1; i >= 0; --i) c->free_list.push_back(i);  // block 0 is handed out first
   if (block_bytes > 0) {  // token_dim 0: manager only (planning, host tests), no device memory
     if (hipMalloc(&c->pool, (size_t)n_blocks * block_bytes) != hipSuccess ||
-        hipMalloc((void**)&c->d_ids_a, (size_t)n_blocks * sizeof(int)) != hipSuccess ||
-        hipMalloc((void**)&c->d_ids_b, (size_t)n_blocks * sizeof(int)) != hipSuccess) {
+        hipMalloc((void**)&c->d_ids, (size_t)2 * n_blocks * sizeof(int)) != hipSuccess ||
+        hipHostMalloc((void**)&c->h_ids, (size_t)2 * n_blocks * sizeof(int), hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_ids, hipEventDisableTiming) != hipSuccess) {
       mm_err(nullptr, "epd_mm_cache_create: device allocation failed");
       epd_mm_cache_destroy(c);
       return EPD_ERR_NOMEM;
@@ -65,8 +66,9 @@ epd_status epd_mm_cache_create(int32_t n_blocks, int32_t block_tokens, int32_t t
 void epd_mm_cache_destroy(epd_mm_cache* c) {
   if (!c) return;
   if (c->pool) (void)hipFree(c->pool);
-  if (c->d_ids_a) (void)hipFree(c->d_ids_a);
-  if (c->d_ids_b) (void)hipFree(c->d_ids_b);
+  if (c->d_ids) (void)hipFree(c->d_ids);
+  if (c->h_ids) (void)hipHostFree(c->h_ids);
+  if (c->ev_ids) (void)hipEventDestroy(c->ev_ids);
   delete c;
 }
 
@@ -101,6 +103,23 @@ epd_status epd_mm_free(epd_mm_cache* c, const int32_t* block_ids, int32_t n_ids)
   return EPD_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// `n_lists` id lists of n ints each -> c->d_ids, back to back, through the pinned staging (waits for the
+// previous upload of this cache before the staging is overwritten)
+bool upload_ids(epd_mm_cache* c, const int32_t* const* lists, int n_lists, int n, hipStream_t st) {
+  if (c->ev_pending && hipEventSynchronize(c->ev_ids) != hipSuccess) return false;
+  for (int l = 0; l < n_lists; ++l) memcpy(c->h_ids + (size_t)l * n, lists[l], (size_t)n * sizeof(int));
+  if (hipMemcpyAsync(c->d_ids, c->h_ids, (size_t)n_lists * n * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) return false;
+  if (hipEventRecord(c->ev_ids, st) != hipSuccess) return false;
+  c->ev_pending = true;
+  return true;
+}
+}  // namespace
+
+extern "C" {
+
 epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
                            const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream) {
   if (!src || !dst || n_blocks < 0 || (n_blocks > 0 && (!src_blocks || !dst_blocks))) return EPD_ERR_INVALID_ARG;
@@ -116,13 +135,14 @@ epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, e
   }
   if (n_blocks == 0) return EPD_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  // id lists travel in the destination cache's scratch (one transfer at a time per destination)
-  if (hipMemcpyAsync(dst->d_ids_a, src_blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipMemcpyAsync(dst->d_ids_b, dst_blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) {
+  // id lists travel in the destination cache's scratch (one transfer at a time per destination):
+  // source ids, then destination ids, one upload
+  const int32_t* lists[2] = {src_blocks, dst_blocks};
+  if (!upload_ids(dst, lists, 2, n_blocks, st)) {
     mm_err(dst, "epd_mm_transfer: id upload failed");
     return EPD_ERR_HIP;
   }
-  mm_copy_blocks(src->pool, dst->d_ids_a, dst->pool, dst->d_ids_b, n_blocks, src->block_bytes, st);
+  mm_copy_blocks(src->pool, dst->d_ids, dst->pool, dst->d_ids + n_blocks, n_blocks, src->block_bytes, st);
   return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
 
@@ -137,8 +157,9 @@ epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blo
   }
   if (n_blocks == 0) return EPD_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (hipMemcpyAsync(src->d_ids_a, blocks, (size_t)n_blocks * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) return EPD_ERR_HIP;
-  mm_copy_blocks(src->pool, src->d_ids_a, dst_contiguous, nullptr, n_blocks, src->block_bytes, st);
+  const int32_t* lists[1] = {blocks};
+  if (!upload_ids(src, lists, 1, n_blocks, st)) return EPD_ERR_HIP;
+  mm_copy_blocks(src->pool, src->d_ids, dst_contiguous, nullptr, n_blocks, src->block_bytes, st);
   return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
 
