@@ -18,6 +18,18 @@
 // matching left operand is one 16-byte LDS read.  A K / V^T fragment read
 // from LDS feeds all QT sub-tiles of the wave.
 // Values arrive pre-transposed ([slice, head, hd, token]) from the value GEMM.
+//
+// The softmax shift rides on the matrix core: q is scaled by log2(e)/sqrt(hd)
+// when its fragments are loaded, and every S^T product carries one more
+// k-step whose left operand is all ones and whose right operand holds minus
+// the query's reference value m at k = 0, so the MFMA result is already
+// s - m and the exponential takes it as it comes.  m is a bf16-exact value
+// (it has to pass through a bf16 operand) near the running maximum; it is
+// moved (accumulators rescaled) only when a logit exceeds it by more than
+// 2^RESCALE_LOG2, which bounds the weights by that factor instead of by 1:
+// harmless for bf16 weights and fp32 sums.  Where the V^T tile has spare rows
+// past the head dim (hd = 72 in 96 rows) one of them holds ones, and the
+// row sum of the weights comes out of the second product as well.
 #include "kernels.h"
 
 namespace epd {
@@ -25,6 +37,18 @@ namespace epd {
 namespace {
 
 constexpr int BKEY = 64;  // keys per LDS block
+constexpr float RESCALE_LOG2 = 8.0f;   // a logit may exceed the reference by this much (log2 domain)
+
+// max of a value and the one held by lane ^ 32: the swap leaves the low half's values in both
+// halves of one result and the high half's in both halves of the other
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const unsigned b = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// nearest bf16-exact value
+__device__ __forceinline__ float bf16_exact(float x) { return (float)(bf16_t)x; }
 
 // HD = head dim as stored in q, k, v^T (a multiple of 8).  The products run
 // over HD rounded up to the MFMA shapes (16 for q.k, 32 rows of O^T); the
@@ -97,7 +121,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s * 16 + 8 < HD || lh == 0) {
-        qf[u][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[u][s][e] = (bf16_t)((float)raw[e] * scale_log2e);   // logits come out in the log2 domain
       } else {   // head-dim positions past HD (last k-step of a head dim that is not a multiple of 16)
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[u][s][e] = (bf16_t)0.f;
@@ -105,22 +131,29 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     }
   }
 
+  // A thread's chunks keep their place inside every key block: 32-bit byte offsets once, the
+  // block's base stays in scalar registers.
   u32x4 rk[K_LOADS], rv[V_LOADS];
+  unsigned koff[K_LOADS], voff[V_LOADS];
+#pragma unroll
+  for (int i = 0; i < K_LOADS; ++i) {
+    int c = tid + 256 * i;
+    if (!K_EXACT) c = c < K_TOTAL ? c : 0;   // spare threads of the last round re-read chunk 0, never stored
+    koff[i] = (unsigned)(((long)(c / KCH) * ld_qk + (c % KCH) * 8) * 2);
+  }
+#pragma unroll
+  for (int i = 0; i < V_LOADS; ++i) {
+    int c = tid + 256 * i;
+    if (!V_EXACT) c = c < V_TOTAL ? c : 0;
+    voff[i] = (unsigned)(((long)(c / (BKEY / 8)) * n_tok + (c % (BKEY / 8)) * 8) * 2);
+  }
   auto gload = [&](int kb) {
+    const char* kblk = reinterpret_cast<const char*>(kbase + (long)kb * BKEY * ld_qk);
+    const char* vblk = reinterpret_cast<const char*>(vbase + (long)kb * BKEY);
 #pragma unroll
-    for (int i = 0; i < K_LOADS; ++i) {
-      int c = tid + 256 * i;
-      if (!K_EXACT) c = c < K_TOTAL ? c : 0;   // spare threads of the last round re-read chunk 0, never stored
-      const int row = c / KCH, ch = c % KCH;
-      rk[i] = *reinterpret_cast<const u32x4*>(kbase + (long)(kb * BKEY + row) * ld_qk + ch * 8);
-    }
+    for (int i = 0; i < K_LOADS; ++i) rk[i] = *reinterpret_cast<const u32x4*>(kblk + koff[i]);
 #pragma unroll
-    for (int i = 0; i < V_LOADS; ++i) {
-      int c = tid + 256 * i;
-      if (!V_EXACT) c = c < V_TOTAL ? c : 0;
-      const int row = c / (BKEY / 8), ch = c % (BKEY / 8);
-      rv[i] = *reinterpret_cast<const u32x4*>(vbase + (long)row * n_tok + kb * BKEY + ch * 8);
-    }
+    for (int i = 0; i < V_LOADS; ++i) rv[i] = *reinterpret_cast<const u32x4*>(vblk + voff[i]);
   };
   auto sstore = [&](int buf) {
 #pragma unroll
@@ -145,25 +178,37 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     }
   };
 
+  constexpr bool SUM_MFMA = SM::HDV > HD;   // a spare V^T row of ones makes the second product sum the weights
+  constexpr int SUM_B = HD / 32, SUM_I = 4 * ((HD % 32) / 8);   // O^T row HD: block, register (lanes 0..31; HD % 8 == 0)
   f32x16 oacc[QT][MB];
-  float m_run[QT], l_run[QT];  // running max (log2 domain) and this lane's share of the running sum
+  // m_ref: the reference subtracted from this query's logits (log2 domain, bf16-exact);
+  // l_run: this lane's share of the running sum of weights (unused with SUM_MFMA);
+  // qx: right operand of the extra k-step, -m_ref at k = 0
+  float m_ref[QT], l_run[QT];
+  bf16x8 qx[QT], kones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) kones[e] = (bf16_t)1.0f;
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
-    m_run[u] = -INFINITY;
+    m_ref[u] = 0.f;
     l_run[u] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qx[u][e] = (bf16_t)0.f;
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[u][b][e] = 0.f;
   }
 
-  // S^T of one 32-key step for all sub-tiles (MFMAs only: they run while the
+  // S^T - m of one 32-key step for all sub-tiles (MFMAs only: they run while the
   // wave goes on with the softmax arithmetic of the previous step)
   auto issue_s = [&](f32x16 (&s)[QT], const bf16_t* ks, int kt) {
 #pragma unroll
-    for (int u = 0; u < QT; ++u)
+    for (int u = 0; u < QT; ++u) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[u][e] = 0.f;
+      s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kones, qx[u], s[u], 0, 0, 0);
+    }
 #pragma unroll
     for (int st = 0; st < KS; ++st) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * SM::K_LD + st * 16 + lh * 8);
@@ -171,13 +216,22 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       for (int u = 0; u < QT; ++u) s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][st], s[u], 0, 0, 0);
     }
   };
-  // online softmax of one step, one query per lane (shared with lane ^ 32)
-  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0) {
+  // Online softmax of one step, one query per lane (shared with lane ^ 32).  `stale`: the
+  // products of this step were issued before the reference last moved, by `moved` (per lane).
+  // `force`: the first step of a slice takes its own maximum as the reference, whatever its
+  // size.  On return `moved` is what this step added to the reference (0 for most steps).
+  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0, bool stale, bool force, float (&moved)[QT]) -> bool {
+    bool any_moved = false;
 #pragma unroll
     for (int u = 0; u < QT; ++u) {
+      if (stale) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[u][e] -= moved[u];
+      }
+      moved[u] = 0.f;
       if (MASK && key0 + 32 > n_keys) {   // uniform; only the last steps of a slice whose rows are padded
         // rows past n_keys are no tokens: logit -inf, weight 0 (the first step always holds a real key,
-        // so the running maximum is finite by the time a step is masked entirely)
+        // so the reference is finite by the time a step is masked entirely)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
@@ -185,27 +239,41 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       float mx = fmaxf(s[u][0], s[u][1]);
 #pragma unroll
       for (int e = 2; e < 16; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);  // three-input max
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[u], mx * scale_log2e);
-      // the running maximum rarely moves after the first blocks: rescale only then
-      if (__builtin_amdgcn_ballot_w64(m_new > m_run[u]) != 0) {
-        const float alpha = __builtin_amdgcn_exp2f(m_run[u] - m_new);
+      mx = max_with_other_half(mx);
+      // the reference rarely moves after the first blocks: rescale only then
+      if (force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
+        const bool mine = force || mx > RESCALE_LOG2;
+        const float m_new = mine ? bf16_exact(m_ref[u] + mx) : m_ref[u];
+        const float d = m_new - m_ref[u];
+        const float alpha = __builtin_amdgcn_exp2f(-d);
         l_run[u] *= alpha;
 #pragma unroll
         for (int b = 0; b < MB; ++b)
 #pragma unroll
           for (int e = 0; e < 16; ++e) oacc[u][b][e] *= alpha;
-        m_run[u] = m_new;
-      }
-      float psum = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(s[u][e], scale_log2e, -m_run[u]));
-        psum += pe;
-        pf[u][e >> 3][e & 7] = (bf16_t)pe;
+        for (int e = 0; e < 16; ++e) s[u][e] -= d;
+        m_ref[u] = m_new;
+        qx[u][0] = lh == 0 ? (bf16_t)(-m_new) : (bf16_t)0.f;
+        moved[u] = d;
+        any_moved = true;
       }
-      l_run[u] += psum;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) pf[u][e >> 3][e & 7] = (bf16_t)__builtin_amdgcn_exp2f(s[u][e]);
+      if (!SUM_MFMA) {   // sum of the rounded weights, the values the second product uses: two per instruction
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+        float psum = l_run[u];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 0, 1), ones, psum, false);
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 2, 3), ones, psum, false);
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 4, 5), ones, psum, false);
+          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 6, 7), ones, psum, false);
+        }
+        l_run[u] = psum;
+      }
     }
+    return any_moved;
   };
   // O^T += V^T P^T for one step
   auto issue_pv = [&](bf16x8 (&pf)[QT][2], const bf16_t* vs, int kt) {
@@ -235,7 +303,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   if constexpr (SM::HDV > HD) {
     constexpr int PAD_ELEMS = (SM::HDV - HD) * SM::V_LD;
     for (int e = tid; e < 2 * PAD_ELEMS; e += 256)
-      sV[(e / PAD_ELEMS) * SM::V_ELEMS + HD * SM::V_LD + e % PAD_ELEMS] = (bf16_t)0.f;
+      sV[(e / PAD_ELEMS) * SM::V_ELEMS + HD * SM::V_LD + e % PAD_ELEMS] =
+          (bf16_t)(e % PAD_ELEMS < SM::V_LD ? 1.0f : 0.f);   // row HD: ones (sums the weights), the rest zero
   }
   sstore(0);
   __syncthreads();
@@ -251,10 +320,13 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
     const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
     if (any_act) {
-      issue_s(s1, ks, 1);
-      softmax(s0, p0, kb * BKEY);
+      float moved[QT];
+#pragma unroll
+      for (int u = 0; u < QT; ++u) moved[u] = 0.f;
+      issue_s(s1, ks, 1);   // carries the reference as it is before the softmax of s0
+      const bool stale = softmax(s0, p0, kb * BKEY, false, kb == 0, moved);
       issue_pv(p0, vs, 0);
-      softmax(s1, p1, kb * BKEY + 32);
+      softmax(s1, p1, kb * BKEY + 32, stale, false, moved);
       issue_pv(p1, vs, 1);
     }
     sstore((kb + 1) & 1);   // the other buffer: nobody reads it after the previous barrier
@@ -265,7 +337,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     if (!act[u] || q0 + u * 32 + l32 >= n_q) continue;   // a shared query set need not fill its last 32 rows
-    const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+    // SUM_MFMA: row HD of O^T holds the sum, in lanes 0..31 (query = lane)
+    const float l_tot = SUM_MFMA ? __shfl(oacc[u][SUM_B < MB ? SUM_B : 0][SUM_I], l32, 64)
+                                 : l_run[u] + __shfl_xor(l_run[u], 32, 64);
     const float inv = 1.0f / l_tot;
     bf16_t* op = o + ((long)t * n_q + q0 + u * 32 + l32) * ld_o + (long)h * HD;
 #pragma unroll
