@@ -39,12 +39,12 @@ namespace {
 constexpr int BKEY = 64;  // keys per LDS block
 constexpr float RESCALE_LOG2 = 8.0f;   // a logit may exceed the reference by this much (log2 domain)
 
-// max of a value and the one held by lane ^ 32: the swap leaves the low half's values in both
+// max of two values and the two held by lane ^ 32: the swap leaves the low half's values in both
 // halves of one result and the high half's in both halves of the other
-__device__ __forceinline__ float max_with_other_half(float x) {
-  const unsigned b = __float_as_uint(x);
+__device__ __forceinline__ float max_with_other_half(float x, float y) {
+  const unsigned b = __float_as_uint(fmaxf(fmaxf(x, y), y));
   const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return fmaxf(fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])), __uint_as_float(b));
 }
 
 // nearest bf16-exact value
@@ -188,6 +188,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   bf16x8 qx[QT], kones;
 #pragma unroll
   for (int e = 0; e < 8; ++e) kones[e] = (bf16_t)1.0f;
+  asm volatile("" : "+v"(kones));   // stays in its four registers instead of being rebuilt in front of every product
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     m_ref[u] = 0.f;
@@ -236,10 +237,11 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         for (int e = 0; e < 16; ++e)
           if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
       }
-      float mx = fmaxf(s[u][0], s[u][1]);
+      // three-input maxima throughout (the two-input form would first quieten each MFMA result)
+      float mx = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
 #pragma unroll
-      for (int e = 2; e < 16; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);  // three-input max
-      mx = max_with_other_half(mx);
+      for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);
+      mx = max_with_other_half(mx, s[u][15]);
       // the reference rarely moves after the first blocks: rescale only then
       if (force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
         const bool mine = force || mx > RESCALE_LOG2;
