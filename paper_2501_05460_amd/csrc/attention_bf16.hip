@@ -247,7 +247,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         const bool mine = force || mx > RESCALE_LOG2;
         const float m_new = mine ? bf16_exact(m_ref[u] + mx) : m_ref[u];
         const float d = m_new - m_ref[u];
-        const float alpha = __builtin_amdgcn_exp2f(-d);
+        // nothing has been accumulated before the first step (and 2^-d would overflow for a first
+        // maximum below -127)
+        const float alpha = force ? 1.0f : __builtin_amdgcn_exp2f(-d);
         l_run[u] *= alpha;
 #pragma unroll
         for (int b = 0; b < MB; ++b)

@@ -123,6 +123,60 @@ def test_attention_bf16_ignores_rows_past_n_keys(n_tok, n_keys, heads, hd, hd_pa
         assert rel_err(got[r], want) < 1.5e-2, s
 
 
+def _attention_run(q, k, v, n_slices, n_tok, heads, hd):
+    """q, k, v [M, heads * hd] on the bf16 grid -> kernel output and oracle output, both [M, heads * hd]."""
+    M, D = q.shape
+    qk = np.concatenate([q, k], axis=1).astype(np.float32)
+    vt = v.reshape(n_slices, n_tok, heads, hd).transpose(0, 2, 3, 1).copy().astype(np.float32)
+    qk_d = B.to_device(qk, True)
+    o = B.op_attention_bf16(qk_d, qk_d[:, D:], B.to_device(vt, True), n_slices, n_tok, heads, hd, 2 * D,
+                            1.0 / math.sqrt(hd))
+    torch.cuda.synchronize()
+    got = o.float().cpu().numpy().reshape(M, D)
+    want = np.concatenate([O.attention(q[s * n_tok:(s + 1) * n_tok], k[s * n_tok:(s + 1) * n_tok],
+                                       v[s * n_tok:(s + 1) * n_tok], heads) for s in range(n_slices)])
+    return got, want
+
+
+def _snap_bf16(x):
+    return torch.from_numpy(np.asarray(x, np.float32)).bfloat16().float().numpy()
+
+
+@pytest.mark.parametrize("hd", [64, 72, 128])
+@pytest.mark.parametrize("kind", ["all_low", "rising", "falling", "wide"])
+def test_attention_bf16_extreme_logits(kind, hd):
+    """Logits far from zero and running maxima that move by large steps: the kernel shifts the logits
+    by a reference value that it moves only now and then, and every such move rescales what has
+    been accumulated.  all_low: every logit is -128 (closed form: the mean of V); rising: the
+    maximum grows by ~11 (log2 units) per 32 keys, so the reference moves at every step; falling:
+    the first key dominates and the later weights underflow; wide: random logits with std ~ 9."""
+    n_slices, n_tok, heads = 2, 1024, 2
+    M, D = n_slices * n_tok, heads * hd
+    rng = np.random.default_rng(7 + hd)
+    v = _bf16_grid(rng, (M, D))
+    pos = (np.arange(M) % n_tok).astype(np.float32)[:, None]
+    if kind == "all_low":
+        q = np.full((M, D), 4.0, np.float32) * math.sqrt(64.0 / hd)
+        k = -q
+    elif kind in ("rising", "falling"):
+        q = np.ones((M, D), np.float32)
+        ramp = pos / n_tok if kind == "rising" else 1.0 - pos / n_tok
+        k = np.broadcast_to(ramp * 32.0 * math.sqrt(64.0 / hd), (M, D)).copy()
+    else:
+        q = _bf16_grid(rng, (M, D), 3.0)
+        k = _bf16_grid(rng, (M, D), 3.0)
+    q, k = _snap_bf16(q), _snap_bf16(k)
+    got, want = _attention_run(q, k, v, n_slices, n_tok, heads, hd)
+    assert np.isfinite(got).all()
+    # wide: the kernel rounds q * log2(e)/sqrt(hd) to bf16 once more (2^-9 relative per element); at a
+    # logit std of 9 that is ~0.015 log2 units on a logit, ~1 % on a dominant weight: the bf16 bound
+    assert rel_err(got, want) < (2e-2 if kind == "wide" else 1.5e-2)
+    if kind == "all_low":
+        mean_v = np.concatenate([np.broadcast_to(v[s * n_tok:(s + 1) * n_tok].mean(axis=0), (n_tok, D))
+                                 for s in range(n_slices)])
+        assert np.abs(got - mean_v).max() < 1e-2 * np.abs(v).max()
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (1000, 512, 256), (2304, 1024, 1024), (77, 256, 384)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
