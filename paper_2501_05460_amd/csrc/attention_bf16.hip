@@ -19,17 +19,16 @@
 // from LDS feeds all QT sub-tiles of the wave.
 // Values arrive pre-transposed ([slice, head, hd, token]) from the value GEMM.
 //
-// The softmax shift rides on the matrix core: q is scaled by log2(e)/sqrt(hd)
-// when its fragments are loaded, and every S^T product carries one more
-// k-step whose left operand is all ones and whose right operand holds minus
-// the query's reference value m at k = 0, so the MFMA result is already
-// s - m and the exponential takes it as it comes.  m is a bf16-exact value
-// (it has to pass through a bf16 operand) near the running maximum; it is
-// moved (accumulators rescaled) only when a logit exceeds it by more than
-// 2^RESCALE_LOG2, which bounds the weights by that factor instead of by 1:
-// harmless for bf16 weights and fp32 sums.  Where the V^T tile has spare rows
-// past the head dim (hd = 72 in 96 rows) one of them holds ones, and the
-// row sum of the weights comes out of the second product as well.
+// The reference value m that is subtracted from a query's logits follows the
+// running maximum lazily: it moves (and the accumulators are rescaled) only
+// when a logit exceeds it by more than RESCALE_LOG2 in the log2 domain, which
+// bounds the weights by 2^RESCALE_LOG2 instead of by 1: harmless for bf16
+// weights and fp32 sums, and it takes the rescaling out of almost every step
+// (with the exact running maximum some query of a wave moves it at most steps).
+// The sum of the weights is taken over the rounded values the second product
+// uses: two per v_dot2_f32_bf16, or, where the V^T tile has spare rows past
+// the head dim (hd = 72 in 96 rows), by a row of ones in V^T, so that the sum
+// comes out of the second product itself.
 #include "kernels.h"
 
 namespace epd {
@@ -46,9 +45,6 @@ __device__ __forceinline__ float max_with_other_half(float x, float y) {
   const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
   return fmaxf(fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1])), __uint_as_float(b));
 }
-
-// nearest bf16-exact value
-__device__ __forceinline__ float bf16_exact(float x) { return (float)(bf16_t)x; }
 
 // HD = head dim as stored in q, k, v^T (a multiple of 8).  The products run
 // over HD rounded up to the MFMA shapes (16 for q.k, 32 rows of O^T); the
@@ -121,9 +117,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       if (s * 16 + 8 < HD || lh == 0) {
-        const bf16x8 raw = *reinterpret_cast<const bf16x8*>(qp + s * 16);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[u][s][e] = (bf16_t)((float)raw[e] * scale_log2e);   // logits come out in the log2 domain
+        qf[u][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
       } else {   // head-dim positions past HD (last k-step of a head dim that is not a multiple of 16)
 #pragma unroll
         for (int e = 0; e < 8; ++e) qf[u][s][e] = (bf16_t)0.f;
@@ -181,35 +175,26 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   constexpr bool SUM_MFMA = SM::HDV > HD;   // a spare V^T row of ones makes the second product sum the weights
   constexpr int SUM_B = HD / 32, SUM_I = 4 * ((HD % 32) / 8);   // O^T row HD: block, register (lanes 0..31; HD % 8 == 0)
   f32x16 oacc[QT][MB];
-  // m_ref: the reference subtracted from this query's logits (log2 domain, bf16-exact);
-  // l_run: this lane's share of the running sum of weights (unused with SUM_MFMA);
-  // qx: right operand of the extra k-step, -m_ref at k = 0
+  // m_ref: the reference subtracted from this query's logits (log2 domain);
+  // l_run: this lane's share of the running sum of weights (unused with SUM_MFMA)
   float m_ref[QT], l_run[QT];
-  bf16x8 qx[QT], kones;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) kones[e] = (bf16_t)1.0f;
-  asm volatile("" : "+v"(kones));   // stays in its four registers instead of being rebuilt in front of every product
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     m_ref[u] = 0.f;
     l_run[u] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) qx[u][e] = (bf16_t)0.f;
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[u][b][e] = 0.f;
   }
 
-  // S^T - m of one 32-key step for all sub-tiles (MFMAs only: they run while the
+  // S^T of one 32-key step for all sub-tiles (MFMAs only: they run while the
   // wave goes on with the softmax arithmetic of the previous step)
   auto issue_s = [&](f32x16 (&s)[QT], const bf16_t* ks, int kt) {
 #pragma unroll
-    for (int u = 0; u < QT; ++u) {
+    for (int u = 0; u < QT; ++u)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[u][e] = 0.f;
-      s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kones, qx[u], s[u], 0, 0, 0);
-    }
 #pragma unroll
     for (int st = 0; st < KS; ++st) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * SM::K_LD + st * 16 + lh * 8);
@@ -217,19 +202,11 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       for (int u = 0; u < QT; ++u) s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][st], s[u], 0, 0, 0);
     }
   };
-  // Online softmax of one step, one query per lane (shared with lane ^ 32).  `stale`: the
-  // products of this step were issued before the reference last moved, by `moved` (per lane).
-  // `force`: the first step of a slice takes its own maximum as the reference, whatever its
-  // size.  On return `moved` is what this step added to the reference (0 for most steps).
-  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0, bool stale, bool force, float (&moved)[QT]) -> bool {
-    bool any_moved = false;
+  // Online softmax of one step, one query per lane (shared with lane ^ 32).  `force`: the first
+  // step of a slice takes its own maximum as the reference, whatever its size.
+  auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0, bool force) {
 #pragma unroll
     for (int u = 0; u < QT; ++u) {
-      if (stale) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[u][e] -= moved[u];
-      }
-      moved[u] = 0.f;
       if (MASK && key0 + 32 > n_keys) {   // uniform; only the last steps of a slice whose rows are padded
         // rows past n_keys are no tokens: logit -inf, weight 0 (the first step always holds a real key,
         // so the reference is finite by the time a step is masked entirely)
@@ -237,18 +214,19 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         for (int e = 0; e < 16; ++e)
           if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
       }
-      // three-input maxima throughout (the two-input form would first quieten each MFMA result)
+      // shifted logits first (log2 domain, relative to the reference as it stands), then their
+      // maximum: three-input maxima throughout (the two-input form would first quieten its inputs)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[u][e] = fmaf(s[u][e], scale_log2e, -m_ref[u]);
       float mx = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
 #pragma unroll
       for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);
       mx = max_with_other_half(mx, s[u][15]);
       // the reference rarely moves after the first blocks: rescale only then
       if (force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
-        const bool mine = force || mx > RESCALE_LOG2;
-        const float m_new = mine ? bf16_exact(m_ref[u] + mx) : m_ref[u];
-        const float d = m_new - m_ref[u];
-        // nothing has been accumulated before the first step (and 2^-d would overflow for a first
-        // maximum below -127)
+        const float d = (force || mx > RESCALE_LOG2) ? mx : 0.f;   // this query's reference moves by d
+        // nothing has been accumulated before the first step (and the factor would overflow for a
+        // first maximum below -127)
         const float alpha = force ? 1.0f : __builtin_amdgcn_exp2f(-d);
         l_run[u] *= alpha;
 #pragma unroll
@@ -257,10 +235,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
           for (int e = 0; e < 16; ++e) oacc[u][b][e] *= alpha;
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[u][e] -= d;
-        m_ref[u] = m_new;
-        qx[u][0] = lh == 0 ? (bf16_t)(-m_new) : (bf16_t)0.f;
-        moved[u] = d;
-        any_moved = true;
+        m_ref[u] += d;
       }
 #pragma unroll
       for (int e = 0; e < 16; ++e) pf[u][e >> 3][e & 7] = (bf16_t)__builtin_amdgcn_exp2f(s[u][e]);
@@ -277,7 +252,6 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         l_run[u] = psum;
       }
     }
-    return any_moved;
   };
   // O^T += V^T P^T for one step
   auto issue_pv = [&](bf16x8 (&pf)[QT][2], const bf16_t* vs, int kt) {
@@ -324,13 +298,10 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
     const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
     if (any_act) {
-      float moved[QT];
-#pragma unroll
-      for (int u = 0; u < QT; ++u) moved[u] = 0.f;
-      issue_s(s1, ks, 1);   // carries the reference as it is before the softmax of s0
-      const bool stale = softmax(s0, p0, kb * BKEY, false, kb == 0, moved);
+      issue_s(s1, ks, 1);
+      softmax(s0, p0, kb * BKEY, kb == 0);
       issue_pv(p0, vs, 0);
-      softmax(s1, p1, kb * BKEY + 32, stale, false, moved);
+      softmax(s1, p1, kb * BKEY + 32, false);
       issue_pv(p1, vs, 1);
     }
     sstore((kb + 1) & 1);   // the other buffer: nobody reads it after the previous barrier

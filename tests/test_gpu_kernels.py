@@ -146,7 +146,7 @@ def _snap_bf16(x):
 @pytest.mark.parametrize("kind", ["all_low", "rising", "falling", "wide"])
 def test_attention_bf16_extreme_logits(kind, hd):
     """Logits far from zero and running maxima that move by large steps: the kernel shifts the logits
-    by a reference value that it moves only now and then, and every such move rescales what has
+    by a reference value that follows the running maximum lazily, and every move rescales what has
     been accumulated.  all_low: every logit is -128 (closed form: the mean of V); rising: the
     maximum grows by ~11 (log2 units) per 32 keys, so the reference moves at every step; falling:
     the first key dominates and the later weights underflow; wide: random logits with std ~ 9."""
@@ -168,9 +168,7 @@ def test_attention_bf16_extreme_logits(kind, hd):
     q, k = _snap_bf16(q), _snap_bf16(k)
     got, want = _attention_run(q, k, v, n_slices, n_tok, heads, hd)
     assert np.isfinite(got).all()
-    # wide: the kernel rounds q * log2(e)/sqrt(hd) to bf16 once more (2^-9 relative per element); at a
-    # logit std of 9 that is ~0.015 log2 units on a logit, ~1 % on a dominant weight: the bf16 bound
-    assert rel_err(got, want) < (2e-2 if kind == "wide" else 1.5e-2)
+    assert rel_err(got, want) < 1.5e-2
     if kind == "all_low":
         mean_v = np.concatenate([np.broadcast_to(v[s * n_tok:(s + 1) * n_tok].mean(axis=0), (n_tok, D))
                                  for s in range(n_slices)])
