@@ -37,6 +37,7 @@ namespace {
 
 constexpr int BKEY = 64;  // keys per LDS block
 constexpr float RESCALE_LOG2 = 8.0f;   // a logit may exceed the reference by this much (log2 domain)
+constexpr float RESCALE_SUM = 256.0f;  // 2^RESCALE_LOG2: what a lane's 16 weights of a step may sum to
 
 // max of two values and the two held by lane ^ 32: the swap leaves the low half's values in both
 // halves of one result and the high half's in both halves of the other
@@ -202,6 +203,23 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       for (int u = 0; u < QT; ++u) s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[u][st], s[u], 0, 0, 0);
     }
   };
+  // weights of one step from its shifted logits, and (unless the second product sums them) their
+  // sum over the rounded values that product uses, two per instruction
+  auto weights = [&](const f32x16& sv, bf16x8 (&pv)[2], float& psum) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pv[e >> 3][e & 7] = (bf16_t)__builtin_amdgcn_exp2f(sv[e]);
+    psum = 0.f;
+    if (!SUM_MFMA) {
+      const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv[j], pv[j], 0, 1), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv[j], pv[j], 2, 3), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv[j], pv[j], 4, 5), ones, psum, false);
+        psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv[j], pv[j], 6, 7), ones, psum, false);
+      }
+    }
+  };
   // Online softmax of one step, one query per lane (shared with lane ^ 32).  `force`: the first
   // step of a slice takes its own maximum as the reference, whatever its size.
   auto softmax = [&](f32x16 (&s)[QT], bf16x8 (&pf)[QT][2], int key0, bool force) {
@@ -214,43 +232,45 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         for (int e = 0; e < 16; ++e)
           if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
       }
-      // shifted logits first (log2 domain, relative to the reference as it stands), then their
-      // maximum: three-input maxima throughout (the two-input form would first quieten its inputs)
+      // shifted logits (log2 domain, relative to the reference as it stands)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[u][e] = fmaf(s[u][e], scale_log2e, -m_ref[u]);
-      float mx = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
-#pragma unroll
-      for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);
-      mx = max_with_other_half(mx, s[u][15]);
-      // the reference rarely moves after the first blocks: rescale only then
-      if (force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
-        const float d = (force || mx > RESCALE_LOG2) ? mx : 0.f;   // this query's reference moves by d
-        // nothing has been accumulated before the first step (and the factor would overflow for a
-        // first maximum below -127)
-        const float alpha = force ? 1.0f : __builtin_amdgcn_exp2f(-d);
-        l_run[u] *= alpha;
-#pragma unroll
-        for (int b = 0; b < MB; ++b)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[u][b][e] *= alpha;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) s[u][e] -= d;
-        m_ref[u] += d;
+      float psum = 0.f;
+      bool move;
+      if (!SUM_MFMA) {
+        // No maximum in the common step: the weights are taken against the reference as it stands and
+        // their sum tells whether one of them was too large (a logit above RESCALE_LOG2 alone makes the
+        // sum exceed 2^RESCALE_LOG2; an overflowed weight makes it infinite).
+        weights(s[u], pf[u], psum);
+        move = force || __builtin_amdgcn_ballot_w64(!(psum <= RESCALE_SUM)) != 0;
+      } else {
+        move = true;   // the sum sits in the accumulator of the second product: decide by the maximum
       }
+      if (move) {
+        // three-input maxima throughout (the two-input form would first quieten its inputs)
+        float mx = fmaxf(fmaxf(s[u][0], s[u][1]), s[u][2]);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) pf[u][e >> 3][e & 7] = (bf16_t)__builtin_amdgcn_exp2f(s[u][e]);
-      if (!SUM_MFMA) {   // sum of the rounded weights, the values the second product uses: two per instruction
-        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
-        float psum = l_run[u];
+        for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);
+        mx = max_with_other_half(mx, s[u][15]);
+        if (!SUM_MFMA || force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
+          // a lane whose sum exceeded 2^RESCALE_LOG2 holds a logit above RESCALE_LOG2 - 4 (16 weights)
+          const float d = (force || mx > RESCALE_LOG2 - 4.0f) ? mx : 0.f;   // this query's reference moves by d
+          // nothing has been accumulated before the first step (and the factor would overflow for a
+          // first maximum below -127)
+          const float alpha = force ? 1.0f : __builtin_amdgcn_exp2f(-d);
+          l_run[u] *= alpha;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 0, 1), ones, psum, false);
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 2, 3), ones, psum, false);
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 4, 5), ones, psum, false);
-          psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pf[u][j], pf[u][j], 6, 7), ones, psum, false);
+          for (int b = 0; b < MB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[u][b][e] *= alpha;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) s[u][e] -= d;
+          m_ref[u] += d;
+          if (!SUM_MFMA) weights(s[u], pf[u], psum);   // again, against the new reference
         }
-        l_run[u] = psum;
       }
+      if (SUM_MFMA) weights(s[u], pf[u], psum);
+      else l_run[u] += psum;
     }
   };
   // O^T += V^T P^T for one step
