@@ -102,12 +102,16 @@ def test_class_token_at_a_257_token_sequence_vs_oracle():
 
 def test_resampler_at_a_1024_patch_slice_vs_oracle():
     """448-pixel slices (1024 keys per query, 16 key blocks), 64 learned queries, more slices than one
-    micro-batch holds; logits sharpened so the key side (LayerNorm, position table, in-projection) shows."""
+    micro-batch holds; logits sharpened so the key side (LayerNorm, position table, in-projection) shows.
+    In-projections scaled by 1.25: at 1.5 the bf16 rounding of q and k alone, amplified by the sharper
+    softmax, puts the maximum error of any attention kernel at 0.013 .. 0.02 over seeds, i.e. at the bound
+    itself; 1.25 gives ~0.009."""
     desc = small_desc(wl.DT_BF16, tile_size=448, final_norm=1, proj_kind=wl.PROJ_RESAMPLER, proj_mid=64,
                       proj_heads=2, proj_out=256, layers=1, max_tiles_per_call=2)
-    got, want = run_case(desc, 25, 3, [0, 3], scale={"r_in_w": 1.5})
-    assert got.shape == (3 * 64, 256)
-    assert rel_err(got, want) < tol(desc)
+    for seed in (25, 26):
+        got, want = run_case(desc, seed, 3, [0, 3], scale={"r_in_w": 1.25})
+        assert got.shape == (3 * 64, 256)
+        assert rel_err(got, want) < tol(desc), seed
 
 
 def test_c1_tiny_fp32_vs_oracle():
