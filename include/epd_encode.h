@@ -310,7 +310,8 @@ epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_s
  * call on this context, measured with HIP events on the call's stream.
  * epd_profile_enable(ctx, 1) makes subsequent calls bracket every launch
  * with two event records; epd_profile_read synchronises the device and fills
- * ms[family] (summed) and launches[family].  Families: 0 im2col + patch-embed
+ * ms[family] (summed) and launches[family] (kernels launched: a product that
+ * the library cuts into two launches counts twice).  Families: 0 im2col + patch-embed
  * GEMM, 1 pre-norms, 2 QKV GEMM, 3 attention, 4 q/k norm, 5 projector input
  * (shuffle / norm / convert), 6 out-proj GEMM, 7 FC1 GEMM, 8 FC2 GEMM,
  * 9 projector GEMMs. */

@@ -220,22 +220,30 @@ struct epd_ctx {
   bool prof = false;
   std::vector<hipEvent_t> ev;
   std::vector<int> ev_family;
+  std::vector<int> ev_kernels;   // kernels launched inside each bracket
   size_t ev_used = 0;
 };
 
 namespace {
 
 struct ProfScope {
-  epd_ctx* c; hipStream_t st; bool on;
-  ProfScope(epd_ctx* c_, int family, hipStream_t st_) : c(c_), st(st_), on(false) {
+  epd_ctx* c; hipStream_t st; bool on; long gemm_before;
+  ProfScope(epd_ctx* c_, int family, hipStream_t st_) : c(c_), st(st_), on(false), gemm_before(0) {
     if (c->prof && c->ev_used + 2 <= c->ev.size()) {
       on = true;
       c->ev_family.push_back(family);
+      gemm_before = bf16_gemm_kernel_launches();
       hipEventRecord(c->ev[c->ev_used], st);
     }
   }
   ~ProfScope() {
-    if (on) { hipEventRecord(c->ev[c->ev_used + 1], st); c->ev_used += 2; }
+    if (on) {
+      hipEventRecord(c->ev[c->ev_used + 1], st);
+      c->ev_used += 2;
+      // a bracket around a product counts the kernels it was cut into; any other bracket holds one kernel
+      const long k = bf16_gemm_kernel_launches() - gemm_before;
+      c->ev_kernels.push_back(k > 0 ? (int)k : 1);
+    }
   }
 };
 
@@ -786,7 +794,7 @@ epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, in
   const int map_rows = stage == STAGE_FULL ? x.N_out : x.N;
   const int map_origin = stage == STAGE_FULL ? 0 : b;
   const int out_origin = stage == STAGE_PROJECT ? b : 0;
-  if (c->prof) { c->ev_used = 0; c->ev_family.clear(); }
+  if (c->prof) { c->ev_used = 0; c->ev_family.clear(); c->ev_kernels.clear(); }
   for (int t0 = b; t0 < e; t0 += c->mb) {
     const int T = (e - t0) < c->mb ? (e - t0) : c->mb;
     const float* tp = tiles ? tiles + (size_t)t0 * tile_elems : nullptr;
@@ -1095,6 +1103,7 @@ epd_status epd_profile_enable(epd_ctx* ctx, int32_t on) {
   ctx->prof = on != 0;
   ctx->ev_used = 0;
   ctx->ev_family.clear();
+  ctx->ev_kernels.clear();
   return EPD_OK;
 }
 
@@ -1106,7 +1115,7 @@ epd_status epd_profile_read(epd_ctx* ctx, float* ms, int32_t* launches) {
     float t = 0.f;
     HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->ev[2 * i], ctx->ev[2 * i + 1]));
     ms[ctx->ev_family[i]] += t;
-    launches[ctx->ev_family[i]] += 1;
+    launches[ctx->ev_family[i]] += i < ctx->ev_kernels.size() ? ctx->ev_kernels[i] : 1;
   }
   return EPD_OK;
 }

@@ -768,6 +768,8 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
 template <int BN, int NT>
 constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT>() + BN * sizeof(float); }
 
+long g_kernel_launches = 0;   // kernels launched by bf16_gemm so far (a product may be cut into two launches)
+
 template <int BN, int NT, int WN, int EPI, int PIPE>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
@@ -787,6 +789,7 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
   k_gemm_bf16<BN, NT, WN, EPI, PIPE><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
+  ++g_kernel_launches;
   return hipGetLastError();
 }
 
@@ -819,6 +822,7 @@ hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   if (p.band > 0 && p.band <= gn) gw = p.band;
   const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
   k_gemm_bf16_persist<EPI><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  ++g_kernel_launches;
   return hipGetLastError();
 }
 
@@ -869,6 +873,8 @@ hipError_t set_attr_all() {
 }
 
 }  // namespace
+
+long bf16_gemm_kernel_launches() { return g_kernel_launches; }
 
 hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();

@@ -55,6 +55,7 @@ struct GemmParams {
   int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
 };
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
+long bf16_gemm_kernel_launches();   // kernels launched by bf16_gemm so far in this process (not thread-safe: a figure for the profiling hooks)
 hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (once per process)
 
 // A_pe[row][e] = bf16(pixel) for e < 3*p*p, 0 for the K padding up to lda.
