@@ -53,16 +53,18 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 //   BN = 128  256x128 tile, 64x64 per wave, PIPE = 0: outputs narrower than 256 columns.
 // (Tried and dropped, none faster on the six workloads: 4 waves of 128x128 with AGPR
 // accumulators, 256x128 tiles with two 4-wave workgroups per CU, 32-deep slabs.)
-template <int BN, int NT>
+template <int BN, int NT, int BM_ = BM>
 constexpr size_t smem_main_bytes() {
-  // operand slabs, or the epilogue staging tile (256 x BN bf16 / 64 x BN fp32), whichever is larger
-  constexpr size_t operands = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  constexpr size_t staging = (size_t)BM * BN * sizeof(bf16_t);
+  // operand slabs, or the epilogue staging tile (BM x BN bf16 / 64 x BN fp32), whichever is larger
+  constexpr size_t operands = (size_t)2 * (BM_ + BN) * BK * sizeof(bf16_t);
+  constexpr size_t staging = (size_t)BM_ * BN * sizeof(bf16_t);
   return operands > staging ? operands : staging;
 }
 
-template <int BN, int NTHREADS, int WN, int EPI, int PIPE>
-__global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
+template <int BN, int NTHREADS, int WN, int EPI, int PIPE, int BM_ = 256>
+__global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
+  constexpr int BM = BM_;   // token rows of the tile: 256, or 128 for launches of a few slices
+  static_assert(BM_ == 256 || (BM_ == 128 && BN == 128 && PIPE == 0), "tile shapes compiled");
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
   constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void k_gemm_bf16(const GemmParams p, c
   // direct global-to-LDS loads
   bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [NBUF][BN][64]
   bf16_t* sA = sB + NBUF * BN * BK;              // [NBUF][BM][64]
-  float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());  // [BN]
+  float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS, BM>());  // [BN]
 
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
   // XCD x takes a contiguous run of the tile sequence, and the sequence walks
@@ -765,14 +767,14 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
   }
 }
 
-template <int BN, int NT>
-constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT>() + BN * sizeof(float); }
+template <int BN, int NT, int BM_ = BM>
+constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT, BM_>() + BN * sizeof(float); }
 
 long g_kernel_launches = 0;   // kernels launched by bf16_gemm so far (a product may be cut into two launches)
 
-template <int BN, int NT, int WN, int EPI, int PIPE>
+template <int BN, int NT, int WN, int EPI, int PIPE, int BM_ = BM>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
-  const int gm = (p.M + BM - 1) / BM, gn = p.Npad / BN;
+  const int gm = (p.M + BM_ - 1) / BM_, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
   if (n_tiles == 0) return hipSuccess;
   // Band width.  The ~32 workgroups an XCD runs at once cover (32 / gw) tile rows x gw tile
@@ -788,7 +790,7 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     if (cost < best * 0.999) { best = cost; gw = c; }
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
-  k_gemm_bf16<BN, NT, WN, EPI, PIPE><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT>(), st>>>(p, gm, gw);
+  k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT, BM_>(), st>>>(p, gm, gw);
   ++g_kernel_launches;
   return hipGetLastError();
 }
@@ -842,34 +844,34 @@ hipError_t set_attr_persist() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>());
 }
 
-template <int BN, int NT, int WN, int PIPE = 0>
+template <int BN, int NT, int WN, int PIPE = 0, int BM_ = BM>
 hipError_t dispatch(const GemmParams& p, hipStream_t st) {
   switch (p.epi) {
-    case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS, PIPE>(p, st);
-    case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE>(p, st);
-    case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE>(p, st);
-    case EPI_BIAS_RESIDUAL: return launch<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE>(p, st);
-    case EPI_BIAS_POS: return launch<BN, NT, WN, EPI_BIAS_POS, PIPE>(p, st);
-    case EPI_VT: return launch<BN, NT, WN, EPI_VT, PIPE>(p, st);
+    case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS, PIPE, BM_>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE, BM_>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE, BM_>(p, st);
+    case EPI_BIAS_RESIDUAL: return launch<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_>(p, st);
+    case EPI_BIAS_POS: return launch<BN, NT, WN, EPI_BIAS_POS, PIPE, BM_>(p, st);
+    case EPI_VT: return launch<BN, NT, WN, EPI_VT, PIPE, BM_>(p, st);
   }
   return hipErrorInvalidValue;
 }
 
-template <int BN, int NT, int WN, int EPI, int PIPE>
+template <int BN, int NT, int WN, int EPI, int PIPE, int BM_>
 hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI, PIPE>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, NT>());
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, NT, BM_>());
 }
 
-template <int BN, int NT, int WN, int PIPE = 0>
+template <int BN, int NT, int WN, int PIPE = 0, int BM_ = BM>
 hipError_t set_attr_all() {
   hipError_t e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS, PIPE>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE>()) != hipSuccess) return e;
-  if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS, PIPE>()) != hipSuccess) return e;
-  return set_attr<BN, NT, WN, EPI_VT, PIPE>();
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS, PIPE, BM_>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE, BM_>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE, BM_>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS, PIPE, BM_>()) != hipSuccess) return e;
+  return set_attr<BN, NT, WN, EPI_VT, PIPE, BM_>();
 }
 
 }  // namespace
@@ -885,6 +887,7 @@ hipError_t bf16_gemm_init() {
   if ((e = set_attr_persist<EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_VT>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
+  if ((e = set_attr_all<128, 512, 64, 0, 128>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -898,6 +901,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
   switch (p.cfg) {
     case 1: return dispatch<128, 512, 64>(p, st);
+    case 2: return dispatch<128, 512, 64, 0, 128>(p, st);
     case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
@@ -926,6 +930,10 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   // three slabs ahead in four register sets, 5 % slower: with two waves per SIMD the slab time is
   // the LDS-read -> MFMA chain of a wave, not the memory latency.)
   const long tiles256 = (long)((p.M + BM - 1) / BM) * (p.Npad / 256);
+  // A few slices: when even the 256 x 128 tiles leave half of the CUs without one, 128 x 128 tiles double the
+  // workgroups once more.  Same bits again: a tile shape changes which lane holds an element, never the
+  // order in which its k-steps are summed.
+  if (tiles256 * 4 <= 2 * cu_count()) return dispatch<128, 512, 64, 0, 128>(p, st);   // two such workgroups fit a CU
   if (tiles256 * 2 <= cu_count()) return dispatch<128, 512, 64>(p, st);
   if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st);
   // A last round that fills at most half of the CUs costs a whole tile time.  The residual product
