@@ -2,7 +2,7 @@
 // fused epilogues (bias, GELU, residual add into the fp32 stream, position
 // embedding, transposed store of the attention values).
 //
-// Block tile 256 x BN x 64 (BN = 256 or 128), 8 waves of 64 lanes.  Both
+// Block tile 256 x BN x 64 (BN = 256 or 128; 128 x 128 x 64 for small launches), 8 waves of 64 lanes.  Both
 // operands are K-contiguous, staged through LDS as [row][64] bf16 with the
 // 16-byte chunks of a row XOR-swizzled by the row so that the 32 rows a
 // wave reads for one MFMA operand fall into different banks (64 banks, 16
@@ -50,7 +50,9 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 //   BN = 256  256x256 tile, 128x64 per wave (PIPE = 1: pipelined loop, the default; PIPE = 0:
 //             both operands two slabs ahead in two register sets, fragment reads left to the
 //             compiler: the reference the pipelined loop is checked against bit for bit);
-//   BN = 128  256x128 tile, 64x64 per wave, PIPE = 0: outputs narrower than 256 columns.
+//   BN = 128  256x128 tile, 64x64 per wave, PIPE = 0: outputs narrower than 256 columns;
+//   BN = 128, BM = 128  128x128 tile, 32x64 per wave, PIPE = 0, two workgroups per CU: launches of
+//             a few slices, whose time is a sum of single-tile latencies.
 // (Tried and dropped, none faster on the six workloads: 4 waves of 128x128 with AGPR
 // accumulators, 256x128 tiles with two 4-wave workgroups per CU, 32-deep slabs.)
 template <int BN, int NT, int BM_ = BM>
