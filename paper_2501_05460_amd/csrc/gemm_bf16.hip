@@ -261,6 +261,33 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(cons
   auto compute = [&](int buf) {
     const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
     const bf16_t* b_s = sB + buf * BN * BK + (wn * WN + l32) * BK;
+    if constexpr (TM * TN <= 2) {
+      // Small tiles run alone on their CU and their time is the chain LDS read -> MFMA of one wave:
+      // all fragments of the slab are read first (two k-steps' worth per batch of registers), so the
+      // LDS latency is paid once per half slab instead of once per k-step.  The k-steps of an element
+      // are still added in order.
+#pragma unroll
+      for (int k2 = 0; k2 < BK / 16; k2 += 2) {
+        bf16x8 xf[2][TM], wf[2][TN];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int coff = (((2 * (k2 + q) + lh) ^ frag_sw) * 8);
+#pragma unroll
+          for (int i = 0; i < TM; ++i) xf[q][i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * BK + coff);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) wf[q][j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * BK + coff);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // the scheduler would otherwise sink each read to its MFMA
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = tok_major ? mfma32(xf[q][i], wf[q][j], acc[i][j]) : mfma32(wf[q][j], xf[q][i], acc[i][j]);
+      }
+      return;
+    }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
