@@ -282,7 +282,7 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
 /* One launch of the bf16 MFMA GEMM in a chosen form, for tests that hold the forms against each
  * other: epi 0 bias, 1 bias + GELU(erf), 2 bias + GELU(tanh) -> C [M,N] bf16; epi 3 -> R [M,N]
  * fp32 += A W^T + bias (C unused).  form 0 = what the library would pick, 1 = 256x128 tile,
- * 2 = 128x128 tile, 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
+ * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
  * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 9), K % 128 == 0; bias [N] fp32.
  * The kernels read whole 256-row tiles: A must be readable for round_up(M, 256) rows and R for
  * round_up(M, 256) rows plus 256 floats; no row past M is written. */

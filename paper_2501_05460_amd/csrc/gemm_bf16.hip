@@ -64,9 +64,9 @@ constexpr size_t smem_main_bytes() {
 }
 
 template <int BN, int NTHREADS, int WN, int EPI, int PIPE, int BM_ = 256>
-__global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
+__global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int BM = BM_;   // token rows of the tile: 256, or 128 for launches of a few slices
-  static_assert(BM_ == 256 || (BM_ == 128 && BN == 128 && PIPE == 0), "tile shapes compiled");
+  static_assert(BM_ == 256 ? PIPE <= 1 : (BM_ == 128 && BN == 128 && (PIPE == 0 || PIPE == 2)), "tile shapes compiled");
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
   constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
@@ -75,7 +75,11 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(cons
   constexpr int TN = WN / 32;                // 2 | 4
   constexpr int A_LD = BM * 8 / NTHREADS;    // 16-byte chunks per thread per slab
   constexpr int B_LD = BN * 8 / NTHREADS;
-  constexpr int NBUF = 2;  // LDS slab buffers = register sets
+  constexpr int NBUF = 2;  // LDS slab buffers
+  // register sets the global loads land in = slabs they run ahead of the MFMAs.  PIPE = 2 (128 x 128
+  // tiles of launches with at most one tile per CU): four, because such a launch is bound by the bytes
+  // it keeps in flight, not by the matrix cores
+  constexpr int NSET = PIPE == 2 ? 4 : 2;
   constexpr int ROWS_PER_LD = NTHREADS / 8;      // rows covered by one 16-byte load per thread
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(cons
 
   // Two register sets: the loads of slab k+2 are in flight while slab k is
   // multiplied and slab k+1 (loaded one iteration earlier) moves to LDS.
-  u32x4 ra[NBUF][A_LD], rb[NBUF][B_DIRECT ? 1 : B_LD];
+  u32x4 ra[NSET][A_LD], rb[NSET][B_DIRECT ? 1 : B_LD];
   auto gload = [&](auto set, int kt) {
     constexpr int S = decltype(set)::value;
     // Residual epilogue: the two loads past the last slab (kt == KT_ into set
@@ -186,6 +190,7 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(cons
     const bool past = kt >= KT_;
     const int xpass = kt - KT_;
     kt = past ? KT_ - 1 : kt;  // past the end (other epilogues): re-read the last slab, result unused
+    if (X_IN_LOOP && past && xpass >= 2) return;   // four register sets: only two of them carry residual rows
     if (X_IN_LOOP && past) {   // one uniform branch per slab, taken for the last two slabs of a tile
       auto so_x = [&](int c) {
         const int pass = B_DIRECT ? 0 : xpass, ci = B_DIRECT ? xpass * A_LD + c : c;
@@ -387,6 +392,42 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 ? 2 : 1) void k_gemm_bf16(cons
       for (int i = 0; i < XPER_T; ++i) xr[0][i] = __builtin_bit_cast(f32x4, ra[i / A_LD][i % A_LD]);
       xload(S1{}, 1);   // into the registers the operand fragments have left
     } else if constexpr (X_IN_LOOP) {
+#pragma unroll
+      for (int i = 0; i < XPER_T; ++i) {
+        xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
+        xr[1][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[1][i < A_LD ? i : 0] : rb[1][i < A_LD ? 0 : i - A_LD]);
+      }
+    }
+  } else if constexpr (PIPE == 2) {
+    // four slabs ahead (the launcher takes this form only for K % 256 == 0)
+    using S2 = std::integral_constant<int, 2>;
+    using S3 = std::integral_constant<int, 3>;
+    gload(S0{}, 0);
+    gload(S1{}, 1);
+    gload(S2{}, 2);
+    gload(S3{}, 3);
+    sstore(S0{}, 0);
+    __syncthreads();
+    for (int kt = 0; kt < KT_; kt += 4) {
+      gload(S0{}, kt + 4);   // past the last slab: residual rows of epilogue pass 0 (see gload)
+      compute(0);
+      sstore(S1{}, 1);
+      __syncthreads();
+      gload(S1{}, kt + 5);   // ... and of pass 1
+      compute(1);
+      sstore(S2{}, 0);
+      __syncthreads();
+      gload(S2{}, kt + 6);
+      compute(0);
+      sstore(S3{}, 1);
+      __syncthreads();
+      gload(S3{}, kt + 7);
+      compute(1);
+      if (X_IN_LOOP && kt + 4 >= KT_) break;   // nothing left to hand over
+      sstore(S0{}, 0);
+      __syncthreads();
+    }
+    if constexpr (X_IN_LOOP) {
 #pragma unroll
       for (int i = 0; i < XPER_T; ++i) {
         xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
@@ -917,6 +958,7 @@ hipError_t bf16_gemm_init() {
   if ((e = set_attr_persist<EPI_VT>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64, 0, 128>()) != hipSuccess) return e;
+  if ((e = set_attr_all<128, 512, 64, 2, 128>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -931,6 +973,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   switch (p.cfg) {
     case 1: return dispatch<128, 512, 64>(p, st);
     case 2: return dispatch<128, 512, 64, 0, 128>(p, st);
+    case 3: if (p.K % 256 == 0) return dispatch<128, 512, 64, 2, 128>(p, st); break;
     case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
@@ -962,6 +1005,8 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   // A few slices: when even the 256 x 128 tiles leave half of the CUs without one, 128 x 128 tiles double the
   // workgroups once more.  Same bits again: a tile shape changes which lane holds an element, never the
   // order in which its k-steps are summed.
+  // at most one 128 x 128 tile per CU: the loop that keeps four slabs in flight (K in whole groups of four slabs)
+  if (tiles256 * 4 <= cu_count() && p.K % 256 == 0) return dispatch<128, 512, 64, 2, 128>(p, st);
   if (tiles256 * 4 <= 2 * cu_count()) return dispatch<128, 512, 64, 0, 128>(p, st);   // two such workgroups fit a CU
   if (tiles256 * 2 <= cu_count()) return dispatch<128, 512, 64>(p, st);
   if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st);
