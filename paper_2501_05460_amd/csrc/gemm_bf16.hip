@@ -996,19 +996,16 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     const hipError_t e = bf16_gemm(a, st);
     return e != hipSuccess ? e : bf16_gemm(b, st);
   }
-  // Small batches: when 256-wide tiles would leave half of the CUs without one, the 128-wide tile
-  // doubles the number of workgroups and halves the time of the one round there is.  Same bits.
-  // (Measured and not kept for this regime: the pipelined loop on this tile, 8 % slower, and operands
-  // three slabs ahead in four register sets, 5 % slower: with two waves per SIMD the slab time is
-  // the LDS-read -> MFMA chain of a wave, not the memory latency.)
+  // Small batches: when 256-wide tiles would leave half of the CUs without one, 128 x 128 tiles
+  // quadruple the number of workgroups (two of them fit a CU) and shorten the one round there is.  Same
+  // bits: a tile shape changes which lane holds an element, never the order in which its k-steps are
+  // summed.  With at most one such tile per CU the launch is bound by the bytes it keeps in flight:
+  // the loop with four register sets (loads four slabs ahead; K in whole groups of four slabs) takes
+  // it.  (Measured and not kept: 256 x 128 tiles for this regime, 17 % slower on one slice; the
+  // pipelined loop on them, 8 % slower still.)
   const long tiles256 = (long)((p.M + BM - 1) / BM) * (p.Npad / 256);
-  // A few slices: when even the 256 x 128 tiles leave half of the CUs without one, 128 x 128 tiles double the
-  // workgroups once more.  Same bits again: a tile shape changes which lane holds an element, never the
-  // order in which its k-steps are summed.
-  // at most one 128 x 128 tile per CU: the loop that keeps four slabs in flight (K in whole groups of four slabs)
   if (tiles256 * 4 <= cu_count() && p.K % 256 == 0) return dispatch<128, 512, 64, 2, 128>(p, st);
-  if (tiles256 * 4 <= 2 * cu_count()) return dispatch<128, 512, 64, 0, 128>(p, st);   // two such workgroups fit a CU
-  if (tiles256 * 2 <= cu_count()) return dispatch<128, 512, 64>(p, st);
+  if (tiles256 * 2 <= cu_count()) return dispatch<128, 512, 64, 0, 128>(p, st);   // beyond that the small tiles lose (13 slices: +9 %)
   if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st);
   // A last round that fills at most half of the CUs costs a whole tile time.  The residual product
   // (rows are independent, all addressing is by pointer) is cut by rows instead: whole rounds of
