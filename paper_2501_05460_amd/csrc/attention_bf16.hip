@@ -28,7 +28,10 @@
 // The sum of the weights is taken over the rounded values the second product
 // uses: two per v_dot2_f32_bf16, or, where the V^T tile has spare rows past
 // the head dim (hd = 72 in 96 rows), by a row of ones in V^T, so that the sum
-// comes out of the second product itself.
+// comes out of the second product itself.  Where the sum is taken on the VALU
+// the common step computes no maximum at all: a step whose weights sum to
+// more than 2^RESCALE_LOG2 (or overflow) is what triggers the maximum, the
+// move of the reference and a second round of exponentials.
 #include "kernels.h"
 
 namespace epd {
