@@ -61,6 +61,10 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also encode the batch in FCFS groups of 1, 2, 4, ... requests per call (maximum encode "
                          "batch size) and report per-call latency and throughput for each")
+    ap.add_argument("--shard-sweep", action="store_true",
+                    help="also encode the first 1, 2, 4, ... slices of the first request alone (what one encode "
+                         "worker sees when a request's slices are cut over several workers) and report the "
+                         "latency of each share next to that of the whole request")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -172,6 +176,31 @@ def main():
                 break
             b *= 2
 
+    # ---- intra-request parallelism: one worker's share of the first request ----
+    shard = None
+    if args.shard_sweep:
+        n_req = offsets[1] - offsets[0]
+        n_out = desc.tokens_per_tile
+        sizes = sorted({n for n in (1, 2, 4, 8, 16, 32) if n < n_req} | {-(-n_req // w) for w in (2, 3, 4)} | {n_req})
+        lat = {}
+        for n in sizes:
+            for _ in range(3):
+                enc.encode(tiles[:n], [0, n], out[:n * n_out])
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 20
+            ev0.record()
+            for _ in range(reps):
+                enc.encode(tiles[:n], [0, n], out[:n * n_out])
+            ev1.record()
+            torch.cuda.synchronize()
+            lat[n] = ev0.elapsed_time(ev1) / reps
+        shard = {"request_tiles": n_req,
+                 "ms_by_tiles": {str(n): round(v, 3) for n, v in lat.items()},
+                 # a request cut over w workers takes as long as its largest share
+                 "speedup_by_workers": {str(w): round(lat[n_req] / lat[-(-n_req // w)], 2) for w in (2, 3, 4)}}
+        enc.encode(tiles, offsets, out)    # the whole batch again: the parity sample below reads `out`
+        torch.cuda.synchronize()
+
     # ---- paged cache: encode into blocks of 16 tokens, then move every block to a second cache ----
     mm = None
     if not args.no_mm_cache and desc.tokens_per_tile % 16 == 0:
@@ -273,6 +302,7 @@ def main():
         "cpu_baseline": cpu,
         "mm_cache": mm,
         "batch_sweep": sweep,
+        "shard_sweep": shard,
     }
     print(json.dumps(line))
 
