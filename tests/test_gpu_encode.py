@@ -114,6 +114,33 @@ def test_resampler_at_a_1024_patch_slice_vs_oracle():
         assert rel_err(got, want) < tol(desc), seed
 
 
+def test_profile_brackets_count_kernels_and_leave_the_result_alone():
+    """Per-family timing: every family that runs reports time and launches, the products of a layer
+    count at least one kernel each (a product the dispatch cuts in two counts twice), and the call's
+    output is bit-identical with and without the event brackets."""
+    desc = small_desc(wl.DT_BF16, layers=3, proj_kind=wl.PROJ_MLP, proj_mid=200, max_tiles_per_call=8)
+    w = wl.gen_weights(desc, 31, std=0.08)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 31, 5)).cuda()
+    enc = make_encoder(desc, w)
+    plain = enc.encode(tiles, [0, 2, 5]).clone()
+    enc.profile_enable(True)
+    timed = enc.encode(tiles, [0, 2, 5]).clone()
+    fam = enc.profile_read()
+    enc.profile_enable(False)
+    again = enc.encode(tiles, [0, 2, 5]).clone()
+    torch.cuda.synchronize()
+    enc.close()
+    assert torch.equal(plain, timed) and torch.equal(plain, again)
+    L = desc.layers
+    for name in ("gemm_qkv", "gemm_out", "gemm_fc1", "gemm_fc2"):
+        assert fam[name]["ms"] > 0.0, name
+        assert fam[name]["launches"] >= (2 * L if name == "gemm_qkv" else L), (name, fam[name])   # q/k and v are two products
+        assert fam[name]["launches"] <= 4 * L, (name, fam[name])
+    assert fam["norm"]["launches"] == 2 * L and fam["attention"]["launches"] == L
+    assert fam["embed"]["launches"] >= 1 and fam["gemm_proj"]["launches"] >= 2
+    assert fam["qk_norm"]["launches"] == 0 and fam["qk_norm"]["ms"] == 0.0
+
+
 def test_c1_tiny_fp32_vs_oracle():
     wk = wl.workload("c1")
     w = wl.gen_weights(wk.desc, wk.weight_seed)
