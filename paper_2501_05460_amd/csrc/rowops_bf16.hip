@@ -154,22 +154,23 @@ void bf16_rowop(const RowOpParams& p, hipStream_t st) {
 
 // --------------------------------------------------------- q/k RMSNorm ------
 // One wave per logical row, q rows first, then k rows (k = q + k_off elements, its own gain).  The
-// row waits in registers between the sum of squares and the scaling when it fits (NV 8-byte chunks per
+// row waits in registers between the sum of squares and the scaling when it fits (NV chunks per
 // lane), otherwise it is read twice.
-template <int NV>
+template <int NV, int W>   // W = elements per chunk: 8 (16-byte accesses) when the row length allows, else 4
 __global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld, long k_off,
                                                      const float* __restrict__ gamma_q,
                                                      const float* __restrict__ gamma_k, long rows,
                                                      int dim, int groups, int count, float eps) {
+  typedef __bf16 vec_t __attribute__((ext_vector_type(W)));
   long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (R >= 2 * rows) return;
   const bool is_k = R >= rows;
   if (is_k) R -= rows;
   const float* gamma = is_k ? gamma_k : gamma_q;
   const int lane = threadIdx.x & 63;
-  bf16x4* x = reinterpret_cast<bf16x4*>(buf + (is_k ? k_off : 0) + (R / groups) * ld + (R % groups) * (long)dim);
-  const int nchunk = dim >> 2;
-  bf16x4 v[NV > 0 ? NV : 1];
+  vec_t* x = reinterpret_cast<vec_t*>(buf + (is_k ? k_off : 0) + (R / groups) * ld + (R % groups) * (long)dim);
+  const int nchunk = dim / W;
+  vec_t v[NV > 0 ? NV : 1];
   float qs = 0.f;
   if (NV > 0) {
 #pragma unroll
@@ -178,24 +179,27 @@ __global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld, long 
       if (c < nchunk) {
         v[i] = x[c];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) qs += (float)v[i][e] * (float)v[i][e];
+        for (int e = 0; e < W; ++e) qs += (float)v[i][e] * (float)v[i][e];
       }
     }
   } else {
     for (int c = lane; c < nchunk; c += 64) {
-      const bf16x4 a = x[c];
+      const vec_t a = x[c];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) qs += (float)a[e] * (float)a[e];
+      for (int e = 0; e < W; ++e) qs += (float)a[e] * (float)a[e];
     }
   }
   const float rstd = 1.0f / sqrtf(wave_sum(qs) / count + eps);
-  auto emit = [&](int c, bf16x4 a) {
-    const float4 gm = *(reinterpret_cast<const float4*>(gamma) + c);
-    bf16x4 o;
-    o[0] = (bf16_t)((float)a[0] * rstd * gm.x);
-    o[1] = (bf16_t)((float)a[1] * rstd * gm.y);
-    o[2] = (bf16_t)((float)a[2] * rstd * gm.z);
-    o[3] = (bf16_t)((float)a[3] * rstd * gm.w);
+  auto emit = [&](int c, vec_t a) {
+    vec_t o;
+#pragma unroll
+    for (int h = 0; h < W / 4; ++h) {
+      const float4 gm = *(reinterpret_cast<const float4*>(gamma) + c * (W / 4) + h);
+      o[4 * h + 0] = (bf16_t)((float)a[4 * h + 0] * rstd * gm.x);
+      o[4 * h + 1] = (bf16_t)((float)a[4 * h + 1] * rstd * gm.y);
+      o[4 * h + 2] = (bf16_t)((float)a[4 * h + 2] * rstd * gm.z);
+      o[4 * h + 3] = (bf16_t)((float)a[4 * h + 3] * rstd * gm.w);
+    }
     x[c] = o;
   };
   if (NV > 0) {
@@ -209,14 +213,24 @@ __global__ __launch_bounds__(256) void k_bf16_qknorm(bf16_t* buf, long ld, long 
   }
 }
 
+template <int W>
+static void bf16_qknorm_w(bf16_t* buf, long ld, long k_off, const float* gamma_q, const float* gamma_k, long rows,
+                          int dim, int groups, int count, float eps, hipStream_t st) {
+  const dim3 grid((unsigned)((2 * rows + 3) / 4)), block(256);
+  const int per_lane = (dim / W + 63) / 64;
+  if (per_lane <= 2) k_bf16_qknorm<2, W><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  else if (per_lane <= 8) k_bf16_qknorm<8, W><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  else if (per_lane <= 16 && W == 4) k_bf16_qknorm<16, W><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  else k_bf16_qknorm<0, W><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+}
+
 void bf16_qknorm(bf16_t* buf, long ld, long k_off, const float* gamma_q, const float* gamma_k, long rows, int dim,
                  int groups, int count, float eps, hipStream_t st) {
   if (rows == 0) return;
-  const dim3 grid((unsigned)((2 * rows + 3) / 4)), block(256);
-  const int per_lane = (dim / 4 + 63) / 64;
-  if (per_lane <= 2) k_bf16_qknorm<2><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
-  else if (per_lane <= 16) k_bf16_qknorm<16><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
-  else k_bf16_qknorm<0><<<grid, block, 0, st>>>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps);
+  // 16-byte chunks when every row starts on a 16-byte boundary and holds whole chunks
+  const bool wide = dim % 8 == 0 && ld % 8 == 0 && k_off % 8 == 0 && (reinterpret_cast<uintptr_t>(buf) & 15) == 0;
+  if (wide) bf16_qknorm_w<8>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps, st);
+  else bf16_qknorm_w<4>(buf, ld, k_off, gamma_q, gamma_k, rows, dim, groups, count, eps, st);
 }
 
 // ---------------------------------------------- LayerNorm of bf16 rows ------
