@@ -1006,7 +1006,31 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   const long tiles256 = (long)((p.M + BM - 1) / BM) * (p.Npad / 256);
   if (tiles256 * 4 <= cu_count() && p.K % 256 == 0) return dispatch<128, 512, 64, 2, 128>(p, st);
   if (tiles256 * 2 <= cu_count()) return dispatch<128, 512, 64, 0, 128>(p, st);   // beyond that the small tiles lose (13 slices: +9 %)
-  if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st);
+  if (p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) {
+    // A batch of a few rounds whose last round fills at most half of the CUs (the SigLIP-shaped request of
+    // 10 slices: 360 tiles of its q/k projection = 1.4 rounds) is cut by rows like the long-K residual
+    // products below: whole rounds on the persistent kernel, the remaining rows as one round of 256 x 128
+    // tiles.  Same bits.  The plain loop of those tiles is slower per flop, so the cut pays only while the
+    // last round is a large part of the launch.
+    if (p.cfg == 0 && p.epi != EPI_VT && (!p.row_map || p.block_tokens > 0)) {
+      const long cu = cu_count(), gn = p.Npad / 256, gm = (p.M + BM - 1) / BM;
+      const long rounds = tiles256 / cu, rem = tiles256 % cu;
+      const long rows_a = rounds * cu / gn;
+      const long tiles_b = (gm - rows_a) * gn;
+      if (rounds >= 1 && rounds <= 2 && rem > 0 && rows_a >= 1 && rows_a < gm && tiles_b * 2 <= cu &&
+          (!p.row_map || (rows_a * BM) % p.block_tokens == 0)) {
+        GemmParams a = p, b = p;
+        a.M = (int)(rows_a * BM);
+        b.M = p.M - a.M;
+        b.A = p.A + (long)a.M * p.lda;
+        if (p.row_map) b.row_map = p.row_map + a.M / p.block_tokens;
+        else b.C = p.C + (long)a.M * p.ldc;
+        const hipError_t e = dispatch_persist(a, st);
+        return e != hipSuccess ? e : dispatch<128, 512, 64>(b, st);
+      }
+    }
+    return dispatch_persist(p, st);
+  }
   // A last round that fills at most half of the CUs costs a whole tile time.  The residual product
   // (rows are independent, all addressing is by pointer) is cut by rows instead: whole rounds of
   // 256-wide tiles, then the remaining rows as one round of 128-wide tiles, half as long.  Same bits.

@@ -55,6 +55,33 @@ def test_c2_siglip_shape_10_slices():
     enc.close()
 
 
+def test_c2_paged_encode_and_shares_carry_the_bits_of_the_whole_call():
+    """At this size the library cuts some products by rows (whole rounds of 256-wide tiles plus one round of
+    narrower ones): the paged output, whose rows go through the block table on both sides of the cut, and the
+    shares of 3 + 7 slices, whose products are cut elsewhere or not at all, must carry the same bits."""
+    wk = wl.workload("c2")
+    enc, tiles = build(wk)
+    n = enc.tokens_per_tile
+    whole = enc.encode(tiles, list(wk.tile_offsets)).clone()
+    parts = torch.empty_like(whole)
+    enc.encode(tiles[:3], [0, 3], parts[:3 * n])
+    enc.encode(tiles[3:], [0, 7], parts[3 * n:])
+    torch.cuda.synchronize()
+    assert torch.equal(whole.view(torch.int16), parts.view(torch.int16))
+    n_blocks = 10 * n // 16
+    cache = B.MMCache(n_blocks + 7, 16, wk.desc.out_dim, True)
+    hole = cache.alloc(5 * 16)
+    table = cache.alloc(10 * n)[::-1]            # scattered, descending
+    cache.free(hole)
+    B.encode_paged(enc, tiles, list(wk.tile_offsets), cache, [table])
+    torch.cuda.synchronize()
+    got = cache.gather(table)
+    torch.cuda.synchronize()
+    assert torch.equal(whole.view(torch.int16), got.view(torch.int16))
+    cache.close()
+    enc.close()
+
+
 def test_c3_internvit300m_shape_104_slices():
     wk = wl.workload("c3")
     enc, tiles = build(wk)
