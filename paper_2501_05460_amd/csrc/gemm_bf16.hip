@@ -1017,7 +1017,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
       const long rounds = tiles256 / cu, rem = tiles256 % cu;
       const long rows_a = rounds * cu / gn;
       const long tiles_b = (gm - rows_a) * gn;
-      if (rounds >= 1 && rounds <= 2 && rem > 0 && rows_a >= 1 && rows_a < gm && tiles_b * 2 <= cu &&
+      if (rounds >= 1 && rounds <= 4 && rem > 0 && rows_a >= 1 && rows_a < gm && tiles_b * 2 <= cu &&
           (!p.row_map || (rows_a * BM) % p.block_tokens == 0)) {
         GemmParams a = p, b = p;
         a.M = (int)(rows_a * BM);
