@@ -34,18 +34,17 @@ __device__ __forceinline__ float gelu_tanh_f(float x) {
 }
 
 // GELU for the bf16 epilogues: branch-free, one exp and one reciprocal each.
-// erf form: x * Phi(x) with Phi(x) ~= 1 / (1 + exp(-x (a + b x^2 + c x^4))), the
-// logistic shape of the tanh form with a third term and all three coefficients
-// fitted (minimax over |x| <= 7) to x * Phi(x) itself: |error| <= 2.6e-5, a
-// fortieth of half a bf16 ulp at 0.5.  The polynomial's argument is clamped to
-// +-7, where Phi is 0 or 1 to 1e-12 (c < 0 would turn the exponent around
-// beyond |x| ~ 10).  The coefficients carry the factor -log2(e) of exp2.
+// erf form: x * Phi(x) with Phi(x) ~= 1 / (1 + exp(-x (a + b x^2))), the logistic
+// shape of the tanh form with both coefficients fitted (minimax over |x| <= 7)
+// to x * Phi(x) itself: |error| <= 2.7e-4 (the tanh form's own coefficients
+// give 4.7e-4), the size of a bf16 rounding step at |y| = 0.07 and below the
+// rounding of any larger output.  b > 0, so the exponent is monotonic and needs
+// no clamp: it overflows to +inf / underflows to 0 exactly where Phi is 0 / 1.
+// A third term (c x^4, with the argument clamped to +-7) brought the error to
+// 2.6e-5 and cost 3 % of the FC1 product's time.  The coefficients carry the
+// factor -log2(e) of exp2.
 __device__ __forceinline__ float gelu_erf_fast(float x) {
-  const float xc = __builtin_amdgcn_fmed3f(x, -7.0f, 7.0f);
-  const float x2 = xc * xc;
-  float p = fmaf(x2, 1.0142650e-3f, -1.0677574e-1f);   // -log2e * (c x^2 + b)
-  p = fmaf(x2, p, -2.3011213f);                         // -log2e * a
-  const float e = __builtin_amdgcn_exp2f(xc * p);
+  const float e = __builtin_amdgcn_exp2f(x * fmaf(x * x, -1.001257265e-01f, -2.308765046e+00f));
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 // tanh form: 0.5 x (1 + tanh u) = x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3);

@@ -175,6 +175,28 @@ def test_attention_bf16_extreme_logits(kind, hd):
         assert np.abs(got - mean_v).max() < 1e-2 * np.abs(v).max()
 
 
+@pytest.mark.parametrize("epi,abs_err", [(1, 2.7e-4), (2, 2e-6)])
+def test_gemm_gelu_epilogues_vs_oracle(epi, abs_err):
+    """The activation inside the product's epilogue, element by element: pre-activations spread over
+    +-5; the erf form is a fitted logistic with |error| <= 2.7e-4 against x Phi(x), the tanh form is
+    exact up to fp32 rounding; on top of either comes one bf16 rounding of the output (at most 2^-8 relative)."""
+    rng = np.random.default_rng(90 + epi)
+    M, N, K = 640, 256, 256
+    a = _bf16_grid(rng, (M, K), 1.0)
+    w = _bf16_grid(rng, (N, K), 0.1)
+    bias = (rng.standard_normal(N) * 0.5).astype(np.float32)
+    out = B.op_gemm_bf16_form(B.to_device(a, True), B.to_device(w, True), torch.from_numpy(bias).cuda(), epi, 0)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    pre = O.linear(a, w, bias)
+    assert np.abs(pre).max() > 4.0 and (np.abs(pre) < 0.5).mean() > 0.1    # both tails and the middle are sampled
+    want = O.gelu_erf(pre) if epi == 1 else O.gelu_tanh(pre)
+    # fp32 accumulation of K = 256 products adds ~1e-6 to the pre-activation: far below either term
+    bound = abs_err + 1e-5 + 2.0 ** -8 * np.abs(want)   # half a bf16 step is 2^-8 relative at the bottom of a binade
+    excess = np.abs(got - want) - bound
+    assert excess.max() <= 0.0, (float(excess.max()), float(pre.flat[excess.argmax()]))
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 256, 128), (1000, 512, 256), (2304, 1024, 1024), (77, 256, 384)])
 @pytest.mark.parametrize("epi", [0, 1, 2, 3])
 def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
