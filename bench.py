@@ -25,7 +25,7 @@ PEAK_FP32_TFLOPS = 157.3
 # L2 <-> fabric bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain
 # 1 GiB copy kernel gives), averaged over all k_gemm_bf16 launches of one step; measured with
 # rocprofv3 --pmc, summary and commands in profiles/c3_bench_hbm_traffic.txt.
-TRAFFIC_BYTES_PER_GEMM_LAUNCH = {"c3": 1331.0e6, "c2": 213.9e6}
+TRAFFIC_BYTES_PER_GEMM_LAUNCH = {"c3": 1329.0e6, "c2": 176.6e6}
 
 
 def gemm_flops_per_tile(desc):
