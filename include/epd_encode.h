@@ -18,7 +18,12 @@
  * allocates or frees the caller's buffers; all device work of a call is
  * enqueued on the caller's HIP stream and the call returns after enqueueing.
  * A context serves one stream at a time (calls on one context must not
- * overlap).  epd_encode / epd_encode_range allocate nothing.
+ * overlap); different contexts may be driven from different host threads.
+ * epd_encode / epd_encode_range allocate nothing.  If a HIP call fails in the
+ * middle of a call (EPD_ERR_HIP: a launch or copy refused by the runtime),
+ * earlier launches of that call may already have written part of the output:
+ * its contents are then undefined.  Every other error is found before the
+ * first launch and leaves the output untouched.
  */
 #ifndef EPD_ENCODE_H
 #define EPD_ENCODE_H
@@ -128,7 +133,10 @@ epd_status epd_check_desc(const epd_model_desc* desc, char* errbuf, int32_t errb
 epd_status epd_check_offsets(const int32_t* tile_offsets_per_request /*host*/, int32_t n_requests,
                              int32_t n_tiles);
 
-/* Create a worker context on the current HIP device: validates the
+/* Create an encode worker's context on the current HIP device.  An encode
+ * worker holds the encoder weights and its multimodal-token cache and nothing
+ * of the language model (Section 3.2, "System Design and Optimization"): the
+ * context is that state.  Validates the
  * description, copies and repacks the weights into the kernels' layout
  * (device allocations owned by the context), allocates the workspace for
  * max_tiles_per_call slices.  `hip_stream` (a hipStream_t, may be null = the
@@ -166,14 +174,21 @@ epd_status epd_encode_range(epd_ctx* ctx, const float* tiles, int32_t n_tiles_to
                             int32_t tile_begin, int32_t tile_end, void* out_token_cache,
                             void* hip_stream);
 
-int64_t epd_tokens_per_tile(const epd_ctx* ctx); /* N_out = N or N/4 */
-int64_t epd_out_dim(const epd_ctx* ctx);         /* D_out            */
+/* Shape of the token block a slice yields, v = E(i_m) (Section 3.1): the block
+ * manager sizes a request's cache entry from its slice count times these
+ * (Section 3.2.1).  -1 for a null ctx. */
+int64_t epd_tokens_per_tile(const epd_ctx* ctx); /* N_out = N, N/4 with pixel shuffle, or the resampler's query count */
+int64_t epd_out_dim(const epd_ctx* ctx);         /* D_out */
 
 /* Last error message of this context (owned by the context, never freed by
  * the caller); for a null ctx the message of the last failed epd_create /
  * host-only check on this thread. */
 const char* epd_last_error(const epd_ctx* ctx);
 
+/* Release the worker's state: packed weights and workspace (what the paper's
+ * role switching offloads when an encode worker is turned into another
+ * stage's worker, Section 3.2.4).  The caller synchronises the stream first.
+ * Null is a no-op. */
 void epd_destroy(epd_ctx* ctx);
 
 /* ---- paged multimodal-token cache ---------------------------------------
@@ -261,63 +276,6 @@ epd_status epd_encode_trunk_paged(epd_ctx* ctx, const float* tiles, int32_t n_ti
  * (16-byte aligned).  The cache is only read. */
 epd_status epd_project_merge(epd_ctx* ctx, const epd_mm_cache* cache, const int32_t* block_table,
                              int32_t n_tiles, void* out_tokens, void* hip_stream);
-
-/* ---- measurement and test hooks (not needed to serve) ------------------ */
-
-/* Copy the residual stream (float32 [rows, D], the encoder state after the
- * last layer of the last micro-batch of the previous call) to host memory.
- * Synchronises the device.  rows * D * 4 must be <= dst_bytes. */
-epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst /*host*/, int64_t rows, int64_t dst_bytes);
-
-/* Time the dominant kernel family in isolation: runs `iters` launches of the
- * bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  (+ bias) on dev buffers the
- * caller provides, bracketed by HIP events on `hip_stream`; returns the mean
- * milliseconds per launch in *ms_per_launch.  A [M,K] bf16, W [N,K] bf16,
- * bias [N] fp32 (may be null), C [M,N] bf16.  M % 256 == 0, N % 128 == 0,
- * K % 128 == 0. */
-epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M,
-                            int32_t N, int32_t K, int32_t iters, float* ms_per_launch,
-                            void* hip_stream);
-
-/* One launch of the bf16 MFMA GEMM in a chosen form, for tests that hold the forms against each
- * other: epi 0 bias, 1 bias + GELU(erf), 2 bias + GELU(tanh) -> C [M,N] bf16; epi 3 -> R [M,N]
- * fp32 += A W^T + bias (C unused).  form 0 = what the library would pick, 1 = 256x128 tile,
- * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
- * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 9), K % 128 == 0; bias [N] fp32.
- * The kernels read whole 256-row tiles: A must be readable for round_up(M, 256) rows and R for
- * round_up(M, 256) rows plus 256 floats; no row past M is written. */
-epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias, void* C, float* R,
-                                 int32_t M, int32_t N, int32_t K, int32_t epi, int32_t form,
-                                 void* hip_stream);
-
-/* Tile-local non-causal attention on packed slices, bf16:  for every slice t
- * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
- * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
- * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
- * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0;
- * `scale` multiplies the logits.  Only the first n_keys (1 .. n_tokens) rows of a slice are tokens:
- * the others are left out of every softmax as keys, and their rows of o hold unused values. */
-epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
-                                 int32_t n_slices, int32_t n_tokens, int32_t n_keys, int32_t heads,
-                                 int32_t hd_pad, int32_t ld_qk, float scale, void* hip_stream);
-
-/* Check of the MFMA operand / result lane layout the kernels assume:
- * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one
- * v_mfma_f32_32x32x16_bf16.  All pointers dev. */
-epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream);
-
-/* Per-kernel-family timing of the previous epd_encode / epd_encode_range
- * call on this context, measured with HIP events on the call's stream.
- * epd_profile_enable(ctx, 1) makes subsequent calls bracket every launch
- * with two event records; epd_profile_read synchronises the device and fills
- * ms[family] (summed) and launches[family] (kernels launched: a product that
- * the library cuts into two launches counts twice).  Families: 0 im2col + patch-embed
- * GEMM, 1 pre-norms, 2 QKV GEMM, 3 attention, 4 q/k norm, 5 projector input
- * (shuffle / norm / convert), 6 out-proj GEMM, 7 FC1 GEMM, 8 FC2 GEMM,
- * 9 projector GEMMs. */
-enum { EPD_PROF_FAMILIES = 10 };
-epd_status epd_profile_enable(epd_ctx* ctx, int32_t on);
-epd_status epd_profile_read(epd_ctx* ctx, float* ms /*host [10]*/, int32_t* launches /*host [10]*/);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,76 @@
+/*
+ * epd_encode_test.h  --  measurement and test hooks of the encode-stage library.
+ *
+ * Not needed to serve: single kernels in isolation (parity tests hold them
+ * against the CPU oracle step by step), per-kernel-family timing (the
+ * benchmark's roofline figures) and a read-back of the residual stream.  Same
+ * conventions as epd_encode.h.  These calls may allocate and synchronise.
+ */
+#ifndef EPD_ENCODE_TEST_H
+#define EPD_ENCODE_TEST_H
+
+#include "epd_encode.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Copy the residual stream (float32 [rows, D], the encoder state after the
+ * last layer of the last micro-batch of the previous call) to host memory.
+ * Synchronises the device.  rows * D * 4 must be <= dst_bytes. */
+epd_status epd_debug_read_stream(epd_ctx* ctx, void* dst /*host*/, int64_t rows, int64_t dst_bytes);
+
+/* Time the dominant kernel family in isolation: runs `iters` launches of the
+ * bf16 MFMA GEMM  C[M,N] = A[M,K] * W[N,K]^T  (+ bias) on dev buffers the
+ * caller provides, bracketed by HIP events on `hip_stream`; returns the mean
+ * milliseconds per launch in *ms_per_launch.  A [M,K] bf16, W [N,K] bf16,
+ * bias [N] fp32 (may be null), C [M,N] bf16.  M % 256 == 0, N % 128 == 0,
+ * K % 128 == 0. */
+epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int32_t M,
+                            int32_t N, int32_t K, int32_t iters, float* ms_per_launch,
+                            void* hip_stream);
+
+/* One launch of the bf16 MFMA GEMM in a chosen form, for tests that hold the forms against each
+ * other: epi 0 bias, 1 bias + GELU(erf), 2 bias + GELU(tanh) -> C [M,N] bf16; epi 3 -> R [M,N]
+ * fp32 += A W^T + bias (C unused).  form 0 = what the library would pick, 1 = 256x128 tile,
+ * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
+ * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 9), K % 128 == 0; bias [N] fp32.
+ * A [M,K], C [M,N] and R [M,N] hold exactly M rows; no row past M is written.  (The kernels read whole
+ * 256-row tiles; for a ragged M, and for R, the call runs on padded copies it allocates, and synchronises.) */
+epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias, void* C, float* R,
+                                 int32_t M, int32_t N, int32_t K, int32_t epi, int32_t form,
+                                 void* hip_stream);
+
+/* Tile-local non-causal attention on packed slices, bf16:  for every slice t
+ * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
+ * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
+ * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
+ * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0;
+ * `scale` multiplies the logits.  Only the first n_keys (1 .. n_tokens) rows of a slice are tokens:
+ * the others are left out of every softmax as keys, and their rows of o hold unused values. */
+epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
+                                 int32_t n_slices, int32_t n_tokens, int32_t n_keys, int32_t heads,
+                                 int32_t hd_pad, int32_t ld_qk, float scale, void* hip_stream);
+
+/* Check of the MFMA operand / result lane layout the kernels assume:
+ * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one
+ * v_mfma_f32_32x32x16_bf16.  All pointers dev. */
+epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream);
+
+/* Per-kernel-family timing of the previous epd_encode / epd_encode_range
+ * call on this context, measured with HIP events on the call's stream.
+ * epd_profile_enable(ctx, 1) makes subsequent calls bracket every launch
+ * with two event records; epd_profile_read synchronises the device and fills
+ * ms[family] (summed) and launches[family] (kernels launched: a product that
+ * the library cuts into two launches counts twice).  Families: 0 im2col + patch-embed
+ * GEMM, 1 pre-norms, 2 QKV GEMM, 3 attention, 4 q/k norm, 5 projector input
+ * (shuffle / norm / convert), 6 out-proj GEMM, 7 FC1 GEMM, 8 FC2 GEMM,
+ * 9 projector GEMMs. */
+enum { EPD_PROF_FAMILIES = 10 };
+epd_status epd_profile_enable(epd_ctx* ctx, int32_t on);
+epd_status epd_profile_read(epd_ctx* ctx, float* ms /*host [10]*/, int32_t* launches /*host [10]*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPD_ENCODE_TEST_H */

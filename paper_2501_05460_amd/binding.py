@@ -283,6 +283,18 @@ class MMCache:
     def free_blocks(self) -> int:
         return lib().epd_mm_cache_free_blocks(self._h)
 
+    def pool_tensor(self) -> torch.Tensor:
+        """The device pool itself as a tensor [n_blocks, block_tokens, token_dim] (a view of the library's
+        memory, no copy): valid until close()."""
+        base = lib().epd_mm_cache_base(self._h)
+        shape = (self.n_blocks, self.block_tokens, self.token_dim)
+
+        class _Raw:   # bf16 has no typestr: the pool is exposed as 16-bit integers and viewed as bf16
+            __cuda_array_interface__ = {"shape": shape, "typestr": "<i2" if self.bf16 else "<f4",
+                                        "data": (int(base), False), "version": 2}
+        t = torch.as_tensor(_Raw(), device="cuda")
+        return t.view(torch.bfloat16) if self.bf16 else t
+
     def alloc(self, n_tokens: int) -> List[int]:
         cap = (n_tokens + self.block_tokens - 1) // self.block_tokens
         ids = (ctypes.c_int32 * max(cap, 1))()
@@ -361,32 +373,26 @@ def op_gemm_bf16_form(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, epi:
                       R: Optional[torch.Tensor] = None) -> torch.Tensor:
     """One GEMM launch in the given form; returns C (bf16) or, for epi 3, the updated R (fp32, in place).
 
-    The kernels read whole 256-row tiles of A and R, so both are handed over in buffers of
-    round_up(M, 256) rows; the output buffer carries the same rows as a guard, and a call that
-    writes any row past M raises."""
+    The output buffer carries guard rows behind row M; a call that writes any of them raises."""
     M, K = A.shape
     N = W.shape[0]
-    Mp = (M + 255) // 256 * 256
-    Ap = torch.zeros((Mp, K), dtype=A.dtype, device=A.device)
-    Ap[:M] = A
     guard = 12345.0
-    if epi != 3:
-        Cp = torch.full((Mp, N), guard, dtype=torch.bfloat16, device=A.device)
-        Rp = None
-    else:
-        Cp = None
-        Rp = torch.full((Mp * N + 256,), guard, dtype=torch.float32, device=A.device)
-        Rp[:M * N] = R.reshape(-1)
-    s = lib().epd_op_gemm_bf16_form(Ap.data_ptr(), W.data_ptr(), bias.data_ptr(), Cp.data_ptr() if Cp is not None else None,
-                                    Rp.data_ptr() if Rp is not None else None, M, N, K, epi, form, _stream_ptr())
+    Cg = torch.full((M + 64, N), guard, dtype=torch.bfloat16, device=A.device) if epi != 3 else None
+    Rg = None
+    if epi == 3:
+        Rg = torch.full((M + 64, N), guard, dtype=torch.float32, device=A.device)
+        Rg[:M] = R
+    s = lib().epd_op_gemm_bf16_form(A.contiguous().data_ptr(), W.data_ptr(), bias.data_ptr(),
+                                    Cg.data_ptr() if Cg is not None else None,
+                                    Rg.data_ptr() if Rg is not None else None, M, N, K, epi, form, _stream_ptr())
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())
-    tail = Cp[M:] if epi != 3 else Rp[M * N:]
+    tail = Cg[M:] if epi != 3 else Rg[M:]
     if not bool((tail == guard).all()):
         raise RuntimeError("GEMM form %d wrote rows past M=%d" % (form, M))
     if epi != 3:
-        return Cp[:M]
-    R.copy_(Rp[:M * N].view(M, N))
+        return Cg[:M]
+    R.copy_(Rg[:M])
     return R
 
 

@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) rv[i] = *reinterpret_cast<const u32x4*>(vblk + voff[i]);
   };
-  auto sstore = [&](int buf) {
+  // kb: the key block the staged registers hold
+  auto sstore = [&](int buf, int kb) {
 #pragma unroll
     for (int i = 0; i < K_LOADS; ++i) {
       const int c = tid + 256 * i;
@@ -170,6 +171,15 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       // [0-3, 8-11, 4-7, 12-15]: keys 8ch+0..3 -> position 16(ch/2) + 4(ch%2),
       // keys 8ch+4..7 -> position 16(ch/2) + 8 + 4(ch%2)
       bf16_t* dst = sV + buf * SM::V_ELEMS + row * SM::V_LD + (ch >> 1) * 16 + (ch & 1) * 4;
+      if (MASK && (kb + 1) * BKEY > n_keys) {   // uniform: only the last block(s) of a slice whose rows are padded
+        // Values of keys past n_keys are no part of the slice (the next slice's, or whatever an earlier call
+        // left in the workspace): their weights are exactly zero, but 0 * NaN or 0 * Inf would still poison
+        // the sum, so they are cleared on the way into LDS.  Word j of the chunk holds keys key0 + 2j, + 2j + 1.
+        const int key0 = kb * BKEY + ch * 8;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          rv[i][j] &= (key0 + 2 * j < n_keys ? 0x0000ffffu : 0u) | (key0 + 2 * j + 1 < n_keys ? 0xffff0000u : 0u);
+      }
       u32x2 lo = {rv[i][0], rv[i][1]}, hi = {rv[i][2], rv[i][3]};
       *reinterpret_cast<u32x2*>(dst) = lo;
       *reinterpret_cast<u32x2*>(dst + 8) = hi;
@@ -307,7 +317,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       sV[(e / PAD_ELEMS) * SM::V_ELEMS + HD * SM::V_LD + e % PAD_ELEMS] =
           (bf16_t)(e % PAD_ELEMS < SM::V_LD ? 1.0f : 0.f);   // row HD: ones (sums the weights), the rest zero
   }
-  sstore(0);
+  sstore(0, 0);
   __syncthreads();
 
   // Software pipeline over the 32-key steps: the S^T MFMAs of the next step
@@ -327,7 +337,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
       softmax(s1, p1, kb * BKEY + 32, false);
       issue_pv(p1, vs, 1);
     }
-    sstore((kb + 1) & 1);   // the other buffer: nobody reads it after the previous barrier
+    sstore((kb + 1) & 1, kb + 1 < NB ? kb + 1 : kb);   // the other buffer: nobody reads it after the previous barrier
     __syncthreads();
     if (any_act && kb + 1 < NB) issue_s(s0, sK + ((kb + 1) & 1) * SM::K_ELEMS, 0);
   }
@@ -358,14 +368,11 @@ template <int HD, int QT, bool MASK>
 hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                          int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
                          hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)AttnSmem<HD>::BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  // once per instantiation; the initialisation of a function-local static is safe against concurrent callers
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)AttnSmem<HD>::BYTES);
+  if (attr != hipSuccess) return attr;
   constexpr int BQ = 128 * QT;
   const int n_qb = (n_q + BQ - 1) / BQ, n_pairs = n_slices * heads;
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;

@@ -1,6 +1,7 @@
 // C boundary of the encode-stage library: validation, weight packing,
 // workspace, and the per-micro-batch launch sequence.  See include/epd_encode.h.
 #include "../../include/epd_encode.h"
+#include "../../include/epd_encode_test.h"
 
 #include <cstdarg>
 #include <algorithm>
@@ -148,6 +149,14 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
     }
   }
   if (x.N > 16384) { set_err(err, len, "more than 16384 patches per slice is not supported"); return EPD_ERR_UNSUPPORTED; }
+  if (d->dtype == EPD_DTYPE_FP32) {
+    // the fp32 attention kernel keeps one query's logits and the query itself in LDS (64 KiB without opt-in)
+    const int hdr = d->proj_kind == EPD_PROJ_RESAMPLER ? d->proj_out / d->proj_heads : 0;
+    if (((long)x.Nt + std::max(x.hd, hdr)) * 4 > 65536) {
+      set_err(err, len, "fp32 mode supports at most %d tokens per slice at this head dim", 16384 - std::max(x.hd, hdr));
+      return EPD_ERR_UNSUPPORTED;
+    }
+  }
   return EPD_OK;
 }
 
@@ -212,6 +221,13 @@ struct epd_ctx {
 
   // paged output (epd_encode_paged): device row-block map of the current micro-batch
   int* d_rowmap = nullptr;       // [mb * N] ints (enough for any block size, trunk or projector rows)
+  // the caller's (pageable) block table reaches d_rowmap through two pinned staging buffers used in turn,
+  // each guarded by an event recorded behind its upload: the copy is truly asynchronous, and the host only
+  // waits when a call has more than two micro-batches in flight
+  int* h_rowmap[2] = {nullptr, nullptr};
+  hipEvent_t ev_rowmap[2] = {nullptr, nullptr};
+  bool rowmap_pending[2] = {false, false};
+  int rowmap_turn = 0;
   const int* cur_rowmap = nullptr;  // null: contiguous output
   int cur_block_tokens = 1;
   const void* cur_in_pool = nullptr;  // STAGE_PROJECT: cache pool the pre-projection tokens are read from
@@ -488,6 +504,10 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   // the residual GEMM prefetches whole 256-column tile rows: one padded row of slack behind the last
   c->X = (float*)ws(((size_t)c->Mp * x.D + 256) * sizeof(float));
   c->d_rowmap = (int*)ws((size_t)M * sizeof(int));
+  for (int i = 0; i < 2; ++i) {
+    if (hipHostMalloc((void**)&c->h_rowmap[i], (size_t)M * sizeof(int), hipHostMallocDefault) != hipSuccess) { c->h_rowmap[i] = nullptr; ok = false; }
+    if (hipEventCreateWithFlags(&c->ev_rowmap[i], hipEventDisableTiming) != hipSuccess) { c->ev_rowmap[i] = nullptr; ok = false; }
+  }
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
     // the attention kernel reads whole 64-key blocks: up to 63 rows / elements past the last slice
@@ -805,7 +825,13 @@ epd_status encode_range_impl(epd_ctx* c, const float* tiles, int32_t n_total, in
     if (block_map) {
       // this micro-batch's slice of the map; the copy is stream-ordered behind the previous micro-batch
       const size_t first = (size_t)(t0 - map_origin) * map_rows / block_tokens, count = (size_t)T * map_rows / block_tokens;
-      HIP_TRY(c, hipMemcpyAsync(c->d_rowmap, block_map + first, count * sizeof(int), hipMemcpyHostToDevice, st));
+      const int turn = c->rowmap_turn;
+      c->rowmap_turn ^= 1;
+      if (c->rowmap_pending[turn]) HIP_TRY(c, hipEventSynchronize(c->ev_rowmap[turn]));   // its previous upload has left the staging
+      memcpy(c->h_rowmap[turn], block_map + first, count * sizeof(int));
+      HIP_TRY(c, hipMemcpyAsync(c->d_rowmap, c->h_rowmap[turn], count * sizeof(int), hipMemcpyHostToDevice, st));
+      HIP_TRY(c, hipEventRecord(c->ev_rowmap[turn], st));
+      c->rowmap_pending[turn] = true;
       c->cur_block_tokens = block_tokens;
       if (stage == STAGE_FULL) c->cur_rowmap = c->d_rowmap;   // final GEMM scatters through the map
       if (stage != STAGE_PROJECT) op = (char*)out;            // paged output: `out` is the pool base
@@ -898,54 +924,13 @@ epd_status epd_encode_range(epd_ctx* ctx, const float* tiles, int32_t n_tiles_to
   return encode_range_impl(ctx, tiles, n_tiles_total, tile_begin, tile_end, out, (hipStream_t)hip_stream);
 }
 
-epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles, const int32_t* off, int32_t n_requests,
-                            epd_mm_cache* cache, const int32_t* block_table, const int32_t* block_table_offsets,
-                            void* hip_stream) {
-  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
-  epd_status s = epd_check_offsets(off, n_requests, n_tiles);
-  if (s != EPD_OK) { strncpy(ctx->err, g_err, sizeof(ctx->err) - 1); return s; }
-  if (n_tiles == 0) return EPD_OK;
-  if (!cache || !block_table || !block_table_offsets) {
-    set_err(ctx->err, sizeof(ctx->err), "cache / block_table / block_table_offsets is null");
-    return EPD_ERR_INVALID_ARG;
-  }
-  const Dims& x = ctx->x;
-  if (!cache->pool || cache->token_dim != x.Pout || cache->dtype != ctx->d.dtype) {
-    set_err(ctx->err, sizeof(ctx->err), "cache token width / dtype (%d, %d) does not match the encoder (%d, %d)",
-            cache->token_dim, cache->dtype, x.Pout, ctx->d.dtype);
-    return EPD_ERR_SHAPE;
-  }
-  if (x.N_out % cache->block_tokens) {
-    set_err(ctx->err, sizeof(ctx->err), "tokens per slice %d is not a multiple of the block size %d", x.N_out,
-            cache->block_tokens);
-    return EPD_ERR_UNSUPPORTED;
-  }
-  const int bpt = x.N_out / cache->block_tokens;  // blocks per slice
-  if (block_table_offsets[0] != 0) { set_err(ctx->err, sizeof(ctx->err), "block_table_offsets[0] must be 0"); return EPD_ERR_OFFSETS; }
-  for (int r = 0; r < n_requests; ++r) {
-    const long want = (long)(off[r + 1] - off[r]) * bpt;
-    if (block_table_offsets[r + 1] - block_table_offsets[r] != want) {
-      set_err(ctx->err, sizeof(ctx->err), "request %d needs %ld blocks, its block table holds %d", r, want,
-              block_table_offsets[r + 1] - block_table_offsets[r]);
-      return EPD_ERR_OFFSETS;
-    }
-  }
-  const long total = (long)n_tiles * bpt;
-  for (long i = 0; i < total; ++i)
-    if (block_table[i] < 0 || block_table[i] >= cache->n_blocks || !cache->used[block_table[i]]) {
-      set_err(ctx->err, sizeof(ctx->err), "block table entry %ld (%d) is out of range or not allocated", i, block_table[i]);
-      return EPD_ERR_OFFSETS;
-    }
-  // requests are contiguous in slice order and own whole blocks, so the concatenated
-  // per-request tables are the logical-block -> physical-block map of the packed batch
-  return encode_range_impl(ctx, tiles, n_tiles, 0, n_tiles, cache->pool, (hipStream_t)hip_stream, block_table,
-                           cache->block_tokens);
-}
+}  // extern "C"
 
 namespace {
 // cache shape against a token width, and `count` table entries against the block manager
-epd_status check_cache_table(epd_ctx* ctx, const epd_mm_cache* cache, int token_dim, int rows_per_slice,
-                             const int32_t* table, long count) {
+// (range, allocated, and for a table the call writes through: no block listed twice)
+epd_status check_cache_table(epd_ctx* ctx, epd_mm_cache* cache, int token_dim, int rows_per_slice,
+                             const int32_t* table, long count, bool written) {
   if (!cache || !table) { set_err(ctx->err, sizeof(ctx->err), "cache / block_table is null"); return EPD_ERR_INVALID_ARG; }
   if (!cache->pool || cache->token_dim != token_dim || cache->dtype != ctx->d.dtype) {
     set_err(ctx->err, sizeof(ctx->err), "cache token width / dtype (%d, %d) does not match the encoder (%d, %d)",
@@ -962,9 +947,58 @@ epd_status check_cache_table(epd_ctx* ctx, const epd_mm_cache* cache, int token_
       set_err(ctx->err, sizeof(ctx->err), "block table entry %ld (%d) is out of range or not allocated", i, table[i]);
       return EPD_ERR_OFFSETS;
     }
+  if (written) {
+    // two logical blocks on one physical block would overwrite each other: `mark` (all zero between calls)
+    long dup = -1;
+    for (long i = 0; i < count && dup < 0; ++i) {
+      if (cache->mark[table[i]]) dup = i;
+      else cache->mark[table[i]] = 1;
+    }
+    for (long i = 0; i < (dup < 0 ? count : dup); ++i) cache->mark[table[i]] = 0;
+    if (dup >= 0) {
+      set_err(ctx->err, sizeof(ctx->err), "block table entry %ld names block %d a second time", dup, table[dup]);
+      return EPD_ERR_OFFSETS;
+    }
+  }
   return EPD_OK;
 }
 }  // namespace
+
+extern "C" {
+
+epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles, const int32_t* off, int32_t n_requests,
+                            epd_mm_cache* cache, const int32_t* block_table, const int32_t* block_table_offsets,
+                            void* hip_stream) {
+  if (!ctx) { set_err(g_err, sizeof(g_err), "ctx is null"); return EPD_ERR_INVALID_ARG; }
+  epd_status s = epd_check_offsets(off, n_requests, n_tiles);
+  if (s != EPD_OK) { strncpy(ctx->err, g_err, sizeof(ctx->err) - 1); return s; }
+  if (n_tiles == 0) return EPD_OK;
+  if (!cache || !block_table || !block_table_offsets) {
+    set_err(ctx->err, sizeof(ctx->err), "cache / block_table / block_table_offsets is null");
+    return EPD_ERR_INVALID_ARG;
+  }
+  const Dims& x = ctx->x;
+  s = check_cache_table(ctx, cache, x.Pout, x.N_out, block_table, 0, false);   // shape only; the entries follow
+  if (s != EPD_OK) return s;
+  const int bpt = x.N_out / cache->block_tokens;  // blocks per slice
+  if (block_table_offsets[0] != 0) { set_err(ctx->err, sizeof(ctx->err), "block_table_offsets[0] must be 0"); return EPD_ERR_OFFSETS; }
+  for (int r = 0; r < n_requests; ++r) {
+    const long want = (long)(off[r + 1] - off[r]) * bpt;
+    if (block_table_offsets[r + 1] - block_table_offsets[r] != want) {
+      set_err(ctx->err, sizeof(ctx->err), "request %d needs %ld blocks, its block table holds %d", r, want,
+              block_table_offsets[r + 1] - block_table_offsets[r]);
+      return EPD_ERR_OFFSETS;
+    }
+  }
+  const long total = (long)n_tiles * bpt;
+  s = check_cache_table(ctx, cache, x.Pout, x.N_out, block_table, total, true);
+  if (s != EPD_OK) return s;
+  // requests are contiguous in slice order and own whole blocks, so the concatenated
+  // per-request tables are the logical-block -> physical-block map of the packed batch
+  return encode_range_impl(ctx, tiles, n_tiles, 0, n_tiles, cache->pool, (hipStream_t)hip_stream, block_table,
+                           cache->block_tokens);
+}
+
 
 epd_status epd_encode_trunk_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles_total, int32_t tile_begin,
                                   int32_t tile_end, epd_mm_cache* cache, const int32_t* block_table,
@@ -977,7 +1011,7 @@ epd_status epd_encode_trunk_paged(epd_ctx* ctx, const float* tiles, int32_t n_ti
   if (tile_end == tile_begin) return EPD_OK;
   const Dims& x = ctx->x;
   const long count = cache && cache->block_tokens > 0 ? (long)(tile_end - tile_begin) * (x.N / cache->block_tokens) : 0;
-  epd_status s = check_cache_table(ctx, cache, x.D, x.N, block_table, count);
+  epd_status s = check_cache_table(ctx, cache, x.D, x.N, block_table, count, true);
   if (s != EPD_OK) return s;
   return encode_range_impl(ctx, tiles, n_tiles_total, tile_begin, tile_end, cache->pool, (hipStream_t)hip_stream,
                            block_table, cache->block_tokens, STAGE_TRUNK);
@@ -990,7 +1024,7 @@ epd_status epd_project_merge(epd_ctx* ctx, const epd_mm_cache* cache, const int3
   if (n_tiles == 0) return EPD_OK;
   const Dims& x = ctx->x;
   const long count = cache && cache->block_tokens > 0 ? (long)n_tiles * (x.N / cache->block_tokens) : 0;
-  epd_status s = check_cache_table(ctx, cache, x.D, x.N, block_table, count);
+  epd_status s = check_cache_table(ctx, const_cast<epd_mm_cache*>(cache), x.D, x.N, block_table, count, false);
   if (s != EPD_OK) return s;
   return encode_range_impl(ctx, nullptr, n_tiles, 0, n_tiles, out_tokens, (hipStream_t)hip_stream, block_table,
                            cache->block_tokens, STAGE_PROJECT, cache->pool);
@@ -1004,6 +1038,10 @@ void epd_destroy(epd_ctx* ctx) {
   if (!ctx) return;
   for (void* p : ctx->allocs) (void)hipFree(p);
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->h_rowmap[i]) (void)hipHostFree(ctx->h_rowmap[i]);
+    if (ctx->ev_rowmap[i]) (void)hipEventDestroy(ctx->ev_rowmap[i]);
+  }
   delete ctx;
 }
 
@@ -1068,12 +1106,42 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
     return EPD_ERR_INVALID_ARG;
   }
   if (bf16_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // The kernels read whole 256-row tiles of A and of the residual stream (the library's own workspace is
+  // padded that way).  The caller's buffers hold exactly M rows, so a ragged M runs on padded copies.
+  const long Mp = ((long)M + 255) / 256 * 256;
+  void* Ap = nullptr;
+  float* Rp = nullptr;
+  const bool pad_a = Mp != M, pad_r = residual;   // R also needs 256 floats of slack behind its last row
+  auto fail = [&](epd_status code, const char* what) {
+    if (Ap) (void)hipFree(Ap);
+    if (Rp) (void)hipFree(Rp);
+    set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16_form: %s", what);
+    return code;
+  };
+  if (pad_a) {
+    if (hipMalloc(&Ap, (size_t)Mp * K * 2) != hipSuccess) return fail(EPD_ERR_NOMEM, "allocation failed");
+    if (hipMemsetAsync(Ap, 0, (size_t)Mp * K * 2, st) != hipSuccess ||
+        hipMemcpyAsync(Ap, A, (size_t)M * K * 2, hipMemcpyDeviceToDevice, st) != hipSuccess) return fail(EPD_ERR_HIP, "copy failed");
+  }
+  if (pad_r) {
+    const size_t bytes = ((size_t)Mp * N + 256) * 4;
+    if (hipMalloc((void**)&Rp, bytes) != hipSuccess) return fail(EPD_ERR_NOMEM, "allocation failed");
+    if (hipMemsetAsync(Rp, 0, bytes, st) != hipSuccess ||
+        hipMemcpyAsync(Rp, R, (size_t)M * N * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) return fail(EPD_ERR_HIP, "copy failed");
+  }
   GemmParams p;
   memset(&p, 0, sizeof(p));
-  p.epi = epi; p.cfg = form; p.A = (const bf16_t*)A; p.lda = K; p.W = (const bf16_t*)W; p.bias = bias;
-  p.M = M; p.N = N; p.K = K; p.Npad = N; p.C = (bf16_t*)C; p.ldc = N; p.R = R; p.ldr = N; p.n_pos = 1;
-  const hipError_t err = bf16_gemm(p, (hipStream_t)hip_stream);
-  if (err != hipSuccess) { set_err(g_err, sizeof(g_err), "gemm launch failed: %s", hipGetErrorString(err)); return EPD_ERR_HIP; }
+  p.epi = epi; p.cfg = form; p.A = (const bf16_t*)(pad_a ? Ap : A); p.lda = K; p.W = (const bf16_t*)W; p.bias = bias;
+  p.M = M; p.N = N; p.K = K; p.Npad = N; p.C = (bf16_t*)C; p.ldc = N; p.R = pad_r ? Rp : R; p.ldr = N; p.n_pos = 1;
+  const hipError_t err = bf16_gemm(p, st);
+  if (err != hipSuccess) { fail(EPD_ERR_HIP, hipGetErrorString(err)); return EPD_ERR_HIP; }
+  if (pad_r && hipMemcpyAsync(R, Rp, (size_t)M * N * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) return fail(EPD_ERR_HIP, "copy failed");
+  if (pad_a || pad_r) {
+    if (hipStreamSynchronize(st) != hipSuccess) return fail(EPD_ERR_HIP, "synchronise failed");
+    if (Ap) (void)hipFree(Ap);
+    if (Rp) (void)hipFree(Rp);
+  }
   return EPD_OK;
 }
 

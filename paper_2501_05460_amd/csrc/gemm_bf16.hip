@@ -840,7 +840,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
 template <int BN, int NT, int BM_ = BM>
 constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT, BM_>() + BN * sizeof(float); }
 
-long g_kernel_launches = 0;   // kernels launched by bf16_gemm so far (a product may be cut into two launches)
+thread_local long g_kernel_launches = 0;   // kernels launched by bf16_gemm on this host thread so far (a product may be cut into two launches)
 
 template <int BN, int NT, int WN, int EPI, int PIPE, int BM_ = BM>
 hipError_t launch(const GemmParams& p, hipStream_t st) {

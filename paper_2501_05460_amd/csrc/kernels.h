@@ -55,8 +55,8 @@ struct GemmParams {
   int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
 };
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
-long bf16_gemm_kernel_launches();   // kernels launched by bf16_gemm so far in this process (not thread-safe: a figure for the profiling hooks)
-hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (once per process)
+long bf16_gemm_kernel_launches();   // kernels launched by bf16_gemm on the calling host thread so far (a figure for the profiling hooks)
+hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (idempotent: safe from any thread, any number of times)
 
 // A_pe[row][e] = bf16(pixel) for e < 3*p*p, 0 for the K padding up to lda.
 void bf16_im2col(const float* tiles, bf16_t* A, int lda, int T, int S, int p, hipStream_t st);

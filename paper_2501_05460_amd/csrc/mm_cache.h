@@ -13,5 +13,6 @@ struct epd_mm_cache {
   bool ev_pending = false;
   std::vector<int> free_list;  // LIFO of free block ids
   std::vector<unsigned char> used;
+  std::vector<unsigned char> mark;   // scratch of the table checks (duplicate detection), all zero between calls
   char err[256] = "";
 };

@@ -47,6 +47,7 @@ epd_status epd_mm_cache_create(int32_t n_blocks, int32_t block_tokens, int32_t t
   c->n_blocks = n_blocks; c->block_tokens = block_tokens; c->token_dim = token_dim; c->dtype = dtype;
   c->block_bytes = block_bytes;
   c->used.assign(n_blocks, 0);
+  c->mark.assign(n_blocks, 0);
   c->free_list.reserve(n_blocks);
   for (int i = n_blocks - 1; i >= 0; --i) c->free_list.push_back(i);  // block 0 is handed out first
   if (block_bytes > 0) {  // token_dim 0: manager only (planning, host tests), no device memory

@@ -15,10 +15,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="library not built")
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "epd_encode.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(epd_[a-z0-9_]+)\s*\(", text)))
+def header_functions(names=("epd_encode.h", "epd_encode_test.h")):
+    found = set()
+    for name in names:
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found |= set(re.findall(r"\b(epd_[a-z0-9_]+)\s*\(", text))
+    return sorted(found)
 
 
 def test_library_exports_every_declared_symbol():
@@ -28,6 +31,9 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(B.EXPORTS) == names
+    # the serving header carries no test or measurement hook
+    serving = header_functions(("epd_encode.h",))
+    assert not [n for n in serving if n.startswith(("epd_op_", "epd_profile_", "epd_debug_"))]
 
 
 def test_weight_count_matches_generator_order():
@@ -84,6 +90,14 @@ def test_check_desc_rejects(change, status):
     assert s == status, msg
     assert msg
     assert B.weight_count(d) == status
+
+
+def test_check_desc_caps_the_fp32_sequence_at_what_its_attention_kernel_holds_in_lds():
+    d = wl.workload("c1").desc
+    s, msg = B.check_desc(d.replace(tile_size=14 * 128))      # 16384 patches + head dim 64 floats > 64 KiB
+    assert s == B.EPD_ERR_UNSUPPORTED and "fp32" in msg
+    s, msg = B.check_desc(d.replace(tile_size=14 * 127))
+    assert s == B.EPD_OK, msg
 
 
 def test_check_offsets():

@@ -111,7 +111,10 @@ def test_c5_mixed_batch_sharded_equals_one_call_and_oracle():
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), full.view(torch.int16))
     del out
-    check_sample(wk, enc, full, wk.oracle_sample_tiles[:3])
+    # first / last slice of the first and the last request, and the first slice of each of the four
+    # shards of the largest request (the last slice of the batch lies in the partial last micro-batch)
+    assert len(wk.oracle_sample_tiles) == 8 and wk.oracle_sample_tiles[-1] == wk.n_tiles - 1
+    check_sample(wk, enc, full, wk.oracle_sample_tiles)
     enc.close()
 
 

@@ -145,3 +145,32 @@ def test_a_slice_alone_has_the_bits_it_has_inside_a_large_batch():
     torch.cuda.synchronize()
     assert np.array_equal(bits(few), bits(full[3 * n:7 * n]))
     enc.close()
+
+
+def test_a_slice_of_nan_pixels_poisons_neither_its_neighbours_nor_later_calls():
+    """Class-token shape: 65 tokens in 72 rows, so the last key block of every slice reaches into the next
+    slice's rows and values (masked keys, weight exactly zero).  A slice full of NaN must leave the other
+    slices of its batch bit-identical, and a smaller clean batch encoded afterwards on the same context (its
+    workspace still holding the NaN rows) must give the bits a fresh context gives."""
+    desc = desc_for(wl.DT_BF16, tile_size=112, class_token=1)
+    w = wl.gen_weights(desc, 61, std=0.08)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 61, 4)).cuda()
+    enc = make_encoder(desc, w)
+    n = enc.tokens_per_tile
+    clean = enc.encode(tiles, [0, 4]).clone()
+    bad = tiles.clone()
+    bad[2] = float("nan")
+    out = enc.encode(bad, [0, 4]).clone()
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out[2 * n:3 * n].float()).any())
+    for t in (0, 1, 3):
+        assert np.array_equal(bits(out[t * n:(t + 1) * n]), bits(clean[t * n:(t + 1) * n])), t
+    # a later, smaller call: slices 0 and 1 land where they were, the NaN rows of slice 2 stay behind them
+    later = enc.encode(tiles[:2], [0, 2]).clone()
+    fresh_enc = make_encoder(desc, w)
+    fresh = fresh_enc.encode(tiles[:2], [0, 2])
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(later), bits(fresh))
+    assert np.array_equal(bits(later), bits(clean[:2 * n]))
+    fresh_enc.close()
+    enc.close()

@@ -87,6 +87,38 @@ def test_paged_encode_transfer_and_release(dtype, tail):
     enc.close()
 
 
+@pytest.mark.parametrize("dtype", [wl.DT_BF16, wl.DT_FP32], ids=["bf16", "fp32"])
+def test_raw_pool_holds_the_oracle_index_map(dtype):
+    """The layout check without any copy kernel of the library: the pool is read as a plain tensor view of
+    its device pointer.  Every block a table names holds the 16 tokens the oracle's index map puts there
+    (the bits of the contiguous encode), every other block still holds the fill value."""
+    desc = desc_for(dtype)
+    w = wl.gen_weights(desc, 43, std=0.06)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 43, 5)).cuda()
+    offsets = [0, 2, 2, 5]
+    enc = make_encoder(desc, w)
+    n_out = enc.tokens_per_tile
+    full = enc.encode(tiles, offsets)
+    torch.cuda.synchronize()
+    cache = B.MMCache(40, BT, desc.out_dim, dtype == wl.DT_BF16)
+    pool = cache.pool_tensor()
+    assert tuple(pool.shape) == (40, BT, desc.out_dim)
+    pool.fill_(-7.0)
+    hole = cache.alloc(5 * BT)
+    tables = [cache.alloc((offsets[r + 1] - offsets[r]) * n_out) for r in range(3)]
+    cache.free(hole)
+    tables[0] = tables[0][::-1]
+    B.encode_paged(enc, tiles, offsets, cache, tables)
+    torch.cuda.synchronize()
+    want = np.full((40, BT, desc.out_dim), -7.0, np.float32)
+    for r in range(3):
+        O.paged_scatter(want, full[offsets[r] * n_out:offsets[r + 1] * n_out].float().cpu().numpy(), tables[r], BT)
+    assert np.array_equal(pool.float().cpu().numpy(), want)
+    del pool
+    cache.close()
+    enc.close()
+
+
 def test_paged_encode_leaves_other_blocks_untouched_and_rejects_bad_tables():
     desc = desc_for(wl.DT_BF16)
     w = wl.gen_weights(desc, 42, std=0.06)
@@ -110,6 +142,9 @@ def test_paged_encode_leaves_other_blocks_untouched_and_rejects_bad_tables():
     with pytest.raises(B.EpdError) as e:
         B.encode_paged(enc, tiles, [0, 3], cache, [mine[:-1] + rest[:1]])   # unallocated block
     assert e.value.status == B.EPD_ERR_OFFSETS
+    with pytest.raises(B.EpdError) as e:
+        B.encode_paged(enc, tiles, [0, 3], cache, [mine[:-1] + mine[:1]])   # one block listed twice
+    assert e.value.status == B.EPD_ERR_OFFSETS and "second time" in str(e.value)
     other = B.MMCache(20, BT, desc.out_dim + 8, True)
     with pytest.raises(B.EpdError) as e:
         B.encode_paged(enc, tiles, [0, 3], other, [other.alloc(3 * n_out)])  # wrong token width

@@ -179,7 +179,8 @@ def workload(name: str) -> Workload:
         return Workload("c3_internvit300m_8x13tiles", DESC_C3, 1003, 1003,
                         _prefix([13] * 8), img, (0, 12, 103))
     if name == "c4":
-        return Workload("c4_internvit6b_40tiles", DESC_C4, 1004, 1004, (0, 40), ((40,),), (0,))
+        # oracle sample: first, middle and last slice (the last one sits behind the largest buffer offsets)
+        return Workload("c4_internvit6b_40tiles", DESC_C4, 1004, 1004, (0, 40), ((40,),), (0, 20, 39))
     if name == "c5":
         image_tiles = _mixed_structure(1005)
         off = _prefix([sum(t) for t in image_tiles])
