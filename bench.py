@@ -22,10 +22,54 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_FP32_TFLOPS = 157.3
 
-# L2 <-> fabric bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain
-# 1 GiB copy kernel gives), averaged over all k_gemm_bf16 launches of one step; measured with
-# rocprofv3 --pmc, summary and commands in profiles/c3_bench_hbm_traffic.txt.
-TRAFFIC_BYTES_PER_GEMM_LAUNCH = {"c3": 1329.0e6, "c2": 176.6e6}
+TOL = {"bf16": 2e-2, "f32": 1e-4}   # max |gpu - oracle| / max |oracle| the parity sample must meet
+
+
+def traffic_from_profile(workload: str):
+    """L2 <-> fabric bytes per GEMM launch (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a plain 1 GiB
+    copy kernel gives on the same counters), as the committed rocprofv3 --pmc summary of this command states
+    it: the line `traffic_bytes_per_gemm_launch: <number>` of profiles/<workload>_bench_hbm_traffic.txt.
+    Returns (bytes or None, source)."""
+    rel = os.path.join("profiles", f"{workload}_bench_hbm_traffic.txt")
+    try:
+        for line in open(os.path.join(ROOT, rel)):
+            if line.startswith("traffic_bytes_per_gemm_launch:"):
+                return float(line.split(":", 1)[1].split()[0]), rel
+    except OSError:
+        pass
+    return None, None
+
+
+def roof_report(B, torch):
+    """Measured ceilings of this machine, one JSON line: register-resident MFMA loop (random and constant
+    operands), streaming copy, and the vendor BLAS (through torch.matmul) next to this library's plain
+    bias-epilogue product on the four per-layer shapes of the C3 workload and a large cube, ten launches
+    back to back each, random operands."""
+    out = {"mfma_loop_tflops_random_operands": round(B.op_mfma_peak(True), 1),
+           "mfma_loop_tflops_constant_operands": round(B.op_mfma_peak(False), 1),
+           "copy_GBps_read_plus_write_1GiB": round(B.op_copy_peak(), 1), "gemm": []}
+    g = torch.Generator(device="cuda").manual_seed(2)
+    for name, (M, N, K) in (("qk", (106496, 2048, 1024)), ("out_proj", (106496, 1024, 1024)),
+                            ("fc1", (106496, 4096, 1024)), ("fc2", (106496, 1024, 4096)), ("cube", (8192, 8192, 8192))):
+        A = torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16)
+        W = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        bias = torch.zeros(N, dtype=torch.float32, device="cuda")
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        torch.matmul(A, W.t(), out=C)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            torch.matmul(A, W.t(), out=C)
+        e1.record()
+        torch.cuda.synchronize()
+        vendor_ms = e0.elapsed_time(e1) / 10
+        _, lib_ms = B.op_gemm_bf16(A, W, bias, iters=10)
+        fl = 2.0 * M * N * K
+        out["gemm"].append({"shape": name, "M": M, "N": N, "K": K,
+                            "vendor_blas_tflops": round(fl / vendor_ms / 1e9, 1),
+                            "this_library_tflops": round(fl / lib_ms / 1e9, 1)})
+        del A, W, C
+    return out
 
 
 def gemm_flops_per_tile(desc):
@@ -65,6 +109,9 @@ def main():
                     help="also encode the first 1, 2, 4, ... slices of the first request alone (what one encode "
                          "worker sees when a request's slices are cut over several workers) and report the "
                          "latency of each share next to that of the whole request")
+    ap.add_argument("--roof", action="store_true",
+                    help="measure this box's ceilings instead of the workload (MFMA loop, streaming copy, vendor "
+                         "BLAS and this library on the per-layer shapes) and print them as one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -80,6 +127,10 @@ def main():
     if not os.path.exists(B.LIB_PATH):
         from paper_2501_05460_amd.build import build
         build()
+
+    if args.roof:
+        print(json.dumps({"roof": roof_report(B, torch)}))
+        return
 
     wk = wl.workload(args.workload)
     desc = wk.desc
@@ -112,13 +163,19 @@ def main():
 
     for _ in range(args.warmup):
         enc.encode(tiles, offsets, out)
+    # every step also sits between two events on the call's stream (torch's current stream is the one the
+    # binding hands to the library): their median is reported next to the wall-clock mean
+    step_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for e0, e1 in step_ev:
+        e0.record()
         enc.encode(tiles, offsets, out)
+        e1.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t1
     ms_per_step = elapsed / args.steps * 1e3
+    ms_median = float(np.median([e0.elapsed_time(e1) for e0, e1 in step_ev]))
     tiles_per_s = T * args.steps / elapsed
     tokens_per_s = tiles_per_s * desc.tokens_per_tile
     total_flops = wl.flops_per_tile(desc) * T
@@ -141,16 +198,36 @@ def main():
     gemm_launches = sum(fam[k]["launches"] for k in gf)
     gemm_flops = sum(gf.values()) * T * prof_steps
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    traffic, traffic_source = traffic_from_profile(args.workload) if desc.max_tiles_per_call == wk.desc.max_tiles_per_call else (None, None)
     roofline = {
         "bound": "mfma", "kernel": "k_gemm_bf16 (all epilogue variants)" if bf16 else "k_f32_gemm",
         "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-        "traffic": TRAFFIC_BYTES_PER_GEMM_LAUNCH.get(args.workload) if desc.max_tiles_per_call == wk.desc.max_tiles_per_call else None,
+        # what a register-resident MFMA loop reaches on this machine right now (random operands; no memory, no LDS)
+        "achievable_peak": round(B.op_mfma_peak(True), 1) if bf16 else None,
+        "traffic": traffic, "traffic_source": traffic_source,
         "flops_per_launch": gemm_flops / max(gemm_launches, 1),
         "avg_launch_ms": gemm_ms / max(gemm_launches, 1),
         "families_ms_per_step": {k: round(v["ms"] / prof_steps, 3) for k, v in fam.items()},
         "families_tflops": {k: round(gf[k] * T * prof_steps / (fam[k]["ms"] * 1e-3) / 1e12, 1)
                             for k in gf if fam[k]["ms"] > 0},
     }
+
+    # ---- the kernels bound by memory bandwidth: algorithmic bytes / event-bracketed time ----
+    hbm = None
+    if bf16:
+        M_rows = T * desc.seq_len
+        Dq = desc.hidden                      # q and k rows as stored (head padding not counted)
+        per_launch = {
+            "norm": M_rows * desc.hidden * (4 + 2),                                  # fp32 row in, bf16 row out
+            "qk_norm": M_rows * 2 * Dq * (2 + 2),                                    # q and k, read and written, bf16
+            "proj_input": T * desc.tokens_per_tile * desc.proj_in * (4 + 2) if desc.proj_kind != 2 else None,
+        }
+        hbm = {"peak_GBps": 8000.0, "copy_GBps_measured": round(B.op_copy_peak(), 1)}
+        for k, nbytes in per_launch.items():
+            if nbytes and fam[k]["launches"] > 0 and fam[k]["ms"] > 0:
+                gbps = nbytes * fam[k]["launches"] / (fam[k]["ms"] * 1e-3) / 1e9
+                hbm[k] = {"GBps": round(gbps, 1), "frac_of_peak": round(gbps / 8000.0, 3),
+                          "bytes_per_launch": nbytes, "launches_per_step": fam[k]["launches"] // prof_steps}
 
     # ---- maximum encode batch size: latency of one call against throughput ----
     sweep = None
@@ -232,6 +309,10 @@ def main():
         mm = {"block_tokens": 16, "blocks": n_blocks, "paged_encode_ms_per_step": round(paged_ms, 3),
               "transfer_ms": round(xfer_ms, 4), "transfer_bytes": nbytes,
               "transfer_GBps_read_plus_write": round(2 * nbytes / (xfer_ms * 1e-3) / 1e9, 1)}
+        if hbm is not None:
+            hbm["block_copy"] = {"GBps": mm["transfer_GBps_read_plus_write"],
+                                 "frac_of_peak": round(mm["transfer_GBps_read_plus_write"] / 8000.0, 3),
+                                 "bytes_per_launch": 2 * nbytes, "note": "whole epd_mm_transfer call incl. the id upload"}
         e_cache.close()
         p_cache.close()
         # projection on the prefill side: cache and move pre-projection tokens, project after the move
@@ -296,15 +377,23 @@ def main():
         "patch_tokens_per_sec": round(tiles_per_s * desc.n_patches, 1),
         "algorithmic_tflops": round(tflops, 2),
         "mfma_util_pct_of_peak": round(100.0 * tflops / peak, 2),
+        "ms_per_step_median_events": round(ms_median, 3),
         "parity_max_rel_err_sample": parity,
+        "parity_tolerance": TOL["bf16" if bf16 else "f32"],
+        "parity_ok": None if parity is None else bool(parity < TOL["bf16" if bf16 else "f32"]),
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
+        "hbm_kernels": hbm,
         "cpu_baseline": cpu,
         "mm_cache": mm,
         "batch_sweep": sweep,
         "shard_sweep": shard,
     }
     print(json.dumps(line))
+    if line["parity_ok"] is False:
+        print(f"bench.py: parity sample {parity:.3e} exceeds the tolerance {line['parity_tolerance']:.0e}: "
+              "the throughput above is not a valid result", file=sys.stderr)
+        sys.exit(3)
 
 
 if __name__ == "__main__":

@@ -70,6 +70,18 @@ enum { EPD_PROF_FAMILIES = 10 };
 epd_status epd_profile_enable(epd_ctx* ctx, int32_t on);
 epd_status epd_profile_read(epd_ctx* ctx, float* ms /*host [10]*/, int32_t* launches /*host [10]*/);
 
+/* Measured ceilings next to the nominal ones (the roofline figures of the benchmark).
+ * epd_op_mfma_peak: a register-resident loop of v_mfma_f32_32x32x16_bf16 on every CU (two waves per SIMD,
+ * eight independent accumulators, eight rotating operand fragment pairs, no LDS or memory traffic inside
+ * the loop); *tflops = dense bf16 rate over `reps` launches of `iters` loop trips.  operands: dev, 16 KiB of
+ * bf16 the fragments are loaded from (random values: the operand buses toggle as in a real product), or
+ * null for constant ones (the chip clocks higher on those).  sink: dev, 4 bytes per launched thread
+ * (2 * CUs * 256 floats), keeps the loop alive.
+ * epd_op_copy_peak: dst = src, `bytes` (multiple of 16) in 16-byte pieces; *gbps = read + write rate. */
+epd_status epd_op_mfma_peak(const void* operands, int32_t iters, int32_t reps, float* sink, float* tflops,
+                            void* hip_stream);
+epd_status epd_op_copy_peak(const void* src, void* dst, int64_t bytes, int32_t reps, float* gbps, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ EXPORTS = (
     "epd_weight_count", "epd_check_desc", "epd_check_offsets", "epd_create", "epd_encode",
     "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
-    "epd_profile_enable", "epd_profile_read",
+    "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_gather",
     "epd_encode_trunk_paged", "epd_project_merge",
@@ -103,6 +103,10 @@ def lib() -> ctypes.CDLL:
         L.epd_profile_enable.restype = i32
         L.epd_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.epd_profile_read.restype = i32
+        L.epd_op_mfma_peak.argtypes = [vp, i32, i32, vp, ctypes.POINTER(ctypes.c_float), vp]
+        L.epd_op_mfma_peak.restype = i32
+        L.epd_op_copy_peak.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_float), vp]
+        L.epd_op_copy_peak.restype = i32
         L.epd_mm_cache_create.argtypes = [i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.epd_mm_cache_create.restype = i32
         L.epd_mm_cache_destroy.argtypes = [vp]
@@ -413,3 +417,30 @@ def op_mfma_probe(A: torch.Tensor, B: torch.Tensor) -> torch.Tensor:
     if s != EPD_OK:
         raise EpdError(s, "mfma probe failed")
     return D
+
+
+def op_mfma_peak(random_operands: bool, iters: int = 2000, reps: int = 5) -> float:
+    """Dense bf16 TFLOP/s of a register-resident MFMA loop on every CU (random or constant operands)."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(2 * cus * 256, dtype=torch.float32, device="cuda")
+    ops = None
+    if random_operands:
+        g = torch.Generator(device="cuda").manual_seed(1)
+        ops = torch.randn(8192, device="cuda", generator=g).to(torch.bfloat16)
+    out = ctypes.c_float()
+    s = lib().epd_op_mfma_peak(ops.data_ptr() if ops is not None else None, iters, reps, sink.data_ptr(),
+                               ctypes.byref(out), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "mfma peak probe failed")
+    return out.value
+
+
+def op_copy_peak(n_bytes: int = 1 << 30, reps: int = 5) -> float:
+    """Read + write GB/s of a plain streaming copy of n_bytes."""
+    src = torch.ones(n_bytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    out = ctypes.c_float()
+    s = lib().epd_op_copy_peak(src.data_ptr(), dst.data_ptr(), n_bytes, reps, ctypes.byref(out), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "copy peak probe failed")
+    return out.value

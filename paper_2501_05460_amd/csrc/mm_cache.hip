@@ -97,9 +97,13 @@ epd_status epd_mm_free(epd_mm_cache* c, const int32_t* block_ids, int32_t n_ids)
   if (!c || n_ids < 0 || (n_ids > 0 && !block_ids)) return EPD_ERR_INVALID_ARG;
   // validate everything first: a bad list frees nothing
   if (!ids_ok(c, block_ids, n_ids, true)) { mm_err(c, "epd_mm_free: id out of range or block not allocated"); return EPD_ERR_INVALID_ARG; }
-  for (int i = 0; i < n_ids; ++i)
-    for (int j = i + 1; j < n_ids; ++j)
-      if (block_ids[i] == block_ids[j]) { mm_err(c, "epd_mm_free: duplicate id in the list"); return EPD_ERR_INVALID_ARG; }
+  int dup = -1;   // `mark` is all zero between calls
+  for (int i = 0; i < n_ids && dup < 0; ++i) {
+    if (c->mark[block_ids[i]]) dup = i;
+    else c->mark[block_ids[i]] = 1;
+  }
+  for (int i = 0; i < (dup < 0 ? n_ids : dup); ++i) c->mark[block_ids[i]] = 0;
+  if (dup >= 0) { mm_err(c, "epd_mm_free: duplicate id in the list"); return EPD_ERR_INVALID_ARG; }
   for (int i = 0; i < n_ids; ++i) { c->used[block_ids[i]] = 0; c->free_list.push_back(block_ids[i]); }
   return EPD_OK;
 }
