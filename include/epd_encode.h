@@ -242,6 +242,19 @@ epd_status epd_encode_paged(epd_ctx* ctx, const float* tiles, int32_t n_tiles,
 epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
                            const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream);
 
+/* epd_mm_transfer for callers that must not allocate device memory while they run: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it.  Same arguments, same result, same validation;
+ * the block-id lists the copy kernel reads sit in a static device array of the library
+ * (2 x EPD_MM_NOALLOC_MAX_BLOCKS ints, 512 KiB per GPU, held until the process ends) instead of the
+ * destination cache's own scratch, and the call allocates and frees nothing.  More than
+ * EPD_MM_NOALLOC_MAX_BLOCKS blocks in one call: EPD_ERR_UNSUPPORTED, nothing enqueued (cut the transfer
+ * into several calls).  Every call on a GPU shares that GPU's array and keeps the previous call's ids in
+ * it: calls are safe one after the other on one stream; two of these calls in flight at once on the same
+ * GPU (different streams or host threads) race on the array. */
+enum { EPD_MM_NOALLOC_MAX_BLOCKS = 65536 };
+epd_status epd_mm_transfer_noalloc(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
+                                   const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream);
+
 /* Copy blocks[0..n_blocks) of `src`, in that order, into a contiguous dev
  * buffer (16-byte aligned) of n_blocks * block_tokens tokens. */
 epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blocks, void* dst_contiguous,

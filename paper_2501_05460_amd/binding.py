@@ -33,7 +33,7 @@ EXPORTS = (
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
-    "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_gather",
+    "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_transfer_noalloc", "epd_mm_gather",
     "epd_encode_trunk_paged", "epd_project_merge",
 )
 
@@ -126,6 +126,8 @@ def lib() -> ctypes.CDLL:
         L.epd_encode_paged.restype = i32
         L.epd_mm_transfer.argtypes = [vp, ctypes.POINTER(i32), vp, ctypes.POINTER(i32), i32, vp]
         L.epd_mm_transfer.restype = i32
+        L.epd_mm_transfer_noalloc.argtypes = [vp, ctypes.POINTER(i32), vp, ctypes.POINTER(i32), i32, vp]
+        L.epd_mm_transfer_noalloc.restype = i32
         L.epd_mm_gather.argtypes = [vp, ctypes.POINTER(i32), i32, vp, vp]
         L.epd_mm_gather.restype = i32
         L.epd_encode_trunk_paged.argtypes = [vp, vp, i32, i32, i32, vp, ctypes.POINTER(i32), vp]
@@ -321,8 +323,10 @@ class MMCache:
             self._raise(s)
         return out
 
-    def transfer_to(self, src_ids: Sequence[int], dst: "MMCache", dst_ids: Sequence[int]):
-        s = lib().epd_mm_transfer(self._h, _i32(src_ids), dst._h, _i32(dst_ids), len(src_ids), _stream_ptr())
+    def transfer_to(self, src_ids: Sequence[int], dst: "MMCache", dst_ids: Sequence[int], noalloc: bool = False):
+        """noalloc: the entry point that keeps its id lists in the library's static device array."""
+        fn = lib().epd_mm_transfer_noalloc if noalloc else lib().epd_mm_transfer
+        s = fn(self._h, _i32(src_ids), dst._h, _i32(dst_ids), len(src_ids), _stream_ptr())
         if s != EPD_OK:
             dst._raise(s)
 

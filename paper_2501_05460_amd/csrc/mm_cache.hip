@@ -12,7 +12,36 @@
 
 using namespace epd;
 
+#include <mutex>
+
+// Block-id lists of epd_mm_transfer_noalloc: source ids, then destination ids.  One array per GPU the
+// library runs on, held until the process ends; every call on a GPU shares it.
+static __device__ __align__(256) int scratch[2 * EPD_MM_NOALLOC_MAX_BLOCKS];
+
 namespace {
+// In host code `scratch` is only a handle: the array's address on a device is asked for once per device,
+// with that device current, and kept here.
+constexpr int MAX_DEVICES = 64;
+int* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+std::mutex g_scratch_mu;
+
+hipError_t scratch_on_current_device(int** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    int* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 thread_local char g_mm_err[256] = "";
 void mm_err(epd_mm_cache* c, const char* msg) {
   snprintf(g_mm_err, sizeof(g_mm_err), "%s", msg);
@@ -111,15 +140,51 @@ epd_status epd_mm_free(epd_mm_cache* c, const int32_t* block_ids, int32_t n_ids)
 }  // extern "C"
 
 namespace {
-// `n_lists` id lists of n ints each -> c->d_ids, back to back, through the pinned staging (waits for the
-// previous upload of this cache before the staging is overwritten)
-bool upload_ids(epd_mm_cache* c, const int32_t* const* lists, int n_lists, int n, hipStream_t st) {
+// `n_lists` id lists of n ints each -> d_dst (c->d_ids, or the static array), back to back, through the
+// cache's pinned staging (waits for the previous upload of this cache before the staging is overwritten)
+bool upload_ids(epd_mm_cache* c, int* d_dst, const int32_t* const* lists, int n_lists, int n, hipStream_t st) {
   if (c->ev_pending && hipEventSynchronize(c->ev_ids) != hipSuccess) return false;
   for (int l = 0; l < n_lists; ++l) memcpy(c->h_ids + (size_t)l * n, lists[l], (size_t)n * sizeof(int));
-  if (hipMemcpyAsync(c->d_ids, c->h_ids, (size_t)n_lists * n * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) return false;
+  if (hipMemcpyAsync(d_dst, c->h_ids, (size_t)n_lists * n * sizeof(int), hipMemcpyHostToDevice, st) != hipSuccess) return false;
   if (hipEventRecord(c->ev_ids, st) != hipSuccess) return false;
   c->ev_pending = true;
   return true;
+}
+}  // namespace
+
+namespace {
+// body of the two transfer calls; ids_dev: where the id lists go on the device (null: the static array of
+// the current device, looked up once every argument has passed its checks)
+epd_status transfer_impl(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
+                         const int32_t* dst_blocks, int32_t n_blocks, int* ids_dev, const char* who, hipStream_t st) {
+  char msg[160];
+  if (src->block_bytes != dst->block_bytes || src->block_tokens != dst->block_tokens || src->dtype != dst->dtype ||
+      !src->pool || !dst->pool) {
+    snprintf(msg, sizeof(msg), "%s: the two caches must have the same block shape and a device pool", who);
+    mm_err(dst, msg);
+    return EPD_ERR_SHAPE;
+  }
+  if (n_blocks > src->n_blocks || n_blocks > dst->n_blocks || !ids_ok(src, src_blocks, n_blocks, true) ||
+      !ids_ok(dst, dst_blocks, n_blocks, true)) {
+    snprintf(msg, sizeof(msg), "%s: block id out of range or not allocated", who);
+    mm_err(dst, msg);
+    return EPD_ERR_OFFSETS;
+  }
+  if (n_blocks == 0) return EPD_OK;
+  if (!ids_dev && scratch_on_current_device(&ids_dev) != hipSuccess) {
+    snprintf(msg, sizeof(msg), "%s: the address of the static id array is not available on this device", who);
+    mm_err(dst, msg);
+    return EPD_ERR_HIP;
+  }
+  // source ids, then destination ids, one upload
+  const int32_t* lists[2] = {src_blocks, dst_blocks};
+  if (!upload_ids(dst, ids_dev, lists, 2, n_blocks, st)) {
+    snprintf(msg, sizeof(msg), "%s: id upload failed", who);
+    mm_err(dst, msg);
+    return EPD_ERR_HIP;
+  }
+  mm_copy_blocks(src->pool, ids_dev, dst->pool, ids_dev + n_blocks, n_blocks, src->block_bytes, st);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
 }  // namespace
 
@@ -128,27 +193,23 @@ extern "C" {
 epd_status epd_mm_transfer(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
                            const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream) {
   if (!src || !dst || n_blocks < 0 || (n_blocks > 0 && (!src_blocks || !dst_blocks))) return EPD_ERR_INVALID_ARG;
-  if (src->block_bytes != dst->block_bytes || src->block_tokens != dst->block_tokens || src->dtype != dst->dtype ||
-      !src->pool || !dst->pool) {
-    mm_err(dst, "epd_mm_transfer: the two caches must have the same block shape and a device pool");
-    return EPD_ERR_SHAPE;
+  // id lists travel in the destination cache's own device scratch (one transfer at a time per destination)
+  return transfer_impl(src, src_blocks, dst, dst_blocks, n_blocks, dst->d_ids, "epd_mm_transfer", (hipStream_t)hip_stream);
+}
+
+epd_status epd_mm_transfer_noalloc(const epd_mm_cache* src, const int32_t* src_blocks, epd_mm_cache* dst,
+                                   const int32_t* dst_blocks, int32_t n_blocks, void* hip_stream) {
+  if (!src || !dst || n_blocks < 0 || (n_blocks > 0 && (!src_blocks || !dst_blocks))) return EPD_ERR_INVALID_ARG;
+  if (n_blocks > EPD_MM_NOALLOC_MAX_BLOCKS) {
+    char msg[160];
+    snprintf(msg, sizeof(msg), "epd_mm_transfer_noalloc: %d blocks in one call, the static id array holds %d; "
+             "cut the transfer into several calls", n_blocks, EPD_MM_NOALLOC_MAX_BLOCKS);
+    mm_err(dst, msg);
+    return EPD_ERR_UNSUPPORTED;
   }
-  if (n_blocks > src->n_blocks || n_blocks > dst->n_blocks || !ids_ok(src, src_blocks, n_blocks, true) ||
-      !ids_ok(dst, dst_blocks, n_blocks, true)) {
-    mm_err(dst, "epd_mm_transfer: block id out of range or not allocated");
-    return EPD_ERR_OFFSETS;
-  }
-  if (n_blocks == 0) return EPD_OK;
-  hipStream_t st = (hipStream_t)hip_stream;
-  // id lists travel in the destination cache's scratch (one transfer at a time per destination):
-  // source ids, then destination ids, one upload
-  const int32_t* lists[2] = {src_blocks, dst_blocks};
-  if (!upload_ids(dst, lists, 2, n_blocks, st)) {
-    mm_err(dst, "epd_mm_transfer: id upload failed");
-    return EPD_ERR_HIP;
-  }
-  mm_copy_blocks(src->pool, dst->d_ids, dst->pool, dst->d_ids + n_blocks, n_blocks, src->block_bytes, st);
-  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+  // Nothing in the array has to start at zero: entries [0, 2 n_blocks) are rewritten by this call's upload
+  // and the kernel reads no others.
+  return transfer_impl(src, src_blocks, dst, dst_blocks, n_blocks, nullptr, "epd_mm_transfer_noalloc", (hipStream_t)hip_stream);
 }
 
 epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blocks, void* dst_contiguous,
@@ -163,7 +224,7 @@ epd_status epd_mm_gather(epd_mm_cache* src, const int32_t* blocks, int32_t n_blo
   if (n_blocks == 0) return EPD_OK;
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t* lists[1] = {blocks};
-  if (!upload_ids(src, lists, 1, n_blocks, st)) return EPD_ERR_HIP;
+  if (!upload_ids(src, src->d_ids, lists, 1, n_blocks, st)) return EPD_ERR_HIP;
   mm_copy_blocks(src->pool, src->d_ids, dst_contiguous, nullptr, n_blocks, src->block_bytes, st);
   return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
