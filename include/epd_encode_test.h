@@ -41,6 +41,25 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
                                  int32_t M, int32_t N, int32_t K, int32_t epi, int32_t form,
                                  void* hip_stream);
 
+/* The pre-norms of a layer have no kernel of their own in bf16 mode: the residual epilogue that updates a row
+ * x also stores bf16(x) and the row's statistics, and the product that follows the norm runs on bf16(x) against
+ * weights that carry the norm's gain, applying mean and 1 / sqrt(variance + eps) in its epilogue.  Statistics of
+ * a row: one pair (mean, sum of squared deviations from that mean) per group of 128 columns, stats
+ * [rows][ceil(dim / 128)][2] fp32.
+ * epd_op_row_stats: xb [rows, dim] bf16 = x [rows, dim] fp32 and the pairs of every row (dim % 4 == 0).
+ * epd_op_gemm_residual_stats: R [M,N] fp32 += A [M,K] W [N,K]^T + bias as epd_op_gemm_bf16_form's epi 3 (forms
+ *   0, 1, 2, 3, 6, 7), and xb [M,N] = bf16 of the updated R with its pairs in stats [M][N / 128][2];
+ *   M % 256 == 0 here, and R must hold 256 floats behind its last row.
+ * epd_op_norm_gemm_bf16: C [M,N] bf16 = act(norm(x) W^T + bias) the folded way: x [M,D] fp32, gamma / beta [D]
+ *   fp32 (beta null: RMSNorm), W [N,D] bf16, bias [N] fp32; epi 0 none, 1 GELU(erf), 2 GELU(tanh); form as
+ *   epd_op_gemm_bf16_form; M % 256 == 0, N % 128 == 0, D % 128 == 0.  Allocates and synchronises. */
+epd_status epd_op_row_stats(const float* x, int64_t rows, int32_t dim, void* xb, float* stats, void* hip_stream);
+epd_status epd_op_gemm_residual_stats(const void* A, const void* W, const float* bias, float* R, void* xb, float* stats,
+                                      int32_t M, int32_t N, int32_t K, int32_t form, void* hip_stream);
+epd_status epd_op_norm_gemm_bf16(const float* x, const float* gamma, const float* beta, const void* W, const float* bias,
+                                 void* C, int32_t M, int32_t N, int32_t D, float eps, int32_t epi, int32_t form,
+                                 void* hip_stream);
+
 /* Tile-local non-causal attention on packed slices, bf16:  for every slice t
  * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
  * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk

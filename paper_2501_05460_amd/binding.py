@@ -32,6 +32,7 @@ EXPORTS = (
     "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
+    "epd_op_row_stats", "epd_op_gemm_residual_stats", "epd_op_norm_gemm_bf16",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_transfer_noalloc", "epd_mm_gather",
     "epd_encode_trunk_paged", "epd_project_merge",
@@ -107,6 +108,12 @@ def lib() -> ctypes.CDLL:
         L.epd_op_mfma_peak.restype = i32
         L.epd_op_copy_peak.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.epd_op_copy_peak.restype = i32
+        L.epd_op_row_stats.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.epd_op_row_stats.restype = i32
+        L.epd_op_gemm_residual_stats.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+        L.epd_op_gemm_residual_stats.restype = i32
+        L.epd_op_norm_gemm_bf16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, ctypes.c_float, i32, i32, vp]
+        L.epd_op_norm_gemm_bf16.restype = i32
         L.epd_mm_cache_create.argtypes = [i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.epd_mm_cache_create.restype = i32
         L.epd_mm_cache_destroy.argtypes = [vp]
@@ -448,3 +455,43 @@ def op_copy_peak(n_bytes: int = 1 << 30, reps: int = 5) -> float:
     if s != EPD_OK:
         raise EpdError(s, "copy peak probe failed")
     return out.value
+
+
+def op_row_stats(x: torch.Tensor):
+    """(bf16 copy, statistics pairs [rows, ceil(dim / 128), 2]) of the rows of x [rows, dim] fp32."""
+    rows, dim = x.shape
+    xb = torch.empty((rows, dim), dtype=torch.bfloat16, device=x.device)
+    stats = torch.full((rows, (dim + 127) // 128, 2), float("nan"), dtype=torch.float32, device=x.device)
+    s = lib().epd_op_row_stats(x.data_ptr(), rows, dim, xb.data_ptr(), stats.data_ptr(), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "row stats failed")
+    return xb, stats
+
+
+def op_gemm_residual_stats(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, R: torch.Tensor, form: int):
+    """R += A W^T + bias in place (fp32) in the given form; returns (bf16 copy of the new R, its statistics pairs)."""
+    M, K = A.shape
+    N = W.shape[0]
+    Rp = torch.zeros(M * N + 256, dtype=torch.float32, device=A.device)
+    Rp[:M * N] = R.reshape(-1)
+    xb = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    stats = torch.full((M, N // 128, 2), float("nan"), dtype=torch.float32, device=A.device)
+    s = lib().epd_op_gemm_residual_stats(A.data_ptr(), W.data_ptr(), bias.data_ptr(), Rp.data_ptr(), xb.data_ptr(),
+                                         stats.data_ptr(), M, N, K, form, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    R.copy_(Rp[:M * N].view(M, N))
+    return xb, stats
+
+
+def op_norm_gemm_bf16(x: torch.Tensor, gamma: torch.Tensor, beta: Optional[torch.Tensor], W: torch.Tensor,
+                      bias: torch.Tensor, eps: float, epi: int, form: int) -> torch.Tensor:
+    """act(norm(x) W^T + bias) with the norm folded into the product (beta None: RMSNorm)."""
+    M, D = x.shape
+    N = W.shape[0]
+    C = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    s = lib().epd_op_norm_gemm_bf16(x.data_ptr(), gamma.data_ptr(), beta.data_ptr() if beta is not None else None,
+                                    W.data_ptr(), bias.data_ptr(), C.data_ptr(), M, N, D, eps, epi, form, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return C

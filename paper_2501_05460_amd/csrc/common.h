@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -77,3 +78,97 @@ __device__ __forceinline__ float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
   return v;
 }
+
+// Sum over the 32 lanes of each half of a wave (lanes 0-31 and 32-63 apart); every lane of a half gets its
+// half's sum.  Four DPP exchanges inside the rows of 16 lanes (xor 1, xor 2, mirror inside 8, mirror inside
+// 16), then the two rows of a half are added through the row swap.  The additions of a step are the same
+// pair in both lanes that take part (a + b and b + a), so all lanes hold the same bits, and the order of
+// the additions depends on nothing but the lane numbers.
+__device__ __forceinline__ float half_wave_sum(float v) {
+  auto dpp = [](float x, auto ctrl) {
+    constexpr int C = decltype(ctrl)::value;
+    return __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), C, 0xf, 0xf, true));
+  };
+  v += dpp(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1, 0, 3, 2]
+  v += dpp(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2, 3, 0, 1]
+  v += dpp(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+  v += dpp(v, std::integral_constant<int, 0x140>{});   // row_mirror
+  const unsigned b = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane16_swap(b, b, false, false);   // r[0]: even rows in both rows of a pair, r[1]: odd rows
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Pre-norm statistics of a row of the residual stream, kept as one (mean, sum of squared deviations from that
+// mean) pair per group of 128 columns: each pair is exact to rounding whatever the row's offset, and the pairs
+// combine without cancellation (pairwise update of means and squared deviations).  STAT_GROUP columns per pair.
+#define STAT_GROUP 128
+
+// One group's pair from the four values a lane of the half-wave holds (lanes whose columns lie past the row
+// pass valid = false and contribute nothing); inv_cnt = 1 / (columns of the group inside the row).
+__device__ __forceinline__ void group_mean_m2(const f32x4 v, bool valid, float inv_cnt, float& mean, float& m2) {
+  const float s = valid ? (v[0] + v[1]) + (v[2] + v[3]) : 0.f;
+  mean = half_wave_sum(s) * inv_cnt;
+  float q = 0.f;
+  if (valid) {
+    const float a = v[0] - mean, b = v[1] - mean, c = v[2] - mean, d = v[3] - mean;
+    q = __builtin_fmaf(d, d, __builtin_fmaf(c, c, __builtin_fmaf(b, b, a * a)));
+  }
+  m2 = half_wave_sum(q);
+}
+
+// Mean and sum of squared deviations of a whole row of `dim` columns from its n_part pairs over groups of
+// `group` columns (the last group may be shorter), combined pairwise: no difference of large sums anywhere.
+// get(g) returns pair g as a float2.
+template <typename Get>
+__device__ __forceinline__ float2 combine_pairs(Get get, int n_part, int group, int dim) {
+  float ms = 0.f;
+  for (int g = 0; g < n_part; ++g) {
+    const int cnt = dim - g * group < group ? dim - g * group : group;
+    ms = __builtin_fmaf((float)cnt, get(g).x, ms);
+  }
+  const float mu = ms / (float)dim;
+  float m2 = 0.f;
+  for (int g = 0; g < n_part; ++g) {
+    const int cnt = dim - g * group < group ? dim - g * group : group;
+    const float2 pr = get(g);
+    const float d = pr.x - mu;
+    m2 += __builtin_fmaf((float)cnt * d, d, pr.y);
+  }
+  return make_float2(mu, m2);
+}
+
+// The pairs of one row held in registers: loaded in one batch (the loads are independent, so their latency
+// is paid once and can pass under other work), combined later into the row's mean and 1 / sqrt(variance + eps)
+// (rms: 1 / sqrt(mean square + eps), and the mean returned as 0: nothing is subtracted).  At most STAT_REGS
+// pairs per row: wider rows are first combined into a single pair per row by a kernel of their own.
+#define STAT_REGS 10
+struct RowPairs {
+  float2 pr[STAT_REGS];
+  __device__ __forceinline__ void load(const float* __restrict__ pairs, int n_part) {
+#pragma unroll
+    for (int g = 0; g < STAT_REGS; ++g)
+      pr[g] = g < n_part ? *reinterpret_cast<const float2*>(pairs + 2 * g) : make_float2(0.f, 0.f);
+  }
+  __device__ __forceinline__ void finish(int n_part, int group, int dim, int rms, float eps, float& mean, float& rstd) const {
+    float ms = 0.f;
+#pragma unroll
+    for (int g = 0; g < STAT_REGS; ++g)
+      if (g < n_part) {
+        const int cnt = dim - g * group < group ? dim - g * group : group;
+        ms = __builtin_fmaf((float)cnt, pr[g].x, ms);
+      }
+    const float mu = ms / (float)dim;
+    float m2 = 0.f;
+#pragma unroll
+    for (int g = 0; g < STAT_REGS; ++g)
+      if (g < n_part) {
+        const int cnt = dim - g * group < group ? dim - g * group : group;
+        const float d = pr[g].x - mu;
+        m2 += __builtin_fmaf((float)cnt * d, d, pr[g].y);
+      }
+    float var = m2 / (float)dim;
+    if (rms) var = __builtin_fmaf(mu, mu, var);
+    mean = rms ? 0.f : mu;
+    rstd = 1.0f / sqrtf(var + eps);
+  }
+};

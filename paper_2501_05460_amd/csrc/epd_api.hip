@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <cmath>
 #include <vector>
 
@@ -183,9 +184,14 @@ struct Resampler {
 struct LayerW {
   const float *n1_g = nullptr, *n1_b = nullptr, *n2_g = nullptr, *n2_b = nullptr, *qn_g = nullptr, *kn_g = nullptr;
   Linear qkv, v, o, fc1, fc2;  // bf16 mode: qkv holds q,k only and v the value projection
+  // folded pre-norms (bf16 mode): the weights of qkv, v (first norm) and fc1 (second norm) carry the norm's gain,
+  // their biases its shift, and these are the column sums of the packed weights the epilogues subtract the mean with
+  const float *qkv_cs = nullptr, *v_cs = nullptr, *fc1_cs = nullptr;
 };
 
 }  // namespace
+
+enum { NORM_CLASSIC = 0, NORM_COPY = 1, NORM_FOLD = 2 };
 
 struct epd_ctx {
   epd_model_desc d;
@@ -204,6 +210,20 @@ struct epd_ctx {
 
   // bf16 layout
   int hd_pad = 0, Dq = 0, Dq_k = 0, D_k = 0, F_k = 0, Kp_k = 0, Pin_k = 0, Pmid_k = 0;
+
+  // How the pre-norms of the layers run in bf16 mode (EPD_NORM_MODE = classic | copy | fold at epd_create):
+  //   NORM_CLASSIC  a row kernel reads the fp32 stream and writes the normalised bf16 operand (the default: the
+  //                 fastest of the three as measured, because the products' epilogues run with the matrix cores
+  //                 idle, so every store and every vector operation added there costs more than it saves);
+  //   NORM_COPY     the residual epilogues also leave bf16(x) in Xn and a row kernel normalises those rows in
+  //                 place: a third less traffic per norm;
+  //   NORM_FOLD     no norm kernel at all: the residual epilogues leave bf16(x) and the rows' statistics, the
+  //                 products run on bf16(x) against gain-scaled weights and apply mean / rstd in their epilogues.
+  int norm_mode = 0;
+  bool fold = false;        // norm_mode == NORM_FOLD
+  float* stats = nullptr;   // [Mp][n_part][2]: one pair per 128 columns, as the residual epilogues emit them
+  float* stats1 = nullptr;  // [Mp][2]: one pair per row, made from `stats` when a row has more pairs than the products take (wide models)
+  int n_part = 0;
 
   // workspace (sized for mb slices)
   int mb = 0;
@@ -350,6 +370,18 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     HIP_TRY(c, bf16_gemm_init());
   }
   const PackMap heads{x.hd, c->hd_pad, x.H};
+  if (bf) {
+    const char* m = getenv("EPD_NORM_MODE");
+    c->norm_mode = NORM_CLASSIC;
+    if (m && !strcmp(m, "copy")) c->norm_mode = x.D % 8 == 0 ? NORM_COPY : NORM_CLASSIC;   // the in-place kernel moves 16-byte chunks
+    else if (m && !strcmp(m, "fold")) c->norm_mode = NORM_FOLD;
+    else if (m && *m && strcmp(m, "classic")) {
+      set_err(c->err, sizeof(c->err), "EPD_NORM_MODE must be classic, copy or fold, got '%s'", m);
+      return EPD_ERR_INVALID_ARG;
+    }
+  }
+  c->fold = c->norm_mode == NORM_FOLD;
+  c->n_part = (x.D + STAT_GROUP - 1) / STAT_GROUP;
 
 #define NOMEM_IF(cond) do { if (cond) { set_err(c->err, sizeof(c->err), "device allocation failed (weights)"); return EPD_ERR_NOMEM; } } while (0)
 
@@ -418,6 +450,19 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
       NOMEM_IF(!ls1 || !ls2);
       scale_rows(const_cast<void*>(lw.o.W), bf ? 1 : 0, x.D, lw.o.K, lw.o.K, const_cast<float*>(lw.o.b), ls1, st);
       scale_rows(const_cast<void*>(lw.fc2.W), bf ? 1 : 0, x.D, lw.fc2.K, lw.fc2.K, const_cast<float*>(lw.fc2.b), ls2, st);
+    }
+    if (c->fold) {
+      float* cs_qk = (float*)dalloc(c, (size_t)lw.qkv.Npad * sizeof(float), true, st);
+      float* cs_v = (float*)dalloc(c, (size_t)lw.v.Npad * sizeof(float), true, st);
+      float* cs_f = (float*)dalloc(c, (size_t)lw.fc1.Npad * sizeof(float), true, st);
+      NOMEM_IF(!cs_qk || !cs_v || !cs_f);
+      fold_norm_into_linear((bf16_t*)const_cast<void*>(lw.qkv.W), lw.qkv.Npad, lw.qkv.K, lw.qkv.K, lw.n1_g, lw.n1_b, x.D,
+                            const_cast<float*>(lw.qkv.b), cs_qk, st);
+      fold_norm_into_linear((bf16_t*)const_cast<void*>(lw.v.W), lw.v.Npad, lw.v.K, lw.v.K, lw.n1_g, lw.n1_b, x.D,
+                            const_cast<float*>(lw.v.b), cs_v, st);
+      fold_norm_into_linear((bf16_t*)const_cast<void*>(lw.fc1.W), lw.fc1.Npad, lw.fc1.K, lw.fc1.K, lw.n2_g, lw.n2_b, x.D,
+                            const_cast<float*>(lw.fc1.b), cs_f, st);
+      lw.qkv_cs = cs_qk; lw.v_cs = cs_v; lw.fc1_cs = cs_f;
     }
     c->layers.push_back(lw);
   }
@@ -510,6 +555,10 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   }
   if (bf) {
     c->Xn = ws((size_t)c->Mp * c->D_k * 2);
+    if (c->fold) {
+      c->stats = (float*)ws((size_t)c->Mp * c->n_part * 2 * sizeof(float));
+      if (c->n_part > STAT_REGS) c->stats1 = (float*)ws((size_t)c->Mp * 2 * sizeof(float));
+    }
     // the attention kernel reads whole 64-key blocks: up to 63 rows / elements past the last slice
     c->QKV = ws((size_t)(c->Mp + 64) * 2 * c->Dq * 2);
     c->VT = ws(((size_t)c->mb * x.H * c->hd_pad * x.Ns + 64) * 2);
@@ -683,18 +732,53 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
     p.R = X; p.ldr = x.D; p.pos = c->pos + (long)x.cls * x.D; p.n_pos = x.N; p.xrows = xr;
     HIP_TRY(c, bf16_gemm(p, st));
     if (x.Ns != x.N) fill_slice_rows(X, x.D, T, x.Ns, x.Nt, c->cls, c->pos, st); }
-  for (int l = 0; l < (stage == STAGE_PROJECT ? 0 : x.L); ++l) {
+  const int n_layers = stage == STAGE_PROJECT ? 0 : x.L;
+  const bool fold = c->fold;
+  // folded pre-norm of a product over the bf16 copy of the stream
+  const bool wide = fold && c->stats1 != nullptr;
+  auto with_norm = [&](GemmParams& p, const float* colsum) {
+    if (!fold) return;
+    p.stats = wide ? c->stats1 : c->stats; p.colsum = colsum;
+    p.n_part = wide ? 1 : c->n_part; p.stat_group = wide ? x.D : STAT_GROUP; p.norm_dim = x.D;
+    p.norm_rms = d.norm == EPD_NORM_RMSNORM ? 1 : 0; p.norm_eps = d.eps;
+  };
+  // wide rows: the emitted pairs become one pair per row in front of the products that read them
+  auto combine = [&]() { if (wide) { ProfScope ps(c, 1, st); bf16_combine_stats(c->stats, M, c->n_part, x.D, c->stats1, st); } };
+  const bool copy = c->norm_mode == NORM_COPY;
+  // residual product that also leaves bf16(x) of the rows it updates (and, folded norms, their statistics)
+  auto with_emit = [&](GemmParams& p, bool wanted) {
+    if (!(fold || copy) || !wanted) return;
+    p.xb = Xn; p.ldxb = c->D_k;
+    if (fold) { p.stats_out = c->stats; p.n_part_out = c->n_part; }
+  };
+  // pre-norm as a kernel of its own: from the fp32 stream, or in place on the bf16 rows a residual epilogue left
+  auto norm_kernel = [&](const float* g, const float* b, bool from_stream) {
+    if (fold) return;
+    ProfScope ps(c, 1, st);
+    if (from_stream) {
+      RowOpParams r{d.norm, X, x.D, Xn, c->D_k, g, b, M, x.D, 0, x.g, x.D, d.eps};
+      bf16_rowop(r, st);
+    } else {
+      bf16_norm_rows(Xn, c->D_k, g, b, M, x.D, d.norm, d.eps, st);
+    }
+  };
+  if (fold && n_layers > 0) {   // rows written by the embedding: the only pass of this kind in the call
+    ProfScope ps(c, 1, st);
+    bf16_row_stats(X, x.D, M, x.D, Xn, c->D_k, c->stats, c->n_part, st);
+  }
+  if (n_layers > 0) combine();
+  for (int l = 0; l < n_layers; ++l) {
     const LayerW& w = c->layers[l];
-    { ProfScope ps(c, 1, st);
-      RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n1_g, w.n1_b, M, x.D, 0, x.g, x.D, d.eps};
-      bf16_rowop(r, st); }
+    norm_kernel(w.n1_g, w.n1_b, !copy || l == 0);   // the first layer's rows come from the embedding
     { ProfScope ps(c, 2, st);
       GemmParams p = gp(EPI_BIAS, Xn, c->D_k, w.qkv, M);
       p.C = QK; p.ldc = ld_qk;
+      with_norm(p, w.qkv_cs);
       HIP_TRY(c, bf16_gemm(p, st)); }
     { ProfScope ps(c, 2, st);
       GemmParams pv = gp(EPI_VT, Xn, c->D_k, w.v, M);
       pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.Ns;
+      with_norm(pv, w.v_cs);
       HIP_TRY(c, bf16_gemm(pv, st)); }
     if (d.qk_norm == EPD_QKNORM_FULL) {
       ProfScope ps(c, 4, st);
@@ -708,18 +792,21 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
     { ProfScope ps(c, 6, st);
       GemmParams p = gp(EPI_BIAS_RESIDUAL, O, c->Dq_k, w.o, M);
       p.R = X; p.ldr = x.D;
+      with_emit(p, true);
       HIP_TRY(c, bf16_gemm(p, st)); }
-    { ProfScope ps(c, 1, st);
-      RowOpParams r{d.norm, X, x.D, Xn, c->D_k, w.n2_g, w.n2_b, M, x.D, 0, x.g, x.D, d.eps};
-      bf16_rowop(r, st); }
+    combine();
+    norm_kernel(w.n2_g, w.n2_b, !copy);
     { ProfScope ps(c, 7, st);
       GemmParams p = gp(act_epi, Xn, c->D_k, w.fc1, M);
       p.C = Hd; p.ldc = c->F_k;
+      with_norm(p, w.fc1_cs);
       HIP_TRY(c, bf16_gemm(p, st)); }
     { ProfScope ps(c, 8, st);
       GemmParams p2 = gp(EPI_BIAS_RESIDUAL, Hd, c->F_k, w.fc2, M);
       p2.R = X; p2.ldr = x.D;
+      with_emit(p2, l + 1 < n_layers);   // the next layer's first norm; nothing reads it after the last layer
       HIP_TRY(c, bf16_gemm(p2, st)); }
+    if (l + 1 < n_layers) combine();
   }
   if (d.final_norm && stage != STAGE_PROJECT) { ProfScope ps(c, 1, st); f32_norm(d.norm, X, x.D, X, x.D, c->fn_g, c->fn_b, M, x.D, 1, d.eps, st); }
   if (stage == STAGE_TRUNK) {
@@ -1143,6 +1230,75 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
     if (Rp) (void)hipFree(Rp);
   }
   return EPD_OK;
+}
+
+epd_status epd_op_row_stats(const float* x, int64_t rows, int32_t dim, void* xb, float* stats, void* hip_stream) {
+  if (!x || !xb || !stats || rows < 0 || dim <= 0 || dim % 4) return EPD_ERR_INVALID_ARG;
+  bf16_row_stats(x, dim, rows, dim, (bf16_t*)xb, dim, stats, (dim + STAT_GROUP - 1) / STAT_GROUP, (hipStream_t)hip_stream);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
+}
+
+epd_status epd_op_gemm_residual_stats(const void* A, const void* W, const float* bias, float* R, void* xb, float* stats,
+                                      int32_t M, int32_t N, int32_t K, int32_t form, void* hip_stream) {
+  if (!A || !W || !bias || !R || !xb || !stats || M <= 0 || M % 256 || N <= 0 || N % 128 || K <= 0 || K % 128 ||
+      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7) || (form == 3 && K % 256) || (form >= 6 && N % 256)) {
+    set_err(g_err, sizeof(g_err), "epd_op_gemm_residual_stats: bad argument");
+    return EPD_ERR_INVALID_ARG;
+  }
+  if (bf16_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = EPI_BIAS_RESIDUAL; p.cfg = form; p.A = (const bf16_t*)A; p.lda = K; p.W = (const bf16_t*)W; p.bias = bias;
+  p.M = M; p.N = N; p.K = K; p.Npad = N; p.R = R; p.ldr = N; p.n_pos = 1;
+  p.xb = (bf16_t*)xb; p.ldxb = N; p.stats_out = stats; p.n_part_out = N / STAT_GROUP;
+  const hipError_t err = bf16_gemm(p, (hipStream_t)hip_stream);
+  if (err != hipSuccess) { set_err(g_err, sizeof(g_err), "gemm launch failed: %s", hipGetErrorString(err)); return EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
+epd_status epd_op_norm_gemm_bf16(const float* x, const float* gamma, const float* beta, const void* W, const float* bias,
+                                 void* C, int32_t M, int32_t N, int32_t D, float eps, int32_t epi, int32_t form,
+                                 void* hip_stream) {
+  if (!x || !gamma || !W || !bias || !C || M <= 0 || M % 256 || N <= 0 || N % 128 || D <= 0 || D % 128 ||
+      !(epi == EPI_BIAS || epi == EPI_BIAS_GELU_ERF || epi == EPI_BIAS_GELU_TANH) ||
+      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 9) || (form == 3 && D % 256) || (form >= 6 && N % 256)) {
+    set_err(g_err, sizeof(g_err), "epd_op_norm_gemm_bf16: bad argument");
+    return EPD_ERR_INVALID_ARG;
+  }
+  if (bf16_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int n_part = D / STAT_GROUP;
+  bf16_t *xb = nullptr, *Wf = nullptr;
+  float *stats = nullptr, *bf = nullptr, *cs = nullptr;
+  auto done = [&](epd_status code) {
+    (void)hipStreamSynchronize(st);
+    for (void* q : {(void*)xb, (void*)Wf, (void*)stats, (void*)bf, (void*)cs}) if (q) (void)hipFree(q);
+    return code;
+  };
+  if (hipMalloc((void**)&xb, (size_t)M * D * 2) != hipSuccess || hipMalloc((void**)&Wf, (size_t)N * D * 2) != hipSuccess ||
+      hipMalloc((void**)&stats, (size_t)M * n_part * 8) != hipSuccess || hipMalloc((void**)&bf, (size_t)N * 4) != hipSuccess ||
+      hipMalloc((void**)&cs, (size_t)N * 4) != hipSuccess) return done(EPD_ERR_NOMEM);
+  if (hipMemcpyAsync(Wf, W, (size_t)N * D * 2, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+      hipMemcpyAsync(bf, bias, (size_t)N * 4, hipMemcpyDeviceToDevice, st) != hipSuccess) return done(EPD_ERR_HIP);
+  bf16_row_stats(x, D, M, D, xb, D, stats, n_part, st);
+  float* stats1 = nullptr;
+  if (n_part > STAT_REGS) {
+    if (hipMalloc((void**)&stats1, (size_t)M * 8) != hipSuccess) return done(EPD_ERR_NOMEM);
+    bf16_combine_stats(stats, M, n_part, D, stats1, st);
+  }
+  fold_norm_into_linear(Wf, N, D, D, gamma, beta, D, bf, cs, st);
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = epi; p.cfg = form; p.A = xb; p.lda = D; p.W = Wf; p.bias = bf; p.M = M; p.N = N; p.K = D; p.Npad = N;
+  p.C = (bf16_t*)C; p.ldc = N; p.n_pos = 1;
+  p.stats = stats1 ? stats1 : stats; p.colsum = cs; p.n_part = stats1 ? 1 : n_part; p.stat_group = stats1 ? D : STAT_GROUP;
+  p.norm_dim = D; p.norm_rms = beta ? 0 : 1; p.norm_eps = eps;
+  const hipError_t err = bf16_gemm(p, st);
+  const epd_status rc = err != hipSuccess ? EPD_ERR_HIP : (hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP);
+  if (err != hipSuccess) set_err(g_err, sizeof(g_err), "gemm launch failed: %s", hipGetErrorString(err));
+  (void)hipStreamSynchronize(st);
+  if (stats1) (void)hipFree(stats1);
+  return done(rc);
 }
 
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o, int32_t n_slices,

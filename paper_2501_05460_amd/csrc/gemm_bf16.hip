@@ -63,7 +63,10 @@ constexpr size_t smem_main_bytes() {
   return operands > staging ? operands : staging;
 }
 
-template <int BN, int NTHREADS, int WN, int EPI, int PIPE, int BM_ = 256>
+// FOLD (compiled apart so that the plain kernels keep their code and registers).  bf16-output epilogues: 2 = apply a
+// folded pre-norm (GemmParams::stats).  Residual epilogue: 1 = also store the updated rows as bf16
+// (GemmParams::xb), 2 = and their statistics pairs (GemmParams::stats_out).
+template <int BN, int NTHREADS, int WN, int EPI, int PIPE, int BM_ = 256, int FOLD = 0>
 __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int BM = BM_;   // token rows of the tile: 256, or 128 for launches of a few slices
   static_assert(BM_ == 256 ? PIPE <= 1 : (BM_ == 128 && BN == 128 && (PIPE == 0 || PIPE == 2)), "tile shapes compiled");
@@ -88,6 +91,13 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
   bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [NBUF][BN][64]
   bf16_t* sA = sB + NBUF * BN * BK;              // [NBUF][BM][64]
   float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS, BM>());  // [BN]
+  float* sCol = sBias + BN;   // [BN] column sums of the weights (folded pre-norm)
+  float* sMu = sCol + BN;     // [BM] mean of the tile's rows
+  float* sRs = sMu + BM;      // [BM] 1 / sqrt(variance + eps)
+  constexpr bool BF16_OUT = !(EPI == EPI_BIAS_RESIDUAL || EPI == EPI_BIAS_POS);
+  constexpr bool fold = BF16_OUT && FOLD == 2;
+  constexpr bool emit = EPI == EPI_BIAS_RESIDUAL && FOLD >= 1;        // bf16 rows
+  constexpr bool emit_stats = EPI == EPI_BIAS_RESIDUAL && FOLD == 2;  // and their statistics
 
   // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
   // XCD x takes a contiguous run of the tile sequence, and the sequence walks
@@ -118,6 +128,18 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
   // the tile's bias values wait in LDS for the epilogue (a global load there
   // would sit exposed between the last MFMA and the first store)
   if (tid < BN) sBias[tid] = p.bias[n0 + tid];
+  if (fold) {   // read by the epilogue, many barriers from here
+    if (tid < BN) sCol[tid] = p.colsum[n0 + tid];
+    if (tid < BM) {
+      const float* pairs = p.stats + (long)(m0 + tid < p.M ? m0 + tid : p.M - 1) * p.n_part * 2;   // rows past M: any valid row, never stored
+      RowPairs rp;
+      rp.load(pairs, p.n_part);
+      float mu, rs;
+      rp.finish(p.n_part, p.stat_group, p.norm_dim, p.norm_rms, p.norm_eps, mu, rs);
+      sMu[tid] = mu;
+      sRs[tid] = rs;
+    }
+  }
   const int ld_row = tid >> 3, ld_c = tid & 7;
   const int st_off = ld_row * BK + ((ld_c ^ SWZ(ld_row)) * 8);
 
@@ -496,7 +518,38 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
       // alternative here: the compiler puts no wait state behind that form, and with the next chunk's
       // additions rewriting its data registers in the following cycle a stored row was wrong once in
       // about 1e8 stores on gfx950 (gone with one s_nop behind each store, no faster than this form).
-      if (x_col_ok) {
+      if constexpr (emit) {
+        // The updated rows also leave as bf16 (the operand of the next product, whose pre-norm is folded into
+        // its weights) together with their statistics pairs.  A half-wave holds one row's 128-column group,
+        // four values per lane, whatever the tile shape, so the pairs carry the same bits for every shape.
+        const int c = tid % XNCH;
+        const int grp = x_col / STAT_GROUP;
+        const int left = p.N - grp * STAT_GROUP;
+        const float inv_cnt = left <= 0 ? 0.f : 1.0f / (float)(left < STAT_GROUP ? left : STAT_GROUP);
+#pragma unroll
+        for (int i = 0; i < XPER_T; ++i) {
+          const int r = x_r0 + XSTEP * i;
+          const int row = m0 + pass * XROWS + XSTEP * i + x_r0;
+          const bool ok = x_col_ok && row < p.M;
+          f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+          if (ok) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
+            f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)(row - x_r0) * p.ldr + x_voff);
+            if constexpr (X_IN_LOOP) { sum = xr[S][i] + v; __builtin_nontemporal_store(sum, dst); }
+            else { sum = *dst + v; *dst = sum; }
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16_t)sum[e];
+            *reinterpret_cast<bf16x4*>(p.xb + (long)row * p.ldxb + x_col) = o;
+          }
+          if constexpr (emit_stats) {
+            float mean, m2;
+            group_mean_m2(sum, ok, inv_cnt, mean, m2);
+            if ((tid & 31) == 0 && row < p.M && grp < p.n_part_out)
+              *reinterpret_cast<float2*>(p.stats_out + ((long)row * p.n_part_out + grp) * 2) = make_float2(mean, m2);
+          }
+        }
+      } else if (x_col_ok) {
         const int c = tid % XNCH;
 #pragma unroll
         for (int i = 0; i < XPER_T; ++i) {
@@ -536,19 +589,33 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
     for (int j = 0; j < TN; ++j) {
       // lane dimension: feature (tok_major) or token; register dimension: the other one
       const int r = tok_major ? (wn * WN + j * 32 + l32) : (wm * WM + i * 32 + l32);
-      float bl = 0.f;
-      if (tok_major) bl = sBias[r];
+      // the lane's own scalars: bias and column sum of its feature (tok_major), or mean / rstd of its token
+      float bl = 0.f, cs = 0.f, mu = 0.f, rs = 1.f;
+      if (tok_major) { bl = sBias[r]; if (fold) cs = sCol[r]; }
+      else if (fold) { mu = sMu[r]; rs = sRs[r]; }
 #pragma unroll
       for (int gi = 0; gi < 4; ++gi) {
         const int cl = (tok_major ? (wm * WM + i * 32) : (wn * WN + j * 32)) + gi * 8 + lh * 4;
         float v[4];
         if (tok_major) {
+          if (fold) {   // rstd_t (acc - mean_t colsum) + bias over four consecutive tokens t
+            const f32x4 m4 = *reinterpret_cast<const f32x4*>(sMu + cl), r4 = *reinterpret_cast<const f32x4*>(sRs + cl);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(r4[e], __builtin_fmaf(-m4[e], cs, acc[i][j][gi * 4 + e]), bl);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+          }
         } else {
-          const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
-          v[0] = acc[i][j][gi * 4 + 0] + b4.x; v[1] = acc[i][j][gi * 4 + 1] + b4.y;
-          v[2] = acc[i][j][gi * 4 + 2] + b4.z; v[3] = acc[i][j][gi * 4 + 3] + b4.w;
+          const f32x4 b4 = *reinterpret_cast<const f32x4*>(sBias + cl);
+          if (fold) {
+            const f32x4 c4 = *reinterpret_cast<const f32x4*>(sCol + cl);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(rs, __builtin_fmaf(-mu, c4[e], acc[i][j][gi * 4 + e]), b4[e]);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + b4[e];
+          }
         }
         bf16x4 o;
 #pragma unroll
@@ -591,7 +658,7 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
 // rows: the next tile's main loop starts right behind the last store, without
 // the launch gap and the exposed first-slab latency a fresh workgroup pays.
 // ---------------------------------------------------------------------------
-template <int EPI>
+template <int EPI, bool FOLD>
 __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p, const int gm_, const int gw,
                                                               const int n_tiles) {
   constexpr int BN = 256, NTHREADS = 512, WN = 64, WAVES_N = 4, WM = 128, TM = 4, TN = 2;
@@ -603,12 +670,39 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
   bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [2][BN][64]: bytes 0 .. 64 Ki
   bf16_t* sA = sB + 2 * BN * BK;                 // [2][BM][64]: bytes 64 Ki .. 128 Ki
   float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());
+  float* sCol = sBias + BN;   // column sums of the weights, mean and rstd of the tile's rows (folded pre-norm)
+  float* sMu = sCol + BN;
+  float* sRs = sMu + BM;
+  constexpr bool fold = FOLD;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int l32 = lane & 31, lh = lane >> 5;
   const int KT_ = p.K / BK;  // even
   const int gn = p.Npad / BN;
+  // Per-tile scalars of the epilogue: bias and, with a folded pre-norm, the column sums of the weights and
+  // mean / rstd of the tile's rows.  The statistics pairs of the NEXT tile's rows are loaded into registers at
+  // the start of a tile's epilogue (one thread per row, one batch of independent loads whose latency passes
+  // under the epilogue) and combined at its end, when nobody reads the current tile's scalars any more.
+  // (The register copy of the pairs lives inside one epilogue: a variable carried around the tile loop would
+  // occupy its registers through the main loop as well.)
+  // (t: the calling thread's index, handed in so that the epilogue can pass its opaque copy, see there)
+  auto pairs_of = [&](int t, int mrow0) {
+    return p.stats + (long)(mrow0 + t < p.M ? mrow0 + t : p.M - 1) * p.n_part * 2;   // rows past M: any valid row, never stored
+  };
+  auto stats_load = [&](int t, RowPairs& rp, int mrow0) { if (fold && t < BM) rp.load(pairs_of(t, mrow0), p.n_part); };
+  auto tile_scalars = [&](int t, const RowPairs& rp, int mrow0, int ncol0) {
+    if (t < BN) sBias[t] = p.bias[ncol0 + t];
+    if (fold) {
+      if (t < BN) sCol[t] = p.colsum[ncol0 + t];
+      if (t < BM) {
+        float mu, rs;
+        rp.finish(p.n_part, p.stat_group, p.norm_dim, p.norm_rms, p.norm_eps, mu, rs);
+        sMu[t] = mu;
+        sRs[t] = rs;
+      }
+    }
+  };
 
   // position in the launch order -> tile (same XCD-aware band order as the one-tile kernel; a
   // persistent workgroup keeps pos % 8, i.e. its XCD)
@@ -699,7 +793,11 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
 
   int pos = blockIdx.x, m0, n0, m0n, n0n;
   tile_of(pos, m0, n0);
-  if (tid < BN) sBias[tid] = p.bias[n0 + tid];
+  {
+    RowPairs rp0;
+    stats_load(tid, rp0, m0);
+    tile_scalars(tid, rp0, m0, n0);
+  }
   bload(0, n0, 0);
   gload(S0{}, m0, 0);
   gload(S1{}, m0, 1);
@@ -743,6 +841,16 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
     // complete at the barrier inside its hand-over).
 
     // ---- epilogue through LDS buffer 1: staging rows 0..63 of a pass in sB[1], 64..127 in sA[1] ----
+    {
+    // The epilogue's addresses derive from the thread index through an opaque copy, made anew for every tile:
+    // computed once in front of the tile loop (they are loop invariants) they would sit in registers, that is
+    // in scratch memory, through the main loop, and every tile would wait for their reloads before its
+    // epilogue; recomputing them is a few dozen integer operations.
+    int tid_opaque = threadIdx.x;
+    asm volatile("" : "+v"(tid_opaque));
+    const int tid = tid_opaque, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int l32 = lane & 31, lh = lane >> 5;
     constexpr int ROWB = 512, NCH = 32;
     auto stage_row = [&](int r) -> unsigned char* {   // r = 0..127 inside the pass
       return reinterpret_cast<unsigned char*>(r < 64 ? sB + BN * BK : sA + BM * BK) + (r & 63) * ROWB;
@@ -752,9 +860,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
     // staging rows: slot (r / G) * G + r % G  <->  tile row (slot / G) * 2G + pass * G + slot % G,
     // G = 32 (token-major) or 64.
     constexpr int G = tok_major ? 32 : 64;
+    RowPairs rp;
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
-      if (pass > 0) __syncthreads();   // pass 0 has been read out
+      if (pass > 0) {
+        __syncthreads();       // pass 0 has been read out
+        if constexpr (fold) stats_load(tid, rp, m0n);   // half of the accumulators are gone: room for the next tile's pairs (no next tile: m0n = m0, harmless re-read)
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -763,20 +875,33 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
           // lane dimension: feature (tok_major) or token; register dimension: the other one
           const int rg = tok_major ? (wn * WN + j * 32 + l32) : (wm * WM + i * 32 + l32);
           const int r = (rg / (2 * G)) * G + rg % G;
-          float bl = 0.f;
-          if (tok_major) bl = sBias[rg];
+          float bl = 0.f, cs = 0.f, mu = 0.f, rs = 1.f;
+          if (tok_major) { bl = sBias[rg]; if (fold) cs = sCol[rg]; }
+          else if (fold) { mu = sMu[rg]; rs = sRs[rg]; }
           unsigned char* srow = stage_row(r);
 #pragma unroll
           for (int gi = 0; gi < 4; ++gi) {
             const int cl = (tok_major ? (wm * WM + i * 32) : (wn * WN + j * 32)) + gi * 8 + lh * 4;
             float v[4];
             if (tok_major) {
+              if (fold) {
+                const f32x4 m4 = *reinterpret_cast<const f32x4*>(sMu + cl), r4 = *reinterpret_cast<const f32x4*>(sRs + cl);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+                for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(r4[e], __builtin_fmaf(-m4[e], cs, acc[i][j][gi * 4 + e]), bl);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + bl;
+              }
             } else {
-              const float4 b4 = *reinterpret_cast<const float4*>(sBias + cl);
-              v[0] = acc[i][j][gi * 4 + 0] + b4.x; v[1] = acc[i][j][gi * 4 + 1] + b4.y;
-              v[2] = acc[i][j][gi * 4 + 2] + b4.z; v[3] = acc[i][j][gi * 4 + 3] + b4.w;
+              const f32x4 b4 = *reinterpret_cast<const f32x4*>(sBias + cl);
+              if (fold) {
+                const f32x4 c4 = *reinterpret_cast<const f32x4*>(sCol + cl);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(rs, __builtin_fmaf(-mu, c4[e], acc[i][j][gi * 4 + e]), b4[e]);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][gi * 4 + e] + b4[e];
+              }
             }
             bf16x4 o;
 #pragma unroll
@@ -785,7 +910,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
           }
         }
       __syncthreads();
-      if (pass == 1 && has_next && tid < BN) sBias[tid] = p.bias[n0n + tid];   // every bias read is behind us
+      if (pass == 1 && has_next) tile_scalars(tid, rp, m0n, n0n);   // every read of this tile's scalars is behind us
       // read-out: all LDS reads first, then the stores.  Thread tid owns 16-byte chunk tid % 32 of
       // staging rows tid / 32 + 16 i.
       constexpr int PER_T = 128 * NCH / NTHREADS;   // 8
@@ -831,18 +956,21 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
         }
       }
     }
+    }
     if (!has_next) break;
     __syncthreads();   // buffer 1 has been read out: the next tile's first hand-over may fill it
     pos = nxt; m0 = m0n; n0 = n0n;
   }
 }
 
+// behind the operand slabs: the tile's bias values, and for a folded pre-norm the column sums of its
+// weights and the mean / rstd of its rows
 template <int BN, int NT, int BM_ = BM>
-constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT, BM_>() + BN * sizeof(float); }
+constexpr size_t smem_bytes() { return smem_main_bytes<BN, NT, BM_>() + (2 * BN + 2 * BM_) * sizeof(float); }
 
 thread_local long g_kernel_launches = 0;   // kernels launched by bf16_gemm on this host thread so far (a product may be cut into two launches)
 
-template <int BN, int NT, int WN, int EPI, int PIPE, int BM_ = BM>
+template <int BN, int NT, int WN, int EPI, int PIPE, int BM_ = BM, int FOLD = 0>
 hipError_t launch(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM_ - 1) / BM_, gn = p.Npad / BN;
   const int n_tiles = gm * gn;
@@ -860,7 +988,7 @@ hipError_t launch(const GemmParams& p, hipStream_t st) {
     if (cost < best * 0.999) { best = cost; gw = c; }
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
-  k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT, BM_>(), st>>>(p, gm, gw);
+  k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_, FOLD><<<dim3(n_tiles), dim3(NT), smem_bytes<BN, NT, BM_>(), st>>>(p, gm, gw);
   ++g_kernel_launches;
   return hipGetLastError();
 }
@@ -878,7 +1006,7 @@ int cu_count() {
   return n;
 }
 
-template <int EPI>
+template <int EPI, bool FOLD>
 hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / 256;
   const int n_tiles = gm * gn;
@@ -893,29 +1021,47 @@ hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
   const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
-  k_gemm_bf16_persist<EPI><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  k_gemm_bf16_persist<EPI, FOLD><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
   ++g_kernel_launches;
   return hipGetLastError();
 }
 
-hipError_t dispatch_persist(const GemmParams& p, hipStream_t st) {
+template <bool FOLD>
+hipError_t dispatch_persist_f(const GemmParams& p, hipStream_t st) {
   switch (p.epi) {
-    case EPI_BIAS: return launch_persist<EPI_BIAS>(p, st);
-    case EPI_BIAS_GELU_ERF: return launch_persist<EPI_BIAS_GELU_ERF>(p, st);
-    case EPI_BIAS_GELU_TANH: return launch_persist<EPI_BIAS_GELU_TANH>(p, st);
-    case EPI_VT: return launch_persist<EPI_VT>(p, st);
+    case EPI_BIAS: return launch_persist<EPI_BIAS, FOLD>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch_persist<EPI_BIAS_GELU_ERF, FOLD>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch_persist<EPI_BIAS_GELU_TANH, FOLD>(p, st);
+    case EPI_VT: return launch_persist<EPI_VT, FOLD>(p, st);
   }
   return hipErrorInvalidValue;
 }
+hipError_t dispatch_persist(const GemmParams& p, hipStream_t st) {
+  return p.stats ? dispatch_persist_f<true>(p, st) : dispatch_persist_f<false>(p, st);
+}
 
-template <int EPI>
+template <int EPI, bool FOLD>
 hipError_t set_attr_persist() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist<EPI>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist<EPI, FOLD>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>());
 }
 
 template <int BN, int NT, int WN, int PIPE = 0, int BM_ = BM>
 hipError_t dispatch(const GemmParams& p, hipStream_t st) {
+  if (p.stats) {   // folded pre-norm (bf16-output epilogues)
+    switch (p.epi) {
+      case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS, PIPE, BM_, 2>(p, st);
+      case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE, BM_, 2>(p, st);
+      case EPI_BIAS_GELU_TANH: return launch<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE, BM_, 2>(p, st);
+      case EPI_VT: return launch<BN, NT, WN, EPI_VT, PIPE, BM_, 2>(p, st);
+    }
+    return hipErrorInvalidValue;
+  }
+  if (p.xb) {      // residual epilogue that also stores the rows as bf16, with or without their statistics
+    if (p.epi != EPI_BIAS_RESIDUAL) return hipErrorInvalidValue;
+    return p.stats_out ? launch<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_, 2>(p, st)
+                       : launch<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_, 1>(p, st);
+  }
   switch (p.epi) {
     case EPI_BIAS: return launch<BN, NT, WN, EPI_BIAS, PIPE, BM_>(p, st);
     case EPI_BIAS_GELU_ERF: return launch<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE, BM_>(p, st);
@@ -927,9 +1073,9 @@ hipError_t dispatch(const GemmParams& p, hipStream_t st) {
   return hipErrorInvalidValue;
 }
 
-template <int BN, int NT, int WN, int EPI, int PIPE, int BM_>
+template <int BN, int NT, int WN, int EPI, int PIPE, int BM_, int FOLD = 0>
 hipError_t set_attr() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<BN, NT, WN, EPI, PIPE, BM_, FOLD>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, NT, BM_>());
 }
 
@@ -941,7 +1087,13 @@ hipError_t set_attr_all() {
   if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE, BM_>()) != hipSuccess) return e;
   if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_>()) != hipSuccess) return e;
   if ((e = set_attr<BN, NT, WN, EPI_BIAS_POS, PIPE, BM_>()) != hipSuccess) return e;
-  return set_attr<BN, NT, WN, EPI_VT, PIPE, BM_>();
+  if ((e = set_attr<BN, NT, WN, EPI_VT, PIPE, BM_>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS, PIPE, BM_, 2>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_ERF, PIPE, BM_, 2>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_GELU_TANH, PIPE, BM_, 2>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_, 1>()) != hipSuccess) return e;
+  if ((e = set_attr<BN, NT, WN, EPI_BIAS_RESIDUAL, PIPE, BM_, 2>()) != hipSuccess) return e;
+  return set_attr<BN, NT, WN, EPI_VT, PIPE, BM_, 2>();
 }
 
 }  // namespace
@@ -952,10 +1104,14 @@ hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
-  if ((e = set_attr_persist<EPI_BIAS>()) != hipSuccess) return e;
-  if ((e = set_attr_persist<EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
-  if ((e = set_attr_persist<EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
-  if ((e = set_attr_persist<EPI_VT>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS, false>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_ERF, false>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_TANH, false>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_VT, false>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS, true>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_ERF, true>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_BIAS_GELU_TANH, true>()) != hipSuccess) return e;
+  if ((e = set_attr_persist<EPI_VT, true>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64, 0, 128>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64, 2, 128>()) != hipSuccess) return e;
@@ -964,6 +1120,7 @@ hipError_t bf16_gemm_init() {
 
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   if (p.K % (2 * BK) != 0 || p.Npad % 128 != 0 || p.N % 4 != 0) return hipErrorInvalidValue;
+  if (p.stats && (p.n_part < 1 || p.n_part > STAT_REGS || p.stat_group < 1 || !p.colsum)) return hipErrorInvalidValue;
   // operands are addressed through 32-bit buffer offsets
   if ((long)p.M * p.lda * 2 >= (1L << 32) || (long)p.Npad * p.K * 2 >= (1L << 32) ||
       (p.R && (long)p.M * p.ldr * 4 >= (1L << 32)) || (p.C && !p.row_map && (long)p.M * p.ldc * 2 >= (1L << 32)))
@@ -993,6 +1150,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     a.N = n_a; a.Npad = n_a;
     b.N = p.N - n_a; b.Npad = 128;
     b.W = p.W + (long)n_a * p.K; b.bias = p.bias + n_a; b.R = p.R + n_a;
+    if (p.xb) { b.xb = p.xb + n_a; b.stats_out = p.stats_out + (n_a / STAT_GROUP) * 2; }   // n_a % 256 == 0
     const hipError_t e = bf16_gemm(a, st);
     return e != hipSuccess ? e : bf16_gemm(b, st);
   }
@@ -1023,6 +1181,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
         a.M = (int)(rows_a * BM);
         b.M = p.M - a.M;
         b.A = p.A + (long)a.M * p.lda;
+        if (p.stats) b.stats = p.stats + (long)a.M * p.n_part * 2;
         if (p.row_map) b.row_map = p.row_map + a.M / p.block_tokens;
         else b.C = p.C + (long)a.M * p.ldc;
         const hipError_t e = dispatch_persist(a, st);
@@ -1047,6 +1206,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
       b.M = p.M - a.M;
       b.A = p.A + (long)a.M * p.lda;
       b.R = p.R + (long)a.M * p.ldr;
+      if (p.xb) { b.xb = p.xb + (long)a.M * p.ldxb; b.stats_out = p.stats_out + (long)a.M * p.n_part_out * 2; }
       const hipError_t e = dispatch<256, 512, 64, 1>(a, st);
       return e != hipSuccess ? e : dispatch<128, 512, 64>(b, st);
     }

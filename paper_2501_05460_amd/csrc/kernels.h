@@ -53,6 +53,19 @@ struct GemmParams {
   SliceRows xrows;
   bf16_t* VT;                 // EPI_VT: values, transposed per (slice, head): [T, H, hd_pad, n_tok]
   int hd_pad, heads, n_tok;   // EPI_VT: column c = h * hd_pad + d, row r = t * n_tok + n
+  // Pre-norm folded into the product (bf16-output epilogues; null `stats`: off).  A holds bf16(x) of the
+  // residual stream, W the weights times the norm gain, bias the bias plus W beta, and
+  //   out[r][n] = rstd_r * (acc[r][n] - mean_r * colsum[n]) + bias[n]
+  // with mean_r / rstd_r from the row's statistics pairs (common.h: one pair per 128 columns of x).
+  const float* stats;         // [M][n_part][2], n_part <= STAT_REGS
+  const float* colsum;        // [Npad]: sum over k of the packed (gain-scaled, rounded) weights
+  int n_part, stat_group;     // pairs per row and the columns a pair covers (128 as emitted; the whole row once combined)
+  int norm_dim, norm_rms;     // columns of x; 1: RMSNorm (no mean)
+  float norm_eps;
+  // Residual epilogue (RESIDUAL; null `xb`: off): also stores bf16 of the updated rows to xb [M, ldxb] and
+  // their statistics pairs to stats_out [M][n_part_out][2] (pair index = column / 128).
+  bf16_t* xb; long ldxb;
+  float* stats_out; int n_part_out;
 };
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
 long bf16_gemm_kernel_launches();   // kernels launched by bf16_gemm on the calling host thread so far (a figure for the profiling hooks)
@@ -60,6 +73,26 @@ hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (id
 
 // A_pe[row][e] = bf16(pixel) for e < 3*p*p, 0 for the K padding up to lda.
 void bf16_im2col(const float* tiles, bf16_t* A, int lda, int T, int S, int p, hipStream_t st);
+
+// LayerNorm (kind 0) / RMSNorm (1) of bf16 rows in place: x [rows, dim] bf16 (row stride ld, dim % 8 == 0, rows
+// 16-byte aligned), statistics in fp32.  The rows are bf16 copies of the residual stream left by the residual epilogues.
+void bf16_norm_rows(bf16_t* x, long ld, const float* gamma, const float* beta, long rows, int dim, int kind, float eps,
+                    hipStream_t st);
+
+// bf16(x) and the statistics pairs of every row of the residual stream x [rows, dim] (dim % 4 == 0): what the
+// residual epilogue emits for the rows it updates, for rows that come from elsewhere (embedding, class token).
+void bf16_row_stats(const float* x, long ldx, long rows, int dim, bf16_t* xb, long ldxb, float* stats, int n_part,
+                    hipStream_t st);
+
+// Rows of more than STAT_REGS pairs: one pair (mean, squared deviations) over the whole row from the n_part pairs
+// over 128 columns each.  out [rows][2].
+void bf16_combine_stats(const float* stats, long rows, int n_part, int dim, float* out, hipStream_t st);
+
+// Fold a pre-norm into a packed Linear in place: bias[n] += sum_k W[n][k] beta[k] (beta null: RMSNorm),
+// W[n][k] = bf16(W[n][k] gamma[k]), colsum[n] = sum_k W[n][k] over the rounded products.  rows x cols of the
+// packed matrix (row stride ld); gamma / beta hold `dim` <= cols values, columns past dim are left alone.
+void fold_norm_into_linear(bf16_t* W, int rows, int cols, long ld, const float* gamma, const float* beta, int dim,
+                           float* bias, float* colsum, hipStream_t st);
 
 // Row operation fp32 -> bf16 (rowop_bf16.hip): optional pixel-shuffle gather
 // of the source rows, then LayerNorm (kind 0), RMSNorm (1) or plain convert (2).

@@ -152,6 +152,173 @@ void bf16_rowop(const RowOpParams& p, hipStream_t st) {
   else k_bf16_rowop<0><<<grid, block, 0, st>>>(p);
 }
 
+// ---------------------------------------- pre-norm of bf16 rows, in place ----
+// The residual epilogues leave bf16(x) of the rows they update; this kernel turns such rows into the normalised
+// operand of the next product in place: a third less traffic than reading the fp32 stream (2 + 2 instead of
+// 4 + 2 bytes per element).  One wave per row, the row held in registers (NV chunks of 8 elements per lane;
+// NV = 0: read twice), statistics in fp32 over the rounded values.  dim % 8 == 0, rows 16-byte aligned.
+template <int NV>
+__global__ __launch_bounds__(256) void k_bf16_norm_rows(bf16_t* __restrict__ x, long ld, const float* __restrict__ gamma,
+                                                        const float* __restrict__ beta, long rows, int dim, int kind,
+                                                        float eps) {
+  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= rows) return;
+  const int lane = threadIdx.x & 63;
+  bf16x8* row = reinterpret_cast<bf16x8*>(x + R * ld);
+  const int nchunk = dim >> 3;
+  bf16x8 v[NV > 0 ? NV : 1];
+  float s = 0.f;
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunk) {
+        v[i] = row[c];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += (float)v[i][e];
+      }
+    }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) {
+      const bf16x8 a = row[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s += (float)a[e];
+    }
+  }
+  const float mean = kind == 0 ? wave_sum(s) / dim : 0.f;
+  float qs = 0.f;
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nchunk) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { const float d = (float)v[i][e] - mean; qs = __builtin_fmaf(d, d, qs); }
+      }
+  } else {
+    for (int c = lane; c < nchunk; c += 64) {
+      const bf16x8 a = row[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = (float)a[e] - mean; qs = __builtin_fmaf(d, d, qs); }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(qs) / dim + eps);
+  auto emit = [&](int c, bf16x8 a) {
+    bf16x8 o;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float4 gm = *(reinterpret_cast<const float4*>(gamma) + 2 * c + h);
+      float r[4] = {((float)a[4 * h + 0] - mean) * rstd * gm.x, ((float)a[4 * h + 1] - mean) * rstd * gm.y,
+                    ((float)a[4 * h + 2] - mean) * rstd * gm.z, ((float)a[4 * h + 3] - mean) * rstd * gm.w};
+      if (kind == 0) {
+        const float4 bt = *(reinterpret_cast<const float4*>(beta) + 2 * c + h);
+        r[0] += bt.x; r[1] += bt.y; r[2] += bt.z; r[3] += bt.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[4 * h + e] = (bf16_t)r[e];
+    }
+    row[c] = o;
+  };
+  if (NV > 0) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      if (lane + 64 * i < nchunk) emit(lane + 64 * i, v[i]);
+  } else {
+    for (int c = lane; c < nchunk; c += 64) emit(c, row[c]);
+  }
+}
+
+void bf16_norm_rows(bf16_t* x, long ld, const float* gamma, const float* beta, long rows, int dim, int kind, float eps,
+                    hipStream_t st) {
+  if (rows == 0) return;
+  const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  const int per_lane = (dim / 8 + 63) / 64;
+  if (per_lane <= 2) k_bf16_norm_rows<2><<<grid, block, 0, st>>>(x, ld, gamma, beta, rows, dim, kind, eps);
+  else if (per_lane <= 4) k_bf16_norm_rows<4><<<grid, block, 0, st>>>(x, ld, gamma, beta, rows, dim, kind, eps);
+  else if (per_lane <= 8) k_bf16_norm_rows<8><<<grid, block, 0, st>>>(x, ld, gamma, beta, rows, dim, kind, eps);
+  else k_bf16_norm_rows<0><<<grid, block, 0, st>>>(x, ld, gamma, beta, rows, dim, kind, eps);
+}
+
+// ------------------------------------------------------- row statistics ----
+// One wave per row: lane l holds columns 4 (l + 64 j) .. + 3 in round j, so the lower half of the wave covers
+// group 2 j of 128 columns and the upper half group 2 j + 1: the lane layout of the residual epilogue.
+__global__ __launch_bounds__(256) void k_bf16_row_stats(const float* __restrict__ x, long ldx, long rows, int dim,
+                                                        bf16_t* __restrict__ xb, long ldxb, float* __restrict__ stats,
+                                                        int n_part) {
+  const long R = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (R >= rows) return;
+  const int lane = threadIdx.x & 63;
+  for (int j = 0; j * 256 < dim; ++j) {
+    const int col = 4 * (lane + 64 * j), g = col / STAT_GROUP;
+    const bool valid = col < dim;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (valid) {
+      v = *reinterpret_cast<const f32x4*>(x + R * ldx + col);
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+      *reinterpret_cast<bf16x4*>(xb + R * ldxb + col) = o;
+    }
+    const int cnt = dim - g * STAT_GROUP < STAT_GROUP ? dim - g * STAT_GROUP : STAT_GROUP;
+    float mean, m2;
+    group_mean_m2(v, valid, cnt > 0 ? 1.0f / (float)cnt : 0.f, mean, m2);
+    if ((lane & 31) == 0 && g < n_part) *reinterpret_cast<float2*>(stats + (R * n_part + g) * 2) = make_float2(mean, m2);
+  }
+}
+
+void bf16_row_stats(const float* x, long ldx, long rows, int dim, bf16_t* xb, long ldxb, float* stats, int n_part,
+                    hipStream_t st) {
+  if (rows == 0) return;
+  k_bf16_row_stats<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(x, ldx, rows, dim, xb, ldxb, stats, n_part);
+}
+
+__global__ __launch_bounds__(256) void k_combine_stats(const float* __restrict__ stats, long rows, int n_part, int dim,
+                                                       float* __restrict__ out) {
+  const long r = (long)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  const float* pairs = stats + r * n_part * 2;
+  const float2 c = combine_pairs([&](int g) { return *reinterpret_cast<const float2*>(pairs + 2 * g); }, n_part, STAT_GROUP, dim);
+  *reinterpret_cast<float2*>(out + 2 * r) = c;
+}
+
+void bf16_combine_stats(const float* stats, long rows, int n_part, int dim, float* out, hipStream_t st) {
+  if (rows == 0) return;
+  k_combine_stats<<<dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st>>>(stats, rows, n_part, dim, out);
+}
+
+// One wave per row of the packed matrix.  The sums run lane-strided over k and end in a wave reduction: a
+// fixed order, so a context built twice holds the same bits.
+__global__ __launch_bounds__(256) void k_fold_norm(bf16_t* __restrict__ W, int rows, int cols, long ld,
+                                                   const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                   int dim, float* __restrict__ bias, float* __restrict__ colsum) {
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int lane = threadIdx.x & 63;
+  bf16_t* w = W + (long)r * ld;
+  float dot = 0.f, cs = 0.f;
+  for (int k = lane; k < cols; k += 64) {
+    float v = (float)w[k];
+    if (k < dim) {
+      if (beta) dot = __builtin_fmaf(v, beta[k], dot);
+      const bf16_t scaled = (bf16_t)(v * gamma[k]);
+      w[k] = scaled;
+      v = (float)scaled;
+    }
+    cs += v;
+  }
+  dot = wave_sum(dot);
+  cs = wave_sum(cs);
+  if (lane == 0) {
+    if (beta) bias[r] += dot;
+    colsum[r] = cs;
+  }
+}
+
+void fold_norm_into_linear(bf16_t* W, int rows, int cols, long ld, const float* gamma, const float* beta, int dim,
+                           float* bias, float* colsum, hipStream_t st) {
+  if (rows == 0) return;
+  k_fold_norm<<<dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st>>>(W, rows, cols, ld, gamma, beta, dim, bias, colsum);
+}
+
 // --------------------------------------------------------- q/k RMSNorm ------
 // One wave per logical row, q rows first, then k rows (k = q + k_off elements, its own gain).  The
 // row waits in registers between the sum of squares and the scaling when it fits (NV chunks per

@@ -153,7 +153,8 @@ def test_profile_brackets_count_kernels_and_leave_the_result_alone():
         assert fam[name]["ms"] > 0.0, name
         assert fam[name]["launches"] >= (2 * L if name == "gemm_qkv" else L), (name, fam[name])   # q/k and v are two products
         assert fam[name]["launches"] <= 4 * L, (name, fam[name])
-    assert fam["norm"]["launches"] == 2 * L and fam["attention"]["launches"] == L
+    # two pre-norm kernels per layer (one statistics pass instead when EPD_NORM_MODE=fold folds them into the products)
+    assert fam["norm"]["launches"] in (2 * L, 1) and fam["attention"]["launches"] == L
     assert fam["embed"]["launches"] >= 1 and fam["gemm_proj"]["launches"] >= 2
     assert fam["qk_norm"]["launches"] == 0 and fam["qk_norm"]["ms"] == 0.0
 
