@@ -33,8 +33,9 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
 /* One launch of the bf16 MFMA GEMM in a chosen form, for tests that hold the forms against each
  * other: epi 0 bias, 1 bias + GELU(erf), 2 bias + GELU(tanh) -> C [M,N] bf16; epi 3 -> R [M,N]
  * fp32 += A W^T + bias (C unused).  form 0 = what the library would pick, 1 = 256x128 tile,
- * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 9 = persistent kernel (not epi 3).
- * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 9), K % 128 == 0; bias [N] fp32.
+ * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 8 = pipelined loop with both operand slabs
+ * loaded straight into LDS, 9 = persistent kernel (not epi 3).
+ * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6, 7, 8, 9), K % 128 == 0; bias [N] fp32.
  * A [M,K], C [M,N] and R [M,N] hold exactly M rows; no row past M is written.  (The kernels read whole
  * 256-row tiles; for a ragged M, and for R, the call runs on padded copies it allocates, and synchronises.) */
 epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias, void* C, float* R,
@@ -48,7 +49,7 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
  * [rows][ceil(dim / 128)][2] fp32.
  * epd_op_row_stats: xb [rows, dim] bf16 = x [rows, dim] fp32 and the pairs of every row (dim % 4 == 0).
  * epd_op_gemm_residual_stats: R [M,N] fp32 += A [M,K] W [N,K]^T + bias as epd_op_gemm_bf16_form's epi 3 (forms
- *   0, 1, 2, 3, 6, 7), and xb [M,N] = bf16 of the updated R with its pairs in stats [M][N / 128][2];
+ *   0, 1, 2, 3, 6, 7, 8), and xb [M,N] = bf16 of the updated R with its pairs in stats [M][N / 128][2];
  *   M % 256 == 0 here, and R must hold 256 floats behind its last row.
  * epd_op_norm_gemm_bf16: C [M,N] bf16 = act(norm(x) W^T + bias) the folded way: x [M,D] fp32, gamma / beta [D]
  *   fp32 (beta null: RMSNorm), W [N,D] bf16, bias [N] fp32; epi 0 none, 1 GELU(erf), 2 GELU(tanh); form as

@@ -1187,7 +1187,7 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
   const bool residual = epi == EPI_BIAS_RESIDUAL;
   if (!A || !W || !bias || (residual ? !R : !C) || M <= 0 || N <= 0 || K <= 0 || N % 128 || K % 128 ||
       !(epi == EPI_BIAS || epi == EPI_BIAS_GELU_ERF || epi == EPI_BIAS_GELU_TANH || residual) ||
-      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 9) || (form == 3 && K % 256) || (form >= 6 && N % 256) ||
+      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 8 || form == 9) || (form == 3 && K % 256) || (form >= 6 && N % 256) ||
       (form == 9 && residual)) {
     set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16_form: bad argument");
     return EPD_ERR_INVALID_ARG;
@@ -1241,7 +1241,7 @@ epd_status epd_op_row_stats(const float* x, int64_t rows, int32_t dim, void* xb,
 epd_status epd_op_gemm_residual_stats(const void* A, const void* W, const float* bias, float* R, void* xb, float* stats,
                                       int32_t M, int32_t N, int32_t K, int32_t form, void* hip_stream) {
   if (!A || !W || !bias || !R || !xb || !stats || M <= 0 || M % 256 || N <= 0 || N % 128 || K <= 0 || K % 128 ||
-      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7) || (form == 3 && K % 256) || (form >= 6 && N % 256)) {
+      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 8) || (form == 3 && K % 256) || (form >= 6 && N % 256)) {
     set_err(g_err, sizeof(g_err), "epd_op_gemm_residual_stats: bad argument");
     return EPD_ERR_INVALID_ARG;
   }
@@ -1261,7 +1261,7 @@ epd_status epd_op_norm_gemm_bf16(const float* x, const float* gamma, const float
                                  void* hip_stream) {
   if (!x || !gamma || !W || !bias || !C || M <= 0 || M % 256 || N <= 0 || N % 128 || D <= 0 || D % 128 ||
       !(epi == EPI_BIAS || epi == EPI_BIAS_GELU_ERF || epi == EPI_BIAS_GELU_TANH) ||
-      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 9) || (form == 3 && D % 256) || (form >= 6 && N % 256)) {
+      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 8 || form == 9) || (form == 3 && D % 256) || (form >= 6 && N % 256)) {
     set_err(g_err, sizeof(g_err), "epd_op_norm_gemm_bf16: bad argument");
     return EPD_ERR_INVALID_ARG;
   }

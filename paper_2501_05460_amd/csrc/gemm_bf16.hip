@@ -28,6 +28,7 @@
 // 16-byte fp32 accesses in the epilogue.  For the attention values (EPI_VT)
 // the roles are swapped, so a lane owns four consecutive tokens of one
 // feature, which is what the transposed value layout wants.
+#include <cstdlib>
 #include <type_traits>
 
 #include "kernels.h"
@@ -69,7 +70,7 @@ constexpr size_t smem_main_bytes() {
 template <int BN, int NTHREADS, int WN, int EPI, int PIPE, int BM_ = 256, int FOLD = 0>
 __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_gemm_bf16(const GemmParams p, const int gm_, const int gw) {
   constexpr int BM = BM_;   // token rows of the tile: 256, or 128 for launches of a few slices
-  static_assert(BM_ == 256 ? PIPE <= 1 : (BM_ == 128 && BN == 128 && (PIPE == 0 || PIPE == 2)), "tile shapes compiled");
+  static_assert(BM_ == 256 ? (PIPE <= 1 || PIPE == 3) : (BM_ == 128 && BN == 128 && (PIPE == 0 || PIPE == 2)), "tile shapes compiled");
   constexpr int NWAVES = NTHREADS / 64;
   constexpr int WAVES_N = BN / WN;           // 4 | 2
   constexpr int WAVES_M = NWAVES / WAVES_N;  // 2 | 4 | 2
@@ -166,11 +167,13 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
   // PIPE == 1: the weight slab goes from global memory straight into LDS (no
   // staging registers), one slab ahead; only the activation slab is staged in
   // registers, two slabs ahead.
-  constexpr bool B_DIRECT = PIPE == 1;
+  constexpr bool B_DIRECT = PIPE == 1 || PIPE == 3;
+  // PIPE == 3: the activation slab goes straight into LDS as well, one slab ahead (no staging registers at all)
+  constexpr bool A_DIRECT = PIPE == 3;
   // the operand register sets can carry residual rows of the first passes when the counts match:
   // both sets = passes 0 and 1 (A and B staged), or both sets = the two halves of pass 0 (A staged only)
   constexpr bool X_IN_LOOP = EPI == EPI_BIAS_RESIDUAL &&
-                             (B_DIRECT ? XPER_T == 2 * A_LD : XPER_T == A_LD + B_LD);
+                             (A_DIRECT || (B_DIRECT ? XPER_T == 2 * A_LD : XPER_T == A_LD + B_LD));
   f32x4 xr[2][X_IN_LOOP ? XPER_T : 1];
   auto xload = [&](auto set, int pass) {
     if constexpr (X_IN_LOOP) {
@@ -263,6 +266,20 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
       }
     }
   };
+  // PIPE == 3: activation slab kt -> LDS buffer buf, same scheme (LDS-DMA reaches the whole LDS through M0 on gfx950)
+  const unsigned ad_voff = ((unsigned)ld_row * (unsigned)p.lda + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  auto aload = [&](int buf, int kt) {
+    if constexpr (A_DIRECT) {
+#pragma unroll
+      for (int i = 0; i < A_LD; ++i) {
+        const bf16_t* g = p.A + (long)(m0 + ROWS_PER_LD * i) * p.lda + kt * BK;   // uniform
+        bf16_t* l = sA + buf * BM * BK + (wave_u * 64 + NTHREADS * i) * 8;
+        const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(ad_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+      }
+    }
+  };
   // wait until at most n of this wave's vector-memory loads are outstanding (they complete in order)
   auto wait_vm = [&](auto n) {
     constexpr int N = decltype(n)::value;
@@ -346,7 +363,7 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  if constexpr (PIPE == 1) {
+  if constexpr (PIPE == 1 || PIPE == 3) {
     // The operand fragments run one k-step ahead of the MFMAs in a second
     // register set, so a wave issues its MFMAs back to back instead of
     // waiting for LDS in front of every k-step; the slab hand-over (LDS
@@ -397,6 +414,57 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
       __syncthreads();
       ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
     };
+    // PIPE == 3: both slabs of step kt + 1 are in flight towards the other buffer while step kt is multiplied.
+    // The last two steps also start the residual rows of the first two epilogue passes (PHASE 1: the step
+    // before the last, whose wait leaves those newest loads in flight; PHASE 2: the last step, which has
+    // nothing to fetch for the product).
+    // residual rows of an epilogue pass through the buffer descriptor: every lane of every wave issues exactly
+    // XPER_T loads whatever the tile's position (rows past M are read like any other, columns past N come back
+    // as zero), so the wait below can count them
+    auto xload_all = [&](auto set, int pass) {
+      if constexpr (X_IN_LOOP) {
+        constexpr int S = decltype(set)::value;
+#pragma unroll
+        for (int i = 0; i < XPER_T; ++i)
+          xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+              rsrc_x, x_voff * 4u, (unsigned)(m0 + pass * XROWS + XSTEP * i) * (unsigned)p.ldr * 4u, 2));
+      }
+    };
+    auto slab_direct = [&](int buf, int kt, auto phase) {
+      constexpr int PHASE = decltype(phase)::value;
+      if constexpr (PHASE < 2) { bload(buf ^ 1, kt + 1); aload(buf ^ 1, kt + 1); }
+      if constexpr (PHASE == 1) xload_all(S0{}, 0);
+      if constexpr (PHASE == 2) xload_all(S1{}, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
+      ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
+      ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (PHASE < 2) {
+        // both slabs have landed in the other buffer (loads complete in order: the residual rows are newer)
+        wait_vm(std::integral_constant<int, (PHASE == 1 && X_IN_LOOP) ? XPER_T : 0>{});
+        __syncthreads();
+        ldfrag(S0{}, buf ^ 1, 0);
+      }
+      mma(S1{});
+      if constexpr (PHASE < 2) interleave();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    if constexpr (A_DIRECT) {
+      bload(0, 0);
+      aload(0, 0);
+      wait_vm(std::integral_constant<int, 0>{});
+      __syncthreads();
+      ldfrag(S0{}, 0, 0);
+      for (int kt = 0; kt < KT_ - 2; kt += 2) {
+        slab_direct(0, kt, P0{});
+        slab_direct(1, kt + 1, P0{});
+      }
+      slab_direct(0, KT_ - 2, P1{});
+      slab_direct(1, KT_ - 1, P2{});
+    } else {
     bload(0, 0);
     gload(S0{}, 0);
     gload(S1{}, 1);
@@ -409,11 +477,12 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
       slab(S0{}, S1{}, 0, kt);
       slab(S1{}, S0{}, 1, kt + 1);
     }
-    if constexpr (X_IN_LOOP && B_DIRECT) {
+    }
+    if constexpr (X_IN_LOOP && B_DIRECT && !A_DIRECT) {
 #pragma unroll
       for (int i = 0; i < XPER_T; ++i) xr[0][i] = __builtin_bit_cast(f32x4, ra[i / A_LD][i % A_LD]);
       xload(S1{}, 1);   // into the registers the operand fragments have left
-    } else if constexpr (X_IN_LOOP) {
+    } else if constexpr (X_IN_LOOP && !A_DIRECT) {
 #pragma unroll
       for (int i = 0; i < XPER_T; ++i) {
         xr[0][i] = __builtin_bit_cast(f32x4, i < A_LD ? ra[0][i < A_LD ? i : 0] : rb[0][i < A_LD ? 0 : i - A_LD]);
@@ -658,7 +727,9 @@ __global__ __launch_bounds__(NTHREADS, BM_ == 128 && PIPE == 0 ? 2 : 1) void k_g
 // rows: the next tile's main loop starts right behind the last store, without
 // the launch gap and the exposed first-slab latency a fresh workgroup pays.
 // ---------------------------------------------------------------------------
-template <int EPI, bool FOLD>
+// ADIR: the activation slab also goes from global memory straight into LDS (one slab ahead, like the weight
+// slab) instead of through registers two slabs ahead.
+template <int EPI, bool FOLD, bool ADIR = false>
 __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p, const int gm_, const int gw,
                                                               const int n_tiles) {
   constexpr int BN = 256, NTHREADS = 512, WN = 64, WAVES_N = 4, WM = 128, TM = 4, TN = 2;
@@ -754,6 +825,19 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
     for (int i = 0; i < A_LD; ++i)
       *reinterpret_cast<u32x4*>(sA + buf * BM * BK + ROWS_PER_LD * i * BK + st_off) = ra[S][i];
   };
+  // ADIR: activation slab kt of the tile rows mrow0 .. -> LDS, the swizzle applied on the global side as for the
+  // weights (LDS-DMA reaches the whole LDS through M0 on gfx950, so the activation buffers above 64 KiB are fine)
+  const unsigned ad_voff = ((unsigned)ld_row * (unsigned)p.lda + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  auto aload = [&](int buf, int mrow0, int kt) {
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+      const bf16_t* g = p.A + (long)(mrow0 + ROWS_PER_LD * i) * p.lda + kt * BK;   // uniform
+      bf16_t* l = sA + buf * BM * BK + (wave_u * 64 + NTHREADS * i) * 8;
+      const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(ad_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+    }
+  };
   auto wait_vm = [&](auto n) {
     constexpr int N = decltype(n)::value;
     __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
@@ -798,11 +882,17 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
     stats_load(tid, rp0, m0);
     tile_scalars(tid, rp0, m0, n0);
   }
+  using VM_0 = std::integral_constant<int, 0>;
   bload(0, n0, 0);
-  gload(S0{}, m0, 0);
-  gload(S1{}, m0, 1);
-  sstore(S0{}, 0);
-  wait_vm(VM_A{});   // loads complete in order: all but slab 1's are done, weight slab 0 has landed
+  if constexpr (ADIR) {
+    aload(0, m0, 0);
+    wait_vm(VM_0{});
+  } else {
+    gload(S0{}, m0, 0);
+    gload(S1{}, m0, 1);
+    sstore(S0{}, 0);
+    wait_vm(VM_A{});   // loads complete in order: all but slab 1's are done, weight slab 0 has landed
+  }
   __syncthreads();
 
   for (;;) {
@@ -822,14 +912,19 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
     auto slab = [&](auto lset, auto sset, int buf, int kt) {
       const bool w_own = kt + 1 < KT_, a_own = kt + 2 < KT_;
       bload(buf ^ 1, w_own ? n0 : n0n, w_own ? kt + 1 : kt + 1 - KT_);
-      gload(lset, a_own ? m0 : m0n, a_own ? kt + 2 : kt + 2 - KT_);
+      if constexpr (ADIR) aload(buf ^ 1, w_own ? m0 : m0n, w_own ? kt + 1 : kt + 1 - KT_);
+      else gload(lset, a_own ? m0 : m0n, a_own ? kt + 2 : kt + 2 - KT_);
       __builtin_amdgcn_sched_barrier(0);
       ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
       ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
       ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
       __builtin_amdgcn_sched_barrier(0);
-      sstore(sset, buf ^ 1);
-      wait_vm(VM_A{});
+      if constexpr (ADIR) {
+        wait_vm(VM_0{});        // both slabs have landed in the other buffer
+      } else {
+        sstore(sset, buf ^ 1);
+        wait_vm(VM_A{});
+      }
       __syncthreads();
       ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave();
     };
@@ -1006,6 +1101,15 @@ int cu_count() {
   return n;
 }
 
+// Activation slabs straight into LDS (no register hop): the persistent kernels (-5 % on the q/k, value and FC1
+// products of the 104-slice batch) and the residual product when K is long (FC2 -1 %; the short out-projection
+// is 1 % faster with its rows staged in registers two slabs ahead).  EPD_A_DIRECT=0 keeps the register-staged
+// forms, the ones these were measured against.
+bool a_direct() {
+  static const bool on = !(getenv("EPD_A_DIRECT") && getenv("EPD_A_DIRECT")[0] == '0');
+  return on;
+}
+
 template <int EPI, bool FOLD>
 hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   const int gm = (p.M + BM - 1) / BM, gn = p.Npad / 256;
@@ -1021,7 +1125,8 @@ hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
   const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
-  k_gemm_bf16_persist<EPI, FOLD><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  if (!FOLD && a_direct()) k_gemm_bf16_persist<EPI, false, true><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  else k_gemm_bf16_persist<EPI, FOLD><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
   ++g_kernel_launches;
   return hipGetLastError();
 }
@@ -1042,6 +1147,11 @@ hipError_t dispatch_persist(const GemmParams& p, hipStream_t st) {
 
 template <int EPI, bool FOLD>
 hipError_t set_attr_persist() {
+  if (!FOLD) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist<EPI, false, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>());
+    if (e != hipSuccess) return e;
+  }
   return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist<EPI, FOLD>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>());
 }
@@ -1104,6 +1214,7 @@ hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
+  if ((e = set_attr_all<256, 512, 64, 3>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_ERF, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_TANH, false>()) != hipSuccess) return e;
@@ -1133,6 +1244,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 3: if (p.K % 256 == 0) return dispatch<128, 512, 64, 2, 128>(p, st); break;
     case 6: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 0>(p, st); break;
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
+    case 8: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 3>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
   }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
@@ -1207,11 +1319,11 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
       b.A = p.A + (long)a.M * p.lda;
       b.R = p.R + (long)a.M * p.ldr;
       if (p.xb) { b.xb = p.xb + (long)a.M * p.ldxb; b.stats_out = p.stats_out + (long)a.M * p.n_part_out * 2; }
-      const hipError_t e = dispatch<256, 512, 64, 1>(a, st);
+      const hipError_t e = a_direct() ? dispatch<256, 512, 64, 3>(a, st) : dispatch<256, 512, 64, 1>(a, st);   // K >= 2048 here
       return e != hipSuccess ? e : dispatch<128, 512, 64>(b, st);
     }
   }
-  return dispatch<256, 512, 64, 1>(p, st);
+  return (a_direct() && p.K >= 2048) ? dispatch<256, 512, 64, 3>(p, st) : dispatch<256, 512, 64, 1>(p, st);
 }
 
 }  // namespace epd

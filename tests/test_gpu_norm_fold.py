@@ -69,7 +69,7 @@ def test_residual_epilogue_emits_the_rows_and_their_statistics_in_every_tile_sha
     r0[5] += 500.0
     plain = B.op_gemm_bf16_form(a, w, bias, 3, 0, torch.from_numpy(r0).cuda())
     torch.cuda.synchronize()
-    forms = [0, 1, 2] + ([3] if K % 256 == 0 else []) + ([6, 7] if N % 256 == 0 else [])
+    forms = [0, 1, 2] + ([3] if K % 256 == 0 else []) + ([6, 7, 8] if N % 256 == 0 else [])
     ref = None
     for form in forms:
         r = torch.from_numpy(r0).cuda()
@@ -109,7 +109,7 @@ def test_folded_norm_product_vs_oracle(kind, epi):
     want = O.gelu_erf(want) if epi == 1 else O.gelu_tanh(want) if epi == 2 else want
     dev = lambda a: torch.from_numpy(a).cuda()
     ref = None
-    for form in (0, 1, 2, 3, 6, 7, 9):
+    for form in (0, 1, 2, 3, 6, 7, 8, 9):
         c = B.op_norm_gemm_bf16(dev(x), dev(gamma), dev(beta) if beta is not None else None, B.to_device(w, True),
                                 dev(bias), eps, epi, form)
         torch.cuda.synchronize()
