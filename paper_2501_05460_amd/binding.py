@@ -14,7 +14,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libepd_encode.so")
+# EPD_LIB_PATH: another build of the library (the host-sanitizer build of build.py --sanitize, an A/B build)
+LIB_PATH = os.environ.get("EPD_LIB_PATH") or os.path.join(_HERE, "libepd_encode.so")
 
 EPD_OK = 0
 EPD_ERR_INVALID_ARG = -1

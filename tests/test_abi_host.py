@@ -127,3 +127,19 @@ def test_create_rejects_bad_arguments_before_touching_a_device():
     assert lib.epd_encode(None, None, 0, None, 0, None, None) == B.EPD_ERR_INVALID_ARG
     assert lib.epd_tokens_per_tile(None) == -1
     lib.epd_destroy(None)   # no-op
+
+
+def test_host_side_under_address_and_undefined_behaviour_sanitizers():
+    """The host half of the library (validation, block manager, dispatch arithmetic) built with
+    -fsanitize=address,undefined (`python -m paper_2501_05460_amd.build --sanitize`) runs this file's and the
+    block manager's tests clean.  Skipped when that build is not there (it is not part of the default build)."""
+    import subprocess
+    import sys
+    from paper_2501_05460_amd import build as bld
+    if not os.path.exists(bld.SAN_LIB) or os.environ.get("EPD_LIB_PATH"):
+        pytest.skip("sanitizer build not present (or already running under it)")
+    r = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", "-p", "no:cacheprovider",
+                        os.path.join(ROOT, "tests", "test_abi_host.py"), os.path.join(ROOT, "tests", "test_mm_cache_host.py")],
+                       env=bld.sanitized_env(), capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
+    assert "passed" in r.stdout and "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr
