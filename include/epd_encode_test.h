@@ -63,14 +63,16 @@ epd_status epd_op_norm_gemm_bf16(const float* x, const float* gamma, const float
 
 /* Tile-local non-causal attention on packed slices, bf16:  for every slice t
  * and head h, O = softmax(Q K^T / sqrt(hd)) V over the slice's own n_tokens
- * keys.  q, k dev bf16 [T * n_tokens, H * hd_pad] with row stride ld_qk
- * elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
- * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0;
- * `scale` multiplies the logits.  Only the first n_keys (1 .. n_tokens) rows of a slice are tokens:
+ * keys.  The kernel takes the logits in the log2 domain straight from the product: the caller's q must
+ * carry the factor log2(e) / sqrt(hd) (the library folds it into the q projection), i.e. the weight of
+ * key j for query i is 2^(q_i . k_j) / sum_j' 2^(q_i . k_j').  q, k dev bf16 [T * n_tokens, H * hd_pad]
+ * with row stride ld_qk elements; vt dev bf16 [T, H, hd_pad, n_tokens] (values transposed); o dev
+ * bf16 [T * n_tokens, H * hd_pad].  hd_pad in {64, 72, 96, 128}, n_tokens % 64 == 0.
+ * Only the first n_keys (1 .. n_tokens) rows of a slice are tokens:
  * the others are left out of every softmax as keys, and their rows of o hold unused values. */
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o,
                                  int32_t n_slices, int32_t n_tokens, int32_t n_keys, int32_t heads,
-                                 int32_t hd_pad, int32_t ld_qk, float scale, void* hip_stream);
+                                 int32_t hd_pad, int32_t ld_qk, void* hip_stream);
 
 /* Check of the MFMA operand / result lane layout the kernels assume:
  * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one

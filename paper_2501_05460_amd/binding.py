@@ -97,7 +97,7 @@ def lib() -> ctypes.CDLL:
         L.epd_op_gemm_bf16.restype = i32
         L.epd_op_gemm_bf16_form.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.epd_op_gemm_bf16_form.restype = i32
-        L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, ctypes.c_float, vp]
+        L.epd_op_attention_bf16.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.epd_op_attention_bf16.restype = i32
         L.epd_op_mfma_probe.argtypes = [vp, vp, vp, vp]
         L.epd_op_mfma_probe.restype = i32
@@ -413,10 +413,11 @@ def op_gemm_bf16_form(A: torch.Tensor, W: torch.Tensor, bias: torch.Tensor, epi:
 
 
 def op_attention_bf16(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int,
-                      heads: int, hd_pad: int, ld_qk: int, scale: float, n_keys: Optional[int] = None) -> torch.Tensor:
+                      heads: int, hd_pad: int, ld_qk: int, n_keys: Optional[int] = None) -> torch.Tensor:
+    """q must carry the logit scale log2(e) / sqrt(hd): the kernel's weights are 2^(q . k)."""
     o = torch.empty((n_slices * n_tokens, heads * hd_pad), dtype=torch.bfloat16, device=q.device)
     s = lib().epd_op_attention_bf16(q.data_ptr(), k.data_ptr(), vt.data_ptr(), o.data_ptr(), n_slices,
-                                    n_tokens, n_tokens if n_keys is None else n_keys, heads, hd_pad, ld_qk, scale,
+                                    n_tokens, n_tokens if n_keys is None else n_keys, heads, hd_pad, ld_qk,
                                     _stream_ptr())
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())

@@ -19,6 +19,10 @@
 // from LDS feeds all QT sub-tiles of the wave.
 // Values arrive pre-transposed ([slice, head, hd, token]) from the value GEMM.
 //
+// The queries arrive carrying the logit scale: q = (1 / sqrt(hd)) log2(e) x (the projection that makes them has
+// the factor folded into its weights), so the S^T registers are the logits in the log2 domain as they stand
+// and the weights are exp2 of them with no arithmetic in between.
+//
 // The reference value m that is subtracted from a query's logits follows the
 // running maximum lazily: it moves (and the accumulators are rescaled) only
 // when a logit exceeds it by more than RESCALE_LOG2 in the log2 domain, which
@@ -75,7 +79,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
                                                         const bf16_t* __restrict__ vt,
                                                         bf16_t* __restrict__ o, int n_tok, int n_keys, int n_q,
                                                         int q_shared, int heads, int n_pairs, long ld_qk,
-                                                        long ld_o, float scale_log2e) {
+                                                        long ld_o) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
   constexpr int KS = SM::HDK / 16;   // k-steps of the S^T product
@@ -192,6 +196,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   // m_ref: the reference subtracted from this query's logits (log2 domain);
   // l_run: this lane's share of the running sum of weights (unused with SUM_MFMA)
   float m_ref[QT], l_run[QT];
+  // Wave-uniform: some query of the wave has a reference other than 0.  While it is false (the common case:
+  // logits of a few units) the exponentials are taken of the S^T registers as they are.
+  bool shifted = false;
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     m_ref[u] = 0.f;
@@ -245,9 +252,11 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
         for (int e = 0; e < 16; ++e)
           if (key0 + 8 * (e >> 2) + 4 * lh + (e & 3) >= n_keys) s[u][e] = -INFINITY;
       }
-      // shifted logits (log2 domain, relative to the reference as it stands)
+      // logits relative to the reference as it stands (log2 domain already: q carries the scale)
+      if (shifted) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[u][e] = fmaf(s[u][e], scale_log2e, -m_ref[u]);
+        for (int e = 0; e < 16; ++e) s[u][e] -= m_ref[u];
+      }
       float psum = 0.f;
       bool move;
       if (!SUM_MFMA) {
@@ -265,9 +274,22 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 #pragma unroll
         for (int e = 3; e < 15; e += 2) mx = fmaxf(fmaxf(mx, s[u][e]), s[u][e + 1]);
         mx = max_with_other_half(mx, s[u][15]);
+        // Whether THIS query's reference moves depends on its own logits only (the move is entered when any
+        // query of the wave asks for it): a query's bits must not depend on which other queries share its
+        // wave, which in slices whose rows are padded can be rows of the next slice.
+        bool mine;
+        if (!SUM_MFMA) {
+          const float t = (force || !(psum <= RESCALE_SUM)) ? 1.0f : 0.f;   // this lane's half of the query's keys
+          mine = max_with_other_half(t, t) > 0.f;
+        } else {
+          mine = force || mx > RESCALE_LOG2;
+        }
         if (!SUM_MFMA || force || __builtin_amdgcn_ballot_w64(mx > RESCALE_LOG2) != 0) {
-          // a lane whose sum exceeded 2^RESCALE_LOG2 holds a logit above RESCALE_LOG2 - 4 (16 weights)
-          const float d = (force || mx > RESCALE_LOG2 - 4.0f) ? mx : 0.f;   // this query's reference moves by d
+          // this query's reference moves by d: to the step's maximum (a sum above 2^RESCALE_LOG2 over 16 weights
+          // means a logit above RESCALE_LOG2 - 4).  First step: unless that maximum is within a few units of 0
+          // already (then the reference stays 0 and the step's weights stay below 2^4 each)
+          const float d = !mine ? 0.f : (force ? (fabsf(mx) > 4.0f ? mx : 0.f) : mx);
+          shifted = shifted || __builtin_amdgcn_ballot_w64(d != 0.f) != 0;
           // nothing has been accumulated before the first step (and the factor would overflow for a
           // first maximum below -127)
           const float alpha = force ? 1.0f : __builtin_amdgcn_exp2f(-d);
@@ -366,7 +388,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 
 template <int HD, int QT, bool MASK>
 hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                         int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
+                         int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
                          hipStream_t st) {
   // once per instantiation; the initialisation of a function-local static is safe against concurrent callers
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
@@ -378,34 +400,34 @@ hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf1
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
   k_attention_bf16<HD, QT, MASK><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
-      q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o, scale * 1.4426950408889634f);
+      q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o);
   return hipGetLastError();
 }
 
 template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
-                       int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o, float scale,
+                       int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
                        hipStream_t st) {
   return (n_keys < n_tok || n_tok % BKEY != 0)
-             ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st)
-             : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
+             ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st)
+             : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
 }
 
 }  // namespace
 
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                           int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
-                          long ld_o, float scale, hipStream_t st) {
+                          long ld_o, hipStream_t st) {
   if (n_slices == 0) return hipSuccess;
   // n_tok % 8: V^T rows are read in 16-byte chunks.  A slice whose rows are no multiple of the key block is
   // read up to 63 rows (q, k) / 63 elements (v^T) past its end: the caller's buffers must reach that far.
   if (n_tok % 8 != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok || n_q < 1) return hipErrorInvalidValue;
   if (!q_shared && n_q != n_tok) return hipErrorInvalidValue;   // a slice's own rows: one query per row
   switch (hd_pad) {
-    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
-    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
-    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
-    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, scale, st);
+    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
+    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
+    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
+    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
   }
   return hipErrorInvalidValue;
 }

@@ -391,6 +391,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   NOMEM_IF(!c->pos);
   if (x.cls) { c->cls = make_vec(c, w, wi.cls, x.D, x.D, id, st); NOMEM_IF(!c->cls); }
 
+  const float logit_scale = 1.4426950408889634f / sqrtf((float)x.hd);   // log2(e) / sqrt(hd)
   int f_pad = 0;
   for (int l = 0; l < x.L; ++l) {
     const LayerIdx& li = wi.layers[l];
@@ -425,6 +426,11 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w] + 2L * x.D * x.D, x.D, x.D, Wv, c->Dq, c->D_k, heads, id, st);
         pack_vector_f32(w->tensors[li.qkv_b], 1, 2 * x.D, bqk, qk_cols, heads, st);
         pack_vector_f32((const bf16_t*)w->tensors[li.qkv_b] + 2 * x.D, 1, x.D, bv, c->Dq, heads, st);
+        // The attention kernel takes its logits in the log2 domain straight from the q . k product: the factor
+        // (1 / sqrt(hd)) log2(e) rides on q.  Without a q/k norm it is folded into the q rows of the projection
+        // (each weight rounded to bf16 once more: the rounding errors of a row average out over the hidden
+        // dimension, unlike a second rounding of q itself); with one, into the norm's gain below.
+        if (d.qk_norm == EPD_QKNORM_NONE) scale_rows_by(Wqk, c->Dq, c->D_k, c->D_k, bqk, logit_scale, st);
         lw.qkv.W = Wqk; lw.qkv.b = bqk; lw.qkv.N = qk_cols; lw.qkv.K = c->D_k; lw.qkv.Npad = qk_pad;
         lw.v.W = Wv; lw.v.b = bv; lw.v.N = c->Dq; lw.v.K = c->D_k; lw.v.Npad = v_pad;
       }
@@ -437,10 +443,12 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         lw.qn_g = make_vec(c, w, li.qn_g, x.D, c->Dq, heads, st);
         lw.kn_g = make_vec(c, w, li.kn_g, x.D, c->Dq, heads, st);
         NOMEM_IF(!lw.qn_g || !lw.kn_g);
+        scale_vector(const_cast<float*>(lw.qn_g), c->Dq, logit_scale, st);
       } else if (d.qk_norm == EPD_QKNORM_PER_HEAD) {
         lw.qn_g = make_vec(c, w, li.qn_g, x.hd, c->hd_pad, id, st);
         lw.kn_g = make_vec(c, w, li.kn_g, x.hd, c->hd_pad, id, st);
         NOMEM_IF(!lw.qn_g || !lw.kn_g);
+        scale_vector(const_cast<float*>(lw.qn_g), c->hd_pad, logit_scale, st);
       }
     }
     if (d.layer_scale) {
@@ -492,6 +500,9 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     Linear lq;
     NOMEM_IF(!make_linear(c, w, wi.r_kv_w, -1, E, x.D, &r.kv, st, pad_n(E), c->D_k, id, id, E));
     NOMEM_IF(!make_linear_p(c, in_w, in_b, E, E, &lq, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
+    if (bf)   // the projected queries carry the logit scale of the cross attention (see the q rows of the layers)
+      scale_rows_by((bf16_t*)const_cast<void*>(lq.W), r.Eq, r.E_k, r.E_k, const_cast<float*>(lq.b),
+                    1.4426950408889634f / sqrtf((float)r.hd), st);
     NOMEM_IF(!make_linear_p(c, tensor_at(c, in_w, (long)E * E), tensor_at(c, in_b, E), E, E, &r.k, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
     NOMEM_IF(!make_linear_p(c, tensor_at(c, in_w, 2L * E * E), tensor_at(c, in_b, 2L * E), E, E, &r.v, st, pad_n(r.Eq), r.E_k, rh, id, r.Eq));
     NOMEM_IF(!make_linear(c, w, wi.r_out_w, wi.r_out_b, E, E, &r.o, st, pad_n(E), r.Eq_k, id, rh, E));
@@ -719,7 +730,6 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   bf16_t* Xn = (bf16_t*)c->Xn; bf16_t* QK = (bf16_t*)c->QKV; bf16_t* VT = (bf16_t*)c->VT; bf16_t* O = (bf16_t*)c->O;
   bf16_t* Hd = (bf16_t*)c->Hd; bf16_t* Ape = (bf16_t*)c->Ape; bf16_t* Pin = (bf16_t*)c->Pin; bf16_t* Pmid = (bf16_t*)c->Pmid;
   const int act_epi = d.act == EPD_ACT_GELU_ERF ? EPI_BIAS_GELU_ERF : EPI_BIAS_GELU_TANH;
-  const float scale = 1.0f / sqrtf((float)x.hd);
   const long ld_qk = 2L * c->Dq;
 
   if (stage == STAGE_PROJECT) {
@@ -788,7 +798,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       bf16_qknorm(QK, ld_qk, c->Dq, w.qn_g, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
     }
     { ProfScope ps(c, 3, st);
-      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, scale, st)); }
+      HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, st)); }
     { ProfScope ps(c, 6, st);
       GemmParams p = gp(EPI_BIAS_RESIDUAL, O, c->Dq_k, w.o, M);
       p.R = X; p.ldr = x.D;
@@ -836,8 +846,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       pv.VT = (bf16_t*)r.V; pv.hd_pad = r.hd_pad; pv.heads = r.H; pv.n_tok = x.N;
       HIP_TRY(c, bf16_gemm(pv, st)); }
     { ProfScope ps(c, 3, st);
-      HIP_TRY(c, bf16_attention((const bf16_t*)r.qp, K, (const bf16_t*)r.V, Oq, T, x.N, x.N, r.Q, 1, r.H, r.hd_pad, r.Eq_k, r.Eq_k,
-                                1.0f / sqrtf((float)r.hd), st)); }
+      HIP_TRY(c, bf16_attention((const bf16_t*)r.qp, K, (const bf16_t*)r.V, Oq, T, x.N, x.N, r.Q, 1, r.H, r.hd_pad, r.Eq_k, r.Eq_k, st)); }
     { ProfScope ps(c, 9, st);
       GemmParams p = gp(EPI_BIAS, Oq, r.Eq_k, r.o, Mo);
       p.C = o2; p.ldc = r.E_k;
@@ -1303,11 +1312,11 @@ epd_status epd_op_norm_gemm_bf16(const float* x, const float* gamma, const float
 
 epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, void* o, int32_t n_slices,
                                  int32_t n_tokens, int32_t n_keys, int32_t heads, int32_t hd_pad, int32_t ld_qk,
-                                 float scale, void* hip_stream) {
+                                 void* hip_stream) {
   if (!q || !k || !vt || !o) return EPD_ERR_INVALID_ARG;
   if (n_tokens % 64) { set_err(g_err, sizeof(g_err), "epd_op_attention_bf16: n_tokens %% 64 != 0"); return EPD_ERR_UNSUPPORTED; }
   hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, (bf16_t*)o, n_slices,
-                                n_tokens, n_keys, n_tokens, 0, heads, hd_pad, ld_qk, (long)heads * hd_pad, scale, (hipStream_t)hip_stream);
+                                n_tokens, n_keys, n_tokens, 0, heads, hd_pad, ld_qk, (long)heads * hd_pad, (hipStream_t)hip_stream);
   if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }
   return EPD_OK;
 }

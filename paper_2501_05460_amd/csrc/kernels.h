@@ -124,9 +124,16 @@ void bf16_qknorm(bf16_t* buf, long ld, long k_off, const float* gamma_q, const f
 // n_q queries per slice (n_tok unless q_shared); q_shared: the query rows are rows 0 .. n_q-1 of q
 // for every slice (learned queries of the resampler; q must be readable for round_up(n_q, 32) rows) instead
 // of the slice's own rows.  Row t * n_q + i of o is query i of slice t.
+// The queries carry the logit scale: weight of key j for query i = 2^(q_i . k_j) / sum_j' 2^(q_i . k_j').
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                           int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
-                          long ld_o, float scale, hipStream_t st);
+                          long ld_o, hipStream_t st);
+
+// W[r][0..cols) *= c (rounded to bf16 again) and b[r] *= c for r < rows: a constant factor of a product's
+// output folded into the rows of its packed weights
+void scale_rows_by(bf16_t* W, int rows, int cols, long ld, float* b, float c, hipStream_t st);
+// v[i] *= c for i < n (fp32)
+void scale_vector(float* v, int n, float c, hipStream_t st);
 
 // LayerNorm of bf16 rows (statistics in fp32 over `dim` elements, dim % 4 == 0): out = LN(in) and, when
 // out_plus is set, out_plus = LN(in) + add[row % add_rows] (fp32 table [add_rows, dim]).

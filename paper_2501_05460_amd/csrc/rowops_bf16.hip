@@ -515,6 +515,31 @@ void scale_rows(void* W, int w_is_bf16, int rows, int cols, long ld, float* b, c
   else k_scale_rows<float><<<grid, block, 0, st>>>((float*)W, rows, cols, ld, b, s);
 }
 
+// W[r][0..cols) *= c and b[r] *= c for r < rows (bf16 matrix, fp32 bias)
+__global__ void k_scale_rows_by(bf16_t* __restrict__ W, int rows, int cols, long ld, float* __restrict__ b, float c) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)rows * cols) return;
+  const int r = (int)(i / cols), k = (int)(i % cols);
+  W[(long)r * ld + k] = (bf16_t)((float)W[(long)r * ld + k] * c);
+  if (k == 0) b[r] *= c;
+}
+
+void scale_rows_by(bf16_t* W, int rows, int cols, long ld, float* b, float c, hipStream_t st) {
+  const long total = (long)rows * cols;
+  if (total == 0) return;
+  k_scale_rows_by<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>(W, rows, cols, ld, b, c);
+}
+
+__global__ void k_scale_vector(float* __restrict__ v, int n, float c) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) v[i] *= c;
+}
+
+void scale_vector(float* v, int n, float c, hipStream_t st) {
+  if (n <= 0) return;
+  k_scale_vector<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(v, n, c);
+}
+
 // ------------------------------------------------- paged cache block copy ----
 // `per_block` consecutive workgroups share one cache block, each moving chunks
 // of 16 KiB: a thread issues four 16-byte loads before the four stores, so a

@@ -44,6 +44,15 @@ def test_gemm_bf16_vs_oracle_linear(M, N, K):
     np.testing.assert_allclose(got, want, rtol=2 ** -7, atol=2 ** -7 * np.abs(want).max() * 0.05)
 
 
+def _scaled_q(q, hd):
+    """The attention kernel takes its logits in the log2 domain straight from q . k: q carries the factor
+    log2(e) / sqrt(hd) (the library folds it into the q projection).  Returns that q on the bf16 grid, and the
+    q the oracle has to be given so that its logits q . k / sqrt(hd) are the same numbers."""
+    c = math.log2(math.e) / math.sqrt(hd)
+    qs = torch.from_numpy(np.asarray(q * c, np.float32)).bfloat16().float().numpy()
+    return qs, qs.astype(np.float64) / c
+
+
 def _attention_case(n_slices, n_tok, heads, hd, hd_pad, qk_scale, seed):
     rng = np.random.default_rng(seed)
     M = n_slices * n_tok
@@ -59,11 +68,11 @@ def _attention_case(n_slices, n_tok, heads, hd, hd_pad, qk_scale, seed):
             out[:, h * hd_pad:h * hd_pad + hd] = x[:, h * hd:(h + 1) * hd]
         return out
 
-    qk = np.concatenate([pad_heads(q), pad_heads(k)], axis=1)          # [M, 2*Dq]
+    q_dev, q = _scaled_q(q, hd)
+    qk = np.concatenate([pad_heads(q_dev), pad_heads(k)], axis=1)          # [M, 2*Dq]
     vt = pad_heads(v).reshape(n_slices, n_tok, heads, hd_pad).transpose(0, 2, 3, 1).copy()
     qk_d = B.to_device(qk, True)
-    o = B.op_attention_bf16(qk_d, qk_d[:, Dq:], B.to_device(vt, True), n_slices, n_tok, heads, hd_pad,
-                            2 * Dq, 1.0 / math.sqrt(hd))
+    o = B.op_attention_bf16(qk_d, qk_d[:, Dq:], B.to_device(vt, True), n_slices, n_tok, heads, hd_pad, 2 * Dq)
     torch.cuda.synchronize()
     got = o.float().cpu().numpy().reshape(M, heads, hd_pad)
     assert np.all(got[:, :, hd:] == 0.0)
@@ -109,11 +118,12 @@ def test_attention_bf16_ignores_rows_past_n_keys(n_tok, n_keys, heads, hd, hd_pa
             out[:, h * hd_pad:h * hd_pad + hd] = x[:, h * hd:(h + 1) * hd]
         return out
 
-    qk = np.concatenate([pad_heads(q), pad_heads(k)], axis=1)
+    q_dev, q = _scaled_q(q, hd)
+    qk = np.concatenate([pad_heads(q_dev), pad_heads(k)], axis=1)
     vt = pad_heads(v).reshape(n_slices, n_tok, heads, hd_pad).transpose(0, 2, 3, 1).copy()
     qk_d = B.to_device(qk, True)
     o = B.op_attention_bf16(qk_d, qk_d[:, Dq:], B.to_device(vt, True), n_slices, n_tok, heads, hd_pad,
-                            2 * Dq, 1.0 / math.sqrt(hd), n_keys=n_keys)
+                            2 * Dq, n_keys=n_keys)
     torch.cuda.synchronize()
     got = o.float().cpu().numpy().reshape(M, heads, hd_pad)[:, :, :hd].reshape(M, D)
     assert np.isfinite(got).all()
@@ -126,11 +136,11 @@ def test_attention_bf16_ignores_rows_past_n_keys(n_tok, n_keys, heads, hd, hd_pa
 def _attention_run(q, k, v, n_slices, n_tok, heads, hd):
     """q, k, v [M, heads * hd] on the bf16 grid -> kernel output and oracle output, both [M, heads * hd]."""
     M, D = q.shape
-    qk = np.concatenate([q, k], axis=1).astype(np.float32)
+    q_dev, q = _scaled_q(q, hd)
+    qk = np.concatenate([q_dev, k], axis=1).astype(np.float32)
     vt = v.reshape(n_slices, n_tok, heads, hd).transpose(0, 2, 3, 1).copy().astype(np.float32)
     qk_d = B.to_device(qk, True)
-    o = B.op_attention_bf16(qk_d, qk_d[:, D:], B.to_device(vt, True), n_slices, n_tok, heads, hd, 2 * D,
-                            1.0 / math.sqrt(hd))
+    o = B.op_attention_bf16(qk_d, qk_d[:, D:], B.to_device(vt, True), n_slices, n_tok, heads, hd, 2 * D)
     torch.cuda.synchronize()
     got = o.float().cpu().numpy().reshape(M, D)
     want = np.concatenate([O.attention(q[s * n_tok:(s + 1) * n_tok], k[s * n_tok:(s + 1) * n_tok],
