@@ -1058,6 +1058,230 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
   }
 }
 
+// ---------------------------------------------------------------------------
+// Persistent form of the residual product, R += A W^T + bias on the fp32 stream: the tile walk and the main loop
+// of the persistent kernel above (both operand slabs straight into LDS, the loads past a tile's last slab fetch
+// the next tile's first slab into buffer 0), and the four-pass fp32 read-modify-write epilogue staged through
+// LDS buffer 1 only.  A pass holds sub-tile row group i = pass of all eight waves (rows wm * 128 + 32 pass ..
+// + 31 of both wave rows: staging row r = 32 wm + row), so every wave stages in every pass.  The stream rows of
+// the first two passes are fetched while the last two slabs are multiplied, those of pass p + 2 behind pass p.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmParams p, const int gm_, const int gw,
+                                                                  const int n_tiles) {
+  constexpr int BN = 256, NTHREADS = 512, WN = 64, WAVES_N = 4, WM = 128, TM = 4, TN = 2;
+  constexpr int A_LD = 4, B_LD = 4, ROWS_PER_LD = 64;
+  constexpr int XNCH = BN * 4 / 16;                // 16-byte chunks per staging row: one wave reads one row
+  constexpr int XSTEP = NTHREADS / XNCH;           // 8 staging rows between a thread's chunks
+  constexpr int XPER_T = 64 * XNCH / NTHREADS;     // 8 chunks per thread and pass
+  constexpr int ROWB = BN * 4;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* sB = reinterpret_cast<bf16_t*>(smem);  // [2][BN][64]: bytes 0 .. 64 Ki
+  bf16_t* sA = sB + 2 * BN * BK;                 // [2][BM][64]: bytes 64 Ki .. 128 Ki
+  float* sBias = reinterpret_cast<float*>(smem + smem_main_bytes<BN, NTHREADS>());
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int KT_ = p.K / BK;  // even
+  const int gn = p.Npad / BN;
+
+  auto tile_of = [&](int pos, int& m0, int& n0) {
+    const int x = pos & 7, slot = pos >> 3;
+    const int q = n_tiles >> 3, r = n_tiles & 7;
+    const int id = x * q + (x < r ? x : r) + slot;
+    const int band_tiles = gm_ * gw;
+    const int full_bands = gn / gw;
+    int band = id / band_tiles, in_band = id % band_tiles, bw = gw;
+    if (band >= full_bands) { band = full_bands; in_band = id - full_bands * band_tiles; bw = gn - full_bands * gw; }
+    m0 = (in_band / bw) * BM;
+    n0 = (band * gw + in_band % bw) * BN;
+  };
+
+  const int ld_row = tid >> 3, ld_c = tid & 7;
+  const unsigned ad_voff = ((unsigned)ld_row * (unsigned)p.lda + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  const unsigned bd_voff = ((unsigned)ld_row * (unsigned)p.K + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma = [&](const bf16_t* g, bf16_t* l, unsigned voff) {
+    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+  };
+  auto bload = [&](int buf, int ncol0, int kt) {
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i)
+      dma(p.W + (long)(ncol0 + ROWS_PER_LD * i) * p.K + kt * BK, sB + buf * BN * BK + (wave_u * 64 + NTHREADS * i) * 8, bd_voff);
+  };
+  auto aload = [&](int buf, int mrow0, int kt) {
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i)
+      dma(p.A + (long)(mrow0 + ROWS_PER_LD * i) * p.lda + kt * BK, sA + buf * BM * BK + (wave_u * 64 + NTHREADS * i) * 8, ad_voff);
+  };
+  auto wait_vm = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
+  };
+
+  f32x16 acc[TM][TN];
+  bf16x8 fa[2][TM], fb[2][TN];
+  const int frag_sw = SWZ(l32);
+  auto ldfrag = [&](auto set, int buf, int kk) {
+    constexpr int S = decltype(set)::value;
+    const bf16_t* a_s = sA + buf * BM * BK + (wm * WM + l32) * BK;
+    const bf16_t* b_s = sB + buf * BN * BK + (wn * WN + l32) * BK;
+    const int coff = (((2 * kk + lh) ^ frag_sw) * 8);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[S][i] = *reinterpret_cast<const bf16x8*>(a_s + i * 32 * BK + coff);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[S][j] = *reinterpret_cast<const bf16x8*>(b_s + j * 32 * BK + coff);
+  };
+  auto mma = [&](auto set) {
+    constexpr int S = decltype(set)::value;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fb[S][j], fa[S][i], acc[i][j]);
+  };
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM + TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  using VM_0 = std::integral_constant<int, 0>;
+  using VM_X = std::integral_constant<int, XPER_T>;
+
+  // Stream rows of an epilogue pass through a buffer descriptor: every lane of every wave issues exactly XPER_T
+  // loads whatever the tile's position (rows past M are read like any other: R holds whole tiles; columns past N
+  // fall outside the descriptor's range and come back as zero), so a wait can count them.
+  __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+      p.R, 0, (int)(unsigned)(((long)(p.M - 1) * p.ldr + p.N) * 4), 0x00020000);
+  f32x4 xr[2][XPER_T];
+  // staging row r of a pass <-> tile row (r / 32) * 128 + 32 pass + r % 32
+  auto tile_row = [&](int pass, int r) { return (r >> 5) * 128 + pass * 32 + (r & 31); };
+
+  int pos = blockIdx.x, m0, n0, m0n, n0n;
+  tile_of(pos, m0, n0);
+  if (tid < BN) sBias[tid] = p.bias[n0 + tid];
+  bload(0, n0, 0);
+  aload(0, m0, 0);
+  wait_vm(VM_0{});
+  __syncthreads();
+
+  for (;;) {
+    ldfrag(S0{}, 0, 0);
+    const int nxt = pos + (int)gridDim.x;
+    const bool has_next = nxt < n_tiles;
+    if (has_next) tile_of(nxt, m0n, n0n); else { m0n = m0; n0n = n0; }   // no next tile: harmless re-reads
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // the thread's chunk of the stream: column n0 + 4 (tid % 64), rows given by the pass
+    const int x_col = n0 + (tid % XNCH) * 4;
+    const bool x_col_ok = x_col < p.N;
+    auto xload = [&](auto set, int pass) {
+      constexpr int S = decltype(set)::value;
+#pragma unroll
+      for (int i = 0; i < XPER_T; ++i)
+        xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+            rsrc_x, (unsigned)x_col * 4u, (unsigned)(m0 + tile_row(pass, wave_u + XSTEP * i)) * (unsigned)p.ldr * 4u, 2));
+    };
+    // PHASE 0: a slab in the middle of the tile; 1: the slab before the last (also starts the stream rows of pass 0,
+    // which its wait leaves in flight); 2: the last slab (fetches the next tile's first slab, starts pass 1's rows)
+    auto slab = [&](int buf, int kt, auto phase) {
+      constexpr int PHASE = decltype(phase)::value;
+      const bool own = kt + 1 < KT_;
+      bload(buf ^ 1, own ? n0 : n0n, own ? kt + 1 : 0);
+      aload(buf ^ 1, own ? m0 : m0n, own ? kt + 1 : 0);
+      if constexpr (PHASE == 1) xload(S0{}, 0);
+      if constexpr (PHASE == 2) xload(S1{}, 1);
+      __builtin_amdgcn_sched_barrier(0);
+      ldfrag(S1{}, buf, 1); mma(S0{}); interleave();
+      ldfrag(S0{}, buf, 2); mma(S1{}); interleave();
+      ldfrag(S1{}, buf, 3); mma(S0{}); interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      // loads complete in order: everything but the newest stream rows has landed
+      if constexpr (PHASE == 0) wait_vm(VM_0{}); else wait_vm(VM_X{});
+      __syncthreads();
+      if constexpr (PHASE < 2) { ldfrag(S0{}, buf ^ 1, 0); mma(S1{}); interleave(); }
+      else mma(S1{});
+    };
+    for (int kt = 0; kt < KT_ - 2; kt += 2) {
+      slab(0, kt, std::integral_constant<int, 0>{});
+      slab(1, kt + 1, std::integral_constant<int, 0>{});
+    }
+    slab(0, KT_ - 2, std::integral_constant<int, 1>{});
+    slab(1, KT_ - 1, std::integral_constant<int, 2>{});
+    // LDS buffer 0 now holds slab 0 of the next tile; nobody reads buffer 1 any more.
+
+    // ---- epilogue through LDS buffer 1: staging rows 0..31 in sB[1], 32..63 in sA[1], [row][256] floats ----
+    {
+      // addresses from an opaque copy of the thread index, made anew per tile (see the persistent kernel above)
+      int tid_opaque = threadIdx.x;
+      asm volatile("" : "+v"(tid_opaque));
+      const int tid = tid_opaque, lane = tid & 63, wave = tid >> 6;
+      const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+      const int l32 = lane & 31, lh = lane >> 5;
+      const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+      auto stage_row = [&](int r) -> unsigned char* {
+        return reinterpret_cast<unsigned char*>(r < 32 ? sB + BN * BK : sA + BM * BK) + (r & 31) * ROWB;
+      };
+      auto fp32_pass = [&](auto set, int pass) {
+        constexpr int S = decltype(set)::value;
+        if (pass > 0) __syncthreads();   // the previous pass has been read out
+        {
+          const int r = wm * 32 + l32;   // this lane's staging row: sub-tile i = pass of its wave
+          unsigned char* srow = stage_row(r);
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+              const int cl = wn * WN + j * 32 + gi * 8 + lh * 4;
+              const f32x4 b4 = *reinterpret_cast<const f32x4*>(sBias + cl);
+              f32x4 v;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                // acc[pass][j] with a compile-time first index: the pass loop below is unrolled
+                v[e] = (pass == 0 ? acc[0][j][gi * 4 + e] : pass == 1 ? acc[1][j][gi * 4 + e]
+                        : pass == 2 ? acc[2][j][gi * 4 + e] : acc[3][j][gi * 4 + e]) + b4[e];
+              }
+              *reinterpret_cast<f32x4*>(srow + (((cl >> 2) ^ (r & 15)) << 4)) = v;
+            }
+        }
+        __syncthreads();
+        if (pass == 3 && has_next && tid < BN) sBias[tid] = p.bias[n0n + tid];   // every bias read is behind us
+        if (x_col_ok) {
+          const int c = tid % XNCH;
+#pragma unroll
+          for (int i = 0; i < XPER_T; ++i) {
+            const int r = wave_u + XSTEP * i;
+            const int row = m0 + tile_row(pass, r);              // uniform
+            if (row < p.M) {
+              const f32x4 v = *reinterpret_cast<const f32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
+              __builtin_nontemporal_store(xr[S][i] + v, reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + x_col));
+            }
+          }
+        }
+        if (pass + 2 < 4) xload(set, pass + 2);
+      };
+      fp32_pass(S0{}, 0);
+      fp32_pass(S1{}, 1);
+      fp32_pass(S0{}, 2);
+      fp32_pass(S1{}, 3);
+    }
+    if (!has_next) break;
+    __syncthreads();   // buffer 1 has been read out: the next tile's first hand-over may fill it
+    pos = nxt; m0 = m0n; n0 = n0n;
+  }
+}
+
 // behind the operand slabs: the tile's bias values, and for a folded pre-norm the column sums of its
 // weights and the mean / rstd of its rows
 template <int BN, int NT, int BM_ = BM>
@@ -1127,6 +1351,31 @@ hipError_t launch_persist(const GemmParams& p, hipStream_t st) {
   const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
   if (!FOLD && a_direct()) k_gemm_bf16_persist<EPI, false, true><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
   else k_gemm_bf16_persist<EPI, FOLD><<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  ++g_kernel_launches;
+  return hipGetLastError();
+}
+
+bool persist_res() {   // EPD_PERSIST_RES=0: the residual products stay on the one-tile-per-workgroup kernels
+  static const bool on = !(getenv("EPD_PERSIST_RES") && getenv("EPD_PERSIST_RES")[0] == '0');
+  return on;
+}
+
+// residual product on the persistent kernel (whole 256 x 256 tiles; no bf16 rows / statistics emitted)
+hipError_t launch_persist_res(const GemmParams& p, hipStream_t st) {
+  const int gm = (p.M + BM - 1) / BM, gn = p.Npad / 256;
+  const int n_tiles = gm * gn;
+  if (n_tiles == 0) return hipSuccess;
+  const double panel = 256.0 * p.K * sizeof(bf16_t);
+  int gw = 1;
+  double best = 1e30;
+  for (int c = 1; c <= gn && c <= 32; ++c) {
+    const bool resident = c * 256.0 * p.K * sizeof(bf16_t) <= 2.5 * (1 << 20);
+    const double cost = (32.0 / c) * panel + (resident ? 0.0 : c * panel);
+    if (cost < best * 0.999) { best = cost; gw = c; }
+  }
+  if (p.band > 0 && p.band <= gn) gw = p.band;
+  const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
+  k_gemm_bf16_persist_res<<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
   ++g_kernel_launches;
   return hipGetLastError();
 }
@@ -1215,6 +1464,8 @@ hipError_t bf16_gemm_init() {
   if (e != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 3>()) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist_res),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>())) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_ERF, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_TANH, false>()) != hipSuccess) return e;
@@ -1246,6 +1497,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 7: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 1>(p, st); break;
     case 8: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 3>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
+    case 10: if (p.Npad % 256 == 0 && p.epi == EPI_BIAS_RESIDUAL && !p.xb) return launch_persist_res(p, st); break;
   }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
   // A width like 3200 leaves the last 256-wide tile column half used.  When that column is also what
@@ -1319,10 +1571,12 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
       b.A = p.A + (long)a.M * p.lda;
       b.R = p.R + (long)a.M * p.ldr;
       if (p.xb) { b.xb = p.xb + (long)a.M * p.ldxb; b.stats_out = p.stats_out + (long)a.M * p.n_part_out * 2; }
-      const hipError_t e = a_direct() ? dispatch<256, 512, 64, 3>(a, st) : dispatch<256, 512, 64, 1>(a, st);   // K >= 2048 here
+      const hipError_t e = (persist_res() && !a.xb) ? launch_persist_res(a, st)
+                           : a_direct() ? dispatch<256, 512, 64, 3>(a, st) : dispatch<256, 512, 64, 1>(a, st);   // K >= 2048 here
       return e != hipSuccess ? e : dispatch<128, 512, 64>(b, st);
     }
   }
+  if (p.epi == EPI_BIAS_RESIDUAL && persist_res() && !p.xb) return launch_persist_res(p, st);
   return (a_direct() && p.K >= 2048) ? dispatch<256, 512, 64, 3>(p, st) : dispatch<256, 512, 64, 1>(p, st);
 }
 

@@ -226,7 +226,7 @@ def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
         return out.view(torch.int16 if epi != 3 else torch.int32).cpu().numpy()
 
     ref = run(6)
-    forms = [0, 1, 2, 7, 8] + ([3] if K % 256 == 0 else []) + ([9] if epi != 3 else [])
+    forms = [0, 1, 2, 7, 8] + ([3] if K % 256 == 0 else []) + ([9] if epi != 3 else [10])
     for form in forms:
         assert np.array_equal(run(form), ref), form
     if epi == 0:   # and the value itself, against the oracle
