@@ -1558,7 +1558,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
   // (rows are independent, all addressing is by pointer) is cut by rows instead: whole rounds of
   // 256-wide tiles, then the remaining rows as one round of 128-wide tiles, half as long.  Same bits.
   // Measured: -4 % on the K = 12800 product of the 6B shape, -1 % at K = 4096, +2 % at K = 1024 (the
-  // second launch costs more than the short tiles save), hence the K limit.
+  // second launch costs more than the short tiles save; +0.6 % with the persistent kernel), hence the K limit.
   if (p.epi == EPI_BIAS_RESIDUAL && p.K >= 2048) {
     const long cu = cu_count(), gn = p.Npad / 256, gm = (p.M + BM - 1) / BM;
     const long rounds = tiles256 / cu, rem = tiles256 % cu;
