@@ -259,7 +259,7 @@ def main():
         n_req = offsets[1] - offsets[0]
         n_out = desc.tokens_per_tile
         sizes = sorted({n for n in (1, 2, 4, 8, 16, 32) if n < n_req} | {-(-n_req // w) for w in (2, 3, 4)} | {n_req})
-        lat = {}
+        lat, wall = {}, {}
         for n in sizes:
             for _ in range(3):
                 enc.encode(tiles[:n], [0, n], out[:n * n_out])
@@ -271,8 +271,20 @@ def main():
             ev1.record()
             torch.cuda.synchronize()
             lat[n] = ev0.elapsed_time(ev1) / reps
+            # one call alone, as a worker sees it: host clock from the call to the end of the stream's work
+            ws = []
+            for _ in range(10):
+                torch.cuda.synchronize()
+                h0 = time.perf_counter()
+                enc.encode(tiles[:n], [0, n], out[:n * n_out])
+                torch.cuda.synchronize()
+                ws.append((time.perf_counter() - h0) * 1e3)
+            wall[n] = float(np.median(ws))
         shard = {"request_tiles": n_req,
                  "ms_by_tiles": {str(n): round(v, 3) for n, v in lat.items()},
+                 # wall latency of a single call against its time on the GPU: what issuing ~200 launches from the host costs
+                 "wall_ms_single_call_by_tiles": {str(n): round(v, 3) for n, v in wall.items()},
+                 "wall_over_gpu": {str(n): round(wall[n] / lat[n], 3) for n in sizes},
                  # a request cut over w workers takes as long as its largest share
                  "speedup_by_workers": {str(w): round(lat[n_req] / lat[-(-n_req // w)], 2) for w in (2, 3, 4)}}
         enc.encode(tiles, offsets, out)    # the whole batch again: the parity sample below reads `out`
