@@ -223,11 +223,14 @@ def main():
             "proj_input": T * desc.tokens_per_tile * desc.proj_in * (4 + 2) if desc.proj_kind != 2 else None,
         }
         hbm = {"peak_GBps": 8000.0, "copy_GBps_measured": round(B.op_copy_peak(), 1)}
+        # a call of more slices than max_tiles_per_call runs micro-batches: a launch covers one of them, so the
+        # whole-batch byte counts above are spread over n_mb launches (mean bytes per launch)
+        n_mb = -(-T // desc.max_tiles_per_call)
         for k, nbytes in per_launch.items():
             if nbytes and fam[k]["launches"] > 0 and fam[k]["ms"] > 0:
-                gbps = nbytes * fam[k]["launches"] / (fam[k]["ms"] * 1e-3) / 1e9
+                gbps = nbytes / n_mb * fam[k]["launches"] / (fam[k]["ms"] * 1e-3) / 1e9
                 hbm[k] = {"GBps": round(gbps, 1), "frac_of_peak": round(gbps / 8000.0, 3),
-                          "bytes_per_launch": nbytes, "launches_per_step": fam[k]["launches"] // prof_steps}
+                          "bytes_per_launch": nbytes // n_mb, "launches_per_step": fam[k]["launches"] // prof_steps}
 
     # ---- maximum encode batch size: latency of one call against throughput ----
     sweep = None
