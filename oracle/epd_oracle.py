@@ -31,6 +31,11 @@ tiny encoder (class token placed last there, the library's multi-head
 attention module for the resampler), explicit loops for one resampler query
 and for one patch query next to a class token, and the independence /
 permutation / shard invariants.
+The MXFP8 option (`desc.mx_fp8`) follows the OCP Microscaling Formats (MX)
+specification v1.0 and the OCP 8-bit floating point specification (E4M3); its
+pins (tests/test_oracle_mx.py): the library's own float8 decode and conversion,
+brute-force nearest-value search over the 256 codes, hand-worked blocks,
+power-of-two invariance, a triple loop over codes and block scales.
 Parity unpinned: fidelity to the *trained* SigLIP / InternViT checkpoints (no
 weights or reference activations exist here; the target does not need them).
 """
@@ -129,6 +134,97 @@ def pixel_shuffle_half(x, g: int):
     return t.transpose(0, 2, 1, 3, 4).reshape(h * h, 4 * D)
 
 
+# ------------------------------------------------------------- MXFP8 option ----
+# Checkpoint-fidelity option `mx_fp8` (narrower than the FP16 the paper serves in, Appendix
+# "Implementation Details": an option, never the headline precision).  The operands of the q/k/v,
+# FC1 and FC2 products of every layer are quantised to the MXFP8 format of the OCP Microscaling
+# Formats specification v1.0: along the contraction dimension, blocks of 32 consecutive elements
+# share one power-of-two scale (E8M0: an 8-bit biased exponent, X = 2^(byte - 127)) and each element
+# is an OCP FP8 E4M3 number (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals;
+# largest finite value 448; no infinities).  Conversion (section 6.3 of that specification):
+#   shared exponent = floor(log2(max |v_i|)) - 8      (8 = exponent of the largest E4M3 binade)
+#   element_i       = E4M3 value nearest to v_i / X, ties to the even mantissa, saturated to +-448
+# Readings: a block of zeros takes the scale byte 0 (the specification leaves it open); the scale
+# byte is clamped to 0 .. 254 (255 is the format's NaN); inputs are finite.
+
+MX_BLOCK = 32
+E4M3_MAX = 448.0
+_E4M3_EMAX = 8          # 448 = 1.75 * 2^8
+_E4M3_EMIN = -6         # smallest normal 2^-6; subnormals are multiples of 2^-9
+_E8M0_BIAS = 127
+
+
+def e4m3_decode(code) -> np.ndarray:
+    """Value of an E4M3 byte: (-1)^s * 2^(e - 7) * (1 + m / 8) for e > 0, (-1)^s * 2^-6 * (m / 8)
+    for e = 0; s.1111.111 is NaN."""
+    c = np.asarray(code).astype(np.int64)
+    s, e, m = (c >> 7) & 1, (c >> 3) & 15, c & 7
+    mag = np.where(e > 0, np.ldexp(1.0 + m / 8.0, e - 7), np.ldexp(m / 8.0, _E4M3_EMIN))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(s == 1, -mag, mag).astype(F64)
+
+
+def e4m3_round(x) -> np.ndarray:
+    """Nearest E4M3 value, ties to the even mantissa, saturating at +-448."""
+    x = np.asarray(x, F64)
+    a = np.abs(x)
+    _, e = np.frexp(a)                               # a = f * 2^e with f in [0.5, 1)
+    binade = np.maximum(e - 1, _E4M3_EMIN)           # exponent of the value's binade, subnormals share 2^-6's
+    quantum = np.ldexp(1.0, binade - 3)              # spacing of E4M3 values in that binade (3 mantissa bits)
+    r = np.minimum(np.rint(a / quantum) * quantum, E4M3_MAX)   # rint rounds halves to even
+    return np.copysign(r, x)
+
+
+def e4m3_encode(x) -> np.ndarray:
+    """Byte of e4m3_round(x) (the sign bit of a negative zero is kept)."""
+    v = e4m3_round(x)
+    a = np.abs(v)
+    _, e = np.frexp(a)
+    normal = a >= np.ldexp(1.0, _E4M3_EMIN)
+    ebits = np.where(normal, e - 1 + 7, 0)
+    mbits = np.where(normal, np.rint(np.ldexp(a, -(e - 1)) * 8.0) - 8, np.rint(np.ldexp(a, -_E4M3_EMIN) * 8.0))
+    sign = np.signbit(v).astype(np.int64)
+    return ((sign << 7) | (ebits.astype(np.int64) << 3) | mbits.astype(np.int64)).astype(np.uint8)
+
+
+def mx_quantize(x):
+    """MXFP8 conversion of the rows of x along its last axis (length a multiple of 32).
+    Returns (codes uint8 of x's shape, scale bytes uint8 [..., K / 32])."""
+    x = np.asarray(x, F64)
+    K = x.shape[-1]
+    assert K % MX_BLOCK == 0
+    blocks = x.reshape(x.shape[:-1] + (K // MX_BLOCK, MX_BLOCK))
+    amax = np.abs(blocks).max(axis=-1)
+    _, e = np.frexp(amax)                            # floor(log2(amax)) = e - 1 for amax > 0
+    byte = np.where(amax > 0, np.clip(e - 1 - _E4M3_EMAX + _E8M0_BIAS, 0, 254), 0)
+    scaled = blocks / np.ldexp(1.0, byte - _E8M0_BIAS)[..., None]
+    return e4m3_encode(scaled).reshape(x.shape), byte.astype(np.uint8)
+
+
+def mx_dequantize(codes, scale_bytes) -> np.ndarray:
+    """Values an MXFP8 tensor stands for: element value times its block's 2^(byte - 127)."""
+    codes = np.asarray(codes)
+    K = codes.shape[-1]
+    v = e4m3_decode(codes).reshape(codes.shape[:-1] + (K // MX_BLOCK, MX_BLOCK))
+    return (v * np.ldexp(1.0, np.asarray(scale_bytes).astype(np.int64) - _E8M0_BIAS)[..., None]).reshape(codes.shape)
+
+
+def mx_values(x) -> np.ndarray:
+    """x as an MXFP8 product sees it: converted and read back."""
+    return mx_dequantize(*mx_quantize(x))
+
+
+def mx_linear(x, W, b) -> np.ndarray:
+    """y = Q(x) Q(W)^T + b: both operands converted to MXFP8 along the contraction dimension (zero
+    padded to a multiple of 32; zeros change neither a block's scale nor the sum), exact product."""
+    x, W = np.asarray(x, F64), np.asarray(W, F64)
+    pad = (-x.shape[-1]) % MX_BLOCK
+    if pad:
+        x = np.concatenate([x, np.zeros(x.shape[:-1] + (pad,), F64)], axis=-1)
+        W = np.concatenate([W, np.zeros(W.shape[:-1] + (pad,), F64)], axis=-1)
+    return linear(mx_values(x), mx_values(W), b)
+
+
 # -------------------------------------------------------------- encoder ----
 
 def _norm(x, w: Dict[str, np.ndarray], prefix: str, kind: int, eps: float):
@@ -142,11 +238,15 @@ def _act(x, kind: int):
 
 
 def encoder_layer(x, w, desc, l: int):
-    """One pre-norm transformer layer on the [N, D] tokens of one slice."""
+    """One pre-norm transformer layer on the [N, D] tokens of one slice.  With `desc.mx_fp8` the three
+    products fed by a norm or by the activation (q/k/v, FC1, FC2) take MXFP8 operands; the attention
+    products and the out-projection do not (reading: their operand is made head by head inside the
+    attention step, and they are a tenth of a layer's work)."""
     D, H = desc.hidden, desc.heads
     p = f"l{l}_"
+    big = mx_linear if getattr(desc, "mx_fp8", 0) else linear
     u = _norm(x, w, p + "n1", desc.norm, desc.eps)
-    qkv = linear(u, w[p + "qkv_w"], w[p + "qkv_b"])      # rows of W: q block, k block, v block
+    qkv = big(u, w[p + "qkv_w"], w[p + "qkv_b"])         # rows of W: q block, k block, v block
     q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
     if desc.qk_norm == QKNORM_FULL:
         # reading: RMSNorm of q and of k over all heads together, after the
@@ -163,8 +263,8 @@ def encoder_layer(x, w, desc, l: int):
         branch = branch * np.asarray(w[p + "ls1"], F64)     # per-channel layer scale
     x = x + branch
     u = _norm(x, w, p + "n2", desc.norm, desc.eps)
-    hmid = _act(linear(u, w[p + "fc1_w"], w[p + "fc1_b"]), desc.act)
-    branch = linear(hmid, w[p + "fc2_w"], w[p + "fc2_b"])
+    hmid = _act(big(u, w[p + "fc1_w"], w[p + "fc1_b"]), desc.act)
+    branch = big(hmid, w[p + "fc2_w"], w[p + "fc2_b"])
     if getattr(desc, "layer_scale", 0):
         branch = branch * np.asarray(w[p + "ls2"], F64)
     x = x + branch

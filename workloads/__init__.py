@@ -62,6 +62,7 @@ class ModelDesc:
     layer_scale: int = 0
     class_token: int = 0
     proj_heads: int = 0
+    mx_fp8: int = 0      # 1: MXFP8 operands for the q/k/v, FC1 and FC2 products (bf16 mode only)
 
     # ---- shape bookkeeping only (counts, no arithmetic on data) ----
     @property
