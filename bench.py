@@ -112,6 +112,9 @@ def main():
     ap.add_argument("--roof", action="store_true",
                     help="measure this box's ceilings instead of the workload (MFMA loop, streaming copy, vendor "
                          "BLAS and this library on the per-layer shapes) and print them as one JSON line")
+    ap.add_argument("--mx-fp8", action="store_true",
+                    help="the checkpoint-fidelity option epd_model_desc::mx_fp8: q/k/v, FC1 and FC2 products on MXFP8 "
+                         "operands (narrower than the headline precision: an extra line, never the headline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -136,6 +139,8 @@ def main():
     desc = wk.desc
     if args.micro_batch > 0:
         desc = desc.replace(max_tiles_per_call=args.micro_batch)
+    if args.mx_fp8:
+        desc = desc.replace(mx_fp8=1)
     bf16 = desc.dtype == wl.DT_BF16
     T = wk.n_tiles
 
@@ -198,9 +203,10 @@ def main():
     gemm_launches = sum(fam[k]["launches"] for k in gf)
     gemm_flops = sum(gf.values()) * T * prof_steps
     achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    traffic, traffic_source = traffic_from_profile(args.workload) if desc.max_tiles_per_call == wk.desc.max_tiles_per_call else (None, None)
+    traffic, traffic_source = (traffic_from_profile(args.workload)
+                               if desc.max_tiles_per_call == wk.desc.max_tiles_per_call and not args.mx_fp8 else (None, None))
     roofline = {
-        "bound": "mfma", "kernel": "k_gemm_bf16 (all epilogue variants)" if bf16 else "k_f32_gemm",
+        "bound": "mfma", "kernel": ("k_gemm_mxfp8 (q/k/v, FC1, FC2) + k_gemm_bf16 (the rest)" if args.mx_fp8 else "k_gemm_bf16 (all epilogue variants)") if bf16 else "k_f32_gemm",
         "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
         # what a register-resident MFMA loop reaches on this machine right now (random operands; no memory, no LDS)
         "achievable_peak": round(B.op_mfma_peak(True), 1) if bf16 else None,
@@ -212,13 +218,21 @@ def main():
                             for k in gf if fam[k]["ms"] > 0},
     }
 
+    if args.mx_fp8:
+        # the converted products against the dense FP8 peak of the matrix cores (5.0 PFLOP/s)
+        fams = ("gemm_qkv", "gemm_fc1", "gemm_fc2")
+        mx_ms = sum(fam[k]["ms"] for k in fams)
+        mx_tf = sum(gf[k] for k in fams) * T * prof_steps / (mx_ms * 1e-3) / 1e12 if mx_ms > 0 else 0.0
+        roofline["mx_products"] = {"achieved": round(mx_tf, 1), "peak": 5000.0, "unit": "TFLOP/s", "frac": round(mx_tf / 5000.0, 4)}
+
     # ---- the kernels bound by memory bandwidth: algorithmic bytes / event-bracketed time ----
     hbm = None
     if bf16:
         M_rows = T * desc.seq_len
         Dq = desc.hidden                      # q and k rows as stored (head padding not counted)
         per_launch = {
-            "norm": M_rows * desc.hidden * (4 + 2),                                  # fp32 row in, bf16 row out
+            # fp32 row in, bf16 row out (MXFP8: one byte per element and one scale byte per 32)
+            "norm": int(M_rows * desc.hidden * (4 + (1 + 1 / 32 if args.mx_fp8 else 2))),
             "qk_norm": M_rows * 2 * Dq * (2 + 2),                                    # q and k, read and written, bf16
             "proj_input": T * desc.tokens_per_tile * desc.proj_in * (4 + 2) if desc.proj_kind != 2 else None,
         }
@@ -380,11 +394,14 @@ def main():
                "kind": "oracle",
                "sample": f"slices {sample} of the same batch at full depth, {cpu_s:.1f} s, numpy fp64"}
 
+    # the MXFP8 option against the oracle that converts at the same places: its own bound (two independent draws of
+    # the format's noise once the computations have drifted apart), not the bf16 one
+    tol_line = 1e-1 if args.mx_fp8 else TOL["bf16" if bf16 else "f32"]
     line = {
         "metric": "image_tiles_per_sec", "value": round(tiles_per_s, 2), "unit": "tiles/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "dtype": ("mxfp8 (q/k/v, FC1, FC2 operands) + bf16" if args.mx_fp8 else "bf16") if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wk.name, "tiles": T, "requests": wk.n_requests,
                    "tokens_per_tile": desc.tokens_per_tile, "out_dim": desc.out_dim,
                    "micro_batch_tiles": desc.max_tiles_per_call},
@@ -394,8 +411,8 @@ def main():
         "mfma_util_pct_of_peak": round(100.0 * tflops / peak, 2),
         "ms_per_step_median_events": round(ms_median, 3),
         "parity_max_rel_err_sample": parity,
-        "parity_tolerance": TOL["bf16" if bf16 else "f32"],
-        "parity_ok": None if parity is None else bool(parity < TOL["bf16" if bf16 else "f32"]),
+        "parity_tolerance": tol_line,
+        "parity_ok": None if parity is None else bool(parity < tol_line),
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
         "hbm_kernels": hbm,

@@ -79,6 +79,25 @@ epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, v
  * v_mfma_f32_32x32x16_bf16.  All pointers dev. */
 epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream);
 
+/* MXFP8 operands (epd_model_desc::mx_fp8): element format OCP FP8 E4M3, one power-of-two scale byte
+ * (value 2^(byte - 127)) per block of 32 consecutive elements of the contraction dimension (OCP Microscaling
+ * Formats specification v1.0).  Device layout: codes [rows, K] bytes; scales uint32 [K / 128, rows], word (s, r)
+ * = the scale bytes of blocks 4 s .. 4 s + 3 of row r, block 4 s + b in byte b.
+ * epd_op_mx_rows: conversion of `rows` rows of `dim` elements (dim % 128 == 0; fp32, or bf16 if in_bf16), after
+ *   a LayerNorm (kind 0, gamma / beta [dim] fp32), an RMSNorm (kind 1, gamma) or as they are (kind 2).
+ * epd_op_mx_gemm: out = (A W^T) * cscale[n] + bias[n] on such operands (A [M, K], W [N, K]; M % 256 == 0,
+ *   N % 256 == 0, K % 128 == 0; cscale may be null); epi 0 -> C bf16 [M, N]; epi 5 -> C bf16 transposed per
+ *   slice and head, [M / n_tok, heads, hd_pad, n_tok] with N = heads * hd_pad; epi 1 / 2 -> GELU (erf / tanh form),
+ *   then converted: codes Cq [M, N], scales SC [N / 128, M]; epi 3 -> R fp32 [M, N] += out.
+ * epd_op_mx_mfma_probe: one v_mfma_scale_f32_32x32x64_f8f6f4 on caller-supplied registers (a, b: int32 [64][8],
+ *   sa, sb: int32 [64], scale byte 0 used; d: fp32 [64][16]), for the operand-layout test.  All pointers dev. */
+epd_status epd_op_mx_rows(const void* in, int32_t in_bf16, int64_t rows, int32_t dim, int32_t kind, const float* gamma,
+                          const float* beta, float eps, void* codes, void* scales, void* hip_stream);
+epd_status epd_op_mx_gemm(int32_t epi, const void* A, const void* SA, const void* W, const void* SW, const float* bias,
+                          const float* cscale, int32_t M, int32_t N, int32_t K, void* C, float* R, void* Cq, void* SC,
+                          int32_t n_tok, int32_t heads, int32_t hd_pad, void* hip_stream);
+epd_status epd_op_mx_mfma_probe(const void* a, const void* b, const void* sa, const void* sb, float* d, void* hip_stream);
+
 /* Per-kernel-family timing of the previous epd_encode / epd_encode_range
  * call on this context, measured with HIP events on the call's stream.
  * epd_profile_enable(ctx, 1) makes subsequent calls bracket every launch

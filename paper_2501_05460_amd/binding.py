@@ -34,6 +34,7 @@ EXPORTS = (
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
     "epd_op_row_stats", "epd_op_gemm_residual_stats", "epd_op_norm_gemm_bf16",
+    "epd_op_mx_rows", "epd_op_mx_gemm", "epd_op_mx_mfma_probe",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_transfer_noalloc", "epd_mm_gather",
     "epd_encode_trunk_paged", "epd_project_merge",
@@ -45,7 +46,7 @@ class ModelDescC(ctypes.Structure):
         "dtype", "tile_size", "patch", "hidden", "heads", "mlp", "layers", "norm", "qk_norm", "act",
         "final_norm", "pixel_shuffle", "proj_kind", "proj_prenorm", "proj_mid", "proj_out")] + [
         ("eps", ctypes.c_float), ("max_tiles_per_call", ctypes.c_int32), ("layer_scale", ctypes.c_int32),
-        ("class_token", ctypes.c_int32), ("proj_heads", ctypes.c_int32)]
+        ("class_token", ctypes.c_int32), ("proj_heads", ctypes.c_int32), ("mx_fp8", ctypes.c_int32)]
 
 
 class WeightsC(ctypes.Structure):
@@ -115,6 +116,12 @@ def lib() -> ctypes.CDLL:
         L.epd_op_gemm_residual_stats.restype = i32
         L.epd_op_norm_gemm_bf16.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, ctypes.c_float, i32, i32, vp]
         L.epd_op_norm_gemm_bf16.restype = i32
+        L.epd_op_mx_rows.argtypes = [vp, i32, i64, i32, i32, vp, vp, ctypes.c_float, vp, vp, vp]
+        L.epd_op_mx_rows.restype = i32
+        L.epd_op_mx_gemm.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, i32, vp]
+        L.epd_op_mx_gemm.restype = i32
+        L.epd_op_mx_mfma_probe.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.epd_op_mx_mfma_probe.restype = i32
         L.epd_mm_cache_create.argtypes = [i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.epd_mm_cache_create.restype = i32
         L.epd_mm_cache_destroy.argtypes = [vp]
@@ -497,3 +504,55 @@ def op_norm_gemm_bf16(x: torch.Tensor, gamma: torch.Tensor, beta: Optional[torch
     if s != EPD_OK:
         raise EpdError(s, lib().epd_last_error(None).decode())
     return C
+
+
+def op_mx_rows(x: torch.Tensor, kind: int = 2, gamma: Optional[torch.Tensor] = None, beta: Optional[torch.Tensor] = None,
+               eps: float = 0.0):
+    """MXFP8 conversion of the rows of x [rows, dim] (fp32 or bf16), optionally behind a LayerNorm (kind 0) or an
+    RMSNorm (kind 1).  Returns (codes uint8 [rows, dim], scale words int32 [dim / 128, rows])."""
+    rows, dim = x.shape
+    codes = torch.full((rows, dim), 0xAA, dtype=torch.uint8, device=x.device)
+    scales = torch.full((dim // 128, rows), -1, dtype=torch.int32, device=x.device)
+    s = lib().epd_op_mx_rows(x.contiguous().data_ptr(), 1 if x.dtype == torch.bfloat16 else 0, rows, dim, kind,
+                             gamma.data_ptr() if gamma is not None else None, beta.data_ptr() if beta is not None else None,
+                             eps, codes.data_ptr(), scales.data_ptr(), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return codes, scales
+
+
+def op_mx_gemm(epi: int, A: torch.Tensor, SA: torch.Tensor, W: torch.Tensor, SW: torch.Tensor, bias: torch.Tensor,
+               cscale: Optional[torch.Tensor] = None, R: Optional[torch.Tensor] = None, n_tok: int = 0, heads: int = 0,
+               hd_pad: int = 0):
+    """Product of MXFP8 operands (codes uint8 [M, K] / [N, K], scale words int32 [K / 128, M] / [K / 128, N]).
+    epi 0: bf16 [M, N]; 5: bf16 [M / n_tok, heads, hd_pad, n_tok]; 1 / 2: (codes [M, N], scale words [N / 128, M])
+    of the activated output; 3: R (fp32, in place) += product."""
+    M, K = A.shape
+    N = W.shape[0]
+    C = Cq = SC = None
+    if epi in (0, 5):
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=A.device)
+    elif epi in (1, 2):
+        Cq = torch.full((M, N), 0xAA, dtype=torch.uint8, device=A.device)
+        SC = torch.full((N // 128, M), -1, dtype=torch.int32, device=A.device)
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    s = lib().epd_op_mx_gemm(epi, A.data_ptr(), SA.data_ptr(), W.data_ptr(), SW.data_ptr(), bias.data_ptr(), ptr(cscale),
+                             M, N, K, ptr(C), ptr(R), ptr(Cq), ptr(SC), n_tok, heads, hd_pad, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    if epi == 0:
+        return C
+    if epi == 5:
+        return C.view(M // n_tok, heads, hd_pad, n_tok)
+    if epi == 3:
+        return R
+    return Cq, SC
+
+
+def op_mx_mfma_probe(a: torch.Tensor, b: torch.Tensor, sa: torch.Tensor, sb: torch.Tensor) -> torch.Tensor:
+    """One 32x32x64 scaled FP8 MFMA on raw registers: a, b int32 [64, 8], sa, sb int32 [64] -> fp32 [64, 16]."""
+    d = torch.empty((64, 16), dtype=torch.float32, device=a.device)
+    s = lib().epd_op_mx_mfma_probe(a.data_ptr(), b.data_ptr(), sa.data_ptr(), sb.data_ptr(), d.data_ptr(), _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "mx mfma probe failed")
+    return d

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libepd_encode.so")
 
-SOURCES = ["epd_api.hip", "mm_cache.hip", "simple_f32.hip", "gemm_bf16.hip", "attention_bf16.hip", "rowops_bf16.hip", "roof_probe.hip"]
+SOURCES = ["epd_api.hip", "mm_cache.hip", "simple_f32.hip", "gemm_bf16.hip", "gemm_mxfp8.hip", "attention_bf16.hip", "rowops_bf16.hip", "roof_probe.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-result",

@@ -117,7 +117,8 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
   if (d->norm < 0 || d->norm > 1 || d->qk_norm < 0 || d->qk_norm > 2 || d->act < 0 || d->act > 1 ||
       d->final_norm < 0 || d->final_norm > 1 || d->pixel_shuffle < 0 || d->pixel_shuffle > 1 ||
       d->proj_kind < 0 || d->proj_kind > 2 || d->proj_prenorm < 0 || d->proj_prenorm > 1 ||
-      d->layer_scale < 0 || d->layer_scale > 1 || d->class_token < 0 || d->class_token > 1) {
+      d->layer_scale < 0 || d->layer_scale > 1 || d->class_token < 0 || d->class_token > 1 ||
+      d->mx_fp8 < 0 || d->mx_fp8 > 1) {
     set_err(err, len, "an enum field of the description is out of range"); return EPD_ERR_INVALID_ARG;
   }
   if (d->tile_size <= 0 || d->patch <= 0 || d->hidden <= 0 || d->heads <= 0 || d->mlp <= 0 ||
@@ -148,6 +149,10 @@ epd_status check_desc(const epd_model_desc* d, char* err, size_t len) {
         return EPD_ERR_UNSUPPORTED;
       }
     }
+  }
+  if (d->mx_fp8 && (d->dtype != EPD_DTYPE_BF16 || x.D % 128)) {
+    set_err(err, len, "mx_fp8 needs bf16 mode and hidden %% 128 == 0 (blocks of 32 along whole 128-element slabs), got hidden %d", x.D);
+    return EPD_ERR_UNSUPPORTED;
   }
   if (x.N > 16384) { set_err(err, len, "more than 16384 patches per slice is not supported"); return EPD_ERR_UNSUPPORTED; }
   if (d->dtype == EPD_DTYPE_FP32) {
@@ -181,12 +186,22 @@ struct Resampler {
        *o2 = nullptr, *o3 = nullptr;   // V: bf16 [mb, H, hd_pad, N] (transposed) / fp32 [M, E]
 };
 
+// A Linear whose weights are kept as MXFP8 codes and block scales (gemm_mxfp8.hip), rows padded to 256
+struct MxLinear {
+  const unsigned char* W = nullptr;   // [Npad, K]
+  const unsigned* SW = nullptr;       // [K / 128][Npad]
+  const float* b = nullptr;           // [Npad]
+  const float* cs = nullptr;          // [Npad] factor applied to the product in the epilogue, or null
+  int N = 0, K = 0, Npad = 0;
+};
+
 struct LayerW {
   const float *n1_g = nullptr, *n1_b = nullptr, *n2_g = nullptr, *n2_b = nullptr, *qn_g = nullptr, *kn_g = nullptr;
   Linear qkv, v, o, fc1, fc2;  // bf16 mode: qkv holds q,k only and v the value projection
   // folded pre-norms (bf16 mode): the weights of qkv, v (first norm) and fc1 (second norm) carry the norm's gain,
   // their biases its shift, and these are the column sums of the packed weights the epilogues subtract the mean with
   const float *qkv_cs = nullptr, *v_cs = nullptr, *fc1_cs = nullptr;
+  MxLinear mqkv, mv, mfc1, mfc2;   // epd_model_desc::mx_fp8: the same four matrices as MXFP8 operands
 };
 
 }  // namespace
@@ -221,6 +236,8 @@ struct epd_ctx {
   //                 products run on bf16(x) against gain-scaled weights and apply mean / rstd in their epilogues.
   int norm_mode = 0;
   bool fold = false;        // norm_mode == NORM_FOLD
+  bool mx = false;          // epd_model_desc::mx_fp8: q/k, value, FC1 and FC2 products on MXFP8 operands
+  std::vector<std::vector<float>> host_keep;   // host vectors with copies to the device in flight (epd_create only)
   float* stats = nullptr;   // [Mp][n_part][2]: one pair per 128 columns, as the residual epilogues emit them
   float* stats1 = nullptr;  // [Mp][2]: one pair per row, made from `stats` when a row has more pairs than the products take (wide models)
   int n_part = 0;
@@ -352,6 +369,40 @@ bool make_linear(epd_ctx* c, const epd_weights* w, int wi, int bi, int N, int K,
 
 GemmParams gp(int epi, const void* A, long lda, const Linear& lin, int M);
 
+// MXFP8 copy of a packed bf16 Linear: codes and block scales of its rows as they are now (call it before any
+// factor is folded into the rows: conversion is not invariant under factors that are not powers of two)
+bool mx_make(epd_ctx* c, const Linear& lin, MxLinear* out, hipStream_t st) {
+  const int np = round_up(lin.Npad, 256);
+  unsigned char* codes = (unsigned char*)dalloc(c, (size_t)np * lin.K, true, st);
+  unsigned* sw = (unsigned*)dalloc(c, (size_t)(lin.K / 128) * np * sizeof(unsigned), true, st);
+  if (!codes || !sw) return false;
+  MxRowParams p;
+  memset(&p, 0, sizeof(p));
+  p.kind = 2; p.in = lin.W; p.ld_in = lin.K; p.in_bf16 = 1; p.rows = lin.Npad; p.dim = lin.K;
+  p.codes = codes; p.ld_codes = lin.K; p.scales = sw; p.ld_scales = np;
+  if (mx_rows(p, st) != hipSuccess) return false;
+  out->W = codes; out->SW = sw; out->N = lin.N; out->K = lin.K; out->Npad = np;
+  return true;
+}
+// ... and its bias as it is at the end of the layer's set-up (factors folded in), plus the factor of the product:
+// `cs_dev` (device, n_cs values) or the constant `cs_const` for the first n_cs columns, 1 elsewhere; n_cs == 0: none
+bool mx_finish(epd_ctx* c, const Linear& lin, MxLinear* out, const float* cs_dev, float cs_const, int n_cs, hipStream_t st) {
+  float* b = (float*)dalloc(c, (size_t)out->Npad * sizeof(float), true, st);
+  if (!b || hipMemcpyAsync(b, lin.b, (size_t)lin.Npad * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return false;
+  out->b = b;
+  if (n_cs > 0) {
+    float* cs = (float*)dalloc(c, (size_t)out->Npad * sizeof(float), false, st);
+    if (!cs) return false;
+    c->host_keep.emplace_back((size_t)out->Npad, 1.0f);
+    std::vector<float>& h = c->host_keep.back();
+    if (!cs_dev) for (int i = 0; i < n_cs; ++i) h[i] = cs_const;
+    if (hipMemcpyAsync(cs, h.data(), h.size() * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess) return false;
+    if (cs_dev && hipMemcpyAsync(cs, cs_dev, (size_t)n_cs * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess) return false;
+    out->cs = cs;
+  }
+  return true;
+}
+
 epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   const epd_model_desc& d = c->d;
   const Dims& x = c->x;
@@ -382,6 +433,14 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   }
   c->fold = c->norm_mode == NORM_FOLD;
   c->n_part = (x.D + STAT_GROUP - 1) / STAT_GROUP;
+  c->mx = bf && d.mx_fp8;
+  if (c->mx) {
+    if (c->norm_mode != NORM_CLASSIC) {
+      set_err(c->err, sizeof(c->err), "mx_fp8 converts in the pre-norm kernel: EPD_NORM_MODE must be classic");
+      return EPD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(c, mx_gemm_init());
+  }
 
 #define NOMEM_IF(cond) do { if (cond) { set_err(c->err, sizeof(c->err), "device allocation failed (weights)"); return EPD_ERR_NOMEM; } } while (0)
 
@@ -430,15 +489,17 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         // (1 / sqrt(hd)) log2(e) rides on q.  Without a q/k norm it is folded into the q rows of the projection
         // (each weight rounded to bf16 once more: the rounding errors of a row average out over the hidden
         // dimension, unlike a second rounding of q itself); with one, into the norm's gain below.
-        if (d.qk_norm == EPD_QKNORM_NONE) scale_rows_by(Wqk, c->Dq, c->D_k, c->D_k, bqk, logit_scale, st);
         lw.qkv.W = Wqk; lw.qkv.b = bqk; lw.qkv.N = qk_cols; lw.qkv.K = c->D_k; lw.qkv.Npad = qk_pad;
         lw.v.W = Wv; lw.v.b = bv; lw.v.N = c->Dq; lw.v.K = c->D_k; lw.v.Npad = v_pad;
+        if (c->mx) NOMEM_IF(!mx_make(c, lw.qkv, &lw.mqkv, st) || !mx_make(c, lw.v, &lw.mv, st));   // from the unscaled rows
+        if (d.qk_norm == EPD_QKNORM_NONE) scale_rows_by(Wqk, c->Dq, c->D_k, c->D_k, bqk, logit_scale, st);
       }
 
       NOMEM_IF(!make_linear(c, w, li.o_w, li.o_b, x.D, x.D, &lw.o, st, pad_n(x.D), c->Dq_k, id, heads, x.D));
       f_pad = pad_n(x.F);
       NOMEM_IF(!make_linear(c, w, li.fc1_w, li.fc1_b, x.F, x.D, &lw.fc1, st, f_pad, c->D_k, id, id, x.F));
       NOMEM_IF(!make_linear(c, w, li.fc2_w, li.fc2_b, x.D, x.F, &lw.fc2, st, pad_n(x.D), f_pad, id, id, x.D));
+      if (c->mx) NOMEM_IF(!mx_make(c, lw.fc1, &lw.mfc1, st) || !mx_make(c, lw.fc2, &lw.mfc2, st));   // before the layer scale below
       if (d.qk_norm == EPD_QKNORM_FULL) {
         lw.qn_g = make_vec(c, w, li.qn_g, x.D, c->Dq, heads, st);
         lw.kn_g = make_vec(c, w, li.kn_g, x.D, c->Dq, heads, st);
@@ -451,13 +512,21 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         scale_vector(const_cast<float*>(lw.qn_g), c->hd_pad, logit_scale, st);
       }
     }
+    const float* ls2 = nullptr;
     if (d.layer_scale) {
       // layer scale is folded into the branch's last Linear: rows of W and the bias times ls
       const float* ls1 = make_vec(c, w, li.ls1, x.D, x.D, id, st);
-      const float* ls2 = make_vec(c, w, li.ls2, x.D, x.D, id, st);
+      ls2 = make_vec(c, w, li.ls2, x.D, x.D, id, st);
       NOMEM_IF(!ls1 || !ls2);
       scale_rows(const_cast<void*>(lw.o.W), bf ? 1 : 0, x.D, lw.o.K, lw.o.K, const_cast<float*>(lw.o.b), ls1, st);
       scale_rows(const_cast<void*>(lw.fc2.W), bf ? 1 : 0, x.D, lw.fc2.K, lw.fc2.K, const_cast<float*>(lw.fc2.b), ls2, st);
+    }
+    if (c->mx) {
+      // the biases carry the factors by now; the MXFP8 products apply them to the accumulator in the epilogue
+      NOMEM_IF(!mx_finish(c, lw.qkv, &lw.mqkv, nullptr, logit_scale, d.qk_norm == EPD_QKNORM_NONE ? c->Dq : 0, st));
+      NOMEM_IF(!mx_finish(c, lw.v, &lw.mv, nullptr, 1.f, 0, st));
+      NOMEM_IF(!mx_finish(c, lw.fc1, &lw.mfc1, nullptr, 1.f, 0, st));
+      NOMEM_IF(!mx_finish(c, lw.fc2, &lw.mfc2, ls2, 1.f, ls2 ? x.D : 0, st));
     }
     if (c->fold) {
       float* cs_qk = (float*)dalloc(c, (size_t)lw.qkv.Npad * sizeof(float), true, st);
@@ -608,6 +677,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
   if (!ok) { set_err(c->err, sizeof(c->err), "device allocation failed (workspace for %d slices)", c->mb); return EPD_ERR_NOMEM; }
   HIP_TRY(c, hipStreamSynchronize(st));
   HIP_TRY(c, hipGetLastError());
+  c->host_keep.clear();
   return EPD_OK;
 }
 
@@ -772,6 +842,25 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       bf16_norm_rows(Xn, c->D_k, g, b, M, x.D, d.norm, d.eps, st);
     }
   };
+  // MXFP8 operands (epd_model_desc::mx_fp8): the converted rows live where the bf16 ones would, codes first,
+  // their scale words behind them (a bf16 buffer of Mp rows holds both)
+  unsigned char* XnQ = (unsigned char*)c->Xn; unsigned* SXn = (unsigned*)(XnQ + (size_t)c->Mp * c->D_k);
+  unsigned char* HdQ = (unsigned char*)c->Hd; unsigned* SHd = (unsigned*)(HdQ + (size_t)c->Mp * c->F_k);
+  auto mx_norm = [&](const float* g, const float* b) -> hipError_t {
+    ProfScope ps(c, 1, st);
+    MxRowParams r;
+    memset(&r, 0, sizeof(r));
+    r.kind = d.norm; r.in = X; r.ld_in = x.D; r.gamma = g; r.beta = b; r.eps = d.eps; r.rows = M; r.dim = x.D;
+    r.codes = XnQ; r.ld_codes = c->D_k; r.scales = SXn; r.ld_scales = c->Mp;
+    return mx_rows(r, st);
+  };
+  auto mxp = [&](int epi, const unsigned char* A, long lda, const unsigned* SA, const MxLinear& lin) {
+    MxGemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.epi = epi; p.A = A; p.lda = lda; p.SA = SA; p.sa_ld = c->Mp; p.W = lin.W; p.SW = lin.SW; p.bias = lin.b; p.cscale = lin.cs;
+    p.M = M; p.N = lin.N; p.K = lin.K; p.Npad = lin.Npad;
+    return p;
+  };
   if (fold && n_layers > 0) {   // rows written by the embedding: the only pass of this kind in the call
     ProfScope ps(c, 1, st);
     bf16_row_stats(X, x.D, M, x.D, Xn, c->D_k, c->stats, c->n_part, st);
@@ -779,6 +868,17 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
   if (n_layers > 0) combine();
   for (int l = 0; l < n_layers; ++l) {
     const LayerW& w = c->layers[l];
+    if (c->mx) {
+      HIP_TRY(c, mx_norm(w.n1_g, w.n1_b));
+      { ProfScope ps(c, 2, st);
+        MxGemmParams p = mxp(EPI_BIAS, XnQ, c->D_k, SXn, w.mqkv);
+        p.C = QK; p.ldc = ld_qk;
+        HIP_TRY(c, mx_gemm(p, st)); }
+      { ProfScope ps(c, 2, st);
+        MxGemmParams pv = mxp(EPI_VT, XnQ, c->D_k, SXn, w.mv);
+        pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.Ns;
+        HIP_TRY(c, mx_gemm(pv, st)); }
+    } else {
     norm_kernel(w.n1_g, w.n1_b, !copy || l == 0);   // the first layer's rows come from the embedding
     { ProfScope ps(c, 2, st);
       GemmParams p = gp(EPI_BIAS, Xn, c->D_k, w.qkv, M);
@@ -790,6 +890,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.Ns;
       with_norm(pv, w.v_cs);
       HIP_TRY(c, bf16_gemm(pv, st)); }
+    }
     if (d.qk_norm == EPD_QKNORM_FULL) {
       ProfScope ps(c, 4, st);
       bf16_qknorm(QK, ld_qk, c->Dq, w.qn_g, w.kn_g, M, c->Dq, 1, x.D, d.eps, st);
@@ -805,6 +906,18 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       with_emit(p, true);
       HIP_TRY(c, bf16_gemm(p, st)); }
     combine();
+    if (c->mx) {
+      HIP_TRY(c, mx_norm(w.n2_g, w.n2_b));
+      { ProfScope ps(c, 7, st);
+        MxGemmParams p = mxp(act_epi, XnQ, c->D_k, SXn, w.mfc1);
+        p.Cq = HdQ; p.ldcq = c->F_k; p.SC = SHd; p.sc_ld = c->Mp;
+        HIP_TRY(c, mx_gemm(p, st)); }
+      { ProfScope ps(c, 8, st);
+        MxGemmParams p2 = mxp(EPI_BIAS_RESIDUAL, HdQ, c->F_k, SHd, w.mfc2);
+        p2.R = X; p2.ldr = x.D;
+        HIP_TRY(c, mx_gemm(p2, st)); }
+      continue;
+    }
     norm_kernel(w.n2_g, w.n2_b, !copy);
     { ProfScope ps(c, 7, st);
       GemmParams p = gp(act_epi, Xn, c->D_k, w.fc1, M);
@@ -1351,6 +1464,48 @@ epd_status epd_profile_read(epd_ctx* ctx, float* ms, int32_t* launches) {
     launches[ctx->ev_family[i]] += i < ctx->ev_kernels.size() ? ctx->ev_kernels[i] : 1;
   }
   return EPD_OK;
+}
+
+epd_status epd_op_mx_rows(const void* in, int32_t in_bf16, int64_t rows, int32_t dim, int32_t kind, const float* gamma,
+                          const float* beta, float eps, void* codes, void* scales, void* hip_stream) {
+  if (!in || !codes || !scales || rows <= 0 || dim <= 0 || dim % 128 || kind < 0 || kind > 2) {
+    set_err(g_err, sizeof(g_err), "epd_op_mx_rows: bad argument (dim %% 128 == 0, kind 0..2)");
+    return EPD_ERR_INVALID_ARG;
+  }
+  MxRowParams p;
+  memset(&p, 0, sizeof(p));
+  p.kind = kind; p.in = in; p.ld_in = dim; p.in_bf16 = in_bf16 ? 1 : 0; p.gamma = gamma; p.beta = beta; p.eps = eps;
+  p.rows = rows; p.dim = dim; p.codes = (unsigned char*)codes; p.ld_codes = dim; p.scales = (unsigned*)scales; p.ld_scales = rows;
+  const hipError_t e = mx_rows(p, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "epd_op_mx_rows: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_INVALID_ARG : EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
+epd_status epd_op_mx_gemm(int32_t epi, const void* A, const void* SA, const void* W, const void* SW, const float* bias,
+                          const float* cscale, int32_t M, int32_t N, int32_t K, void* C, float* R, void* Cq, void* SC,
+                          int32_t n_tok, int32_t heads, int32_t hd_pad, void* hip_stream) {
+  if (!A || !SA || !W || !SW || !bias || M <= 0 || M % 256 || N <= 0 || N % 256 || K <= 0 || K % 128) {
+    set_err(g_err, sizeof(g_err), "epd_op_mx_gemm: bad argument (M %% 256, N %% 256, K %% 128)");
+    return EPD_ERR_INVALID_ARG;
+  }
+  if (epi == EPI_VT && (n_tok <= 0 || heads <= 0 || hd_pad <= 0 || M % n_tok || heads * hd_pad != N)) return EPD_ERR_INVALID_ARG;
+  if (mx_gemm_init() != hipSuccess) return EPD_ERR_HIP;
+  MxGemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.epi = epi; p.A = (const unsigned char*)A; p.lda = K; p.SA = (const unsigned*)SA; p.sa_ld = M;
+  p.W = (const unsigned char*)W; p.SW = (const unsigned*)SW; p.bias = bias; p.cscale = cscale;
+  p.M = M; p.N = N; p.K = K; p.Npad = N;
+  p.C = (bf16_t*)C; p.ldc = N; p.R = R; p.ldr = N; p.VT = (bf16_t*)C; p.hd_pad = hd_pad; p.heads = heads; p.n_tok = n_tok;
+  p.Cq = (unsigned char*)Cq; p.ldcq = N; p.SC = (unsigned*)SC; p.sc_ld = M;
+  const hipError_t e = mx_gemm(p, (hipStream_t)hip_stream);
+  if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "epd_op_mx_gemm: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_INVALID_ARG : EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
+epd_status epd_op_mx_mfma_probe(const void* a, const void* b, const void* sa, const void* sb, float* d, void* hip_stream) {
+  if (!a || !b || !sa || !sb || !d) return EPD_ERR_INVALID_ARG;
+  mx_mfma_probe((const int*)a, (const int*)b, (const int*)sa, (const int*)sb, d, (hipStream_t)hip_stream);
+  return hipGetLastError() == hipSuccess ? EPD_OK : EPD_ERR_HIP;
 }
 
 }  // extern "C"

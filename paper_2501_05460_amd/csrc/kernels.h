@@ -170,6 +170,50 @@ void stream_to_blocks(const float* X, long ldx, SliceRows xr, void* pool, int po
 void blocks_to_stream(const void* pool, int pool_is_bf16, int dim, const int* row_map, int block_tokens,
                       float* X, long ldx, SliceRows xr, long rows, hipStream_t st);
 
+// ---- MXFP8 operands (gemm_mxfp8.hip) -----------------------------------------------------------------------
+// codes [rows][K] bytes (E4M3), K contiguous; scales [K / 128][ld] 32-bit words: word (s, r) = the scale bytes
+// of row r's four 32-element blocks of K slab s (byte b = block 4 s + b, value 2^(byte - 127)).
+//
+// Rows -> MXFP8, optionally behind a norm: kind 0 LayerNorm, 1 RMSNorm, 2 plain conversion; input fp32 or
+// bf16 rows of `dim` elements (dim % 128 == 0), statistics and normalised values in fp32, converted from fp32.
+struct MxRowParams {
+  int kind;
+  const void* in; long ld_in; int in_bf16;
+  const float* gamma; const float* beta; float eps;
+  long rows; int dim;
+  unsigned char* codes; long ld_codes;     // bytes per row, >= dim, % 4 == 0
+  unsigned* scales; long ld_scales;        // words per K slab, >= rows
+};
+hipError_t mx_rows(const MxRowParams& p, hipStream_t st);
+
+// C[M,N] = A[M,K] W[N,K]^T on MXFP8 operands, fp32 accumulation, out = acc * cscale[n] + bias[n], then:
+//   EPI_BIAS            bf16 C [M, ldc];
+//   EPI_VT              bf16, transposed per (slice, head) as in GemmParams;
+//   EPI_BIAS_GELU_*     activation, then MXFP8 along the output features: codes Cq [M, ldcq] and scale words
+//                       SC [ldcq / 128][sc_ld] (the operand of the next product);
+//   EPI_BIAS_RESIDUAL   R[M, ldr] (fp32) += out.
+// A and SA must be readable for round_up(M, 256) rows, W / SW / bias / cscale for Npad rows (Npad % 256 == 0,
+// zero rows past N); K % 128 == 0.  cscale may be null (all ones).
+struct MxGemmParams {
+  int epi;
+  const unsigned char* A; long lda;
+  const unsigned* SA; long sa_ld;
+  const unsigned char* W;
+  const unsigned* SW;          // [K / 128][Npad]
+  const float* bias;
+  const float* cscale;
+  int M, N, K, Npad;
+  bf16_t* C; long ldc;
+  float* R; long ldr;
+  bf16_t* VT; int hd_pad, heads, n_tok;
+  unsigned char* Cq; long ldcq;
+  unsigned* SC; long sc_ld;
+};
+hipError_t mx_gemm(const MxGemmParams& p, hipStream_t st);
+hipError_t mx_gemm_init();   // raises the dynamic-LDS limit of the kernels (idempotent)
+// one v_mfma_scale_f32_32x32x64_f8f6f4 on caller-supplied registers (operand-layout test): a, b [64][8], sa, sb [64], d [64][16]
+void mx_mfma_probe(const int* a, const int* b, const int* sa, const int* sb, float* d, hipStream_t st);
+
 // MFMA lane-layout check: D[32,32] = A[32,16] * B[16,32] with operands loaded
 // and the result stored under the layout the kernels assume.
 void mfma_probe(const bf16_t* A, const bf16_t* B, float* D, hipStream_t st);
