@@ -19,6 +19,7 @@
 // slabs and their scale words go from global memory straight into LDS one slab ahead (LDS-DMA); LDS rows of
 // 128 bytes with the 16-byte chunks XOR-swizzled by (row >> 1) & 7, as in the bf16 kernel.
 #include <cstring>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -61,6 +62,11 @@ __device__ __forceinline__ unsigned mx_pack4(float a, float b, float c, float d)
   r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, r, false);
   r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
   return (unsigned)r;
+}
+
+template <typename C>
+__device__ __forceinline__ float dpp_f(float x, C) {
+  return __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), C::value, 0xf, 0xf, true));
 }
 
 __device__ __forceinline__ float max4abs(float a, float b, float c, float d) {
@@ -132,20 +138,18 @@ __global__ __launch_bounds__(256) void k_mx_rows(const MxRowParams p) {
         r[0] += bt.x; r[1] += bt.y; r[2] += bt.z; r[3] += bt.w;
       }
     }
+    // largest magnitude of the block's eight lanes: three exchanges inside a row of 16 lanes (no LDS traffic)
     float amax = max4abs(r[0], r[1], r[2], r[3]);
-    amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
-    amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
-    amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+    amax = fmaxf(amax, dpp_f(amax, std::integral_constant<int, 0xB1>{}));    // quad_perm [1, 0, 3, 2]
+    amax = fmaxf(amax, dpp_f(amax, std::integral_constant<int, 0x4E>{}));    // quad_perm [2, 3, 0, 1]
+    amax = fmaxf(amax, dpp_f(amax, std::integral_constant<int, 0x141>{}));   // row_half_mirror: the other quad of the eight
     const unsigned byte = mx_scale_byte(amax);
     const float inv = mx_inv_scale(byte);
     const unsigned word = mx_pack4(r[0] * inv, r[1] * inv, r[2] * inv, r[3] * inv);
-    // the four scale bytes of this half-wave's slab, gathered from the first lane of every block
-    const int h = lane & 32;
-    const unsigned sw = (unsigned)__shfl((int)byte, h, 64) | ((unsigned)__shfl((int)byte, h + 8, 64) << 8) |
-                        ((unsigned)__shfl((int)byte, h + 16, 64) << 16) | ((unsigned)__shfl((int)byte, h + 24, 64) << 24);
     if (in_row) {
       codes[c] = word;
-      if ((lane & 31) == 0) p.scales[(long)(c >> 5) * p.ld_scales + R] = sw;
+      // block c / 8 of the row = byte (c / 8) % 4 of scale word (c / 32, R): the block's first lane stores it
+      if ((lane & 7) == 0) reinterpret_cast<unsigned char*>(p.scales + (long)(c >> 5) * p.ld_scales + R)[(c >> 3) & 3] = (unsigned char)byte;
     }
   };
   if (NV > 0) {

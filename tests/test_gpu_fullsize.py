@@ -93,6 +93,35 @@ def test_c3_internvit300m_shape_104_slices():
     enc.close()
 
 
+def test_c3_with_mx_fp8_104_slices():
+    """The MXFP8 option at the full C3 size, in the configuration `bench.py --mx-fp8` times: the last slice of the batch
+    against the oracle that converts at the same places (the option's own bound, two independent draws of the
+    format's noise at this depth) and against the exact oracle (no noisier than the format itself), and the whole
+    batch again for the same bits."""
+    wk = wl.workload("c3")
+    desc = wk.desc.replace(mx_fp8=1)
+    enc, tiles = build(wk, desc)
+    out = enc.encode(tiles, list(wk.tile_offsets)).clone()
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    again = enc.encode(tiles, list(wk.tile_offsets))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), again.view(torch.int16))
+    t = wk.n_tiles - 1
+    n = enc.tokens_per_tile
+    w = wl.gen_weights(desc, wk.weight_seed)
+    tile = wl.gen_tile(desc, wk.input_seed, t)
+    want = O.encode_tile(tile, w, desc)
+    exact = O.encode_tile(tile, w, wk.desc)
+    got = out[t * n:(t + 1) * n].float().cpu().numpy()
+    e, e_exact, fmt = rel_err(got, want), rel_err(got, exact), rel_err(want, exact)
+    print(f"c3 + mx_fp8 slice {t}: vs converting oracle {e:.3e} (l2 {rel_l2(got, want):.3e}), vs exact oracle {e_exact:.3e} "
+          f"(l2 {rel_l2(got, exact):.3e}), converting oracle vs exact {fmt:.3e} (l2 {rel_l2(want, exact):.3e})", flush=True)
+    assert e < 1e-1
+    assert e_exact < 1.5 * fmt + 2e-2
+    enc.close()
+
+
 def test_c5_mixed_batch_sharded_equals_one_call_and_oracle():
     wk = wl.workload("c5")
     enc, tiles = build(wk)
