@@ -910,7 +910,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       HIP_TRY(c, mx_norm(w.n2_g, w.n2_b));
       { ProfScope ps(c, 7, st);
         MxGemmParams p = mxp(act_epi, XnQ, c->D_k, SXn, w.mfc1);
-        p.Cq = HdQ; p.ldcq = c->F_k; p.SC = SHd; p.sc_ld = c->Mp;
+        p.Cq = HdQ; p.ldcq = c->F_k; p.ncq = c->F_k; p.SC = SHd; p.sc_ld = c->Mp;
         HIP_TRY(c, mx_gemm(p, st)); }
       { ProfScope ps(c, 8, st);
         MxGemmParams p2 = mxp(EPI_BIAS_RESIDUAL, HdQ, c->F_k, SHd, w.mfc2);
@@ -1496,7 +1496,7 @@ epd_status epd_op_mx_gemm(int32_t epi, const void* A, const void* SA, const void
   p.W = (const unsigned char*)W; p.SW = (const unsigned*)SW; p.bias = bias; p.cscale = cscale;
   p.M = M; p.N = N; p.K = K; p.Npad = N;
   p.C = (bf16_t*)C; p.ldc = N; p.R = R; p.ldr = N; p.VT = (bf16_t*)C; p.hd_pad = hd_pad; p.heads = heads; p.n_tok = n_tok;
-  p.Cq = (unsigned char*)Cq; p.ldcq = N; p.SC = (unsigned*)SC; p.sc_ld = M;
+  p.Cq = (unsigned char*)Cq; p.ldcq = N; p.ncq = N; p.SC = (unsigned*)SC; p.sc_ld = M;
   const hipError_t e = mx_gemm(p, (hipStream_t)hip_stream);
   if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "epd_op_mx_gemm: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_INVALID_ARG : EPD_ERR_HIP; }
   return EPD_OK;

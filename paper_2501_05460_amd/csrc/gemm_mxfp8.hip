@@ -381,14 +381,14 @@ __global__ __launch_bounds__(NT, 1) void k_gemm_mxfp8(const MxGemmParams p, cons
       const int q = tid + NT * i;
       const int r = q / NCH, c = q % NCH;
       const int row = m0 + r, col = n0 + c * 16;
-      if (row < p.M && col < p.ldcq)
+      if (row < p.M && col < p.ncq)
         __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + r * BN + ((c ^ (r & 15)) << 4)),
                                     reinterpret_cast<u32x4*>(p.Cq + (long)row * p.ldcq + col));
     }
     {
       const int r = tid & (BM - 1), half = tid >> 8;    // 256 rows x 2 slabs of 128 features
       const int slab = n0 / BKB + half;
-      if (m0 + r < p.M && slab * BKB < p.ldcq)
+      if (m0 + r < p.M && slab * BKB < p.ncq)
         p.SC[(long)slab * p.sc_ld + m0 + r] = *reinterpret_cast<const unsigned*>(sScale + r * 8 + half * 4);
     }
   } else {
@@ -492,7 +492,7 @@ hipError_t mx_gemm(const MxGemmParams& p, hipStream_t st) {
     case EPI_VT: return p.VT && p.n_tok % 8 == 0 && p.hd_pad > 0 ? launch<EPI_VT>(p, st) : hipErrorInvalidValue;
     case EPI_BIAS_GELU_ERF:
     case EPI_BIAS_GELU_TANH:
-      if (!p.Cq || !p.SC || p.ldcq % BKB || p.sc_ld < (long)(p.M + BM - 1) / BM * BM) return hipErrorInvalidValue;
+      if (!p.Cq || !p.SC || p.ncq <= 0 || p.ncq % BKB || p.ldcq < p.ncq || p.ldcq % 16 || p.sc_ld < (long)(p.M + BM - 1) / BM * BM) return hipErrorInvalidValue;
       return p.epi == EPI_BIAS_GELU_ERF ? launch<EPI_BIAS_GELU_ERF>(p, st) : launch<EPI_BIAS_GELU_TANH>(p, st);
     case EPI_BIAS_RESIDUAL: return p.R && p.N % 4 == 0 ? launch<EPI_BIAS_RESIDUAL>(p, st) : hipErrorInvalidValue;
     default: return hipErrorInvalidValue;

@@ -189,8 +189,9 @@ hipError_t mx_rows(const MxRowParams& p, hipStream_t st);
 // C[M,N] = A[M,K] W[N,K]^T on MXFP8 operands, fp32 accumulation, out = acc * cscale[n] + bias[n], then:
 //   EPI_BIAS            bf16 C [M, ldc];
 //   EPI_VT              bf16, transposed per (slice, head) as in GemmParams;
-//   EPI_BIAS_GELU_*     activation, then MXFP8 along the output features: codes Cq [M, ldcq] and scale words
-//                       SC [ldcq / 128][sc_ld] (the operand of the next product);
+//   EPI_BIAS_GELU_*     activation, then MXFP8 along the output features: codes Cq [M, ldcq] (the first ncq
+//                       columns are written, ncq % 128 == 0, zeros past N) and scale words SC [ncq / 128][sc_ld]
+//                       (the operand of the next product);
 //   EPI_BIAS_RESIDUAL   R[M, ldr] (fp32) += out.
 // A and SA must be readable for round_up(M, 256) rows, W / SW / bias / cscale for Npad rows (Npad % 256 == 0,
 // zero rows past N); K % 128 == 0.  cscale may be null (all ones).
@@ -206,7 +207,7 @@ struct MxGemmParams {
   bf16_t* C; long ldc;
   float* R; long ldr;
   bf16_t* VT; int hd_pad, heads, n_tok;
-  unsigned char* Cq; long ldcq;
+  unsigned char* Cq; long ldcq; int ncq;
   unsigned* SC; long sc_ld;
 };
 hipError_t mx_gemm(const MxGemmParams& p, hipStream_t st);

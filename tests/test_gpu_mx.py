@@ -307,3 +307,41 @@ def test_mx_fp8_is_refused_where_it_does_not_apply():
     assert s == B.EPD_ERR_UNSUPPORTED and "128" in msg
     s, msg = B.check_desc(small_mx_desc(dtype=wl.DT_FP32))
     assert s == B.EPD_ERR_UNSUPPORTED
+
+
+def test_mx_fp8_paged_output_and_the_split_path_carry_the_fused_calls_bits():
+    """The option changes the layer products only: the paged output, the shares of a request and the
+    trunk / transfer / project-on-the-prefill-side split give what the one fused call gives (bit for bit where the
+    bf16 path promises it: paged and shared output always, the split path behind a projector that starts with a
+    plain conversion)."""
+    desc = small_mx_desc(tile_size=224, final_norm=1, max_tiles_per_call=4)    # 256 patches per slice, post norm + Linear
+    w = wl.gen_weights(desc, 41, std=0.08)
+    tiles = torch.from_numpy(wl.gen_tiles(desc, 41, 5)).cuda()
+    enc = make_encoder(desc, w)
+    n = enc.tokens_per_tile
+    fused = enc.encode(tiles, [0, 2, 5]).clone()
+    torch.cuda.synchronize()
+    # shares
+    parts = torch.empty_like(fused)
+    enc.encode_range(tiles, 0, 3, parts)
+    enc.encode_range(tiles, 3, 5, parts)
+    torch.cuda.synchronize()
+    assert torch.equal(parts.view(torch.int16), fused.view(torch.int16))
+    # paged output
+    cache = B.MMCache(5 * n // 16 + 3, 16, desc.out_dim, True)
+    t0, t1 = cache.alloc(2 * n)[::-1], cache.alloc(3 * n)
+    B.encode_paged(enc, tiles, [0, 2, 5], cache, [t0, t1])
+    torch.cuda.synchronize()
+    got = torch.cat([cache.gather(t0), cache.gather(t1)])
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(torch.int16), fused.view(torch.int16))
+    # trunk on the encode side, projection on the prefill side
+    pre = B.MMCache(5 * desc.n_patches // 16, 16, desc.hidden, True)
+    ids = pre.alloc(5 * desc.n_patches)
+    B.encode_trunk_paged(enc, tiles, 0, 5, pre, ids)
+    merged = B.project_merge(enc, pre, ids, 5)
+    torch.cuda.synchronize()
+    assert torch.equal(merged.view(torch.int16), fused.view(torch.int16))
+    for c in (cache, pre):
+        c.close()
+    enc.close()
