@@ -115,6 +115,8 @@ def main():
     ap.add_argument("--mx-fp8", action="store_true",
                     help="the checkpoint-fidelity option epd_model_desc::mx_fp8: q/k/v, FC1 and FC2 products on MXFP8 "
                          "operands (narrower than the headline precision: an extra line, never the headline)")
+    ap.add_argument("--no-mx-option", action="store_true",
+                    help="skip the extra timing of the same workload with the MXFP8 option on (reported as mx_fp8_option)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB elementwise copy kernel (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -370,6 +372,30 @@ def main():
             p_pre.close()
             del out2
 
+    # ---- the same workload with the MXFP8 option on: an extra figure next to the headline, never the headline ----
+    mx_opt = None
+    if bf16 and not args.mx_fp8 and not args.no_mx_option and desc.hidden % 128 == 0 and desc.layers > 0:
+        wdev = [B.to_device(wl.gen_weight(desc, wk.weight_seed, i), True) for i in range(len(wl.weight_specs(desc)))]
+        enc_mx = B.Encoder(desc.replace(mx_fp8=1), wdev)
+        del wdev
+        out_mx = enc_mx.alloc_out(T)
+        for _ in range(2):
+            enc_mx.encode(tiles, offsets, out_mx)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for e0, e1 in evs:
+            e0.record()
+            enc_mx.encode(tiles, offsets, out_mx)
+            e1.record()
+        torch.cuda.synchronize()
+        mx_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
+        mx_opt = {"ms_per_step": round(mx_ms, 3), "tiles_per_s": round(T / mx_ms * 1e3, 1),
+                  "speedup_vs_bf16": round(ms_median / mx_ms, 3),
+                  "dtype": "mxfp8 (q/k/v, FC1, FC2 operands) + bf16",
+                  "distance_from_bf16_output": round(float((out_mx.float() - out.float()).abs().max() / out.float().abs().max()), 4),
+                  "note": "epd_model_desc::mx_fp8; parity of the option: tests/test_gpu_mx.py, tests/test_gpu_fullsize.py"}
+        enc_mx.close()
+        del out_mx
+
     # ---- parity spot check and CPU baseline: the oracle on a bounded sample ----
     cpu = None
     parity = None
@@ -417,6 +443,7 @@ def main():
         "roofline": roofline,
         "hbm_kernels": hbm,
         "cpu_baseline": cpu,
+        "mx_fp8_option": mx_opt,
         "mm_cache": mm,
         "batch_sweep": sweep,
         "shard_sweep": shard,
