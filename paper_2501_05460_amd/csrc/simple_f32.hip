@@ -46,14 +46,29 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
   const int tx = tid % 16, ty = tid / 16;
   const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
   float acc[4][4] = {};
+  // the slab after the current one waits in registers (four elements of each operand per thread), so its memory
+  // latency passes under the current slab's arithmetic instead of in front of every slab
+  float ra[4], rw[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = tid + 256 * u;
+      const int r = i / 16, kk = i % 16;
+      const int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
+      ra[u] = (gm < M && gk < K) ? A[(long)gm * lda + gk] : 0.f;
+      rw[u] = (gn < N && gk < K) ? W[(long)gn * K + gk] : 0.f;
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < K; k0 += 16) {
-    for (int i = tid; i < 64 * 16; i += 256) {
-      int r = i / 16, kk = i % 16;
-      int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
-      sA[kk][r] = (gm < M && gk < K) ? A[(long)gm * lda + gk] : 0.f;
-      sW[kk][r] = (gn < N && gk < K) ? W[(long)gn * K + gk] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = tid + 256 * u;
+      sA[i % 16][i / 16] = ra[u];
+      sW[i % 16][i / 16] = rw[u];
     }
     __syncthreads();
+    if (k0 + 16 < K) fetch(k0 + 16);
 #pragma unroll
     for (int kk = 0; kk < 16; ++kk) {
       float a[4], w[4];
