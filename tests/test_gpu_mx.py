@@ -345,3 +345,38 @@ def test_mx_fp8_paged_output_and_the_split_path_carry_the_fused_calls_bits():
     for c in (cache, pre):
         c.close()
     enc.close()
+
+
+def _random_mx_desc(rng):
+    """A small encoder description with the option on, drawn within its limits (hidden a multiple of 128; otherwise
+    the bf16 mode's: head dim % 4 and <= 128, widths % 8, resampler: patches % 64)."""
+    hidden, heads = [(128, 1), (128, 2), (128, 4), (256, 2), (256, 4), (384, 3), (384, 4), (256, 8)][int(rng.integers(0, 8))]
+    proj_kind = int(rng.choice([wl.PROJ_LINEAR, wl.PROJ_MLP, wl.PROJ_RESAMPLER]))
+    if proj_kind == wl.PROJ_RESAMPLER:
+        tile, shuffle, prenorm = int(rng.choice([112, 224])), 0, 0
+    else:
+        tile = int(rng.choice([70, 84, 98, 112, 140]))
+        shuffle = int(rng.integers(0, 2)) if (tile // 14) % 2 == 0 else 0
+        prenorm = int(rng.integers(0, 2))
+    r_heads = int(rng.choice([1, 2, 4]))
+    return wl.ModelDesc(
+        dtype=wl.DT_BF16, tile_size=tile, patch=14, hidden=hidden, heads=heads, mlp=8 * int(rng.integers(8, 70)),
+        layers=int(rng.integers(1, 4)), norm=int(rng.integers(0, 2)), qk_norm=int(rng.integers(0, 3)),
+        act=int(rng.integers(0, 2)), final_norm=int(rng.integers(0, 2)), pixel_shuffle=shuffle, proj_kind=proj_kind,
+        proj_prenorm=prenorm, proj_mid=8 * int(rng.integers(1, 20)), proj_out=r_heads * 8 * int(rng.integers(2, 12)),
+        eps=1e-6, max_tiles_per_call=int(rng.integers(1, 4)), layer_scale=int(rng.integers(0, 2)),
+        class_token=int(rng.integers(0, 2)), proj_heads=r_heads, mx_fp8=1)
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_seeded_random_descriptions_with_mx_fp8_vs_oracle(case):
+    rng = np.random.default_rng([78, case])
+    desc = _random_mx_desc(rng)
+    n_tiles = int(rng.integers(1, 6))
+    cut = int(rng.integers(0, n_tiles + 1))
+    got, want, plain = _run_mx(desc, seed=200 + case, n_tiles=n_tiles, offsets=(0, cut, n_tiles))
+    e, e_plain, fmt = rel_err(got, want), rel_err(got, plain), rel_err(want, plain)
+    print(f"case {case} {desc} tiles={n_tiles}: vs converting oracle {e:.3e}, vs exact {e_plain:.3e}, format {fmt:.3e}")
+    assert got.shape == want.shape
+    assert e < TOL_MX
+    assert e_plain < 1.5 * fmt + 2e-2
