@@ -59,7 +59,7 @@ def test_scaled_fp8_mfma_operand_and_result_layout():
     D[8 (i / 4) + 4 (l / 32) + i % 4][l % 32] with D = A B^T, A the first operand."""
     rng = np.random.default_rng(101)
     ca, cb = random_codes(rng, (32, 64)), random_codes(rng, (32, 64))
-    ea = rng.integers(120, 131, size=(32, 2)).astype(np.uint8)   # scale bytes around 2^0
+    ea = rng.integers(120, 131, size=(32, 2)).astype(np.uint8)   # scale bytes near 127 (factor 1)
     eb = rng.integers(120, 131, size=(32, 2)).astype(np.uint8)
     a_regs = np.zeros((64, 32), np.uint8); b_regs = np.zeros((64, 32), np.uint8)
     sa = np.zeros(64, np.int32); sb = np.zeros(64, np.int32)
