@@ -304,10 +304,30 @@ __global__ __launch_bounds__(NT, 1) void k_gemm_mxfp8(const MxGemmParams p, cons
   // through LDS (the operand buffers are idle), so that global memory sees 16-byte chunks of whole rows
   u8* stage = smem;
   if constexpr (EPI == EPI_BIAS_RESIDUAL) {
-    // R[row][col] += acc * cscale + bias on the fp32 stream, four passes of 64 token rows: [64][BN] floats
-    constexpr int XROWS = 64, ROWB = BN * 4, XNCH = ROWB / 16, PER_T = XROWS * XNCH / NT;
+    // R[row][col] += acc * cscale + bias on the fp32 stream, four passes of 64 token rows: [64][BN] floats.  The
+    // stream rows of a pass wait in registers, fetched two passes ahead (those of the first two passes in one batch
+    // in front of the first staging), through a buffer descriptor: one lane offset for all of a thread's chunks, the
+    // row part of the address in scalar registers, so the 16 loads in flight cost 64 data registers and no more.
+    // (The descriptor's range check covers the lane offset only: R holds round_up(M, 256) rows, rows past M are
+    // read like any other and never written.)
+    constexpr int XROWS = 64, ROWB = BN * 4, XNCH = ROWB / 16, PER_T = XROWS * XNCH / NT, XSTEP = NT / XNCH;
+    int et = tid;
+    asm volatile("" : "+v"(et));   // opaque copy: what the epilogue derives from it is not hoisted above the main loop
+    const int x_r0 = et / XNCH, x_c = et % XNCH;
+    const int x_col = n0 + x_c * 4;
+    const bool col_ok = x_col < p.N;
+    __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(p.R, 0, (int)0x7fffffff, 0x00020000);
+    const unsigned x_voff = ((unsigned)x_r0 * (unsigned)p.ldr + (unsigned)x_col) * 4u;
+    f32x4 xr[2][PER_T];
+    auto xload = [&](auto set, int pass) {
+      constexpr int S = decltype(set)::value;
 #pragma unroll
-    for (int pass = 0; pass < BM / XROWS; ++pass) {
+      for (int i = 0; i < PER_T; ++i)
+        xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+            rsrc_x, x_voff, (unsigned)(m0 + pass * XROWS + XSTEP * i) * (unsigned)p.ldr * 4u, 2));
+    };
+    auto one_pass = [&](auto set, int pass) {
+      constexpr int S = decltype(set)::value;
       if (pass > 0) __syncthreads();
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -329,16 +349,23 @@ __global__ __launch_bounds__(NT, 1) void k_gemm_mxfp8(const MxGemmParams p, cons
       __syncthreads();
 #pragma unroll
       for (int i = 0; i < PER_T; ++i) {
-        const int q = tid + NT * i;
-        const int r = q / XNCH, c = q % XNCH;
-        const int row = m0 + pass * XROWS + r, col = n0 + c * 4;
-        if (row < p.M && col < p.N) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((c ^ (r & 15)) << 4));
-          f32x4* dst = reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + col);
-          __builtin_nontemporal_store(__builtin_nontemporal_load(dst) + v, dst);
+        const int r = x_r0 + XSTEP * i;
+        const int row = m0 + pass * XROWS + r;
+        if (row < p.M && col_ok) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(stage + r * ROWB + ((x_c ^ (r & 15)) << 4));
+          __builtin_nontemporal_store(xr[S][i] + v, reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + x_col));
         }
       }
-    }
+      if (pass + 2 < BM / XROWS) xload(set, pass + 2);
+    };
+    using X0 = std::integral_constant<int, 0>;
+    using X1 = std::integral_constant<int, 1>;
+    xload(X0{}, 0);
+    xload(X1{}, 1);
+    one_pass(X0{}, 0);
+    one_pass(X1{}, 1);
+    one_pass(X0{}, 2);
+    one_pass(X1{}, 3);
   } else if constexpr (MX_OUT) {
     // act(acc * cscale + bias) converted to MXFP8 along the output features (the contraction dimension of the
     // next product).  A lane and its partner lane ^ 32 together hold the 32 features of one block of one token:
@@ -494,7 +521,9 @@ hipError_t mx_gemm(const MxGemmParams& p, hipStream_t st) {
     case EPI_BIAS_GELU_TANH:
       if (!p.Cq || !p.SC || p.ncq <= 0 || p.ncq % BKB || p.ldcq < p.ncq || p.ldcq % 16 || p.sc_ld < (long)(p.M + BM - 1) / BM * BM) return hipErrorInvalidValue;
       return p.epi == EPI_BIAS_GELU_ERF ? launch<EPI_BIAS_GELU_ERF>(p, st) : launch<EPI_BIAS_GELU_TANH>(p, st);
-    case EPI_BIAS_RESIDUAL: return p.R && p.N % 4 == 0 ? launch<EPI_BIAS_RESIDUAL>(p, st) : hipErrorInvalidValue;
+    case EPI_BIAS_RESIDUAL:   // the stream rows are addressed through 32-bit offsets
+      if (!p.R || p.N % 4 || p.ldr < p.N || ((long)(p.M + BM - 1) / BM * BM) * p.ldr * 4 >= (1L << 32)) return hipErrorInvalidValue;
+      return launch<EPI_BIAS_RESIDUAL>(p, st);
     default: return hipErrorInvalidValue;
   }
 }
