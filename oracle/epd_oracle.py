@@ -137,7 +137,7 @@ def pixel_shuffle_half(x, g: int):
 # ------------------------------------------------------------- MXFP8 option ----
 # Checkpoint-fidelity option `mx_fp8` (narrower than the FP16 the paper serves in, Appendix
 # "Implementation Details": an option, never the headline precision).  The operands of the q/k/v,
-# FC1 and FC2 products of every layer are quantised to the MXFP8 format of the OCP Microscaling
+# out-projection, FC1 and FC2 products of every layer are quantised to the MXFP8 format of the OCP Microscaling
 # Formats specification v1.0: along the contraction dimension, blocks of 32 consecutive elements
 # share one power-of-two scale (E8M0: an 8-bit biased exponent, X = 2^(byte - 127)) and each element
 # is an OCP FP8 E4M3 number (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals;
@@ -238,13 +238,16 @@ def _act(x, kind: int):
 
 
 def encoder_layer(x, w, desc, l: int):
-    """One pre-norm transformer layer on the [N, D] tokens of one slice.  With `desc.mx_fp8` the three
-    products fed by a norm or by the activation (q/k/v, FC1, FC2) take MXFP8 operands; the attention
-    products and the out-projection do not (reading: their operand is made head by head inside the
-    attention step, and they are a tenth of a layer's work)."""
+    """One pre-norm transformer layer on the [N, D] tokens of one slice.  With `desc.mx_fp8` the four
+    weight products of the layer (q/k/v, out-projection, FC1, FC2) take MXFP8 operands; the two attention
+    products do not.  Reading: the out-projection's operand is converted only when the head dim is one the
+    kernels store without padding (64, 72, 96, 128: every encoder the paper evaluates); for any other head dim
+    the packed layout pads each head, blocks of 32 along it would not be the blocks of 32 along the hidden
+    dimension this definition converts, and the out-projection stays unconverted on both sides."""
     D, H = desc.hidden, desc.heads
     p = f"l{l}_"
     big = mx_linear if getattr(desc, "mx_fp8", 0) else linear
+    big_o = big if (D // H) in (64, 72, 96, 128) else linear
     u = _norm(x, w, p + "n1", desc.norm, desc.eps)
     qkv = big(u, w[p + "qkv_w"], w[p + "qkv_b"])         # rows of W: q block, k block, v block
     q, k, v = qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:]
@@ -258,7 +261,7 @@ def encoder_layer(x, w, desc, l: int):
         q = rms_norm(q.reshape(-1, H, hd), w[p + "qn_g"], desc.eps).reshape(-1, D)
         k = rms_norm(k.reshape(-1, H, hd), w[p + "kn_g"], desc.eps).reshape(-1, D)
     o = attention(q, k, v, H)
-    branch = linear(o, w[p + "o_w"], w[p + "o_b"])
+    branch = big_o(o, w[p + "o_w"], w[p + "o_b"])
     if getattr(desc, "layer_scale", 0):
         branch = branch * np.asarray(w[p + "ls1"], F64)     # per-channel layer scale
     x = x + branch

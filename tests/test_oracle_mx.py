@@ -173,10 +173,11 @@ def _tiny_desc(**kw):
     return wl.DESC_C1.replace(layers=2, **kw)
 
 
-def test_encoder_layer_with_mx_fp8_quantises_exactly_the_three_products_it_names():
+def test_encoder_layer_with_mx_fp8_quantises_exactly_the_four_products_it_names():
     """Composition check: the layer with the option equals the layer written out with explicit conversions
-    (library float8 type for the elements, explicit power-of-two block scales), and each of the three
-    conversions matters."""
+    (block scales from log2 here; the element rounding itself is pinned against the library's float8 type in the
+    tests above -- going through it here would round float64 -> float32 -> float8, and that double rounding moves
+    an element that sits within 2^-24 of a tie), and each of the four conversions matters."""
     desc = _tiny_desc(mx_fp8=1)
     w = wl.gen_weights(desc, 4242)
     rng = np.random.default_rng(1)
@@ -188,7 +189,7 @@ def test_encoder_layer_with_mx_fp8_quantises_exactly_the_three_products_it_names
         blk = a.reshape(-1, K // 32, 32)
         amax = np.abs(blk).max(-1, keepdims=True)
         X = 2.0 ** (np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 8)
-        q = torch.from_numpy(np.clip(blk / X, -448, 448)).to(torch.float32).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+        q = O.e4m3_round(blk / X)
         return (q * X).reshape(a.shape)
 
     def layer(xx, l, which):
@@ -198,18 +199,33 @@ def test_encoder_layer_with_mx_fp8_quantises_exactly_the_three_products_it_names
         qkv = q(u, "qkv") @ q(w[p + "qkv_w"], "qkv").T + w[p + "qkv_b"]
         D = desc.hidden
         o = O.attention(qkv[:, :D], qkv[:, D:2 * D], qkv[:, 2 * D:], desc.heads)
-        xx = xx + o @ np.asarray(w[p + "o_w"], np.float64).T + w[p + "o_b"]
+        xx = xx + q(o, "o") @ q(w[p + "o_w"], "o").T + w[p + "o_b"]
         u = O.layer_norm(xx, w[p + "n2_g"], w[p + "n2_b"], desc.eps)
         h = O.gelu_erf(q(u, "fc1") @ q(w[p + "fc1_w"], "fc1").T + w[p + "fc1_b"])
         return xx + q(h, "fc2") @ q(w[p + "fc2_w"], "fc2").T + w[p + "fc2_b"]
 
     got = O.encoder_layer(x, w, desc, 0)
-    want = layer(x, 0, {"qkv", "fc1", "fc2"})
+    want = layer(x, 0, {"qkv", "o", "fc1", "fc2"})
     assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
     plain = O.encoder_layer(x, w, desc.replace(mx_fp8=0), 0)
     assert np.allclose(plain, layer(x, 0, set()), rtol=1e-12, atol=1e-12)
-    for drop in ("qkv", "fc1", "fc2"):                     # leaving any one conversion out is visible
-        other = layer(x, 0, {"qkv", "fc1", "fc2"} - {drop})
+    for drop in ("qkv", "o", "fc1", "fc2"):                # leaving any one conversion out is visible
+        other = layer(x, 0, {"qkv", "o", "fc1", "fc2"} - {drop})
         assert np.abs(other - got).max() > 1e-6
     # the option is a perturbation of the plain layer, not a different function
     assert 1e-6 < np.abs(got - plain).max() / np.abs(plain).max() < 5e-2
+
+
+def test_out_projection_stays_unconverted_for_head_dims_the_kernels_pad():
+    """Head dim 48 (padded to 64 in the packed layout): blocks of 32 along the padded index are not blocks of 32
+    along the hidden dimension, so the reading leaves that product alone; head dim 64 converts it."""
+    import unittest.mock as mock
+    rng = np.random.default_rng(2)
+    for heads, calls in ((4, 3), (3, 4)):       # hidden 192: head dims 48 and 64
+        desc = _tiny_desc(mx_fp8=1, heads=heads)
+        w = wl.gen_weights(desc, 4243)
+        x = rng.normal(size=(desc.n_patches, desc.hidden))
+        with mock.patch.object(O, "mx_linear", side_effect=O.mx_linear) as spy:
+            got = O.encoder_layer(x, w, desc, 0)
+        assert spy.call_count == calls
+        assert np.isfinite(got).all()
