@@ -113,7 +113,7 @@ def main():
                     help="measure this box's ceilings instead of the workload (MFMA loop, streaming copy, vendor "
                          "BLAS and this library on the per-layer shapes) and print them as one JSON line")
     ap.add_argument("--mx-fp8", action="store_true",
-                    help="the checkpoint-fidelity option epd_model_desc::mx_fp8: q/k/v, FC1 and FC2 products on MXFP8 "
+                    help="the checkpoint-fidelity option epd_model_desc::mx_fp8: q/k/v, out-projection, FC1 and FC2 products on MXFP8 "
                          "operands (narrower than the headline precision: an extra line, never the headline)")
     ap.add_argument("--no-mx-option", action="store_true",
                     help="skip the extra timing of the same workload with the MXFP8 option on (reported as mx_fp8_option)")
@@ -208,7 +208,7 @@ def main():
     traffic, traffic_source = (traffic_from_profile(args.workload)
                                if desc.max_tiles_per_call == wk.desc.max_tiles_per_call and not args.mx_fp8 else (None, None))
     roofline = {
-        "bound": "mfma", "kernel": ("k_gemm_mxfp8 (q/k/v, FC1, FC2) + k_gemm_bf16 (the rest)" if args.mx_fp8 else "k_gemm_bf16 (all epilogue variants)") if bf16 else "k_f32_gemm",
+        "bound": "mfma", "kernel": ("k_gemm_mxfp8 (q/k/v, out-proj, FC1, FC2) + k_gemm_bf16 (the rest)" if args.mx_fp8 else "k_gemm_bf16 (all epilogue variants)") if bf16 else "k_f32_gemm",
         "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
         # what a register-resident MFMA loop reaches on this machine right now (random operands; no memory, no LDS)
         "achievable_peak": round(B.op_mfma_peak(True), 1) if bf16 else None,
@@ -222,7 +222,7 @@ def main():
 
     if args.mx_fp8:
         # the converted products against the dense FP8 peak of the matrix cores (5.0 PFLOP/s)
-        fams = ("gemm_qkv", "gemm_fc1", "gemm_fc2")
+        fams = ("gemm_qkv", "gemm_out", "gemm_fc1", "gemm_fc2")   # out-proj: converted for the head dims of the named workloads
         mx_ms = sum(fam[k]["ms"] for k in fams)
         mx_tf = sum(gf[k] for k in fams) * T * prof_steps / (mx_ms * 1e-3) / 1e12 if mx_ms > 0 else 0.0
         roofline["mx_products"] = {"achieved": round(mx_tf, 1), "peak": 5000.0, "unit": "TFLOP/s", "frac": round(mx_tf / 5000.0, 4)}
@@ -390,7 +390,7 @@ def main():
         mx_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in evs]))
         mx_opt = {"ms_per_step": round(mx_ms, 3), "tiles_per_s": round(T / mx_ms * 1e3, 1),
                   "speedup_vs_bf16": round(ms_median / mx_ms, 3),
-                  "dtype": "mxfp8 (q/k/v, FC1, FC2 operands) + bf16",
+                  "dtype": "mxfp8 (q/k/v, out-proj, FC1, FC2 operands) + bf16",
                   "distance_from_bf16_output": round(float((out_mx.float() - out.float()).abs().max() / out.float().abs().max()), 4),
                   "note": "epd_model_desc::mx_fp8; parity of the option: tests/test_gpu_mx.py, tests/test_gpu_fullsize.py"}
         enc_mx.close()
@@ -427,7 +427,7 @@ def main():
         "metric": "image_tiles_per_sec", "value": round(tiles_per_s, 2), "unit": "tiles/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("mxfp8 (q/k/v, FC1, FC2 operands) + bf16" if args.mx_fp8 else "bf16") if bf16 else "f32", "data": "synthetic",
+        "dtype": ("mxfp8 (q/k/v, out-proj, FC1, FC2 operands) + bf16" if args.mx_fp8 else "bf16") if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wk.name, "tiles": T, "requests": wk.n_requests,
                    "tokens_per_tile": desc.tokens_per_tile, "out_dim": desc.out_dim,
                    "micro_batch_tiles": desc.max_tiles_per_call},

@@ -94,14 +94,16 @@ typedef struct {
                               out-projection with bias), out = LN_post(o) Wp^T;
                             needs pixel_shuffle = 0, proj_prenorm = 0, E % proj_heads == 0;
                             bf16 mode: N % 64 == 0 and E / proj_heads <= 128             */
-  int32_t mx_fp8;        /* 1 (bf16 mode, hidden % 128 == 0): the q/k/v, FC1 and FC2 products of every
-                            layer take MXFP8 operands (OCP Microscaling Formats v1.0: E4M3 elements,
-                            one power-of-two scale per 32 consecutive elements of the contraction
-                            dimension); activations are converted by the kernel that produces them
-                            (pre-norm, FC1 epilogue), weights in epd_create; accumulation, residual
-                            stream, attention and the out-projection are as without the option.
-                            Narrower than the FP16 the paper serves in (Appendix "Implementation
-                            Details"): a fidelity / speed option with its own tolerance            */
+  int32_t mx_fp8;        /* 1 (bf16 mode, hidden % 128 == 0): the q/k/v, out-projection, FC1 and FC2 products
+                            of every layer take MXFP8 operands (OCP Microscaling Formats v1.0: E4M3
+                            elements, one power-of-two scale per 32 consecutive elements of the
+                            contraction dimension); activations are converted by the kernel that produces
+                            them (pre-norm, attention output, FC1 epilogue), weights in epd_create;
+                            accumulation, residual stream and the attention products are as without the
+                            option.  The out-projection is converted only for head dims stored without
+                            padding (64, 72, 96, 128); for others it stays bf16.  Narrower than the FP16
+                            the paper serves in (Appendix "Implementation Details"): a fidelity / speed
+                            option with its own tolerance                                          */
 } epd_model_desc;
 
 /* Encoder weights: `n_tensors` dev pointers in this fixed order, every matrix

@@ -79,7 +79,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
                                                         const bf16_t* __restrict__ vt,
                                                         bf16_t* __restrict__ o, int n_tok, int n_keys, int n_q,
                                                         int q_shared, int heads, int n_pairs, long ld_qk,
-                                                        long ld_o) {
+                                                        long ld_o, unsigned char* __restrict__ oq,
+                                                        unsigned* __restrict__ so, long ld_so) {
   using SM = AttnSmem<HD>;
   constexpr int BQ = 128 * QT;  // queries per workgroup
   constexpr int KS = SM::HDK / 16;   // k-steps of the S^T product
@@ -371,6 +372,31 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     const float l_tot = SUM_MFMA ? __shfl(oacc[u][SUM_B < MB ? SUM_B : 0][SUM_I], l32, 64)
                                  : l_run[u] + __shfl_xor(l_run[u], 32, 64);
     const float inv = 1.0f / l_tot;
+    if constexpr (HD % 32 == 0) {
+      if (oq) {
+        // MXFP8 output (the out-projection's operand): block b of this head = the 32 head-dim rows of O^T block b,
+        // 16 in this lane and 16 in lane ^ 32 (register group gi -> rows 8 gi + 4 lh .. + 3), so the block's
+        // largest magnitude is one exchange away; codes [row][ld_o bytes], scale words [column / 128][ld_so].
+        const long row = (long)t * n_q + q0 + u * 32 + l32;
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+          float v[16];
+          float amax = 0.f;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { v[e] = oacc[u][b][e] * inv; amax = fmaxf(amax, fabsf(v[e])); }
+          amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+          const unsigned byte = mx_scale_byte(amax);
+          const float sc = mx_inv_scale(byte);
+          const int col0 = h * HD + b * 32;
+#pragma unroll
+          for (int gi = 0; gi < 4; ++gi)
+            *reinterpret_cast<unsigned*>(oq + row * ld_o + col0 + gi * 8 + lh * 4) =
+                mx_pack4(v[gi * 4] * sc, v[gi * 4 + 1] * sc, v[gi * 4 + 2] * sc, v[gi * 4 + 3] * sc);
+          if (lh == 0) reinterpret_cast<unsigned char*>(so + (long)(col0 >> 7) * ld_so + row)[(col0 >> 5) & 3] = (unsigned char)byte;
+        }
+        continue;
+      }
+    }
     bf16_t* op = o + ((long)t * n_q + q0 + u * 32 + l32) * ld_o + (long)h * HD;
 #pragma unroll
     for (int b = 0; b < MB; ++b)
@@ -389,7 +415,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
 template <int HD, int QT, bool MASK>
 hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                          int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
-                         hipStream_t st) {
+                         unsigned char* oq, unsigned* so, long ld_so, hipStream_t st) {
   // once per instantiation; the initialisation of a function-local static is safe against concurrent callers
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -400,34 +426,36 @@ hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf1
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
   k_attention_bf16<HD, QT, MASK><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
-      q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o);
+      q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o, oq, so, ld_so);
   return hipGetLastError();
 }
 
 template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                        int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
-                       hipStream_t st) {
+                       unsigned char* oq, unsigned* so, long ld_so, hipStream_t st) {
   return (n_keys < n_tok || n_tok % BKEY != 0)
-             ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st)
-             : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
+             ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st)
+             : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
 }
 
 }  // namespace
 
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                           int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
-                          long ld_o, hipStream_t st) {
+                          long ld_o, hipStream_t st, unsigned char* oq, unsigned* so, long ld_so) {
   if (n_slices == 0) return hipSuccess;
+  // MXFP8 output: whole blocks of 32 per head only, rows of at least heads * hd_pad bytes, 4-byte pieces
+  if (oq && (hd_pad % 32 != 0 || !so || ld_o % 4 != 0 || ld_o < (long)heads * hd_pad || ld_so < (long)n_slices * n_q)) return hipErrorInvalidValue;
   // n_tok % 8: V^T rows are read in 16-byte chunks.  A slice whose rows are no multiple of the key block is
   // read up to 63 rows (q, k) / 63 elements (v^T) past its end: the caller's buffers must reach that far.
   if (n_tok % 8 != 0 || n_tok <= 0 || n_keys < 1 || n_keys > n_tok || n_q < 1) return hipErrorInvalidValue;
   if (!q_shared && n_q != n_tok) return hipErrorInvalidValue;   // a slice's own rows: one query per row
   switch (hd_pad) {
-    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
-    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
-    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
-    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, st);
+    case 64: return launch_attn<64, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
+    case 72: return launch_attn<72, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
+    case 96: return launch_attn<96, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
+    case 128: return launch_attn<128, 1>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
   }
   return hipErrorInvalidValue;
 }

@@ -68,6 +68,30 @@ __device__ __forceinline__ float apply_act_fast(float v) {
   return v;
 }
 
+// ---- MXFP8 conversion (OCP Microscaling Formats v1.0: E4M3 elements, one power-of-two scale per block of 32) ----
+// Scale byte of a block whose largest magnitude is amax (finite fp32): floor(log2(amax)) - 8 + 127 is the
+// biased fp32 exponent minus 8; clamped at 0 (zero blocks, and magnitudes below 2^-119).
+__device__ __forceinline__ unsigned mx_scale_byte(float amax) {
+  const int b = (int)((__float_as_uint(amax) >> 23) & 0xffu) - 8;
+  return (unsigned)(b > 0 ? b : 0);
+}
+// 2^(127 - byte): the factor that brings a block's elements into E4M3's range (exact: a power of two)
+__device__ __forceinline__ float mx_inv_scale(unsigned byte) { return __uint_as_float((254u - byte) << 23); }
+
+// four scaled values -> four E4M3 bytes (element 0 in the low byte); saturation by the clamp, rounding to
+// nearest even by the conversion instruction
+__device__ __forceinline__ unsigned mx_pack4(float a, float b, float c, float d) {
+  a = __builtin_amdgcn_fmed3f(a, -448.f, 448.f);
+  b = __builtin_amdgcn_fmed3f(b, -448.f, 448.f);
+  c = __builtin_amdgcn_fmed3f(c, -448.f, 448.f);
+  d = __builtin_amdgcn_fmed3f(d, -448.f, 448.f);
+  int r = 0;
+  r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, r, false);
+  r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
+  return (unsigned)r;
+}
+
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -201,7 +201,7 @@ struct LayerW {
   // folded pre-norms (bf16 mode): the weights of qkv, v (first norm) and fc1 (second norm) carry the norm's gain,
   // their biases its shift, and these are the column sums of the packed weights the epilogues subtract the mean with
   const float *qkv_cs = nullptr, *v_cs = nullptr, *fc1_cs = nullptr;
-  MxLinear mqkv, mv, mfc1, mfc2;   // epd_model_desc::mx_fp8: the same four matrices as MXFP8 operands
+  MxLinear mqkv, mv, mo, mfc1, mfc2;   // epd_model_desc::mx_fp8: the same matrices as MXFP8 operands (mo: only when the heads are stored unpadded)
 };
 
 }  // namespace
@@ -237,6 +237,8 @@ struct epd_ctx {
   int norm_mode = 0;
   bool fold = false;        // norm_mode == NORM_FOLD
   bool mx = false;          // epd_model_desc::mx_fp8: q/k, value, FC1 and FC2 products on MXFP8 operands
+  bool mx_o = false;        // ... and the out-projection (head dim stored without padding: the blocks of 32 are the definition's)
+  void* OQ = nullptr;       // attention output as MXFP8: codes [Mp, Dq_k], then scale words [Dq_k / 128][Mp]
   std::vector<std::vector<float>> host_keep;   // host vectors with copies to the device in flight (epd_create only)
   float* stats = nullptr;   // [Mp][n_part][2]: one pair per 128 columns, as the residual epilogues emit them
   float* stats1 = nullptr;  // [Mp][2]: one pair per row, made from `stats` when a row has more pairs than the products take (wide models)
@@ -440,6 +442,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
       return EPD_ERR_INVALID_ARG;
     }
     HIP_TRY(c, mx_gemm_init());
+    c->mx_o = c->hd_pad == x.hd;
   }
 
 #define NOMEM_IF(cond) do { if (cond) { set_err(c->err, sizeof(c->err), "device allocation failed (weights)"); return EPD_ERR_NOMEM; } } while (0)
@@ -496,6 +499,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
       }
 
       NOMEM_IF(!make_linear(c, w, li.o_w, li.o_b, x.D, x.D, &lw.o, st, pad_n(x.D), c->Dq_k, id, heads, x.D));
+      if (c->mx_o) NOMEM_IF(!mx_make(c, lw.o, &lw.mo, st));   // before the layer scale below
       f_pad = pad_n(x.F);
       NOMEM_IF(!make_linear(c, w, li.fc1_w, li.fc1_b, x.F, x.D, &lw.fc1, st, f_pad, c->D_k, id, id, x.F));
       NOMEM_IF(!make_linear(c, w, li.fc2_w, li.fc2_b, x.D, x.F, &lw.fc2, st, pad_n(x.D), f_pad, id, id, x.D));
@@ -512,10 +516,11 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
         scale_vector(const_cast<float*>(lw.qn_g), c->hd_pad, logit_scale, st);
       }
     }
+    const float* ls1 = nullptr;
     const float* ls2 = nullptr;
     if (d.layer_scale) {
       // layer scale is folded into the branch's last Linear: rows of W and the bias times ls
-      const float* ls1 = make_vec(c, w, li.ls1, x.D, x.D, id, st);
+      ls1 = make_vec(c, w, li.ls1, x.D, x.D, id, st);
       ls2 = make_vec(c, w, li.ls2, x.D, x.D, id, st);
       NOMEM_IF(!ls1 || !ls2);
       scale_rows(const_cast<void*>(lw.o.W), bf ? 1 : 0, x.D, lw.o.K, lw.o.K, const_cast<float*>(lw.o.b), ls1, st);
@@ -527,6 +532,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
       NOMEM_IF(!mx_finish(c, lw.v, &lw.mv, nullptr, 1.f, 0, st));
       NOMEM_IF(!mx_finish(c, lw.fc1, &lw.mfc1, nullptr, 1.f, 0, st));
       NOMEM_IF(!mx_finish(c, lw.fc2, &lw.mfc2, ls2, 1.f, ls2 ? x.D : 0, st));
+      if (c->mx_o) NOMEM_IF(!mx_finish(c, lw.o, &lw.mo, ls1, 1.f, ls1 ? x.D : 0, st));
     }
     if (c->fold) {
       float* cs_qk = (float*)dalloc(c, (size_t)lw.qkv.Npad * sizeof(float), true, st);
@@ -643,6 +649,7 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
     c->QKV = ws((size_t)(c->Mp + 64) * 2 * c->Dq * 2);
     c->VT = ws(((size_t)c->mb * x.H * c->hd_pad * x.Ns + 64) * 2);
     c->O = ws((size_t)c->Mp * c->Dq_k * 2);
+    if (c->mx_o) c->OQ = ws((size_t)c->Mp * c->Dq_k + (size_t)(c->Dq_k / 128) * c->Mp * sizeof(unsigned));
     c->Hd = ws((size_t)c->Mp * c->F_k * 2);
     c->Ape = ws((size_t)c->Mp * c->Kp_k * 2);
     c->Pin = ws((size_t)c->Mp_out * c->Pin_k * 2);
@@ -898,6 +905,26 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       ProfScope ps(c, 4, st);
       bf16_qknorm(QK, ld_qk, c->Dq, w.qn_g, w.kn_g, (long)M * x.H, c->hd_pad, x.H, x.hd, d.eps, st);
     }
+    if (c->mx_o) {
+      // the out-projection's operand as MXFP8: converted inside the attention kernel's output store when a head is
+      // whole blocks of 32 (64, 96, 128), by a pass over the bf16 output otherwise (72)
+      unsigned char* OQ = (unsigned char*)c->OQ; unsigned* SO = (unsigned*)(OQ + (size_t)c->Mp * c->Dq_k);
+      const bool fused = c->hd_pad % 32 == 0;
+      { ProfScope ps(c, 3, st);
+        HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, st,
+                                  fused ? OQ : nullptr, fused ? SO : nullptr, c->Mp));
+        if (!fused) {
+          MxRowParams r;
+          memset(&r, 0, sizeof(r));
+          r.kind = 2; r.in = O; r.ld_in = c->Dq_k; r.in_bf16 = 1; r.rows = M; r.dim = c->Dq_k;
+          r.codes = OQ; r.ld_codes = c->Dq_k; r.scales = SO; r.ld_scales = c->Mp;
+          HIP_TRY(c, mx_rows(r, st));
+        } }
+      { ProfScope ps(c, 6, st);
+        MxGemmParams p = mxp(EPI_BIAS_RESIDUAL, OQ, c->Dq_k, SO, w.mo);
+        p.R = X; p.ldr = x.D;
+        HIP_TRY(c, mx_gemm(p, st)); }
+    } else {
     { ProfScope ps(c, 3, st);
       HIP_TRY(c, bf16_attention(QK, QK + c->Dq, VT, O, T, x.Ns, x.Nt, x.Ns, 0, x.H, c->hd_pad, ld_qk, c->Dq_k, st)); }
     { ProfScope ps(c, 6, st);
@@ -905,6 +932,7 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
       p.R = X; p.ldr = x.D;
       with_emit(p, true);
       HIP_TRY(c, bf16_gemm(p, st)); }
+    }
     combine();
     if (c->mx) {
       HIP_TRY(c, mx_norm(w.n2_g, w.n2_b));

@@ -125,9 +125,12 @@ void bf16_qknorm(bf16_t* buf, long ld, long k_off, const float* gamma_q, const f
 // for every slice (learned queries of the resampler; q must be readable for round_up(n_q, 32) rows) instead
 // of the slice's own rows.  Row t * n_q + i of o is query i of slice t.
 // The queries carry the logit scale: weight of key j for query i = 2^(q_i . k_j) / sum_j' 2^(q_i . k_j').
+// oq != null (hd_pad % 32 == 0 only): the output leaves as MXFP8 instead of bf16, converted from the fp32
+// accumulators: codes oq [rows][ld_o bytes] (column h * hd_pad + d), scale words so [column / 128][ld_so]
+// (ld_so >= rows; layout of gemm_mxfp8.hip); o is not written then.
 hipError_t bf16_attention(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                           int n_tok, int n_keys, int n_q, int q_shared, int heads, int hd_pad, long ld_qk,
-                          long ld_o, hipStream_t st);
+                          long ld_o, hipStream_t st, unsigned char* oq = nullptr, unsigned* so = nullptr, long ld_so = 0);
 
 // W[r][0..cols) *= c (rounded to bf16 again) and b[r] *= c for r < rows: a constant factor of a product's
 // output folded into the rows of its packed weights
