@@ -74,6 +74,12 @@ epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, v
                                  int32_t n_slices, int32_t n_tokens, int32_t n_keys, int32_t heads,
                                  int32_t hd_pad, int32_t ld_qk, void* hip_stream);
 
+/* The same attention with its output leaving as MXFP8 (the out-projection's operand under epd_model_desc::mx_fp8),
+ * converted from the kernel's fp32 accumulators: codes dev uint8 [T * n_tokens, H * hd_pad], scales dev uint32
+ * [H * hd_pad / 128, T * n_tokens] (layout of epd_op_mx_rows).  hd_pad % 32 == 0, H * hd_pad % 128 == 0. */
+epd_status epd_op_attention_mx(const void* q, const void* k, const void* vt, void* codes, void* scales, int32_t n_slices,
+                               int32_t n_tokens, int32_t n_keys, int32_t heads, int32_t hd_pad, int32_t ld_qk, void* hip_stream);
+
 /* Check of the MFMA operand / result lane layout the kernels assume:
  * D[32,32] (fp32, row-major) = A[32,16] * B[16,32] (bf16, row-major), one
  * v_mfma_f32_32x32x16_bf16.  All pointers dev. */

@@ -34,7 +34,7 @@ EXPORTS = (
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
     "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
     "epd_op_row_stats", "epd_op_gemm_residual_stats", "epd_op_norm_gemm_bf16",
-    "epd_op_mx_rows", "epd_op_mx_gemm", "epd_op_mx_mfma_probe",
+    "epd_op_mx_rows", "epd_op_mx_gemm", "epd_op_mx_mfma_probe", "epd_op_attention_mx",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
     "epd_mm_last_error", "epd_mm_alloc", "epd_mm_free", "epd_encode_paged", "epd_mm_transfer", "epd_mm_transfer_noalloc", "epd_mm_gather",
     "epd_encode_trunk_paged", "epd_project_merge",
@@ -120,6 +120,8 @@ def lib() -> ctypes.CDLL:
         L.epd_op_mx_rows.restype = i32
         L.epd_op_mx_gemm.argtypes = [i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, i32, i32, i32, vp]
         L.epd_op_mx_gemm.restype = i32
+        L.epd_op_attention_mx.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
+        L.epd_op_attention_mx.restype = i32
         L.epd_op_mx_mfma_probe.argtypes = [vp, vp, vp, vp, vp, vp]
         L.epd_op_mx_mfma_probe.restype = i32
         L.epd_mm_cache_create.argtypes = [i32, i32, i32, i32, ctypes.POINTER(vp)]
@@ -556,3 +558,16 @@ def op_mx_mfma_probe(a: torch.Tensor, b: torch.Tensor, sa: torch.Tensor, sb: tor
     if s != EPD_OK:
         raise EpdError(s, "mx mfma probe failed")
     return d
+
+
+def op_attention_mx(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, n_slices: int, n_tokens: int, heads: int,
+                    hd_pad: int, ld_qk: int, n_keys: Optional[int] = None):
+    """op_attention_bf16 with the output as MXFP8: (codes uint8 [rows, heads * hd_pad], scale words int32 [cols / 128, rows])."""
+    rows, cols = n_slices * n_tokens, heads * hd_pad
+    codes = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device=q.device)
+    scales = torch.full((cols // 128, rows), -1, dtype=torch.int32, device=q.device)
+    s = lib().epd_op_attention_mx(q.data_ptr(), k.data_ptr(), vt.data_ptr(), codes.data_ptr(), scales.data_ptr(), n_slices,
+                                  n_tokens, n_tokens if n_keys is None else n_keys, heads, hd_pad, ld_qk, _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, lib().epd_last_error(None).decode())
+    return codes, scales

@@ -1462,6 +1462,21 @@ epd_status epd_op_attention_bf16(const void* q, const void* k, const void* vt, v
   return EPD_OK;
 }
 
+epd_status epd_op_attention_mx(const void* q, const void* k, const void* vt, void* codes, void* scales, int32_t n_slices,
+                               int32_t n_tokens, int32_t n_keys, int32_t heads, int32_t hd_pad, int32_t ld_qk, void* hip_stream) {
+  if (!q || !k || !vt || !codes || !scales) return EPD_ERR_INVALID_ARG;
+  if (n_tokens % 64 || hd_pad % 32 || (heads * hd_pad) % 128) {
+    set_err(g_err, sizeof(g_err), "epd_op_attention_mx: n_tokens %% 64, hd_pad %% 32 and heads * hd_pad %% 128 must be 0");
+    return EPD_ERR_UNSUPPORTED;
+  }
+  const long rows = (long)n_slices * n_tokens;
+  hipError_t e = bf16_attention((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)vt, nullptr, n_slices, n_tokens, n_keys,
+                                n_tokens, 0, heads, hd_pad, ld_qk, (long)heads * hd_pad, (hipStream_t)hip_stream,
+                                (unsigned char*)codes, (unsigned*)scales, rows);
+  if (e != hipSuccess) { set_err(g_err, sizeof(g_err), "attention launch failed: %s", hipGetErrorString(e)); return e == hipErrorInvalidValue ? EPD_ERR_UNSUPPORTED : EPD_ERR_HIP; }
+  return EPD_OK;
+}
+
 epd_status epd_op_mfma_probe(const void* A, const void* B, float* D, void* hip_stream) {
   if (!A || !B || !D) return EPD_ERR_INVALID_ARG;
   mfma_probe((const bf16_t*)A, (const bf16_t*)B, D, (hipStream_t)hip_stream);

@@ -384,3 +384,47 @@ def test_seeded_random_descriptions_with_mx_fp8_vs_oracle(case):
     assert got.shape == want.shape
     assert e < max(TOL_MX, 0.6 * fmt) and e < fmt
     assert e_plain < 1.5 * fmt + 2e-2
+
+
+@pytest.mark.parametrize("n_tok,n_keys,heads,hd", [(256, 256, 2, 64), (128, 100, 4, 96), (1024, 1024, 1, 128), (192, 129, 4, 64)])
+def test_attention_output_converted_in_the_kernel(n_tok, n_keys, heads, hd):
+    """The attention kernel's MXFP8 output (the out-projection's operand) against its own bf16 output and the oracle:
+    both outputs are roundings of the same fp32 accumulators, so the scale byte of a block follows the largest bf16
+    magnitude of that block (or sits one below it where bf16 rounding carried that magnitude over a power of two),
+    every code is within one spacing of the format of the bf16 value, and the numbers agree with the oracle's
+    attention to the format's spacing.  Rows past n_keys are padding: computed, never used."""
+    import math
+    rng = np.random.default_rng(n_tok + hd)
+    n_slices = 2
+    M, D = n_slices * n_tok, heads * hd
+    snap = lambda a: wl.to_bf16_grid(np.asarray(a, np.float32))
+    c = math.log2(math.e) / math.sqrt(hd)
+    q_dev = torch.from_numpy(snap(rng.standard_normal((M, D))) * np.float32(c)).bfloat16().float().numpy()
+    q = q_dev.astype(np.float64) / c
+    k, v = snap(rng.standard_normal((M, D))), snap(rng.standard_normal((M, D)) * np.exp(rng.uniform(-2, 2, size=(M, 1))))
+    qk = np.concatenate([q_dev, k], axis=1).astype(np.float32)
+    vt = v.reshape(n_slices, n_tok, heads, hd).transpose(0, 2, 3, 1).copy().astype(np.float32)
+    qk_d, vt_d = B.to_device(qk, True), B.to_device(vt, True)
+    o = B.op_attention_bf16(qk_d, qk_d[:, D:], vt_d, n_slices, n_tok, heads, hd, 2 * D, n_keys=n_keys).float().cpu().numpy()
+    codes, scales = B.op_attention_mx(qk_d, qk_d[:, D:], vt_d, n_slices, n_tok, heads, hd, 2 * D, n_keys=n_keys)
+    torch.cuda.synchronize()
+    real = (np.arange(M) % n_tok) < n_keys
+    got_codes, got_bytes = codes.cpu().numpy()[real], unpack_scale_words(scales.cpu().numpy())[real]
+    o = o[real].astype(np.float64)
+    _, bytes_of_bf16 = O.mx_quantize(o)
+    d = got_bytes.astype(int) - bytes_of_bf16.astype(int)
+    assert ((d == 0) | (d == -1)).all() and (d != 0).mean() < 2e-2
+    val = O.mx_dequantize(got_codes, got_bytes)
+    X = np.ldexp(1.0, got_bytes.astype(np.int64) - 127).repeat(32, axis=1)
+    spacing = np.ldexp(1.0, (np.floor(np.log2(np.maximum(np.abs(o) / X, 2.0 ** -6))) - 3).astype(np.int64)) * X
+    # half a spacing from the fp32 value plus the bf16 rounding of o itself (2^-5 of a spacing at most); a saturated
+    # element (scaled magnitude above 448) loses up to an eighth of its value instead
+    bound = np.where(np.abs(o) / X > 440, np.abs(o) / 8 + spacing, spacing)
+    assert (np.abs(val - o) <= bound).all()
+    want = np.concatenate([O.attention(q[s * n_tok:s * n_tok + n_keys], k[s * n_tok:s * n_tok + n_keys],
+                                       v[s * n_tok:s * n_tok + n_keys], heads) for s in range(n_slices)])
+    assert rel_err(val, want) < 0.126
+    exact_codes, exact_bytes = O.mx_quantize(want)
+    same = (got_bytes == exact_bytes).repeat(32, axis=1) & (got_codes == exact_codes)
+    print(f"attention -> MXFP8: {same.mean():.4f} of the codes are the oracle's")
+    assert same.mean() > 0.9
