@@ -104,6 +104,34 @@ def test_micro_batch_size_does_not_change_the_bits(setup):
         enc2.close()
 
 
+def test_a_call_captured_in_a_hip_graph_replays_the_eager_bits(setup):
+    """A call allocates nothing, copies nothing from the host and clears no memory with the runtime's fill, so
+    after one eager call on the context (kernel attributes are set at a kernel's first launch) its launch
+    sequence can be recorded into a HIP graph (a serving loop's way to issue the ~10 launches per layer of a
+    one-slice share, Section 3.2.2).  Every replay, with eager calls on the same context and a cleared
+    output between the replays, gives the bits of the eager call."""
+    desc, w, tiles, enc, full = setup
+    out = enc.alloc_out(7)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        enc.encode(tiles, [0, 7], out)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enc.encode(tiles, [0, 7], out)
+    torch.cuda.synchronize()
+    n = enc.tokens_per_tile
+    for rep in range(3):
+        out.fill_(3.0)
+        part = enc.encode(tiles[rep:rep + 2].contiguous(), [0, 2])     # eager work on the same workspace
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(part), bits(full[rep * n:(rep + 2) * n])), rep
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(out), bits(full)), rep
+
+
 def test_empty_batch_and_error_paths_leave_the_cache_untouched(setup):
     desc, w, tiles, enc, full = setup
     out = enc.alloc_out(7)
