@@ -1282,6 +1282,167 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
   }
 }
 
+// ---------------------------------------------------------------------------
+// Small-tile form for launches of one or two slices (a worker's share of a request under intra-request
+// parallelism, Section 3.2.2).  Such a launch has a handful of 128 x 128 tiles, most CUs idle and the busy ones
+// waiting for operand slabs: its time is the latency chain of one tile, not matrix work.  Here a tile is
+// 64 x 64 (four times as many workgroups, each asking for a quarter of the bytes), four waves of 32 x 32, and
+// both operand slabs go from global memory straight into an LDS ring of RING stages, RING - 1 slabs ahead of
+// the MFMAs, one barrier per slab.  An element's k-steps are added in the order of every other form (same
+// instruction, k ascending), so the bits are those of the large tiles.  The epilogue writes from registers:
+// a lane owns one token and 4 consecutive features per register group (EPI_VT: one feature, 4 tokens).
+// ---------------------------------------------------------------------------
+constexpr int SM_T = 64, SM_RING = 4;
+constexpr int SM_STAGE = 2 * SM_T * BK;   // bf16 elements of a ring stage: activation slab, then weight slab
+constexpr size_t SM_LDS = (size_t)SM_RING * SM_STAGE * sizeof(bf16_t);
+
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, const int gm, const int bw_) {
+  constexpr bool tok_major = (EPI == EPI_VT);
+  constexpr int LPS = 4;   // direct loads per thread and slab: two 32-row halves of each operand
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* ring = reinterpret_cast<bf16_t*>(smem);
+
+  // XCD x (workgroups are dealt round-robin) takes a contiguous run of the tile sequence; the sequence walks
+  // bands of bw_ tile columns top to bottom, so the ~32 tiles an XCD holds at once share few operand panels
+  const int gn = p.Npad / SM_T;
+  int id = blockIdx.x;
+  {
+    const int nb = gridDim.x, x = id & 7, slot = id >> 3, q = nb >> 3, r = nb & 7;
+    id = x * q + (x < r ? x : r) + slot;
+  }
+  const int band_tiles = gm * bw_, full_bands = gn / bw_;
+  int band = id / band_tiles, in_band = id % band_tiles, bw = bw_;
+  if (band >= full_bands) { band = full_bands; in_band = id - full_bands * band_tiles; bw = gn - full_bands * bw_; }
+  const int m0 = (in_band / bw) * SM_T;
+  const int n0 = (band * bw_ + in_band % bw) * SM_T;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int ld_row = tid >> 3, ld_c = tid & 7;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // the lane that lands on physical chunk ld_c of its LDS row fetches logical chunk ld_c ^ SWZ(row)
+  const unsigned a_voff = ((unsigned)ld_row * (unsigned)p.lda + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  const unsigned b_voff = ((unsigned)ld_row * (unsigned)p.K + ((ld_c ^ SWZ(ld_row)) * 8)) * 2;
+  const int KT_ = p.K / BK;
+
+  // slab kt -> ring stage kt % RING (rows of a ragged last tile past M are read like any other: A holds whole
+  // 256-row tiles; their results are never stored)
+  auto issue = [&](int kt) {
+    bf16_t* st = ring + (kt % SM_RING) * SM_STAGE;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const bf16_t* g = p.A + (long)(m0 + 32 * i) * p.lda + kt * BK;   // uniform
+      const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(st + (wave_u * 64 + 256 * i) * 8);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(a_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const bf16_t* g = p.W + (long)(n0 + 32 * i) * p.K + kt * BK;
+      const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(st + SM_T * BK + (wave_u * 64 + 256 * i) * 8);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :: "v"(b_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+    }
+  };
+  auto wait_vm = [&](auto n) {
+    constexpr int N = decltype(n)::value;
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
+  };
+
+#pragma unroll
+  for (int s = 0; s < SM_RING - 1; ++s)
+    if (s < KT_) issue(s);
+
+  // what the epilogue reads, fetched under the main loop: bias, and the residual rows it adds to.
+  // Register group g of a lane: tile row (token) wm * 32 + l32, tile columns wn * 32 + 8 g + 4 lh .. + 3
+  // (EPI_VT: feature wn * 32 + l32, tokens wm * 32 + 8 g + 4 lh .. + 3)
+  const int row = m0 + wm * 32 + l32;                 // token of this lane (not EPI_VT)
+  const int col0 = n0 + wn * 32 + 4 * lh;             // first feature of register group 0 (not EPI_VT)
+  f32x4 b4[4], x4[4];
+  float b1 = 0.f;
+  if constexpr (tok_major) {
+    b1 = p.bias[n0 + wn * 32 + l32];
+  } else {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) b4[g] = *reinterpret_cast<const f32x4*>(p.bias + col0 + 8 * g);
+  }
+  if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      if (row < p.M && col0 + 8 * g < p.N) x4[g] = *reinterpret_cast<const f32x4*>(p.R + (long)row * p.ldr + col0 + 8 * g);
+  } else if constexpr (EPI == EPI_BIAS_POS) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      if (row < p.M && col0 + 8 * g < p.N) x4[g] = *reinterpret_cast<const f32x4*>(p.pos + (long)(row % p.n_pos) * p.N + col0 + 8 * g);
+  }
+
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  const int frag_sw = SWZ(l32);
+  for (int kt = 0; kt < KT_; ++kt) {
+    // Loads complete in order: slab kt has landed once at most LPS x (slabs issued behind it) of this
+    // thread's loads are outstanding.  (The epilogue's own loads above are older than every slab but the
+    // first RING - 1, and counted among the outstanding ones only before those have landed.)
+    const int behind = KT_ - 1 - kt;
+    if (behind >= SM_RING - 2) wait_vm(std::integral_constant<int, (SM_RING - 2) * LPS>{});
+    else if (behind == 1) wait_vm(std::integral_constant<int, LPS>{});
+    else wait_vm(std::integral_constant<int, 0>{});
+    __syncthreads();   // everyone's part of slab kt is in LDS, and everyone is done reading slab kt - 1
+    if (kt + SM_RING - 1 < KT_) issue(kt + SM_RING - 1);   // into the stage slab kt - 1 has left
+    const bf16_t* a_s = ring + (kt % SM_RING) * SM_STAGE + (wm * 32 + l32) * BK;
+    const bf16_t* b_s = ring + (kt % SM_RING) * SM_STAGE + SM_T * BK + (wn * 32 + l32) * BK;
+    bf16x8 xf[BK / 16], wf[BK / 16];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int coff = ((2 * kk + lh) ^ frag_sw) * 8;
+      xf[kk] = *reinterpret_cast<const bf16x8*>(a_s + coff);
+      wf[kk] = *reinterpret_cast<const bf16x8*>(b_s + coff);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // all fragment reads of the slab first: their latency is paid once
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) acc = tok_major ? mfma32(xf[kk], wf[kk], acc) : mfma32(wf[kk], xf[kk], acc);
+  }
+
+  if constexpr (tok_major) {
+    const int f = n0 + wn * 32 + l32;
+    if (f < p.N) {
+      const int h = f / p.hd_pad, d = f % p.hd_pad;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int tok = m0 + wm * 32 + 8 * g + 4 * lh;   // n_tok % 8 == 0: the four tokens share a slice
+        if (tok < p.M) {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)(acc[4 * g + e] + b1);
+          const int t = tok / p.n_tok, n = tok % p.n_tok;
+          *reinterpret_cast<bf16x4*>(p.VT + (((long)t * p.heads + h) * p.hd_pad + d) * p.n_tok + n) = o;
+        }
+      }
+    }
+  } else if (row < p.M) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int col = col0 + 8 * g;
+      if (col >= p.N) continue;
+      const f32x4 v = {acc[4 * g + 0] + b4[g][0], acc[4 * g + 1] + b4[g][1], acc[4 * g + 2] + b4[g][2], acc[4 * g + 3] + b4[g][3]};
+      if constexpr (EPI == EPI_BIAS_RESIDUAL) {
+        *reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + col) = x4[g] + v;
+      } else if constexpr (EPI == EPI_BIAS_POS) {
+        *reinterpret_cast<f32x4*>(p.R + p.xrows.row(row) * p.ldr + col) = v + x4[g];
+      } else {
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16_t)apply_act_fast<EPI>(v[e]);
+        const long orow = p.row_map ? (long)p.row_map[row / p.block_tokens] * p.block_tokens + row % p.block_tokens : row;
+        *reinterpret_cast<bf16x4*>(p.C + orow * p.ldc + col) = o;
+      }
+    }
+  }
+}
+
 // behind the operand slabs: the tile's bias values, and for a folded pre-norm the column sums of its
 // weights and the mean / rstd of its rows
 template <int BN, int NT, int BM_ = BM>
@@ -1323,6 +1484,38 @@ int cu_count() {
       n = 256;
   }
   return n;
+}
+
+template <int EPI>
+hipError_t launch_small_e(const GemmParams& p, hipStream_t st) {
+  const int gm = (p.M + SM_T - 1) / SM_T, gn = p.Npad / SM_T;
+  if (gm * gn == 0) return hipSuccess;
+  k_gemm_bf16_small<EPI><<<dim3(gm * gn), dim3(256), SM_LDS, st>>>(p, gm, gn < 4 ? gn : 4);
+  ++g_kernel_launches;
+  return hipGetLastError();
+}
+// the small-tile form has neither the folded pre-norm nor the bf16 copy of the residual rows
+bool small_form_has(const GemmParams& p) { return !p.stats && !p.xb; }
+hipError_t launch_small(const GemmParams& p, hipStream_t st) {
+  switch (p.epi) {
+    case EPI_BIAS: return launch_small_e<EPI_BIAS>(p, st);
+    case EPI_BIAS_GELU_ERF: return launch_small_e<EPI_BIAS_GELU_ERF>(p, st);
+    case EPI_BIAS_GELU_TANH: return launch_small_e<EPI_BIAS_GELU_TANH>(p, st);
+    case EPI_BIAS_RESIDUAL: return launch_small_e<EPI_BIAS_RESIDUAL>(p, st);
+    case EPI_BIAS_POS: return launch_small_e<EPI_BIAS_POS>(p, st);
+    case EPI_VT: return launch_small_e<EPI_VT>(p, st);
+  }
+  return hipErrorInvalidValue;
+}
+template <int EPI>
+hipError_t set_attr_small() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_small<EPI>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM_LDS);
+}
+// EPD_SMALL_TILES=0: launches of a slice or two stay on the 128 x 128 tiles (what the small form was measured against)
+bool small_tiles() {
+  static const bool on = !(getenv("EPD_SMALL_TILES") && getenv("EPD_SMALL_TILES")[0] == '0');
+  return on;
 }
 
 // Activation slabs straight into LDS (no register hop): the persistent kernels (-5 % on the q/k, value and FC1
@@ -1477,6 +1670,12 @@ hipError_t bf16_gemm_init() {
   if ((e = set_attr_all<128, 512, 64>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64, 0, 128>()) != hipSuccess) return e;
   if ((e = set_attr_all<128, 512, 64, 2, 128>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS_GELU_ERF>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS_GELU_TANH>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS_POS>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_VT>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -1498,7 +1697,13 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 8: if (p.Npad % 256 == 0) return dispatch<256, 512, 64, 3>(p, st); break;
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
     case 10: if (p.Npad % 256 == 0 && p.epi == EPI_BIAS_RESIDUAL && !p.xb) return launch_persist_res(p, st); break;
+    case 11: if (small_form_has(p)) return launch_small(p, st); break;
   }
+  // One or two slices: 64 x 64 tiles while there are at most two of them per CU (measured against the
+  // 128 x 128 tiles on 1024 and 2048 rows: ahead up to 512 tiles, behind from 1024 on).  Same bits.
+  if (p.cfg == 0 && small_tiles() && small_form_has(p) &&
+      (long)((p.M + SM_T - 1) / SM_T) * (p.Npad / SM_T) <= 2L * cu_count())
+    return launch_small(p, st);
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
   // A width like 3200 leaves the last 256-wide tile column half used.  When that column is also what
   // spills the launch into a nearly empty last round (at most a quarter of the CUs busy), the residual

@@ -52,3 +52,33 @@ def resampler_policy_error(desc, w, tiles, only_qkp: bool = False) -> float:
         got = resampler_bf16_policy(x, w, desc, only_qkp)
         num, den = max(num, float(np.abs(got - ref).max())), max(den, float(np.abs(ref).max()))
     return num / den
+
+
+def encoder_policy_error(tile, w, desc, stream_bf16: bool) -> float:
+    """max |model - oracle| / max |oracle| for one slice, the layers taken with the bf16 mode's roundings (bf16
+    operands of every product: norm outputs, q, k, v, softmax weights, attention output, MLP activations; exact
+    arithmetic in between; embedding and projector exact).  stream_bf16: the residual stream is snapped to bf16
+    after every residual add as well, which is what a bf16 stream would store; False is the fp32 stream."""
+    keep = snap_bf16 if stream_bf16 else (lambda a: np.asarray(a, np.float64))
+    D, H = desc.hidden, desc.heads
+    hd = D // H
+    x = keep(O.embed_tile(tile, w, desc))
+    for l in range(desc.layers):
+        p = f"l{l}_"
+        u = snap_bf16(O._norm(x, w, p + "n1", desc.norm, desc.eps))
+        qkv = O.linear(u, w[p + "qkv_w"], w[p + "qkv_b"])
+        q, k, v = snap_bf16(qkv[:, :D]), snap_bf16(qkv[:, D:2 * D]), snap_bf16(qkv[:, 2 * D:])
+        o = np.empty_like(q)
+        for h in range(H):
+            sl = slice(h * hd, (h + 1) * hd)
+            logits = q[:, sl] @ k[:, sl].T / np.sqrt(float(hd))
+            e = snap_bf16(np.exp(logits - logits.max(axis=-1, keepdims=True)))
+            o[:, sl] = (e / e.sum(axis=-1, keepdims=True)) @ v[:, sl]
+        x = keep(x + O.linear(snap_bf16(o), w[p + "o_w"], w[p + "o_b"]))
+        u = snap_bf16(O._norm(x, w, p + "n2", desc.norm, desc.eps))
+        hmid = snap_bf16(O._act(O.linear(u, w[p + "fc1_w"], w[p + "fc1_b"]), desc.act))
+        x = keep(x + O.linear(hmid, w[p + "fc2_w"], w[p + "fc2_b"]))
+    if desc.final_norm:
+        x = O._norm(x, w, "fn", desc.norm, desc.eps)
+    got, ref = O.project(x, w, desc), O.encode_tile(tile, w, desc)
+    return float(np.abs(got - ref).max() / np.abs(ref).max())

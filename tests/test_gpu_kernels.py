@@ -212,7 +212,7 @@ def test_gemm_gelu_epilogues_vs_oracle(epi, abs_err):
 def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
     """The plain loop, the pipelined loop (weights straight into LDS, fragments one k-step ahead) and
     the persistent kernel order every sum the same way: identical bits, ragged M included; the
-    256x128 and 128x128 tiles too."""
+    256x128, 128x128 and 64x64 tiles too."""
     rng = np.random.default_rng(M + N + K + epi)
     A = B.to_device(_bf16_grid(rng, (M, K), 0.5), True)
     W = B.to_device(_bf16_grid(rng, (N, K), 0.05), True)
@@ -226,7 +226,7 @@ def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
         return out.view(torch.int16 if epi != 3 else torch.int32).cpu().numpy()
 
     ref = run(6)
-    forms = [0, 1, 2, 7, 8] + ([3] if K % 256 == 0 else []) + ([9] if epi != 3 else [10])
+    forms = [0, 1, 2, 7, 8, 11] + ([3] if K % 256 == 0 else []) + ([9] if epi != 3 else [10])
     for form in forms:
         assert np.array_equal(run(form), ref), form
     if epi == 0:   # and the value itself, against the oracle
