@@ -32,64 +32,71 @@ void f32_im2col(const float* tiles, float* A, int T, int S, int p, hipStream_t s
 }
 
 // ------------------------------------------------------------------ GEMM ----
-// C[M,N] = A[M,K] * W[N,K]^T, 64x64 block tile, 16-deep k slab, 4x4 per thread.
-template <int EPI>
+// C[M,N] = A[M,K] * W[N,K]^T, TS x TS block tile (64: 4x4 outputs per thread, 32: 2x2), 64-deep k slab, 256 threads.
+// The launches of this mode are small: with 64 x 64 tiles the tiny configuration has a dozen workgroups on 256
+// CUs and its time is one thread's chain of 16 K multiply-adds, so launches that would leave most CUs idle take
+// 32 x 32 tiles (a quarter of the chain, four times the workgroups).  A thread adds the k-steps of an element in
+// ascending order whatever the tile or slab shape: same bits.
+constexpr int F32_BK = 64;
+template <int EPI, int TS>
 __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, int lda,
                                                   const float* __restrict__ W,
                                                   const float* __restrict__ bias, float* C, int ldc,
                                                   const float* __restrict__ pos, int n_pos, int M,
                                                   int N, int K, const int* __restrict__ row_map,
                                                   int block_tokens, SliceRows xrows) {
-  __shared__ float sA[16][64 + 1];
-  __shared__ float sW[16][64 + 1];
+  constexpr int R = TS / 16;   // outputs per thread in each direction
+  __shared__ float sA[F32_BK][TS + 1];
+  __shared__ float sW[F32_BK][TS + 1];
   const int tid = threadIdx.x;
   const int tx = tid % 16, ty = tid / 16;
-  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
-  float acc[4][4] = {};
-  // the slab after the current one waits in registers (four elements of each operand per thread), so its memory
-  // latency passes under the current slab's arithmetic instead of in front of every slab
-  float ra[4], rw[4];
+  const int m0 = blockIdx.y * TS, n0 = blockIdx.x * TS;
+  float acc[R][R] = {};
+  // the slab after the current one waits in registers, so its memory latency passes under the current slab's
+  // arithmetic instead of in front of every slab
+  constexpr int PER_T = TS * F32_BK / 256;
+  float ra[PER_T], rw[PER_T];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < PER_T; ++u) {
       const int i = tid + 256 * u;
-      const int r = i / 16, kk = i % 16;
+      const int r = i / F32_BK, kk = i % F32_BK;
       const int gm = m0 + r, gn = n0 + r, gk = k0 + kk;
       ra[u] = (gm < M && gk < K) ? A[(long)gm * lda + gk] : 0.f;
       rw[u] = (gn < N && gk < K) ? W[(long)gn * K + gk] : 0.f;
     }
   };
   fetch(0);
-  for (int k0 = 0; k0 < K; k0 += 16) {
+  for (int k0 = 0; k0 < K; k0 += F32_BK) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < PER_T; ++u) {
       const int i = tid + 256 * u;
-      sA[i % 16][i / 16] = ra[u];
-      sW[i % 16][i / 16] = rw[u];
+      sA[i % F32_BK][i / F32_BK] = ra[u];
+      sW[i % F32_BK][i / F32_BK] = rw[u];
     }
     __syncthreads();
-    if (k0 + 16 < K) fetch(k0 + 16);
+    if (k0 + F32_BK < K) fetch(k0 + F32_BK);
+#pragma unroll 16
+    for (int kk = 0; kk < F32_BK; ++kk) {
+      float a[R], w[R];
 #pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-      float a[4], w[4];
+      for (int i = 0; i < R; ++i) a[i] = sA[kk][ty * R + i];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = sA[kk][ty * 4 + i];
+      for (int j = 0; j < R; ++j) w[j] = sW[kk][tx * R + j];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) w[j] = sW[kk][tx * 4 + j];
+      for (int i = 0; i < R; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+        for (int j = 0; j < R; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
     }
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int r = m0 + ty * 4 + i;
+  for (int i = 0; i < R; ++i) {
+    int r = m0 + ty * R + i;
     if (r >= M) continue;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int c = n0 + tx * 4 + j;
+    for (int j = 0; j < R; ++j) {
+      int c = n0 + tx * R + j;
       if (c >= N) continue;
       float v = acc[i][j] + (bias ? bias[c] : 0.f);
       // paged output: row r of the product lives in block row_map[r / block_tokens]
@@ -106,18 +113,37 @@ __global__ __launch_bounds__(256) void k_f32_gemm(const float* __restrict__ A, i
   }
 }
 
+static int f32_cu_count() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, v = 0;
+    n = (hipGetDevice(&dev) == hipSuccess &&
+         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+  }
+  return n;
+}
+
+template <int TS>
+static void f32_gemm_ts(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
+                        const float* pos, int n_pos, int M, int N, int K, hipStream_t st, const int* row_map,
+                        int block_tokens, SliceRows xrows) {
+  dim3 grid((N + TS - 1) / TS, (M + TS - 1) / TS), block(256);
+  switch (epi) {
+    case EPI_BIAS: k_f32_gemm<EPI_BIAS, TS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF, TS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH, TS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL, TS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+    default: k_f32_gemm<EPI_BIAS_POS, TS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
+  }
+}
+
 void f32_gemm(int epi, const float* A, int lda, const float* W, const float* bias, float* C, int ldc,
               const float* pos, int n_pos, int M, int N, int K, hipStream_t st, const int* row_map,
               int block_tokens, SliceRows xrows) {
   if (M == 0 || N == 0) return;
-  dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
-  switch (epi) {
-    case EPI_BIAS: k_f32_gemm<EPI_BIAS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
-    case EPI_BIAS_GELU_ERF: k_f32_gemm<EPI_BIAS_GELU_ERF><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
-    case EPI_BIAS_GELU_TANH: k_f32_gemm<EPI_BIAS_GELU_TANH><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
-    case EPI_BIAS_RESIDUAL: k_f32_gemm<EPI_BIAS_RESIDUAL><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
-    default: k_f32_gemm<EPI_BIAS_POS><<<grid, block, 0, st>>>(A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, row_map, block_tokens, xrows); break;
-  }
+  const long tiles64 = (long)((N + 63) / 64) * ((M + 63) / 64);
+  if (tiles64 * 2 <= f32_cu_count()) f32_gemm_ts<32>(epi, A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, st, row_map, block_tokens, xrows);
+  else f32_gemm_ts<64>(epi, A, lda, W, bias, C, ldc, pos, n_pos, M, N, K, st, row_map, block_tokens, xrows);
 }
 
 // ------------------------------------------------------------------ norm ----
