@@ -99,6 +99,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5", "c6", "c7", "c8"])
     ap.add_argument("--micro-batch", type=int, default=0, help="slices per micro-batch (0: workload default)")
+    ap.add_argument("--first-tiles", type=int, default=0,
+                    help="encode only the first N slices of the first request: one worker's share under "
+                         "intra-request parallelism (Section 3.2.2) as the timed step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mm-cache", action="store_true", help="skip the paged-cache encode / block-transfer leg")
     ap.add_argument("--cpu-tiles", type=int, default=0, help="slices the oracle encodes (0: bounded default)")
@@ -145,6 +148,13 @@ def main():
         desc = desc.replace(mx_fp8=1)
     bf16 = desc.dtype == wl.DT_BF16
     T = wk.n_tiles
+    n_requests = wk.n_requests
+    offsets = list(wk.tile_offsets)
+    sample_tiles = list(wk.oracle_sample_tiles)
+    if args.first_tiles > 0:
+        T = min(args.first_tiles, offsets[1] - offsets[0])
+        n_requests, offsets = 1, [0, T]
+        sample_tiles = [t for t in sample_tiles if t < T] or [0]
 
     t0 = time.time()
     weights_dev = []
@@ -157,7 +167,6 @@ def main():
     for t in range(T):
         tiles[t] = torch.from_numpy(wl.gen_tile(desc, wk.input_seed, t))
     out = enc.alloc_out(T)
-    offsets = list(wk.tile_offsets)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -255,7 +264,7 @@ def main():
         n_out = desc.tokens_per_tile
         b = 1
         while True:
-            groups = [(r, min(r + b, wk.n_requests)) for r in range(0, wk.n_requests, b)]
+            groups = [(r, min(r + b, n_requests)) for r in range(0, n_requests, b)]
             lat = []
             for rep in range(2):                                  # first pass warms
                 evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(groups) + 1)]
@@ -268,7 +277,7 @@ def main():
                 lat = [evs[i].elapsed_time(evs[i + 1]) for i in range(len(groups))]
             sweep.append({"max_batch_requests": b, "calls": len(groups), "mean_call_ms": round(sum(lat) / len(lat), 3),
                           "max_call_ms": round(max(lat), 3), "tiles_per_s": round(T / (sum(lat) * 1e-3), 1)})
-            if b >= wk.n_requests:
+            if b >= n_requests:
                 break
             b *= 2
 
@@ -315,7 +324,7 @@ def main():
         n_blocks = T * desc.tokens_per_tile // 16
         e_cache = B.MMCache(n_blocks, 16, desc.out_dim, bf16)
         p_cache = B.MMCache(n_blocks, 16, desc.out_dim, bf16)
-        tables = [e_cache.alloc((offsets[r + 1] - offsets[r]) * desc.tokens_per_tile) for r in range(wk.n_requests)]
+        tables = [e_cache.alloc((offsets[r + 1] - offsets[r]) * desc.tokens_per_tile) for r in range(n_requests)]
         p_tables = [p_cache.alloc(len(t) * 16) for t in tables]
         flat_e = [b for t in tables for b in t]
         flat_p = [b for t in p_tables for b in t][::-1]          # scattered destination order
@@ -402,7 +411,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import epd_oracle as O
         n_cpu = args.cpu_tiles or {"c1": 1, "c2": 2, "c3": 3, "c4": 1, "c5": 2, "c6": 2, "c7": 3, "c8": 2}[args.workload]
-        sample = list(wk.oracle_sample_tiles)[:n_cpu]
+        sample = sample_tiles[:n_cpu]
         w_host = wl.gen_weights(desc, wk.weight_seed)
         host_tiles = [wl.gen_tile(desc, wk.input_seed, t) for t in sample]
         c0 = time.perf_counter()
@@ -428,7 +437,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("mxfp8 (q/k/v, out-proj, FC1, FC2 operands) + bf16" if args.mx_fp8 else "bf16") if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": wk.name, "tiles": T, "requests": wk.n_requests,
+        "config": {"workload": wk.name + (f", first {T} slices of the first request" if args.first_tiles > 0 else ""),
+                   "tiles": T, "requests": n_requests,
                    "tokens_per_tile": desc.tokens_per_tile, "out_dim": desc.out_dim,
                    "micro_batch_tiles": desc.max_tiles_per_call},
         "vision_tokens_per_sec": round(tokens_per_s, 1),

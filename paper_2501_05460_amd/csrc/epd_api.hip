@@ -479,11 +479,13 @@ epd_status build_ctx(epd_ctx* c, const epd_weights* w, hipStream_t st) {
       // projection (stored transposed by its epilogue) are two products over the same input
       {
         const int qk_cols = 2 * c->Dq, qk_pad = pad_n(qk_cols), v_pad = pad_n(c->Dq);
-        bf16_t* Wqk = (bf16_t*)dalloc(c, (size_t)qk_pad * c->D_k * sizeof(bf16_t), true, st);
-        float* bqk = (float*)dalloc(c, (size_t)qk_pad * sizeof(float), true, st);
-        bf16_t* Wv = (bf16_t*)dalloc(c, (size_t)v_pad * c->D_k * sizeof(bf16_t), true, st);
-        float* bv = (float*)dalloc(c, (size_t)v_pad * sizeof(float), true, st);
-        NOMEM_IF(!Wqk || !bqk || !Wv || !bv);
+        // one block each for the two weight matrices and the two bias vectors, the value projection's behind the
+        // q/k projection's: a single slice runs both products as one launch (GemmParams::n2)
+        bf16_t* Wqk = (bf16_t*)dalloc(c, (size_t)(qk_pad + v_pad) * c->D_k * sizeof(bf16_t), true, st);
+        float* bqk = (float*)dalloc(c, (size_t)(qk_pad + v_pad) * sizeof(float), true, st);
+        NOMEM_IF(!Wqk || !bqk);
+        bf16_t* Wv = Wqk + (size_t)qk_pad * c->D_k;
+        float* bv = bqk + qk_pad;
         pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w], 2 * x.D, x.D, Wqk, qk_cols, c->D_k, heads, id, st);
         pack_matrix_bf16((const bf16_t*)w->tensors[li.qkv_w] + 2L * x.D * x.D, x.D, x.D, Wv, c->Dq, c->D_k, heads, id, st);
         pack_vector_f32(w->tensors[li.qkv_b], 1, 2 * x.D, bqk, qk_cols, heads, st);
@@ -887,12 +889,18 @@ epd_status run_bf16(epd_ctx* c, const float* tiles, int T, bf16_t* out, hipStrea
         HIP_TRY(c, mx_gemm(pv, st)); }
     } else {
     norm_kernel(w.n1_g, w.n1_b, !copy || l == 0);   // the first layer's rows come from the embedding
+    bool paired = false;
     { ProfScope ps(c, 2, st);
       GemmParams p = gp(EPI_BIAS, Xn, c->D_k, w.qkv, M);
       p.C = QK; p.ldc = ld_qk;
       with_norm(p, w.qkv_cs);
-      HIP_TRY(c, bf16_gemm(p, st)); }
-    { ProfScope ps(c, 2, st);
+      // a slice alone: the value projection rides in the same launch (its weights follow the q/k projection's)
+      GemmParams pp = p;
+      pp.n2 = w.v.N; pp.n2_pad = w.v.Npad; pp.VT = VT; pp.hd_pad = c->hd_pad; pp.heads = x.H; pp.n_tok = x.Ns;
+      paired = (const bf16_t*)w.v.W == (const bf16_t*)w.qkv.W + (size_t)w.qkv.Npad * w.qkv.K && w.v.b == w.qkv.b + w.qkv.Npad &&
+               bf16_gemm_pair_fits(pp);
+      HIP_TRY(c, bf16_gemm(paired ? pp : p, st)); }
+    if (!paired) { ProfScope ps(c, 2, st);
       GemmParams pv = gp(EPI_VT, Xn, c->D_k, w.v, M);
       pv.VT = VT; pv.hd_pad = c->hd_pad; pv.heads = x.H; pv.n_tok = x.Ns;
       with_norm(pv, w.v_cs);

@@ -1296,8 +1296,11 @@ constexpr int SM_T = 64, SM_RING = 4;
 constexpr int SM_STAGE = 2 * SM_T * BK;   // bf16 elements of a ring stage: activation slab, then weight slab
 constexpr size_t SM_LDS = (size_t)SM_RING * SM_STAGE * sizeof(bf16_t);
 
-template <int EPI>
+// DUAL (EPI_BIAS): tile columns from Npad on are a second product over the same activations, the value projection,
+// whose tiles run with the operand roles of EPI_VT and leave through its store (GemmParams::n2).
+template <int EPI, bool DUAL = false>
 __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, const int gm, const int bw_) {
+  static_assert(!DUAL || EPI == EPI_BIAS, "the second product rides on the plain bias epilogue");
   constexpr bool tok_major = (EPI == EPI_VT);
   constexpr int LPS = 4;   // direct loads per thread and slab: two 32-row halves of each operand
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1305,7 +1308,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, 
 
   // XCD x (workgroups are dealt round-robin) takes a contiguous run of the tile sequence; the sequence walks
   // bands of bw_ tile columns top to bottom, so the ~32 tiles an XCD holds at once share few operand panels
-  const int gn = p.Npad / SM_T;
+  const int gn = (p.Npad + (DUAL ? p.n2_pad : 0)) / SM_T;
   int id = blockIdx.x;
   {
     const int nb = gridDim.x, x = id & 7, slot = id >> 3, q = nb >> 3, r = nb & 7;
@@ -1316,6 +1319,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, 
   if (band >= full_bands) { band = full_bands; in_band = id - full_bands * band_tiles; bw = gn - full_bands * bw_; }
   const int m0 = (in_band / bw) * SM_T;
   const int n0 = (band * bw_ + in_band % bw) * SM_T;
+  const bool vt_tile = tok_major || (DUAL && n0 >= p.Npad);   // uniform over the workgroup
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -1362,7 +1366,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, 
   const int col0 = n0 + wn * 32 + 4 * lh;             // first feature of register group 0 (not EPI_VT)
   f32x4 b4[4], x4[4];
   float b1 = 0.f;
-  if constexpr (tok_major) {
+  if (vt_tile) {
     b1 = p.bias[n0 + wn * 32 + l32];
   } else {
 #pragma unroll
@@ -1382,6 +1386,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, 
 #pragma unroll
   for (int e = 0; e < 16; ++e) acc[e] = 0.f;
   const int frag_sw = SWZ(l32);
+  auto main_loop = [&](auto tm) {
+  constexpr bool TOKM = decltype(tm)::value;
   for (int kt = 0; kt < KT_; ++kt) {
     // Loads complete in order: slab kt has landed once at most LPS x (slabs issued behind it) of this
     // thread's loads are outstanding.  (The epilogue's own loads above are older than every slab but the
@@ -1403,12 +1409,15 @@ __global__ __launch_bounds__(256, 2) void k_gemm_bf16_small(const GemmParams p, 
     }
     __builtin_amdgcn_sched_barrier(0);   // all fragment reads of the slab first: their latency is paid once
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) acc = tok_major ? mfma32(xf[kk], wf[kk], acc) : mfma32(wf[kk], xf[kk], acc);
+    for (int kk = 0; kk < BK / 16; ++kk) acc = TOKM ? mfma32(xf[kk], wf[kk], acc) : mfma32(wf[kk], xf[kk], acc);
   }
+  };
+  if (DUAL && vt_tile) main_loop(std::true_type{});
+  else main_loop(std::integral_constant<bool, tok_major>{});
 
-  if constexpr (tok_major) {
-    const int f = n0 + wn * 32 + l32;
-    if (f < p.N) {
+  if (vt_tile) {
+    const int f = n0 - (DUAL ? p.Npad : 0) + wn * 32 + l32;   // feature of the value projection
+    if (f < (DUAL ? p.n2 : p.N)) {
       const int h = f / p.hd_pad, d = f % p.hd_pad;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -1486,17 +1495,18 @@ int cu_count() {
   return n;
 }
 
-template <int EPI>
+template <int EPI, bool DUAL = false>
 hipError_t launch_small_e(const GemmParams& p, hipStream_t st) {
-  const int gm = (p.M + SM_T - 1) / SM_T, gn = p.Npad / SM_T;
+  const int gm = (p.M + SM_T - 1) / SM_T, gn = (p.Npad + (DUAL ? p.n2_pad : 0)) / SM_T;
   if (gm * gn == 0) return hipSuccess;
-  k_gemm_bf16_small<EPI><<<dim3(gm * gn), dim3(256), SM_LDS, st>>>(p, gm, gn < 4 ? gn : 4);
+  k_gemm_bf16_small<EPI, DUAL><<<dim3(gm * gn), dim3(256), SM_LDS, st>>>(p, gm, gn < 4 ? gn : 4);
   ++g_kernel_launches;
   return hipGetLastError();
 }
 // the small-tile form has neither the folded pre-norm nor the bf16 copy of the residual rows
 bool small_form_has(const GemmParams& p) { return !p.stats && !p.xb; }
 hipError_t launch_small(const GemmParams& p, hipStream_t st) {
+  if (p.n2_pad > 0) return p.epi == EPI_BIAS ? launch_small_e<EPI_BIAS, true>(p, st) : hipErrorInvalidValue;
   switch (p.epi) {
     case EPI_BIAS: return launch_small_e<EPI_BIAS>(p, st);
     case EPI_BIAS_GELU_ERF: return launch_small_e<EPI_BIAS_GELU_ERF>(p, st);
@@ -1507,9 +1517,9 @@ hipError_t launch_small(const GemmParams& p, hipStream_t st) {
   }
   return hipErrorInvalidValue;
 }
-template <int EPI>
+template <int EPI, bool DUAL = false>
 hipError_t set_attr_small() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_small<EPI>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_small<EPI, DUAL>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)SM_LDS);
 }
 // EPD_SMALL_TILES=0: launches of a slice or two stay on the 128 x 128 tiles (what the small form was measured against)
@@ -1652,6 +1662,13 @@ hipError_t set_attr_all() {
 
 long bf16_gemm_kernel_launches() { return g_kernel_launches; }
 
+// The q/k and the value projection of a single slice as one launch of small tiles: three tiles per CU on the
+// 300M shape, where two launches of two and one were measured 5 us slower per layer.
+bool bf16_gemm_pair_fits(const GemmParams& p) {
+  return p.cfg == 0 && p.epi == EPI_BIAS && p.n2_pad > 0 && p.n2_pad % SM_T == 0 && small_tiles() && small_form_has(p) &&
+         (long)((p.M + SM_T - 1) / SM_T) * ((p.Npad + p.n2_pad) / SM_T) * 2 <= 7L * cu_count();
+}
+
 hipError_t bf16_gemm_init() {
   hipError_t e = set_attr_all<256, 512, 64>();
   if (e != hipSuccess) return e;
@@ -1676,6 +1693,7 @@ hipError_t bf16_gemm_init() {
   if ((e = set_attr_small<EPI_BIAS_RESIDUAL>()) != hipSuccess) return e;
   if ((e = set_attr_small<EPI_BIAS_POS>()) != hipSuccess) return e;
   if ((e = set_attr_small<EPI_VT>()) != hipSuccess) return e;
+  if ((e = set_attr_small<EPI_BIAS, true>()) != hipSuccess) return e;
   return hipSuccess;
 }
 
@@ -1688,6 +1706,7 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     return hipErrorInvalidValue;
   const bool f32_out = p.epi == EPI_BIAS_RESIDUAL || p.epi == EPI_BIAS_POS;
   if (!f32_out && p.epi != EPI_VT && (p.N % 8 != 0 || p.ldc % 8 != 0)) return hipErrorInvalidValue;
+  if (p.n2_pad > 0) return bf16_gemm_pair_fits(p) ? launch_small(p, st) : hipErrorInvalidValue;
   switch (p.cfg) {
     case 1: return dispatch<128, 512, 64>(p, st);
     case 2: return dispatch<128, 512, 64, 0, 128>(p, st);

@@ -67,8 +67,15 @@ struct GemmParams {
   // their statistics pairs to stats_out [M][n_part_out][2] (pair index = column / 128).
   bf16_t* xb; long ldxb;
   float* stats_out; int n_part_out;
+  // A second product over the same A in the same launch (epi EPI_BIAS, small launches only: bf16_gemm_pair_fits):
+  // the value projection next to the q/k projection.  Its packed weights and bias follow the first product's
+  // directly (rows Npad .. Npad + n2_pad of W, entries Npad .. of bias); its n2 columns leave through the
+  // EPI_VT store (VT, hd_pad, heads, n_tok).  n2_pad == 0: off.
+  int n2, n2_pad;
 };
 hipError_t bf16_gemm(const GemmParams& p, hipStream_t st);
+// true: bf16_gemm runs p with its second product (n2_pad > 0) as one launch; false: the caller issues two products
+bool bf16_gemm_pair_fits(const GemmParams& p);
 long bf16_gemm_kernel_launches();   // kernels launched by bf16_gemm on the calling host thread so far (a figure for the profiling hooks)
 hipError_t bf16_gemm_init();  // raises the dynamic-LDS limit of the kernels (idempotent: safe from any thread, any number of times)
 

@@ -151,7 +151,7 @@ def test_profile_brackets_count_kernels_and_leave_the_result_alone():
     L = desc.layers
     for name in ("gemm_qkv", "gemm_out", "gemm_fc1", "gemm_fc2"):
         assert fam[name]["ms"] > 0.0, name
-        assert fam[name]["launches"] >= (2 * L if name == "gemm_qkv" else L), (name, fam[name])   # q/k and v are two products
+        assert fam[name]["launches"] >= L, (name, fam[name])   # q/k and v: two products, one launch for a small batch
         assert fam[name]["launches"] <= 4 * L, (name, fam[name])
     # two pre-norm kernels per layer (one statistics pass instead when EPD_NORM_MODE=fold folds them into the products)
     assert fam["norm"]["launches"] in (2 * L, 1) and fam["attention"]["launches"] == L
