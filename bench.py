@@ -112,6 +112,8 @@ def main():
                     help="also encode the first 1, 2, 4, ... slices of the first request alone (what one encode "
                          "worker sees when a request's slices are cut over several workers) and report the "
                          "latency of each share next to that of the whole request")
+    ap.add_argument("--no-shard-sweep", action="store_true",
+                    help="skip the brief per-worker-share sweep a default run takes (profiling runs of the headline step)")
     ap.add_argument("--roof", action="store_true",
                     help="measure this box's ceilings instead of the workload (MFMA loop, streaming copy, vendor "
                          "BLAS and this library on the per-layer shapes) and print them as one JSON line")
@@ -283,10 +285,14 @@ def main():
 
     # ---- intra-request parallelism: one worker's share of the first request ----
     shard = None
-    if args.shard_sweep:
+    # (always taken in brief — the shares of 2, 3, 4 and n workers — since a default run is what gets recorded;
+    # --shard-sweep adds the other sizes)
+    if args.shard_sweep or (not args.no_shard_sweep and not args.mx_fp8 and bf16 and args.first_tiles == 0 and offsets[1] - offsets[0] > 1 and T <= 256):
         n_req = offsets[1] - offsets[0]
         n_out = desc.tokens_per_tile
-        sizes = sorted({n for n in (1, 2, 4, 8, 16, 32) if n < n_req} | {-(-n_req // w) for w in (2, 3, 4)} | {n_req})
+        sizes = sorted({-(-n_req // w) for w in (2, 3, 4)} | {1, n_req})
+        if args.shard_sweep:
+            sizes = sorted(set(sizes) | {n for n in (1, 2, 4, 8, 16, 32) if n < n_req})
         lat, wall = {}, {}
         for n in sizes:
             for _ in range(3):
@@ -314,7 +320,7 @@ def main():
                  "wall_ms_single_call_by_tiles": {str(n): round(v, 3) for n, v in wall.items()},
                  "wall_over_gpu": {str(n): round(wall[n] / lat[n], 3) for n in sizes},
                  # a request cut over w workers takes as long as its largest share
-                 "speedup_by_workers": {str(w): round(lat[n_req] / lat[-(-n_req // w)], 2) for w in (2, 3, 4)}}
+                 "speedup_by_workers": {str(w): round(lat[n_req] / lat[-(-n_req // w)], 2) for w in (2, 3, 4, n_req)}}
         enc.encode(tiles, offsets, out)    # the whole batch again: the parity sample below reads `out`
         torch.cuda.synchronize()
 
