@@ -160,14 +160,24 @@ def main():
 
     t0 = time.time()
     weights_dev = []
-    for i in range(len(wl.weight_specs(desc))):
+    last_note = time.time()
+
+    def note(what):   # a line on stderr every ~20 s of host-side setup (the 6B shape draws 5.6 G weights on the host)
+        nonlocal last_note
+        if time.time() - last_note > 20.0:
+            print(f"bench.py: setup, {what}", file=sys.stderr, flush=True)
+            last_note = time.time()
+    n_w = len(wl.weight_specs(desc))
+    for i in range(n_w):
         weights_dev.append(B.to_device(wl.gen_weight(desc, wk.weight_seed, i), bf16))
+        note(f"weight tensor {i + 1} of {n_w}")
     enc = B.Encoder(desc, weights_dev)
     del weights_dev
     S = desc.tile_size
     tiles = torch.empty((T, 3, S, S), dtype=torch.float32, device="cuda")
     for t in range(T):
         tiles[t] = torch.from_numpy(wl.gen_tile(desc, wk.input_seed, t))
+        note(f"slice {t + 1} of {T}")
     out = enc.alloc_out(T)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
