@@ -19,7 +19,10 @@
  * enqueued on the caller's HIP stream and the call returns after enqueueing.
  * A context serves one stream at a time (calls on one context must not
  * overlap); different contexts may be driven from different host threads.
- * epd_encode / epd_encode_range allocate nothing.  If a HIP call fails in the
+ * epd_encode / epd_encode_range allocate nothing, copy nothing from the host and
+ * clear no memory through the runtime: once a context has run one call eagerly
+ * (kernel attributes are set by then) a call may be recorded into a HIP graph and
+ * replayed; a replay writes the bits of the eager call.  If a HIP call fails in the
  * middle of a call (EPD_ERR_HIP: a launch or copy refused by the runtime),
  * earlier launches of that call may already have written part of the output:
  * its contents are then undefined.  Every other error is found before the
