@@ -36,6 +36,8 @@
 // the common step computes no maximum at all: a step whose weights sum to
 // more than 2^RESCALE_LOG2 (or overflow) is what triggers the maximum, the
 // move of the reference and a second round of exponentials.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace epd {
@@ -73,8 +75,10 @@ struct AttnSmem {
 // MFMA -> exp -> MFMA dependency chain better than fragment reuse saves LDS reads).
 // MASK: the slices carry rows past n_keys (compiled apart: the unmasked kernel keeps its registers and
 // its step free of the key-index compare).
-template <int HD, int QT, bool MASK>
-__global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const bf16_t* __restrict__ q,
+// W4: four workgroups per CU (head dim 64).  The S^T registers and the weights of one step only, no step
+// issued ahead: 121 registers, and the fourth wave of a SIMD covers what the look-ahead covered.
+template <int HD, int QT, bool MASK, bool W4 = false>
+__global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
                                                         const bf16_t* __restrict__ vt,
                                                         bf16_t* __restrict__ o, int n_tok, int n_keys, int n_q,
@@ -346,6 +350,25 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   // Software pipeline over the 32-key steps: the S^T MFMAs of the next step
   // are in flight while the VALU does the softmax of the current one.  s0 of a
   // block is issued right after the barrier that published the block.
+  if constexpr (W4) {
+    f32x16 s0[QT];
+    bf16x8 p0[QT][2];
+    for (int kb = 0; kb < NB; ++kb) {
+      gload(kb + 1 < NB ? kb + 1 : kb);
+      const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
+      const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
+      if (any_act) {
+        issue_s(s0, ks, 0);
+        softmax(s0, p0, kb * BKEY, kb == 0);
+        issue_s(s0, ks, 1);          // the weights of step 0 are out of the S^T registers: step 1's product starts
+        issue_pv(p0, vs, 0);         // under the second product of step 0
+        softmax(s0, p0, kb * BKEY + 32, false);
+        issue_pv(p0, vs, 1);
+      }
+      sstore((kb + 1) & 1, kb + 1 < NB ? kb + 1 : kb);
+      __syncthreads();
+    }
+  } else {
   f32x16 s0[QT], s1[QT];
   bf16x8 p0[QT][2], p1[QT][2];
   if (any_act) issue_s(s0, sK, 0);
@@ -365,6 +388,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
     if (any_act && kb + 1 < NB) issue_s(s0, sK + ((kb + 1) & 1) * SM::K_ELEMS, 0);
   }
 
+  }
 #pragma unroll
   for (int u = 0; u < QT; ++u) {
     if (!act[u] || q0 + u * 32 + l32 >= n_q) continue;   // a shared query set need not fill its last 32 rows
@@ -412,12 +436,12 @@ __global__ __launch_bounds__(256, HD == 64 ? 3 : 2) void k_attention_bf16(const 
   }
 }
 
-template <int HD, int QT, bool MASK>
+template <int HD, int QT, bool MASK, bool W4 = false>
 hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                          int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
                          unsigned char* oq, unsigned* so, long ld_so, hipStream_t st) {
   // once per instantiation; the initialisation of a function-local static is safe against concurrent callers
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention_bf16<HD, QT, MASK, W4>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      (int)AttnSmem<HD>::BYTES);
   if (attr != hipSuccess) return attr;
@@ -425,7 +449,7 @@ hipError_t launch_attn_m(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf1
   const int n_qb = (n_q + BQ - 1) / BQ, n_pairs = n_slices * heads;
   const long n_wg = (long)((n_pairs + 7) / 8) * 8 * n_qb;
   if (n_wg > 0x7fffffffL) return hipErrorInvalidValue;
-  k_attention_bf16<HD, QT, MASK><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
+  k_attention_bf16<HD, QT, MASK, W4><<<dim3((unsigned)n_wg), dim3(256), AttnSmem<HD>::BYTES, st>>>(
       q, k, vt, o, n_tok, n_keys, n_q, q_shared, heads, n_pairs, ld_qk, ld_o, oq, so, ld_so);
   return hipGetLastError();
 }
@@ -434,6 +458,13 @@ template <int HD, int QT>
 hipError_t launch_attn(const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* o, int n_slices,
                        int n_tok, int n_keys, int n_q, int q_shared, int heads, long ld_qk, long ld_o,
                        unsigned char* oq, unsigned* so, long ld_so, hipStream_t st) {
+  // head dim 64: the four-workgroup form (EPD_ATTN_W4=0: the three-workgroup form with a step issued ahead, which it
+  // was measured against: 660 -> 638 us on 104 slices of 1024 tokens, 16 heads; same bits)
+  static const bool w4 = !(getenv("EPD_ATTN_W4") && getenv("EPD_ATTN_W4")[0] == '0');
+  if (HD == 64 && w4)
+    return (n_keys < n_tok || n_tok % BKEY != 0)
+               ? launch_attn_m<HD, QT, true, HD == 64>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st)
+               : launch_attn_m<HD, QT, false, HD == 64>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
   return (n_keys < n_tok || n_tok % BKEY != 0)
              ? launch_attn_m<HD, QT, true>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st)
              : launch_attn_m<HD, QT, false>(q, k, vt, o, n_slices, n_tok, n_keys, n_q, q_shared, heads, ld_qk, ld_o, oq, so, ld_so, st);
