@@ -143,3 +143,16 @@ def test_host_side_under_address_and_undefined_behaviour_sanitizers():
                        env=bld.sanitized_env(), capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-3000:]
     assert "passed" in r.stdout and "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; `bench.py --gpus N` with N > 1 (or a WORLD_SIZE above 1) says so and exits with a
+    status of its own before anything touches a device."""
+    import subprocess
+    import sys
+    bench = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, bench], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 2 and "one GPU" in r.stderr
