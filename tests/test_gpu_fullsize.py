@@ -254,4 +254,15 @@ def test_full_size_runs_repeat_bit_for_bit(name, reps):
         torch.cuda.synchronize()
         differing += int(not torch.equal(out.view(torch.int16), ref.view(torch.int16)))
     assert differing == 0, f"{differing} of {reps} runs differ from the first"
+    # One worker's share of the first request, alone: other kernels altogether (64 x 64 tiles fed through an LDS ring,
+    # both projections of the input in one launch), whose hand-over rests on counted waits.  Every repeat carries the
+    # bits the same slices have inside the whole batch.
+    n = enc.tokens_per_tile
+    for k in (1, 2, 3):
+        differing = 0
+        for _ in range(60):
+            out = enc.encode(tiles[:k], [0, k])
+            torch.cuda.synchronize()
+            differing += int(not torch.equal(out.view(torch.int16), ref[:k * n].view(torch.int16)))
+        assert differing == 0, f"{k} slices alone: {differing} of 60 runs differ from their rows of the whole batch"
     enc.close()
