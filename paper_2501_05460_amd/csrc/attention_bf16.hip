@@ -94,6 +94,12 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
   constexpr int K_LOADS = (K_TOTAL + 255) / 256;
   constexpr int V_LOADS = (V_TOTAL + 255) / 256;
   constexpr bool K_EXACT = K_TOTAL % 256 == 0, V_EXACT = V_TOTAL % 256 == 0;
+  // KDMA (four-workgroup form at head dim 64): key blocks go from global memory straight into LDS (no staging
+  // registers, no LDS stores by the waves).  A key row is then exactly 128 bytes, rows unpadded, the 16-byte chunks of
+  // a row XOR-swizzled by (row >> 1) & 7 like the GEMM's operand slabs (the hardware puts lane l's 16 bytes at a
+  // wave-uniform base + 16 l, so the swizzle is applied on the global side).
+  constexpr bool KDMA = W4 && HD == 64;
+  constexpr int K_ROW = KDMA ? 64 : SM::K_LD;   // bf16 elements per key row in LDS
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* sK = reinterpret_cast<bf16_t*>(smem);       // [2][BKEY][K_LD]
@@ -140,7 +146,7 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
 
   // A thread's chunks keep their place inside every key block: 32-bit byte offsets once, the
   // block's base stays in scalar registers.
-  u32x4 rk[K_LOADS], rv[V_LOADS];
+  u32x4 rk[KDMA ? 1 : K_LOADS], rv[V_LOADS];
   unsigned koff[K_LOADS], voff[V_LOADS];
 #pragma unroll
   for (int i = 0; i < K_LOADS; ++i) {
@@ -157,19 +163,42 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
   auto gload = [&](int kb) {
     const char* kblk = reinterpret_cast<const char*>(kbase + (long)kb * BKEY * ld_qk);
     const char* vblk = reinterpret_cast<const char*>(vbase + (long)kb * BKEY);
+    if constexpr (!KDMA) {
 #pragma unroll
-    for (int i = 0; i < K_LOADS; ++i) rk[i] = *reinterpret_cast<const u32x4*>(kblk + koff[i]);
+      for (int i = 0; i < K_LOADS; ++i) rk[i] = *reinterpret_cast<const u32x4*>(kblk + koff[i]);
+    }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) rv[i] = *reinterpret_cast<const u32x4*>(vblk + voff[i]);
   };
+  // key block kb -> LDS buffer buf, two instructions of 32 rows each; lane = (row within 8, physical chunk)
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int kd_row = wave * 8 + (lane >> 3);
+  const unsigned kd_voff = (unsigned)((kd_row * ld_qk + (((lane & 7) ^ ((kd_row >> 1) & 7)) * 8)) * 2);
+  auto kdma = [&](int buf, int kb) {
+    if constexpr (KDMA) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bf16_t* g = kbase + ((long)kb * BKEY + 32 * i) * ld_qk;   // uniform
+        bf16_t* l = sK + buf * SM::K_ELEMS + (32 * i + wave_u * 8) * K_ROW;
+        const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) void*)l;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(kd_voff), "s"(g), "s"(lds_addr) : "memory", "m0");
+      }
+    }
+  };
+  auto kdma_wait = [&]() {
+    if constexpr (KDMA) __builtin_amdgcn_s_waitcnt(0 | (0x7 << 4) | (0xf << 8));   // vmcnt(0): this thread's part has landed
+  };
   // kb: the key block the staged registers hold
   auto sstore = [&](int buf, int kb) {
+    if constexpr (!KDMA) {
 #pragma unroll
-    for (int i = 0; i < K_LOADS; ++i) {
-      const int c = tid + 256 * i;
-      if (!K_EXACT && c >= K_TOTAL) continue;
-      const int row = c / KCH, ch = c % KCH;
-      *reinterpret_cast<u32x4*>(sK + buf * SM::K_ELEMS + row * SM::K_LD + ch * 8) = rk[i];
+      for (int i = 0; i < K_LOADS; ++i) {
+        const int c = tid + 256 * i;
+        if (!K_EXACT && c >= K_TOTAL) continue;
+        const int row = c / KCH, ch = c % KCH;
+        *reinterpret_cast<u32x4*>(sK + buf * SM::K_ELEMS + row * SM::K_LD + ch * 8) = rk[i];
+      }
     }
 #pragma unroll
     for (int i = 0; i < V_LOADS; ++i) {
@@ -221,6 +250,20 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
     for (int u = 0; u < QT; ++u)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[u][e] = 0.f;
+    if constexpr (KDMA) {
+      // all fragments of the step first, then the products: the LDS latency is paid once per step (the registers
+      // the staged key block has left make room for the second pair)
+      bf16x8 kf[KS];
+#pragma unroll
+      for (int st = 0; st < KS; ++st)
+        kf[st] = *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * K_ROW + (((2 * st + lh) ^ ((l32 >> 1) & 7)) * 8));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int st = 0; st < KS; ++st)
+#pragma unroll
+        for (int u = 0; u < QT; ++u) s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qf[u][st], s[u], 0, 0, 0);
+      return;
+    }
 #pragma unroll
     for (int st = 0; st < KS; ++st) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + (kt * 32 + l32) * SM::K_LD + st * 16 + lh * 8);
@@ -344,7 +387,9 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
       sV[(e / PAD_ELEMS) * SM::V_ELEMS + HD * SM::V_LD + e % PAD_ELEMS] =
           (bf16_t)(e % PAD_ELEMS < SM::V_LD ? 1.0f : 0.f);   // row HD: ones (sums the weights), the rest zero
   }
+  kdma(0, 0);
   sstore(0, 0);
+  kdma_wait();
   __syncthreads();
 
   // Software pipeline over the 32-key steps: the S^T MFMAs of the next step
@@ -354,6 +399,7 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
     f32x16 s0[QT];
     bf16x8 p0[QT][2];
     for (int kb = 0; kb < NB; ++kb) {
+      kdma((kb + 1) & 1, kb + 1 < NB ? kb + 1 : kb);   // the other buffer: nobody reads it after the previous barrier
       gload(kb + 1 < NB ? kb + 1 : kb);
       const bf16_t* ks = sK + (kb & 1) * SM::K_ELEMS;
       const bf16_t* vs = sV + (kb & 1) * SM::V_ELEMS;
@@ -366,6 +412,7 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
         issue_pv(p0, vs, 1);
       }
       sstore((kb + 1) & 1, kb + 1 < NB ? kb + 1 : kb);
+      kdma_wait();
       __syncthreads();
     }
   } else {
