@@ -70,13 +70,15 @@ struct AttnSmem {
   static constexpr size_t BYTES = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
 };
 
-// Registers: head dim 64 with one sub-tile per wave fits 168 registers, i.e. three workgroups per
-// CU; measured faster than two sub-tiles per wave at two workgroups (more waves hide the
-// MFMA -> exp -> MFMA dependency chain better than fragment reuse saves LDS reads).
+// Registers: with the S^T product of step i + 1 issued ahead of the softmax of step i (two sets of S^T and
+// weight registers) head dim 64 takes 140 registers, three workgroups per CU, head dims 72 / 96 three or two,
+// 128 two; more waves hide the MFMA -> exp -> MFMA dependency chain better than fragment reuse saves LDS
+// reads (two sub-tiles per wave at two workgroups per CU measured slower).
 // MASK: the slices carry rows past n_keys (compiled apart: the unmasked kernel keeps its registers and
 // its step free of the key-index compare).
-// W4: four workgroups per CU (head dim 64).  The S^T registers and the weights of one step only, no step
-// issued ahead: 121 registers, and the fourth wave of a SIMD covers what the look-ahead covered.
+// W4: four workgroups per CU (head dim 64, where 128 registers and 37 KiB of LDS per workgroup allow it).  One
+// step's S^T registers and weights only, no step issued ahead: 118 registers, and the fourth wave of a SIMD
+// covers what the look-ahead covered (-10 % on 104 slices of 1024 tokens, same bits).
 template <int HD, int QT, bool MASK, bool W4 = false>
 __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_bf16(const bf16_t* __restrict__ q,
                                                         const bf16_t* __restrict__ k,
