@@ -48,6 +48,13 @@ def roof_report(B, torch):
     out = {"mfma_loop_tflops_random_operands": round(B.op_mfma_peak(True), 1),
            "mfma_loop_tflops_constant_operands": round(B.op_mfma_peak(False), 1),
            "copy_GBps_read_plus_write_1GiB": round(B.op_copy_peak(), 1), "gemm": []}
+    # issue port of a SIMD: a wave of MFMAs and a wave of exp + fma pairs, each alone and both together (three rounds)
+    co = []
+    for _ in range(3):
+        m, v, both = B.op_coissue(1), B.op_coissue(2), B.op_coissue(3)
+        co.append({"mfma_wave_alone_ms": round(m, 3), "valu_wave_alone_ms": round(v, 3), "both_ms": round(both, 3),
+                   "valu_plus_0.53_mfma_ms": round(v + 0.53 * m, 3)})
+    out["mfma_valu_coissue"] = co
     g = torch.Generator(device="cuda").manual_seed(2)
     for name, (M, N, K) in (("qk", (106496, 2048, 1024)), ("out_proj", (106496, 1024, 1024)),
                             ("fc1", (106496, 4096, 1024)), ("fc2", (106496, 1024, 4096)), ("cube", (8192, 8192, 8192))):

@@ -125,10 +125,18 @@ epd_status epd_profile_read(epd_ctx* ctx, float* ms /*host [10]*/, int32_t* laun
  * bf16 the fragments are loaded from (random values: the operand buses toggle as in a real product), or
  * null for constant ones (the chip clocks higher on those).  sink: dev, 4 bytes per launched thread
  * (2 * CUs * 256 floats), keeps the loop alive.
- * epd_op_copy_peak: dst = src, `bytes` (multiple of 16) in 16-byte pieces; *gbps = read + write rate. */
+ * epd_op_copy_peak: dst = src, `bytes` (multiple of 16) in 16-byte pieces; *gbps = read + write rate.
+ * epd_op_coissue: how matrix and vector instructions of two waves of one SIMD share its issue port (what bounds the
+ * attention kernel, whose step is a matrix product, exponentials, a matrix product).  One workgroup of eight waves
+ * per CU: four waves (one per SIMD) issue iters_mfma x 16 v_mfma_f32_32x32x16_bf16 on independent accumulators, the
+ * other four iters_valu x 32 pairs of v_exp_f32 + fma; which = 1 the matrix waves alone, 2 the vector waves alone,
+ * 3 both together.  *ms_per_launch over `reps` launches.  operands: dev, 8 KiB of bf16; sink: dev, 4 bytes per
+ * launched thread (CUs * 512 floats). */
 epd_status epd_op_mfma_peak(const void* operands, int32_t iters, int32_t reps, float* sink, float* tflops,
                             void* hip_stream);
 epd_status epd_op_copy_peak(const void* src, void* dst, int64_t bytes, int32_t reps, float* gbps, void* hip_stream);
+epd_status epd_op_coissue(const void* operands, int32_t iters_mfma, int32_t iters_valu, int32_t which, int32_t reps,
+                          float* sink, float* ms_per_launch, void* hip_stream);
 
 #ifdef __cplusplus
 }

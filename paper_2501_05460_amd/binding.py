@@ -32,7 +32,7 @@ EXPORTS = (
     "epd_weight_count", "epd_check_desc", "epd_check_offsets", "epd_create", "epd_encode",
     "epd_encode_range", "epd_tokens_per_tile", "epd_out_dim", "epd_last_error", "epd_destroy",
     "epd_debug_read_stream", "epd_op_gemm_bf16", "epd_op_gemm_bf16_form", "epd_op_attention_bf16", "epd_op_mfma_probe",
-    "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak",
+    "epd_profile_enable", "epd_profile_read", "epd_op_mfma_peak", "epd_op_copy_peak", "epd_op_coissue",
     "epd_op_row_stats", "epd_op_gemm_residual_stats", "epd_op_norm_gemm_bf16",
     "epd_op_mx_rows", "epd_op_mx_gemm", "epd_op_mx_mfma_probe", "epd_op_attention_mx",
     "epd_mm_cache_create", "epd_mm_cache_destroy", "epd_mm_cache_free_blocks", "epd_mm_cache_base",
@@ -110,6 +110,8 @@ def lib() -> ctypes.CDLL:
         L.epd_op_mfma_peak.restype = i32
         L.epd_op_copy_peak.argtypes = [vp, vp, i64, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.epd_op_copy_peak.restype = i32
+        L.epd_op_coissue.argtypes = [vp, i32, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_float), vp]
+        L.epd_op_coissue.restype = i32
         L.epd_op_row_stats.argtypes = [vp, i64, i32, vp, vp, vp]
         L.epd_op_row_stats.restype = i32
         L.epd_op_gemm_residual_stats.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
@@ -454,6 +456,20 @@ def op_mfma_peak(random_operands: bool, iters: int = 2000, reps: int = 5) -> flo
                                ctypes.byref(out), _stream_ptr())
     if s != EPD_OK:
         raise EpdError(s, "mfma peak probe failed")
+    return out.value
+
+
+def op_coissue(which: int, iters_mfma: int = 4000, iters_valu: int = 5000, reps: int = 5) -> float:
+    """ms per launch of the issue-port probe: which = 1 matrix waves alone, 2 vector waves alone, 3 both."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(cus * 512, dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(1)
+    ops = torch.randn(4096, device="cuda", generator=g).to(torch.bfloat16)
+    out = ctypes.c_float()
+    s = lib().epd_op_coissue(ops.data_ptr(), iters_mfma, iters_valu, which, reps, sink.data_ptr(), ctypes.byref(out),
+                             _stream_ptr())
+    if s != EPD_OK:
+        raise EpdError(s, "co-issue probe failed")
     return out.value
 
 

@@ -138,6 +138,10 @@ def test_host_side_under_address_and_undefined_behaviour_sanitizers():
     from paper_2501_05460_amd import build as bld
     if not os.path.exists(bld.SAN_LIB) or os.environ.get("EPD_LIB_PATH"):
         pytest.skip("sanitizer build not present (or already running under it)")
+    newest_source = max(os.path.getmtime(os.path.join(d, f)) for d in (bld.CSRC, os.path.join(ROOT, "include"))
+                        for f in os.listdir(d))
+    if os.path.getmtime(bld.SAN_LIB) < newest_source:
+        pytest.skip("sanitizer build is older than the sources: run `python -m paper_2501_05460_amd.build --sanitize`")
     r = subprocess.run([sys.executable, "-m", "pytest", "-q", "-x", "-p", "no:cacheprovider",
                         os.path.join(ROOT, "tests", "test_abi_host.py"), os.path.join(ROOT, "tests", "test_mm_cache_host.py")],
                        env=bld.sanitized_env(), capture_output=True, text=True, timeout=600)
