@@ -233,3 +233,16 @@ def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
         want = O.linear(A.float().cpu().numpy(), W.float().cpu().numpy(), bias.cpu().numpy())
         got = B.op_gemm_bf16_form(A, W, bias, 0, 0).float().cpu().numpy()
         assert rel_err(got, want) < 6e-3
+
+
+def test_measurement_probes_run_and_report_sane_figures():
+    """The probes behind `bench.py --roof` (no part of the encode path): the register-resident MFMA loop stays below the
+    nominal bf16 peak and above a fifth of it, the streaming copy below the nominal HBM rate, and a SIMD that runs a
+    wave of MFMAs and a wave of exp + fma pairs together takes longer than either alone and less than both in turn
+    (the partial overlap the attention kernel's floor is derived from)."""
+    t = B.op_mfma_peak(True, iters=500, reps=2)
+    assert 500.0 < t < 2600.0, t
+    g = B.op_copy_peak(1 << 28, reps=2)
+    assert 1000.0 < g < 8000.0, g
+    m, v, both = B.op_coissue(1, 1000, 1250, 2), B.op_coissue(2, 1000, 1250, 2), B.op_coissue(3, 1000, 1250, 2)
+    assert m > 0 and v > 0 and max(m, v) * 0.98 <= both <= (m + v) * 1.02, (m, v, both)
