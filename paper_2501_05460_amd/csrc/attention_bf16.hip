@@ -408,10 +408,15 @@ __global__ __launch_bounds__(256, W4 ? 4 : (HD == 64 ? 3 : 2)) void k_attention_
       if (any_act) {
         issue_s(s0, ks, 0);
         softmax(s0, p0, kb * BKEY, kb == 0);
-        issue_s(s0, ks, 1);          // the weights of step 0 are out of the S^T registers: step 1's product starts
-        issue_pv(p0, vs, 0);         // under the second product of step 0
-        softmax(s0, p0, kb * BKEY + 32, false);
-        issue_pv(p0, vs, 1);
+        // a step whose keys all lie past n_keys (the second half of a padded slice's last block) has weights of
+        // exactly zero: left out, same bits
+        const bool second = !MASK || kb * BKEY + 32 < n_keys;   // uniform
+        if (second) issue_s(s0, ks, 1);   // the weights of step 0 are out of the S^T registers: step 1's product starts
+        issue_pv(p0, vs, 0);              // under the second product of step 0
+        if (second) {
+          softmax(s0, p0, kb * BKEY + 32, false);
+          issue_pv(p0, vs, 1);
+        }
       }
       sstore((kb + 1) & 1, kb + 1 < NB ? kb + 1 : kb);
       kdma_wait();
