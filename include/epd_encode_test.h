@@ -36,6 +36,8 @@ epd_status epd_op_gemm_bf16(const void* A, const void* W, const float* bias, voi
  * 2 = 128x128 tile, 3 = 128x128 tile with the loads four slabs ahead (K % 256 == 0), 6 = 256x256 tile with the plain loop, 7 = pipelined loop, 8 = pipelined loop with both operand slabs
  * loaded straight into LDS, 9 = persistent kernel (not epi 3), 10 = persistent kernel of the residual product (epi 3 only),
  * 11 = 64x64 tiles with both operand slabs in an LDS ring (what the library picks for launches of a slice or two).
+ * 12 = the persistent residual product on 256x192 tiles (epi 3 only, N % 192 == 0: what the library picks for a
+ * width like 1152, which is six such tile columns and four and a half 256-wide ones).
  * M >= 1 (any), N % 128 == 0 (N % 256 == 0 for forms 6 to 10), K % 128 == 0; bias [N] fp32.
  * A [M,K], C [M,N] and R [M,N] hold exactly M rows; no row past M is written.  (The kernels read whole
  * 256-row tiles; for a ragged M, and for R, the call runs on padded copies it allocates, and synchronises.) */

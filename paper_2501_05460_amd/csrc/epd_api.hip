@@ -1345,8 +1345,9 @@ epd_status epd_op_gemm_bf16_form(const void* A, const void* W, const float* bias
   const bool residual = epi == EPI_BIAS_RESIDUAL;
   if (!A || !W || !bias || (residual ? !R : !C) || M <= 0 || N <= 0 || K <= 0 || N % 128 || K % 128 ||
       !(epi == EPI_BIAS || epi == EPI_BIAS_GELU_ERF || epi == EPI_BIAS_GELU_TANH || residual) ||
-      !(form == 0 || form == 1 || form == 2 || form == 3 || form == 6 || form == 7 || form == 8 || form == 9 || form == 10 || form == 11) ||
-      (form == 3 && K % 256) || (form >= 6 && form <= 10 && N % 256) || (form == 9 && residual) || (form == 10 && !residual)) {
+      !(form == 0 || form == 1 || form == 2 || form == 3 || (form >= 6 && form <= 12)) ||
+      (form == 3 && K % 256) || (form >= 6 && form <= 10 && N % 256) || (form == 9 && residual) || (form == 10 && !residual) ||
+      (form == 12 && (!residual || N % 192))) {
     set_err(g_err, sizeof(g_err), "epd_op_gemm_bf16_form: bad argument");
     return EPD_ERR_INVALID_ARG;
   }

@@ -1065,14 +1065,24 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist(const GemmParams p
 // LDS buffer 1 only.  A pass holds sub-tile row group i = pass of all eight waves (rows wm * 128 + 32 pass ..
 // + 31 of both wave rows: staging row r = 32 wm + row), so every wave stages in every pass.  The stream rows of
 // the first two passes are fetched while the last two slabs are multiplied, those of pass p + 2 behind pass p.
+//
+// BN = 192 (tile 256 x 192) is for output widths that are whole multiples of 192 and not of 256 (1152 = 6 x 192
+// = 4.5 x 256: every fifth 256-wide tile column would be half empty).  Its waves stand 4 x 2, each on 64 x 96
+// (2 x 3 MFMA blocks; the k-steps of an element are summed in the same order, so the bits are those of every
+// other form).  The 64 staging rows of a pass then hold sub-tile row group pass / 2 of wave rows 2 (pass % 2)
+// and 2 (pass % 2) + 1, so half of the waves stage in a pass, and a staging row's 48 chunks no longer match a
+// wave: thread t reads chunks t, t + 512, .. of the 3072 a pass has, row and column per lane.
 // ---------------------------------------------------------------------------
+template <int BN>
 __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmParams p, const int gm_, const int gw,
                                                                   const int n_tiles) {
-  constexpr int BN = 256, NTHREADS = 512, WN = 64, WAVES_N = 4, WM = 128, TM = 4, TN = 2;
-  constexpr int A_LD = 4, B_LD = 4, ROWS_PER_LD = 64;
-  constexpr int XNCH = BN * 4 / 16;                // 16-byte chunks per staging row: one wave reads one row
-  constexpr int XSTEP = NTHREADS / XNCH;           // 8 staging rows between a thread's chunks
-  constexpr int XPER_T = 64 * XNCH / NTHREADS;     // 8 chunks per thread and pass
+  static_assert(BN == 256 || BN == 192, "tile widths compiled");
+  constexpr bool WIDE = BN == 256;
+  constexpr int NTHREADS = 512, WAVES_N = WIDE ? 4 : 2, WN = BN / WAVES_N, WM = BM / (8 / WAVES_N), TM = WM / 32, TN = WN / 32;
+  constexpr int A_LD = 4, B_LD = BN / 64, ROWS_PER_LD = 64;
+  constexpr int XNCH = BN * 4 / 16;                // 16-byte chunks per staging row (BN = 256: one wave reads one row)
+  constexpr int XSTEP = NTHREADS / XNCH;           // BN = 256: 8 staging rows between a thread's chunks
+  constexpr int XPER_T = 64 * XNCH / NTHREADS;     // 8 (6) chunks per thread and pass
   constexpr int ROWB = BN * 4;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -1084,7 +1094,7 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int l32 = lane & 31, lh = lane >> 5;
   const int KT_ = p.K / BK;  // even
-  const int gn = p.Npad / BN;
+  const int gn = WIDE ? p.Npad / BN : p.N / BN;
 
   auto tile_of = [&](int pos, int& m0, int& n0) {
     const int x = pos & 7, slot = pos >> 3;
@@ -1155,13 +1165,21 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
   using VM_X = std::integral_constant<int, XPER_T>;
 
   // Stream rows of an epilogue pass through a buffer descriptor: every lane of every wave issues exactly XPER_T
-  // loads whatever the tile's position (rows past M are read like any other: R holds whole tiles; columns past N
-  // fall outside the descriptor's range and come back as zero), so a wait can count them.
+  // loads whatever the tile's position, so a wait can count them.  BN = 256: the row is a scalar offset, outside
+  // the descriptor's range check (rows past M are read like any other: R holds whole tiles); columns past N fall
+  // outside the range and come back as zero.  BN = 192: row and column are the lane offset; a row past M comes
+  // back as zero.
   __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
       p.R, 0, (int)(unsigned)(((long)(p.M - 1) * p.ldr + p.N) * 4), 0x00020000);
   f32x4 xr[2][XPER_T];
-  // staging row r of a pass <-> tile row (r / 32) * 128 + 32 pass + r % 32
-  auto tile_row = [&](int pass, int r) { return (r >> 5) * 128 + pass * 32 + (r & 31); };
+  // staging row r of a pass <-> tile row: BN = 256: (r / 32) * 128 + 32 pass + r % 32;
+  // BN = 192: (2 (pass % 2) + r / 32) * 64 + 32 (pass / 2) + r % 32
+  auto tile_row = [&](int pass, int r) {
+    return WIDE ? (r >> 5) * 128 + pass * 32 + (r & 31) : (2 * (pass & 1) + (r >> 5)) * 64 + (pass >> 1) * 32 + (r & 31);
+  };
+  // BN = 192: chunk i of this thread in a pass: staging row and chunk column
+  auto x_r = [&](int i) { return (tid + NTHREADS * i) / XNCH; };
+  auto x_c = [&](int i) { return (tid + NTHREADS * i) % XNCH; };
 
   int pos = blockIdx.x, m0, n0, m0n, n0n;
   tile_of(pos, m0, n0);
@@ -1190,8 +1208,12 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
       constexpr int S = decltype(set)::value;
 #pragma unroll
       for (int i = 0; i < XPER_T; ++i)
-        xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-            rsrc_x, (unsigned)x_col * 4u, (unsigned)(m0 + tile_row(pass, wave_u + XSTEP * i)) * (unsigned)p.ldr * 4u, 2));
+        if constexpr (WIDE)
+          xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+              rsrc_x, (unsigned)x_col * 4u, (unsigned)(m0 + tile_row(pass, wave_u + XSTEP * i)) * (unsigned)p.ldr * 4u, 2));
+        else
+          xr[S][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+              rsrc_x, ((unsigned)(m0 + tile_row(pass, x_r(i))) * (unsigned)p.ldr + (unsigned)(n0 + x_c(i) * 4)) * 4u, 0, 2));
     };
     // PHASE 0: a slab in the middle of the tile; 1: the slab before the last (also starts the stream rows of pass 0,
     // which its wait leaves in flight); 2: the last slab (fetches the next tile's first slab, starts pass 1's rows)
@@ -1233,11 +1255,13 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
       auto stage_row = [&](int r) -> unsigned char* {
         return reinterpret_cast<unsigned char*>(r < 32 ? sB + BN * BK : sA + BM * BK) + (r & 31) * ROWB;
       };
-      auto fp32_pass = [&](auto set, int pass) {
+      auto fp32_pass = [&](auto set, auto pass_) {
         constexpr int S = decltype(set)::value;
+        constexpr int pass = decltype(pass_)::value;
+        constexpr int sub = WIDE ? pass : pass >> 1;     // sub-tile row group of a wave that goes through this pass
         if (pass > 0) __syncthreads();   // the previous pass has been read out
-        {
-          const int r = wm * 32 + l32;   // this lane's staging row: sub-tile i = pass of its wave
+        if (WIDE || (wm >> 1) == (pass & 1)) {           // wave-uniform
+          const int r = (WIDE ? wm : wm & 1) * 32 + l32;   // this lane's staging row
           unsigned char* srow = stage_row(r);
 #pragma unroll
           for (int j = 0; j < TN; ++j)
@@ -1247,34 +1271,42 @@ __global__ __launch_bounds__(512, 1) void k_gemm_bf16_persist_res(const GemmPara
               const f32x4 b4 = *reinterpret_cast<const f32x4*>(sBias + cl);
               f32x4 v;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                // acc[pass][j] with a compile-time first index: the pass loop below is unrolled
-                v[e] = (pass == 0 ? acc[0][j][gi * 4 + e] : pass == 1 ? acc[1][j][gi * 4 + e]
-                        : pass == 2 ? acc[2][j][gi * 4 + e] : acc[3][j][gi * 4 + e]) + b4[e];
-              }
+              for (int e = 0; e < 4; ++e) v[e] = acc[sub][j][gi * 4 + e] + b4[e];
               *reinterpret_cast<f32x4*>(srow + (((cl >> 2) ^ (r & 15)) << 4)) = v;
             }
         }
         __syncthreads();
         if (pass == 3 && has_next && tid < BN) sBias[tid] = p.bias[n0n + tid];   // every bias read is behind us
-        if (x_col_ok) {
-          const int c = tid % XNCH;
+        if constexpr (WIDE) {
+          if (x_col_ok) {
+            const int c = tid % XNCH;
+#pragma unroll
+            for (int i = 0; i < XPER_T; ++i) {
+              const int r = wave_u + XSTEP * i;
+              const int row = m0 + tile_row(pass, r);              // uniform
+              if (row < p.M) {
+                const f32x4 v = *reinterpret_cast<const f32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
+                __builtin_nontemporal_store(xr[S][i] + v, reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + x_col));
+              }
+            }
+          }
+        } else {
 #pragma unroll
           for (int i = 0; i < XPER_T; ++i) {
-            const int r = wave_u + XSTEP * i;
-            const int row = m0 + tile_row(pass, r);              // uniform
-            if (row < p.M) {
+            const int r = x_r(i), c = x_c(i);
+            const int row = m0 + tile_row(pass, r), col = n0 + c * 4;
+            if (row < p.M && col < p.N) {
               const f32x4 v = *reinterpret_cast<const f32x4*>(stage_row(r) + ((c ^ (r & 15)) << 4));
-              __builtin_nontemporal_store(xr[S][i] + v, reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + x_col));
+              __builtin_nontemporal_store(xr[S][i] + v, reinterpret_cast<f32x4*>(p.R + (long)row * p.ldr + col));
             }
           }
         }
         if (pass + 2 < 4) xload(set, pass + 2);
       };
-      fp32_pass(S0{}, 0);
-      fp32_pass(S1{}, 1);
-      fp32_pass(S0{}, 2);
-      fp32_pass(S1{}, 3);
+      fp32_pass(S0{}, std::integral_constant<int, 0>{});
+      fp32_pass(S1{}, std::integral_constant<int, 1>{});
+      fp32_pass(S0{}, std::integral_constant<int, 2>{});
+      fp32_pass(S1{}, std::integral_constant<int, 3>{});
     }
     if (!has_next) break;
     __syncthreads();   // buffer 1 has been read out: the next tile's first hand-over may fill it
@@ -1563,24 +1595,32 @@ bool persist_res() {   // EPD_PERSIST_RES=0: the residual products stay on the o
   return on;
 }
 
-// residual product on the persistent kernel (whole 256 x 256 tiles; no bf16 rows / statistics emitted)
+// residual product on the persistent kernel (whole 256 x BN tiles; no bf16 rows / statistics emitted);
+// BN = 192 wants N % 192 == 0
+template <int BN = 256>
 hipError_t launch_persist_res(const GemmParams& p, hipStream_t st) {
-  const int gm = (p.M + BM - 1) / BM, gn = p.Npad / 256;
+  if (BN != 256 && p.N % BN != 0) return hipErrorInvalidValue;
+  const int gm = (p.M + BM - 1) / BM, gn = BN == 256 ? p.Npad / 256 : p.N / BN;
   const int n_tiles = gm * gn;
   if (n_tiles == 0) return hipSuccess;
-  const double panel = 256.0 * p.K * sizeof(bf16_t);
+  const double panel = (double)BN * p.K * sizeof(bf16_t);
   int gw = 1;
   double best = 1e30;
   for (int c = 1; c <= gn && c <= 32; ++c) {
-    const bool resident = c * 256.0 * p.K * sizeof(bf16_t) <= 2.5 * (1 << 20);
+    const bool resident = c * panel <= 2.5 * (1 << 20);
     const double cost = (32.0 / c) * panel + (resident ? 0.0 : c * panel);
     if (cost < best * 0.999) { best = cost; gw = c; }
   }
   if (p.band > 0 && p.band <= gn) gw = p.band;
   const int grid = n_tiles < cu_count() ? n_tiles : cu_count();
-  k_gemm_bf16_persist_res<<<dim3(grid), dim3(512), smem_bytes<256, 512>(), st>>>(p, gm, gw, n_tiles);
+  k_gemm_bf16_persist_res<BN><<<dim3(grid), dim3(512), smem_bytes<BN, 512>(), st>>>(p, gm, gw, n_tiles);
   ++g_kernel_launches;
   return hipGetLastError();
+}
+
+bool tiles_192() {   // EPD_TILES_192=0: widths like 1152 stay on the 256-wide tiles
+  static const bool on = !(getenv("EPD_TILES_192") && getenv("EPD_TILES_192")[0] == '0');
+  return on;
 }
 
 template <bool FOLD>
@@ -1674,8 +1714,10 @@ hipError_t bf16_gemm_init() {
   if (e != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 1>()) != hipSuccess) return e;
   if ((e = set_attr_all<256, 512, 64, 3>()) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist_res),
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist_res<256>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<256, 512>())) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16_persist_res<192>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<192, 512>())) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_ERF, false>()) != hipSuccess) return e;
   if ((e = set_attr_persist<EPI_BIAS_GELU_TANH, false>()) != hipSuccess) return e;
@@ -1717,12 +1759,24 @@ hipError_t bf16_gemm(const GemmParams& p, hipStream_t st) {
     case 9: if (p.Npad % 256 == 0 && p.epi != EPI_BIAS_RESIDUAL && p.epi != EPI_BIAS_POS) return dispatch_persist(p, st); break;
     case 10: if (p.Npad % 256 == 0 && p.epi == EPI_BIAS_RESIDUAL && !p.xb) return launch_persist_res(p, st); break;
     case 11: if (small_form_has(p)) return launch_small(p, st); break;
+    case 12: if (p.N % 192 == 0 && p.epi == EPI_BIAS_RESIDUAL && !p.xb) return launch_persist_res<192>(p, st); break;
   }
   // One or two slices: 64 x 64 tiles while there are at most two of them per CU (measured against the
   // 128 x 128 tiles on 1024 and 2048 rows: ahead up to 512 tiles, behind from 1024 on).  Same bits.
   if (p.cfg == 0 && small_tiles() && small_form_has(p) &&
       (long)((p.M + SM_T - 1) / SM_T) * (p.Npad / SM_T) <= 2L * cu_count())
     return launch_small(p, st);
+  // A width of 1152 is four and a half 256-wide tile columns and six 192-wide ones.  The residual product takes
+  // 256 x 192 tiles when their rounds, at T192 of a 256 x 256 tile's time each, come to less: the 10-slice
+  // SigLIP-shaped request (240 tiles in one round instead of 200: -8 % on both of its residual products), not a
+  // micro-batch of 128 slices (12 rounds for 10).  Same bits.
+  if (p.cfg == 0 && p.epi == EPI_BIAS_RESIDUAL && !p.xb && persist_res() && tiles_192() && p.N % 192 == 0 && p.N % 256 != 0) {
+    const long cus = cu_count(), gm = (p.M + BM - 1) / BM;
+    const long t256 = gm * ((p.N + 255) / 256), t192 = gm * (p.N / 192);
+    constexpr double T192 = 0.92;   // measured: a 256 x 192 tile takes 0.92 of a 256 x 256 tile's time (more operand bytes per flop)
+    if (t256 * 2 > cus && (double)((t192 + cus - 1) / cus) * T192 < (double)((t256 + cus - 1) / cus))
+      return launch_persist_res<192>(p, st);
+  }
   if (p.Npad % 256 != 0) return dispatch<128, 512, 64>(p, st);
   // A width like 3200 leaves the last 256-wide tile column half used.  When that column is also what
   // spills the launch into a nearly empty last round (at most a quarter of the CUs busy), the residual

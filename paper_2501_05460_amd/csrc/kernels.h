@@ -39,7 +39,8 @@ struct GemmParams {
   int epi;
   int cfg;                    // 0: chosen by shape and epilogue; tests / timing: 1 = 256x128 tile, 2 / 3 = 128x128 tile (loads two / four slabs ahead), 6 = 256x256 plain loop,
                               // 7 = 256x256 pipelined loop, 8 = the same with both operands straight into LDS,
-                              // 9 = 256x256 persistent (bf16-output epilogues), 10 = persistent residual product, 11 = 64x64 tiles (small launches)
+                              // 9 = 256x256 persistent (bf16-output epilogues), 10 = persistent residual product, 11 = 64x64 tiles (small launches),
+                              // 12 = persistent residual product on 256x192 tiles (N % 192 == 0)
   int band;                   // 0: automatic; else tile columns per L2 band (must divide Npad / BN)
   const bf16_t* A; long lda;
   const bf16_t* W;            // packed [Npad, K]

@@ -235,6 +235,31 @@ def test_gemm_forms_agree_bit_for_bit(M, N, K, epi):
         assert rel_err(got, want) < 6e-3
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 384, 128), (1000, 1152, 256), (2900, 1152, 1152), (77, 384, 384), (10240, 1152, 128)])
+def test_gemm_192_wide_tiles_agree_bit_for_bit(M, N, K):
+    """The residual product on 256 x 192 tiles (widths that are whole multiples of 192 and not of 256) leaves the
+    bits of the other tile shapes: whole and ragged M, one tile and several per workgroup, and a launch with more
+    tiles than CUs (the persistent walk takes a second tile)."""
+    rng = np.random.default_rng(M + N + K)
+    A = B.to_device(_bf16_grid(rng, (M, K), 0.5), True)
+    W = B.to_device(_bf16_grid(rng, (N, K), 0.05), True)
+    bias = torch.from_numpy(rng.standard_normal(N).astype(np.float32) * 0.1).cuda()
+    r0 = torch.from_numpy(rng.standard_normal((M, N)).astype(np.float32)).cuda()
+
+    def run(form):
+        R = r0.clone()
+        B.op_gemm_bf16_form(A, W, bias, 3, form, R)
+        torch.cuda.synchronize()
+        return R.view(torch.int32).cpu().numpy()
+
+    ref = run(1)
+    assert np.array_equal(run(12), ref)
+    assert np.array_equal(run(2), ref)
+    assert np.array_equal(run(0), ref)          # whichever form the library picks for this shape
+    want = r0.cpu().numpy().astype(np.float64) + O.linear(A.float().cpu().numpy(), W.float().cpu().numpy(), bias.cpu().numpy())
+    assert rel_err(ref.view(np.float32), want) < 1e-4
+
+
 def test_measurement_probes_run_and_report_sane_figures():
     """The probes behind `bench.py --roof` (no part of the encode path): the register-resident MFMA loop stays below the
     nominal bf16 peak and above a fifth of it, the streaming copy below the nominal HBM rate, and a SIMD that runs a
